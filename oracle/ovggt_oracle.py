@@ -1,0 +1,253 @@
+"""CPU oracle for the OVGGT streaming hot path.  TEST INFRASTRUCTURE ONLY.
+
+Only the test-suite, the smoke check and the benchmark's cpu_baseline leg may
+import this file; the product path never does.  It shares no code with the HIP
+library and is written for readability, not speed: plain numpy, fp64 attention,
+fp32 scores with a fixed summation order, a full sort for the top-k.
+
+What it computes, per layer, for every incoming frame t (paper Sec. 3.1-3.3):
+
+  1. append   C_t = [C_{t-1}; (K_t, V_t)]                        (Eq. 2)
+  2. attend   O_t = softmax(Q_t K_c^T / sqrt(d)) V_c over every resident entry,
+              the frame's own tokens included (the temporal causal attention
+              CA of Sec. 3.1; causality is frame-level, so one frame at a time
+              needs no mask)
+  3. score    s_i = || FFN residual of token i ||_2               (Eq. 5)
+  4. protect  tokens named by Dynamic Anchor Protection form P     (Sec. 3.3)
+  5. select   C~_t = P  U  Top-k(U, B - |P|)                       (Eq. 8)
+  6. compact  evicted entries leave the arrays; size becomes min(n, B)
+
+Readings taken where the paper is silent (each is listed in the design notes):
+  * every cached token keeps the activation score it received on entry
+    (stored-score policy); the paper's hybrid re-scoring of history (Eq. 7) is
+    `hybrid_rank` below and is only used when asked for;
+  * ranking uses ss = s^2 (same order as s, no square-root rounding);
+  * ss is an fp32 balanced-binary-tree sum of fp32 squares (so a GPU wave can
+    reproduce it bit for bit);
+  * ties are broken by token id: the older token (lower id) wins;
+  * layout after eviction: the r-th vacated slot below B receives the r-th
+    surviving entry at or above B, both in ascending slot order.
+
+Pins (see tests/test_oracle_pins.py): single key => O = V; equal keys => mean
+of V; dominant key; agreement with a two-pass fp32 formulation and with a
+library attention routine; budget >= stream length reproduces uncompressed
+causal streaming attention; |C~_t| = min((t+1)M, B); anchors never leave;
+brute-force top-k on tiny inputs; whole-stream closed form of the kept set;
+exact integer / power-of-two score rows and a crafted row that separates the
+tree order from left-to-right order; Eq. 9's bound on |P|; the 2 L T M N_h d
+footprint with the paper's "~10 GB at 100 frames" example.
+Parity unpinned by the paper: the slot layout after eviction (our definition,
+pinned only by exhaustive tiny cases and by permutation invariance of
+attention) and `hybrid_rank`/`smooth_scores` beyond their degenerate cases.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+class BudgetError(Exception):
+    """|P| exceeds the budget B: Eq. 8 would ask for a negative k."""
+
+
+# --------------------------------------------------------------------------- #
+# Eq. 5 -- activation score
+# --------------------------------------------------------------------------- #
+def tree_sum_sq_f32(r: np.ndarray) -> np.ndarray:
+    """ss_i = sum_c r[i,c]^2 in fp32, rows of `r` [n, C].
+
+    Each square is rounded to fp32 once; the C squares are zero-padded to a
+    power of two and added pairwise, neighbours first ((0+1), (2+3), ...),
+    level by level, every add rounded to fp32.
+    """
+    r = np.asarray(r, dtype=np.float32)
+    if r.ndim == 1:
+        r = r[None, :]
+    p = r * r                                     # fp32 x fp32 -> fp32, one rounding
+    width = 1
+    while width < p.shape[1]:
+        width *= 2
+    if width != p.shape[1]:
+        p = np.concatenate([p, np.zeros((p.shape[0], width - p.shape[1]), np.float32)], axis=1)
+    while p.shape[1] > 1:
+        p = p[:, 0::2] + p[:, 1::2]               # fp32 adds
+    return p[:, 0].astype(np.float32)
+
+
+def activation_score(r: np.ndarray) -> np.ndarray:
+    """s_i of Eq. 5 (informational; ranking uses ss)."""
+    return np.sqrt(tree_sum_sq_f32(r))
+
+
+# --------------------------------------------------------------------------- #
+# Sec. 3.1 -- attention of the new frame's queries over the cache
+# --------------------------------------------------------------------------- #
+def attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, scale: float | None = None) -> np.ndarray:
+    """softmax(q k^T * scale) v per head, fp64.
+
+    q [M,H,d], k and v [n,H,d] (every resident cache entry).  Returns [M,H,d].
+    """
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    M, H, d = q.shape
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    out = np.empty((M, H, d), dtype=np.float64)
+    for h in range(H):
+        logits = (q[:, h, :] @ k[:, h, :].T) * scale          # [M, n]
+        logits -= logits.max(axis=1, keepdims=True)
+        w = np.exp(logits)
+        w /= w.sum(axis=1, keepdims=True)
+        out[:, h, :] = w @ v[:, h, :]
+    return out
+
+
+# --------------------------------------------------------------------------- #
+# Eq. 8 -- which entries stay
+# --------------------------------------------------------------------------- #
+def rank_order(ss: np.ndarray, gid: np.ndarray) -> np.ndarray:
+    """Indices sorted best-first: larger ss first, equal ss -> lower id first.
+    A NaN score ranks as +0 (lowest)."""
+    ss = np.asarray(ss, dtype=np.float32)
+    key = np.where(np.isnan(ss), np.float32(0), ss).astype(np.float64)
+    return np.lexsort((np.asarray(gid, dtype=np.int64), -key))
+
+
+def select_keep(ss: np.ndarray, gid: np.ndarray, flag: np.ndarray, budget: int) -> np.ndarray:
+    """Boolean keep mask over the n resident entries.
+
+    n <= B keeps everything.  Otherwise the protected entries P (flag != 0) stay
+    and the k = B - |P| best evictable entries join them.
+    """
+    n = len(ss)
+    flag = np.asarray(flag) != 0
+    if n <= budget:
+        return np.ones(n, dtype=bool)
+    n_prot = int(flag.sum())
+    k = budget - n_prot
+    if k < 0:
+        raise BudgetError(f"|P|={n_prot} > B={budget}")
+    evictable = np.flatnonzero(~flag)
+    order = rank_order(np.asarray(ss)[evictable], np.asarray(gid)[evictable])
+    keep = flag.copy()
+    keep[evictable[order[:k]]] = True
+    return keep
+
+
+def hole_fill_moves(keep: np.ndarray, budget: int) -> tuple[np.ndarray, np.ndarray]:
+    """(dst, src) slot pairs: vacated slots below B in ascending order receive
+    the kept slots at or above B in ascending order."""
+    keep = np.asarray(keep, dtype=bool)
+    holes = np.flatnonzero(~keep[:budget])
+    movers = budget + np.flatnonzero(keep[budget:])
+    assert len(holes) == len(movers)
+    return holes, movers
+
+
+# --------------------------------------------------------------------------- #
+# the per-layer streaming cache
+# --------------------------------------------------------------------------- #
+class OracleCache:
+    """One layer's KV cache with scores, ids and protection flags per slot."""
+
+    def __init__(self, M: int, H: int, d: int, budget: int, scale: float | None = None):
+        if budget < M:
+            raise ValueError("budget must hold at least one frame")
+        self.M, self.H, self.d, self.B = M, H, d, budget
+        self.scale = scale
+        self.k = np.zeros((0, H, d), np.float32)
+        self.v = np.zeros((0, H, d), np.float32)
+        self.gid = np.zeros(0, np.uint32)
+        self.ss = np.zeros(0, np.float32)
+        self.flag = np.zeros(0, np.uint8)
+        self.t = 0                       # frames seen
+        self.nan_seen = False
+
+    @property
+    def n(self) -> int:
+        return len(self.gid)
+
+    # step 1 (Eq. 2)
+    def append(self, k_t: np.ndarray, v_t: np.ndarray) -> None:
+        M = self.M
+        assert k_t.shape == (M, self.H, self.d) and v_t.shape == k_t.shape
+        self.k = np.concatenate([self.k, np.asarray(k_t, np.float32)])
+        self.v = np.concatenate([self.v, np.asarray(v_t, np.float32)])
+        self.gid = np.concatenate([self.gid, (self.t * M + np.arange(M)).astype(np.uint32)])
+        self.ss = np.concatenate([self.ss, np.zeros(M, np.float32)])
+        self.flag = np.concatenate([self.flag, np.zeros(M, np.uint8)])
+
+    # step 2
+    def attend(self, q_t: np.ndarray) -> np.ndarray:
+        return attention(q_t, self.k, self.v, self.scale)
+
+    # steps 3-6
+    def update(self, resid_t: np.ndarray, anchor_t: np.ndarray | None) -> np.ndarray:
+        """Score the M newest entries, flag anchors, select, compact.
+        Returns the keep mask over the pre-compaction slots."""
+        M, n = self.M, self.n
+        ss_new = tree_sum_sq_f32(resid_t)
+        assert ss_new.shape == (M,)
+        flag_new = np.zeros(M, np.uint8) if anchor_t is None else (np.asarray(anchor_t) != 0).astype(np.uint8)
+        ss = self.ss.copy(); ss[n - M:] = ss_new
+        flag = self.flag.copy(); flag[n - M:] = flag_new
+        keep = select_keep(ss, self.gid, flag, self.B)     # raises before any state change
+        self.ss, self.flag = ss, flag
+        if np.isnan(ss_new).any():
+            self.nan_seen = True
+        if n > self.B:
+            dst, src = hole_fill_moves(keep, self.B)
+            for arr in (self.k, self.v, self.gid, self.ss, self.flag):
+                arr[dst] = arr[src]
+            self.k, self.v = self.k[:self.B], self.v[:self.B]
+            self.gid, self.ss, self.flag = self.gid[:self.B], self.ss[:self.B], self.flag[:self.B]
+        self.t += 1
+        return keep
+
+    def step(self, q_t, k_t, v_t, resid_t, anchor_t, attend: bool = True):
+        """One frame through steps 1-6; returns O_t (or None when attend=False:
+        cache contents never depend on attention outputs)."""
+        self.append(k_t, v_t)
+        out = self.attend(q_t) if attend else None
+        self.update(resid_t, anchor_t)
+        return out
+
+
+# --------------------------------------------------------------------------- #
+# widening rows: the paper's own treatment of history and of the score map
+# --------------------------------------------------------------------------- #
+def minmax01(x: np.ndarray) -> np.ndarray:
+    x = np.asarray(x, dtype=np.float64)
+    if x.size == 0:
+        return x
+    lo, hi = x.min(), x.max()
+    return np.zeros_like(x) if hi == lo else (x - lo) / (hi - lo)
+
+
+def hybrid_rank(k_hist: np.ndarray, s_new: np.ndarray, beta: float) -> tuple[np.ndarray, np.ndarray]:
+    """Eq. 7: r = (1-beta) * minmax(1 - cos(k_i, kbar)) for evictable history,
+    r = beta * minmax(s_i) for the current frame.  k_hist [n, H*d] with kbar the
+    centroid of those rows.  PARITY UNPINNED beyond beta in {0,1} and range."""
+    k = np.asarray(k_hist, dtype=np.float64).reshape(len(k_hist), -1)
+    if len(k):
+        kbar = k.mean(axis=0)
+        cos = (k @ kbar) / (np.linalg.norm(k, axis=1) * np.linalg.norm(kbar))
+        d = 1.0 - cos
+    else:
+        d = np.zeros(0)
+    return (1.0 - beta) * minmax01(d), beta * minmax01(s_new)
+
+
+def smooth_scores(s_patch: np.ndarray, alpha: float, g: np.ndarray) -> np.ndarray:
+    """Eq. 6: S~ = alpha (G * S) + (1-alpha) S on the H_p x W_p patch map, with
+    an explicit normalised kernel `g` and replicate padding.  PARITY UNPINNED
+    (kernel size, sigma and padding are not given) beyond alpha = 0."""
+    s = np.asarray(s_patch, dtype=np.float64)
+    g = np.asarray(g, dtype=np.float64)
+    ry, rx = g.shape[0] // 2, g.shape[1] // 2
+    pad = np.pad(s, ((ry, ry), (rx, rx)), mode="edge")
+    conv = np.zeros_like(s)
+    for dy in range(g.shape[0]):
+        for dx in range(g.shape[1]):
+            conv += g[dy, dx] * pad[dy:dy + s.shape[0], dx:dx + s.shape[1]]
+    return alpha * conv + (1.0 - alpha) * s
