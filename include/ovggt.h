@@ -1,0 +1,158 @@
+/* ovggt.h -- C ABI of the MI355X (gfx950) OVGGT streaming hot path.
+ *
+ * One handle holds L independent per-layer KV caches of fixed budget B.  For
+ * every incoming frame (M tokens) and layer the caller issues, in this order,
+ *
+ *     ovggt_global_attn  ->  ovggt_score_select  ->  ovggt_cache_compact
+ *
+ * which together implement: append the frame's K/V to the cache (paper Eq. 2),
+ * temporal causal attention of the frame's queries over every resident entry
+ * (Sec. 3.1), Activation Value Rating of the new tokens (Eq. 5), Dynamic
+ * Anchor Protection's exemption of flagged tokens (Sec. 3.3), fixed-budget
+ * top-k retention (Eq. 8), and the in-place removal of evicted entries.
+ *
+ * General rules
+ *  - All `*_dev` / "device" pointers are HIP device memory owned by the caller
+ *    and must outlive the handle; "host" pointers are ordinary host memory.
+ *    The library allocates no device memory and frees none.
+ *  - `hip_stream` is a hipStream_t passed as void* (NULL = default stream).
+ *    Hot-path calls only enqueue work on it and never synchronise; inputs must
+ *    stay valid until the stream has executed the call.  Calls on one handle
+ *    must be issued on streams that order them (normally the same stream).
+ *  - Every function returns OVGGT_OK (0) or a negative error code.  Arguments
+ *    and call order are validated on the host before anything is launched; a
+ *    failed call changes no state.  Conditions only the device can see set bits
+ *    in a per-layer status word (ovggt_cache_status).
+ *  - `layer` is in [0, n_layers) or OVGGT_ALL_LAYERS (-1): one launch covers
+ *    all layers and every tensor argument carries a leading [n_layers]
+ *    dimension; all layers must then be at the same point of the call order.
+ *  - Tensors are dense row-major: Q, K, V, O are [M, n_heads, head_dim] (token-
+ *    major), residuals are [M, resid_dim], in the handle's dtype.  Pointers
+ *    must be 16-byte aligned.
+ *  - The physical layout of the cache buffers is private; use
+ *    ovggt_cache_export for a defined logical view.
+ */
+#ifndef OVGGT_H
+#define OVGGT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ovggt_cache ovggt_cache;     /* opaque host object */
+
+enum { OVGGT_F32 = 0, OVGGT_BF16 = 1 };
+enum { OVGGT_ALL_LAYERS = -1 };
+enum {
+  OVGGT_OK = 0,
+  OVGGT_ERR_ARG = -1,      /* NULL / misaligned pointer, bad layer, bad config value   */
+  OVGGT_ERR_STATE = -2,    /* call out of order for that layer                          */
+  OVGGT_ERR_BUDGET = -3,   /* reserved: protected set larger than the budget (host-known) */
+  OVGGT_ERR_HIP = -4       /* a HIP runtime call failed (launch, copy, query)            */
+};
+/* bits of the device status word */
+enum {
+  OVGGT_STATUS_BUDGET = 1, /* |P| > B at a selection: Eq. 8's k would be negative; the
+                              frame's surplus slots were dropped instead (cache invalid) */
+  OVGGT_STATUS_NONFINITE = 2 /* a NaN (or negative) score was seen; it ranks lowest      */
+};
+
+typedef struct {
+  int32_t n_layers;          /* L >= 1 independent caches                                  */
+  int32_t n_heads;           /* N_h >= 1                                                   */
+  int32_t head_dim;          /* d; must be 64                                              */
+  int32_t tokens_per_frame;  /* M = 1 + 4 + N_p in the paper (Sec. 3.1); any M >= 1        */
+  int32_t resid_dim;         /* C: width of the FFN-residual rows, 1..4096                 */
+  int32_t budget;            /* B tokens per layer, protected tokens included; B >= M      */
+  int32_t dtype;             /* OVGGT_F32 or OVGGT_BF16: Q/K/V/O/residual and cache storage */
+  int32_t score_mode;        /* 0 = every entry keeps the Eq. 5 score it entered with      */
+  float   softmax_scale;     /* 0 => 1/sqrt(head_dim)                                      */
+} ovggt_config;
+
+/* Sizes (bytes) of the three caller-allocated device buffers for `cfg`:
+ * K/V storage (Eq. 2's cache, capacity B+M per layer, 2*N_h*d elements per
+ * token as in the paper's footprint formula), per-slot metadata, and kernel
+ * workspace.  Pure host arithmetic.  ERR_ARG on a bad config. */
+int ovggt_cache_query_bytes(const ovggt_config* cfg, size_t* kv_bytes, size_t* meta_bytes, size_t* ws_bytes);
+
+/* Create a handle over caller-allocated device buffers of at least the queried
+ * sizes (256-byte aligned).  Enqueues zero-fill kernels for all three buffers on
+ * `hip_stream`; the cache starts empty (Sec. 3.1: C_{-1} is empty).  *out is
+ * host memory freed by ovggt_cache_destroy.  ERR_ARG / ERR_HIP. */
+int ovggt_cache_init(ovggt_cache** out, const ovggt_config* cfg,
+                     void* kv_dev, void* meta_dev, void* ws_dev, void* hip_stream);
+
+/* Eq. 2 + Sec. 3.1's temporal causal attention.  Appends (k_new, v_new) as slots
+ * [n, n+M) with token ids t*M+i, then out = softmax(q K^T * scale) V over all
+ * n+M resident slots (frame-level causality: the frame sees itself entirely).
+ * q, k_new, v_new: device, read-only, [M, N_h, d]; out: device, written,
+ * [M, N_h, d].  bf16 runs use bf16 MFMA with fp32 accumulation and fp32 online
+ * softmax; f32 runs compute in fp32.  ERR_STATE unless the layer expects a new
+ * frame. */
+int ovggt_global_attn(ovggt_cache* c, int layer, const void* q, const void* k_new, const void* v_new,
+                      void* out, void* hip_stream);
+
+/* Eq. 5 + Sec. 3.3 + Eq. 8.  Scores the M tokens appended by the preceding
+ * ovggt_global_attn from their FFN-residual rows `resid` (device, [M, C]):
+ * ss_i = fp32 balanced-tree sum of the fp32 squares (s_i = sqrt(ss_i) is Eq. 5's
+ * norm; ranking on ss gives the same order).  `anchor_flags` (device, uint8[M],
+ * nonzero = protected, may be NULL = none) marks new members of the protected
+ * set P.  If more than B entries are resident, keeps P and the B-|P| best
+ * evictable entries under the total order (ss descending, token id ascending)
+ * and writes the move list consumed by ovggt_cache_compact.  ERR_STATE unless
+ * ovggt_global_attn was the previous call for the layer. */
+int ovggt_score_select(ovggt_cache* c, int layer, const void* resid, const uint8_t* anchor_flags,
+                       void* hip_stream);
+
+/* Applies the move list: the r-th vacated slot below B (ascending) receives the
+ * r-th surviving slot at or above B (ascending), for K, V, ids, scores and
+ * flags; the layer then holds min(n+M, B) entries.  Sources and destinations
+ * are disjoint, so the rewrite is in place.  ERR_STATE unless ovggt_score_select
+ * was the previous call for the layer. */
+int ovggt_cache_compact(ovggt_cache* c, int layer, void* hip_stream);
+
+/* Frees the host handle (device buffers stay with the caller). */
+int ovggt_cache_destroy(ovggt_cache* c);
+
+/* ---- helpers, not on the hot path ------------------------------------- */
+
+/* Resident entries of `layer` (host arithmetic, no synchronisation): after a
+ * completed frame this is min((t+1)*M, B); between global_attn and compact it
+ * still counts the frame's M pending slots. */
+int ovggt_cache_size(const ovggt_cache* c, int layer, int32_t* n);
+
+/* Frames fully processed by `layer`. */
+int ovggt_cache_frames(const ovggt_cache* c, int layer, int64_t* t);
+
+/* Synchronises `hip_stream`, reads the layer's device status word into
+ * *status (host) and clears it on the device. */
+int ovggt_cache_status(ovggt_cache* c, int layer, int32_t* status, void* hip_stream);
+
+/* Synchronises `hip_stream` and copies the layer's n resident entries to host
+ * buffers in slot order: ids uint32[n], k and v [n, N_h, d] in the handle's
+ * dtype, ss float[n], flags uint8[n].  Any output pointer may be NULL.  Serves
+ * tests and checkpointing. */
+int ovggt_cache_export(ovggt_cache* c, int layer, uint32_t* ids, void* k, void* v, float* ss,
+                       uint8_t* flags, void* hip_stream);
+
+/* Inverse of export: replaces the layer's contents by n <= B entries given in
+ * host buffers (all required) and sets its processed-frame count to `frames`
+ * (the next frame's token ids start at frames*M).  Synchronous. */
+int ovggt_cache_import(ovggt_cache* c, int layer, int32_t n, int64_t frames, const uint32_t* ids,
+                       const void* k, const void* v, const float* ss, const uint8_t* flags,
+                       void* hip_stream);
+
+/* Copies the most recent move list of `layer` to host (dst, src: uint32[M]) and
+ * its length to *n_moves.  Synchronises `hip_stream`.  For tests/diagnostics. */
+int ovggt_cache_last_moves(ovggt_cache* c, int layer, uint32_t* dst, uint32_t* src, int32_t* n_moves,
+                           void* hip_stream);
+
+const char* ovggt_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OVGGT_H */

@@ -1,0 +1,269 @@
+"""ctypes binding of libovggt.so: same names as the C ABI (include/ovggt.h),
+argument marshalling only.  Every step of the path runs in the HIP kernels;
+torch supplies device memory and the stream.  There is no CPU fallback: a
+missing library raises at first use."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libovggt.so")
+
+OVGGT_F32, OVGGT_BF16 = 0, 1
+OVGGT_ALL_LAYERS = -1
+OVGGT_OK, OVGGT_ERR_ARG, OVGGT_ERR_STATE, OVGGT_ERR_BUDGET, OVGGT_ERR_HIP = 0, -1, -2, -3, -4
+OVGGT_STATUS_BUDGET, OVGGT_STATUS_NONFINITE = 1, 2
+
+EXPORTS = (
+    "ovggt_cache_query_bytes", "ovggt_cache_init", "ovggt_global_attn", "ovggt_score_select",
+    "ovggt_cache_compact", "ovggt_cache_destroy", "ovggt_cache_size", "ovggt_cache_frames",
+    "ovggt_cache_status", "ovggt_cache_export", "ovggt_cache_import", "ovggt_cache_last_moves",
+    "ovggt_strerror",
+)
+
+
+class ovggt_config(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("n_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("tokens_per_frame", C.c_int32), ("resid_dim", C.c_int32), ("budget", C.c_int32),
+                ("dtype", C.c_int32), ("score_mode", C.c_int32), ("softmax_scale", C.c_float)]
+
+
+class OvggtError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {strerror(code)} ({code})")
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load libovggt.so (built by paper_2603_05959_amd/build.py).  Fails loudly."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is not built; run `python -m paper_2603_05959_amd.build` "
+                           "(there is no fallback path)")
+    L = C.CDLL(LIB_PATH)
+    vp, i32, i64, u8p, u32p = C.c_void_p, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p
+    szp = C.POINTER(C.c_size_t)
+    cfgp = C.POINTER(ovggt_config)
+    L.ovggt_cache_query_bytes.argtypes = [cfgp, szp, szp, szp]
+    L.ovggt_cache_init.argtypes = [C.POINTER(vp), cfgp, vp, vp, vp, vp]
+    L.ovggt_global_attn.argtypes = [vp, C.c_int, vp, vp, vp, vp, vp]
+    L.ovggt_score_select.argtypes = [vp, C.c_int, vp, u8p, vp]
+    L.ovggt_cache_compact.argtypes = [vp, C.c_int, vp]
+    L.ovggt_cache_destroy.argtypes = [vp]
+    L.ovggt_cache_size.argtypes = [vp, C.c_int, C.POINTER(i32)]
+    L.ovggt_cache_frames.argtypes = [vp, C.c_int, C.POINTER(i64)]
+    L.ovggt_cache_status.argtypes = [vp, C.c_int, C.POINTER(i32), vp]
+    L.ovggt_cache_export.argtypes = [vp, C.c_int, u32p, vp, vp, vp, u8p, vp]
+    L.ovggt_cache_import.argtypes = [vp, C.c_int, i32, i64, u32p, vp, vp, vp, u8p, vp]
+    L.ovggt_cache_last_moves.argtypes = [vp, C.c_int, u32p, u32p, C.POINTER(i32), vp]
+    L.ovggt_strerror.argtypes = [C.c_int]
+    L.ovggt_strerror.restype = C.c_char_p
+    for name in EXPORTS:
+        if name != "ovggt_strerror":
+            getattr(L, name).restype = C.c_int
+    _lib = L
+    return L
+
+
+def strerror(code: int) -> str:
+    return lib().ovggt_strerror(code).decode()
+
+
+def _check(code: int, where: str) -> None:
+    if code != OVGGT_OK:
+        raise OvggtError(code, where)
+
+
+def _ptr(t) -> int:
+    """Device (or host) address of a torch tensor / numpy array / int / None."""
+    if t is None:
+        return 0
+    if isinstance(t, int):
+        return t
+    if isinstance(t, np.ndarray):
+        return t.ctypes.data
+    return t.data_ptr()
+
+
+def make_config(n_layers, n_heads, head_dim, tokens_per_frame, resid_dim, budget, dtype,
+                score_mode=0, softmax_scale=0.0) -> ovggt_config:
+    code = {"f32": OVGGT_F32, "bf16": OVGGT_BF16}.get(dtype, dtype)
+    return ovggt_config(n_layers, n_heads, head_dim, tokens_per_frame, resid_dim, budget, code,
+                        score_mode, softmax_scale)
+
+
+# ---- the C entry points, one wrapper each -----------------------------------
+def ovggt_cache_query_bytes(cfg: ovggt_config) -> tuple[int, int, int]:
+    kv, meta, ws = C.c_size_t(), C.c_size_t(), C.c_size_t()
+    _check(lib().ovggt_cache_query_bytes(C.byref(cfg), C.byref(kv), C.byref(meta), C.byref(ws)),
+           "ovggt_cache_query_bytes")
+    return kv.value, meta.value, ws.value
+
+
+def ovggt_cache_init(cfg: ovggt_config, kv_dev, meta_dev, ws_dev, stream: int = 0) -> int:
+    h = C.c_void_p()
+    _check(lib().ovggt_cache_init(C.byref(h), C.byref(cfg), _ptr(kv_dev), _ptr(meta_dev), _ptr(ws_dev), stream),
+           "ovggt_cache_init")
+    return h.value
+
+
+def ovggt_global_attn(h, layer, q, k_new, v_new, out, stream: int = 0) -> None:
+    _check(lib().ovggt_global_attn(h, layer, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out), stream),
+           "ovggt_global_attn")
+
+
+def ovggt_score_select(h, layer, resid, anchor_flags, stream: int = 0) -> None:
+    _check(lib().ovggt_score_select(h, layer, _ptr(resid), _ptr(anchor_flags), stream), "ovggt_score_select")
+
+
+def ovggt_cache_compact(h, layer, stream: int = 0) -> None:
+    _check(lib().ovggt_cache_compact(h, layer, stream), "ovggt_cache_compact")
+
+
+def ovggt_cache_destroy(h) -> None:
+    _check(lib().ovggt_cache_destroy(h), "ovggt_cache_destroy")
+
+
+def ovggt_cache_size(h, layer) -> int:
+    n = C.c_int32()
+    _check(lib().ovggt_cache_size(h, layer, C.byref(n)), "ovggt_cache_size")
+    return n.value
+
+
+def ovggt_cache_frames(h, layer) -> int:
+    t = C.c_int64()
+    _check(lib().ovggt_cache_frames(h, layer, C.byref(t)), "ovggt_cache_frames")
+    return t.value
+
+
+def ovggt_cache_status(h, layer, stream: int = 0) -> int:
+    s = C.c_int32()
+    _check(lib().ovggt_cache_status(h, layer, C.byref(s), stream), "ovggt_cache_status")
+    return s.value
+
+
+def ovggt_cache_export(h, layer, ids, k, v, ss, flags, stream: int = 0) -> None:
+    _check(lib().ovggt_cache_export(h, layer, _ptr(ids), _ptr(k), _ptr(v), _ptr(ss), _ptr(flags), stream),
+           "ovggt_cache_export")
+
+
+def ovggt_cache_import(h, layer, n, frames, ids, k, v, ss, flags, stream: int = 0) -> None:
+    _check(lib().ovggt_cache_import(h, layer, n, frames, _ptr(ids), _ptr(k), _ptr(v), _ptr(ss), _ptr(flags), stream),
+           "ovggt_cache_import")
+
+
+def ovggt_cache_last_moves(h, layer, dst, src, stream: int = 0) -> int:
+    n = C.c_int32()
+    _check(lib().ovggt_cache_last_moves(h, layer, _ptr(dst), _ptr(src), C.byref(n), stream),
+           "ovggt_cache_last_moves")
+    return n.value
+
+
+# ---- convenience owner of the device buffers ---------------------------------
+@dataclass
+class _Bufs:
+    kv: object
+    meta: object
+    ws: object
+
+
+class Cache:
+    """Allocates the three device buffers with torch and drives the C calls.
+    Holds no logic of its own beyond marshalling."""
+
+    def __init__(self, n_layers, n_heads, head_dim, tokens_per_frame, resid_dim, budget, dtype,
+                 softmax_scale=0.0, device="cuda:0"):
+        import torch
+        self.torch = torch
+        self.cfg = make_config(n_layers, n_heads, head_dim, tokens_per_frame, resid_dim, budget, dtype,
+                               0, softmax_scale)
+        self.dtype = dtype
+        self.L, self.H, self.d, self.M, self.Cdim, self.B = n_layers, n_heads, head_dim, tokens_per_frame, resid_dim, budget
+        kvb, mb, wsb = ovggt_cache_query_bytes(self.cfg)
+        self.bytes = (kvb, mb, wsb)
+        self.device = torch.device(device)
+        self.bufs = _Bufs(torch.empty(kvb, dtype=torch.uint8, device=self.device),
+                          torch.empty(mb, dtype=torch.uint8, device=self.device),
+                          torch.empty(wsb, dtype=torch.uint8, device=self.device))
+        self.h = ovggt_cache_init(self.cfg, self.bufs.kv, self.bufs.meta, self.bufs.ws, self.stream)
+
+    @property
+    def stream(self) -> int:
+        return self.torch.cuda.current_stream(self.device).cuda_stream
+
+    def global_attn(self, q, k_new, v_new, out, layer=OVGGT_ALL_LAYERS):
+        ovggt_global_attn(self.h, layer, q, k_new, v_new, out, self.stream)
+
+    def score_select(self, resid, anchor_flags, layer=OVGGT_ALL_LAYERS):
+        ovggt_score_select(self.h, layer, resid, anchor_flags, self.stream)
+
+    def compact(self, layer=OVGGT_ALL_LAYERS):
+        ovggt_cache_compact(self.h, layer, self.stream)
+
+    def step(self, q, k_new, v_new, resid, anchor_flags, out, layer=OVGGT_ALL_LAYERS):
+        self.global_attn(q, k_new, v_new, out, layer)
+        self.score_select(resid, anchor_flags, layer)
+        self.compact(layer)
+
+    def size(self, layer=0) -> int:
+        return ovggt_cache_size(self.h, layer)
+
+    def frames(self, layer=0) -> int:
+        return ovggt_cache_frames(self.h, layer)
+
+    def status(self, layer=0) -> int:
+        return ovggt_cache_status(self.h, layer, self.stream)
+
+    def export(self, layer=0) -> dict:
+        """Logical view of a layer as numpy arrays (K/V as float32 values)."""
+        n = self.size(layer)
+        ids = np.zeros(n, np.uint32); ss = np.zeros(n, np.float32); flags = np.zeros(n, np.uint8)
+        edt = np.uint16 if self.dtype == "bf16" else np.float32
+        k = np.zeros((n, self.H, self.d), edt); v = np.zeros((n, self.H, self.d), edt)
+        ovggt_cache_export(self.h, layer, ids, k, v, ss, flags, self.stream)
+        if self.dtype == "bf16":
+            k = (k.astype(np.uint32) << np.uint32(16)).view(np.float32)
+            v = (v.astype(np.uint32) << np.uint32(16)).view(np.float32)
+        return {"ids": ids, "k": k, "v": v, "ss": ss, "flags": flags}
+
+    def import_(self, layer, frames, ids, k_bits, v_bits, ss, flags):
+        """k_bits / v_bits: numpy arrays already in the storage dtype (uint16 bf16 bits or float32)."""
+        ids = np.ascontiguousarray(ids, np.uint32); ss = np.ascontiguousarray(ss, np.float32)
+        flags = np.ascontiguousarray(flags, np.uint8)
+        k_bits = np.ascontiguousarray(k_bits); v_bits = np.ascontiguousarray(v_bits)
+        ovggt_cache_import(self.h, layer, len(ids), frames, ids, k_bits, v_bits, ss, flags, self.stream)
+
+    def last_moves(self, layer=0):
+        dst = np.zeros(self.M, np.uint32); src = np.zeros(self.M, np.uint32)
+        n = ovggt_cache_last_moves(self.h, layer, dst, src, self.stream)
+        return dst[:n], src[:n]
+
+    def close(self):
+        if self.h:
+            self.torch.cuda.synchronize(self.device)
+            ovggt_cache_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def to_device(a: np.ndarray, dtype: str, device="cuda:0"):
+    """numpy float32 (already quantised) -> torch tensor of the run dtype on the device."""
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if a.dtype == np.float32 and dtype == "bf16":
+        return t.to(device).to(torch.bfloat16)       # exact: values are bf16-representable
+    return t.to(device)

@@ -1,0 +1,411 @@
+// bf16 flash-style attention of one frame's queries over the bounded KV cache
+// (paper Sec. 3.1: the temporal causal attention CA; cost O(M*B) per step once
+// the cache is bounded).  gfx950 MFMA kernel.
+//
+// Formulation (chosen so the softmax statistics of one query live in one lane):
+//   S^T = K Q^T      A = K tile rows from LDS,      B = Q^T fragments in registers
+//   O^T = V^T P^T    A = V^T via LDS transpose reads, B = P^T straight from the
+//                    S^T accumulators (the contraction index may be permuted
+//                    freely as long as both operands agree)
+// with v_mfma_f32_32x32x16_bf16, fp32 accumulation, fp32 online softmax in the
+// exp2 domain and a lazily applied running maximum (the accumulators are only
+// rescaled when the maximum grows by more than 2^8).
+//
+// Work split.  An item is (layer, head, 128-query block); its work is T =
+// ceil(n/128) slot tiles.  The flat list of item x tile units is cut into equal
+// chunks, one per workgroup (persistent, stream-K style), so all CUs finish
+// together whatever M, n and H are.  A workgroup that covers an item completely
+// writes the output; otherwise it writes an unnormalised partial (O, m, l) that
+// attn_combine_kernel merges.  Chunks are handed to workgroups so that each
+// XCD's L2 sees as few heads as possible.
+//
+// A workgroup is 4 waves: wave = (query half, slot half) of the 128x128 tile;
+// the two slot halves are merged through LDS at the end of an item.  K and V
+// tiles are streamed global->LDS with 16-byte direct-to-LDS loads, double
+// buffered, one barrier per tile.  LDS rows are 128 bytes; 16-byte pieces are
+// XOR-swizzled with the row index so both the K operand reads and the V
+// transpose reads are bank-conflict free.
+#include "ovggt_internal.h"
+
+namespace ovggt {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
+
+#define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
+#define GLB_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
+
+constexpr int kTileBytes = kSlotTile * 128;            // one K (or V) tile: 128 slots x 64 bf16
+constexpr int kPartialFloats = kQueryTile * 64 + 2 * kQueryTile;
+constexpr float kRescaleThreshold = 8.0f;              // log2 units
+
+size_t attn_ws_bytes() { return (size_t)kMaxAttnWgs * 2 * kPartialFloats * sizeof(float); }
+
+struct AttnParams {
+  const char* q;
+  char* out;
+  const char* kv0;            // K of the first layer of this launch
+  size_t kv_layer_bytes;
+  size_t v_off;               // bytes from a layer's K to its V
+  float* ws;
+  int H, M, cap, n_total, nl;
+  int QB;                     // query blocks per (layer, head)
+  int T;                      // slot tiles
+  int chunk;                  // units per workgroup
+  int total_units;
+  float c;                    // softmax scale * log2(e)
+};
+
+// Lanes l and l+32 hold the two slot groups of the same query.  The swap
+// instruction leaves each lane with both values in (r[0], r[1]) in some order,
+// so symmetric combinations need no lane test.
+__device__ inline float pair_max(float x) {
+  const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ inline float pair_sum(float x) {
+  const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+__device__ inline bf16x8 pack8(const f32x16& s, int base) {
+  bf16x8 r;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) r[j] = (__bf16)s[base + j];
+  return r;
+}
+
+__global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
+  __shared__ __attribute__((aligned(1024))) char lds[4 * kTileBytes];     // [buf][K|V]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int qhalf = wave & 1, khalf = wave >> 1;
+  const int l32 = lane & 31, g = lane >> 5;
+
+  const int G = gridDim.x;
+  const int cidx = (blockIdx.x & 7) * (G >> 3) + (blockIdx.x >> 3);
+  int u = cidx * p.chunk;
+  const int u_end = min(u + p.chunk, p.total_units);
+  if (u >= u_end) return;
+  const int u_begin = u;
+
+  // per-lane LDS offsets
+  int koff[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks)
+    koff[ks] = (khalf * 64 + l32) * 128 + ((((2 * ks + g) ^ (l32 & 7))) << 4);
+  int voff[2];
+  {
+    const int i = lane & 15;
+    const int x = 4 * g + (i >> 2);
+    const int c0 = 2 * ((lane >> 4) & 1) + ((i & 3) >> 1);
+    const int inb = (i & 1) * 8;
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+      voff[db] = (khalf * 64 + x) * 128 + ((((c0 ^ x) ^ (db << 2))) << 4) + inb;
+  }
+  // direct-to-LDS load addressing: wave-instruction j covers LDS rows (wave*4+j)*8 .. +8
+  const int ld_row = lane >> 3;
+  const int ld_piece = ((lane & 7) ^ ld_row) << 4;
+
+  while (u < u_end) {
+    const int item = u / p.T;
+    const int t0 = u - item * p.T;
+    const int t1 = min(p.T, t0 + (u_end - u));
+    const bool first_seg = (u == u_begin);
+    const bool full = (t0 == 0 && t1 == p.T);
+    const int qb_idx = item % p.QB;
+    const int h = (item / p.QB) % p.H;
+    const int li = item / (p.QB * p.H);
+    const char* kbase = p.kv0 + (size_t)li * p.kv_layer_bytes + (size_t)h * p.cap * 128;
+    const char* vbase = kbase + p.v_off;
+    const int q0 = qb_idx * kQueryTile;
+
+    // Q^T fragments: lane holds query (q0 + qhalf*64 + qb*32 + l32), d = ks*16 + 8g .. +8
+    bf16x8 qf[2][4];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      int qrow = q0 + qhalf * 64 + qb * 32 + l32;
+      if (qrow > p.M - 1) qrow = p.M - 1;
+      const char* qp = p.q + ((((size_t)li * p.M + qrow) * p.H + h) * 64) * 2;
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) qf[qb][ks] = *(const bf16x8*)(qp + (ks * 16 + 8 * g) * 2);
+    }
+
+    f32x16 O[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) O[a][b][i] = 0.f;
+    float mrun[2] = {-1e30f, -1e30f};
+    float lrun[2] = {0.f, 0.f};
+
+    // prologue: first tile into buffer 0
+    {
+      const size_t trow = (size_t)t0 * kSlotTile;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int r8 = (wave * 4 + j) * 8;
+        const size_t goff = (trow + r8 + ld_row) * 128 + ld_piece;
+        __builtin_amdgcn_global_load_lds(GLB_PTR(kbase + goff), LDS_PTR(void, lds + r8 * 128), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(GLB_PTR(vbase + goff), LDS_PTR(void, lds + kTileBytes + r8 * 128), 16, 0, 0);
+      }
+    }
+
+    for (int tt = t0; tt < t1; ++tt) {
+      const int cur = (tt - t0) & 1;
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+      if (tt + 1 < t1) {
+        const size_t trow = (size_t)(tt + 1) * kSlotTile;
+        char* nb = lds + (cur ^ 1) * 2 * kTileBytes;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int r8 = (wave * 4 + j) * 8;
+          const size_t goff = (trow + r8 + ld_row) * 128 + ld_piece;
+          __builtin_amdgcn_global_load_lds(GLB_PTR(kbase + goff), LDS_PTR(void, nb + r8 * 128), 16, 0, 0);
+          __builtin_amdgcn_global_load_lds(GLB_PTR(vbase + goff), LDS_PTR(void, nb + kTileBytes + r8 * 128), 16, 0, 0);
+        }
+      }
+      const char* ldsK = lds + cur * 2 * kTileBytes;
+      const char* ldsV = ldsK + kTileBytes;
+
+      // ---- S^T = K Q^T for this wave's 64 slots x 64 queries
+      f32x16 S[2][2];
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) S[a][b][i] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        const bf16x8 k0 = *LDS_PTR(const bf16x8, ldsK + koff[ks]);
+        const bf16x8 k1 = *LDS_PTR(const bf16x8, ldsK + koff[ks] + 32 * 128);
+        S[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0, qf[0][ks], S[0][0], 0, 0, 0);
+        S[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0, qf[1][ks], S[0][1], 0, 0, 0);
+        S[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1, qf[0][ks], S[1][0], 0, 0, 0);
+        S[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1, qf[1][ks], S[1][1], 0, 0, 0);
+      }
+      // slots past the resident count only exist in the last tile
+      if (tt == p.T - 1 && (p.n_total & (kSlotTile - 1))) {
+        const int sbase = tt * kSlotTile + khalf * 64 + 4 * g;
+#pragma unroll
+        for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const int slot = sbase + sb * 32 + (i >> 2) * 8 + (i & 3);
+            if (slot >= p.n_total) { S[sb][0][i] = -INFINITY; S[sb][1][i] = -INFINITY; }
+          }
+      }
+
+      // ---- online softmax; lane owns one query per qb
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb) {
+        float mx = S[0][qb][0];
+#pragma unroll
+        for (int i = 1; i < 16; ++i) mx = fmaxf(mx, S[0][qb][i]);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, S[1][qb][i]);
+        mx = pair_max(mx);
+        const float mnew = fmaxf(mrun[qb], mx);
+        const bool need = (mnew - mrun[qb]) * p.c > kRescaleThreshold;
+        if (__builtin_amdgcn_ballot_w64(need) != 0ull) {
+          const float alpha = __builtin_amdgcn_exp2f((mrun[qb] - mnew) * p.c);
+          mrun[qb] = mnew;
+          lrun[qb] *= alpha;
+#pragma unroll
+          for (int db = 0; db < 2; ++db)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) O[db][qb][i] *= alpha;
+        }
+        const float mc = mrun[qb] * p.c;
+        float ls = 0.f;
+#pragma unroll
+        for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(S[sb][qb][i], p.c, -mc));
+            S[sb][qb][i] = e;
+            ls += e;
+          }
+        lrun[qb] += ls;
+      }
+
+      // ---- O^T += V^T P^T
+#pragma unroll
+      for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+          const bf16x8 pb0 = pack8(S[sb][0], 8 * s2);
+          const bf16x8 pb1 = pack8(S[sb][1], 8 * s2);
+#pragma unroll
+          for (int db = 0; db < 2; ++db) {
+            const int o = voff[db] + (sb * 32 + 16 * s2) * 128;
+            const s16x4 va = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, ldsV + o));
+            const s16x4 vb = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, ldsV + o + 8 * 128));
+            const __attribute__((ext_vector_type(8))) short v8 =
+                __builtin_shufflevector(va, vb, 0, 1, 2, 3, 4, 5, 6, 7);
+            const bf16x8 vf = __builtin_bit_cast(bf16x8, v8);
+            O[db][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pb0, O[db][0], 0, 0, 0);
+            O[db][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pb1, O[db][1], 0, 0, 0);
+          }
+        }
+    }
+
+    // ---- merge the two slot halves through LDS
+    float ltot[2];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) ltot[qb] = pair_sum(lrun[qb]);
+    __syncthreads();                                  // all tile reads done; LDS is free
+    float* mO = (float*)lds + qhalf * (64 * 64);       // [reg][lane]
+    float* mML = (float*)lds + 2 * 64 * 64 + qhalf * (4 * 64);
+    if (khalf == 1) {
+#pragma unroll
+      for (int db = 0; db < 2; ++db)
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) mO[((db * 2 + qb) * 16 + i) * 64 + lane] = O[db][qb][i];
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb) {
+        mML[qb * 64 + lane] = mrun[qb] * p.c;
+        mML[(2 + qb) * 64 + lane] = ltot[qb];
+      }
+    }
+    __syncthreads();
+    if (khalf == 0) {
+      float mfin[2], lfin[2];
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb) {
+        const float m0 = mrun[qb] * p.c, m1 = mML[qb * 64 + lane];
+        const float mt = fmaxf(m0, m1);
+        const float a0 = __builtin_amdgcn_exp2f(m0 - mt), a1 = __builtin_amdgcn_exp2f(m1 - mt);
+        mfin[qb] = mt;
+        lfin[qb] = ltot[qb] * a0 + mML[(2 + qb) * 64 + lane] * a1;
+#pragma unroll
+        for (int db = 0; db < 2; ++db)
+#pragma unroll
+          for (int i = 0; i < 16; ++i)
+            O[db][qb][i] = O[db][qb][i] * a0 + mO[((db * 2 + qb) * 16 + i) * 64 + lane] * a1;
+      }
+      if (full) {
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+          const int qrow = q0 + qhalf * 64 + qb * 32 + l32;
+          if (qrow < p.M) {
+            const float inv = 1.0f / lfin[qb];
+            char* op = p.out + ((((size_t)li * p.M + qrow) * p.H + h) * 64) * 2;
+#pragma unroll
+            for (int db = 0; db < 2; ++db)
+#pragma unroll
+              for (int ig = 0; ig < 4; ++ig) {
+                bf16x4 w;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) w[j] = (__bf16)(O[db][qb][ig * 4 + j] * inv);
+                *(bf16x4*)(op + (db * 32 + ig * 8 + 4 * g) * 2) = w;
+              }
+          }
+        }
+      } else {
+        float* rec = p.ws + (size_t)(2 * cidx + (first_seg ? 0 : 1)) * kPartialFloats;
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+          const int r = qhalf * 64 + qb * 32 + l32;
+#pragma unroll
+          for (int db = 0; db < 2; ++db)
+#pragma unroll
+            for (int ig = 0; ig < 4; ++ig) {
+              float4 w = {O[db][qb][ig * 4], O[db][qb][ig * 4 + 1], O[db][qb][ig * 4 + 2], O[db][qb][ig * 4 + 3]};
+              *(float4*)(rec + r * 64 + db * 32 + ig * 8 + 4 * g) = w;
+            }
+          if (g == 0) {
+            rec[kQueryTile * 64 + r] = mfin[qb];
+            rec[kQueryTile * 64 + kQueryTile + r] = lfin[qb];
+          }
+        }
+      }
+    }
+    __syncthreads();                                  // merge scratch is reused as tile buffers
+    u += t1 - t0;
+  }
+}
+
+// Merge the partials of every item that was split across workgroups.
+__global__ void __launch_bounds__(256) attn_combine_kernel(AttnParams p) {
+  const int item = blockIdx.x;
+  const long ua = (long)item * p.T, ub = ua + p.T - 1;
+  const int cf = (int)(ua / p.chunk), cl = (int)(ub / p.chunk);
+  if (cf == cl) return;                                // one workgroup did the whole item
+  const int row = threadIdx.x >> 1, half = threadIdx.x & 1;
+  const int qb_idx = item % p.QB;
+  const int h = (item / p.QB) % p.H;
+  const int li = item / (p.QB * p.H);
+  const int qrow = qb_idx * kQueryTile + row;
+  if (qrow >= p.M) return;
+  float mt = -INFINITY;
+  for (int c = cf; c <= cl; ++c) {
+    const float* rec = p.ws + (size_t)(2 * c + ((long)c * p.chunk < ua ? 1 : 0)) * kPartialFloats;
+    mt = fmaxf(mt, rec[kQueryTile * 64 + row]);
+  }
+  float acc[32];
+#pragma unroll
+  for (int j = 0; j < 32; ++j) acc[j] = 0.f;
+  float l = 0.f;
+  for (int c = cf; c <= cl; ++c) {
+    const float* rec = p.ws + (size_t)(2 * c + ((long)c * p.chunk < ua ? 1 : 0)) * kPartialFloats;
+    const float w = __builtin_amdgcn_exp2f(rec[kQueryTile * 64 + row] - mt);
+    l += rec[kQueryTile * 64 + kQueryTile + row] * w;
+    const float4* o4 = (const float4*)(rec + row * 64 + half * 32);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const float4 v = o4[j];
+      acc[4 * j] += v.x * w; acc[4 * j + 1] += v.y * w; acc[4 * j + 2] += v.z * w; acc[4 * j + 3] += v.w * w;
+    }
+  }
+  const float inv = 1.0f / l;
+  char* op = p.out + ((((size_t)li * p.M + qrow) * p.H + h) * 64 + half * 32) * 2;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    bf16x8 w;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) w[e] = (__bf16)(acc[8 * j + e] * inv);
+    *(bf16x8*)(op + j * 16) = w;
+  }
+}
+
+hipError_t launch_attn_bf16(const Geom& g, char* kv, int layer0, int nl, const void* q, void* out,
+                            int n_total, float scale, char* ws, int n_wgs, hipStream_t s) {
+  AttnParams p;
+  p.q = (const char*)q;
+  p.out = (char*)out;
+  p.kv0 = layer_k(kv, g, layer0);
+  p.kv_layer_bytes = g.kv_layer_bytes;
+  p.v_off = (size_t)g.H * g.cap * g.d * g.esize;
+  p.ws = (float*)ws;
+  p.H = g.H; p.M = g.M; p.cap = g.cap; p.n_total = n_total; p.nl = nl;
+  p.QB = (g.M + kQueryTile - 1) / kQueryTile;
+  p.T = (n_total + kSlotTile - 1) / kSlotTile;
+  const long total = (long)nl * g.H * p.QB * p.T;
+  if (total > 0x7FFFFFFFL) return hipErrorInvalidValue;
+  p.total_units = (int)total;
+  if (n_wgs > kMaxAttnWgs) n_wgs = kMaxAttnWgs;
+  n_wgs &= ~7;
+  if (n_wgs < 8) n_wgs = 8;
+  p.chunk = (int)((total + n_wgs - 1) / n_wgs);
+  p.c = scale * 1.4426950408889634f;
+  hipLaunchKernelGGL(attn_bf16_kernel, dim3((unsigned)n_wgs), dim3(256), 0, s, p);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int items = nl * g.H * p.QB;
+  hipLaunchKernelGGL(attn_combine_kernel, dim3((unsigned)items), dim3(256), 0, s, p);
+  return hipGetLastError();
+}
+
+}  // namespace ovggt

@@ -1,0 +1,107 @@
+// Cache maintenance kernels: zero fill, append (paper Eq. 2) and the in-place
+// hole-fill compaction that follows Eq. 8's selection.  All are pure copies,
+// bound by HBM bandwidth; every lane moves 16-byte pieces of 128-byte-or-longer
+// contiguous rows.
+#include "ovggt_internal.h"
+
+namespace ovggt {
+
+// --------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) fill_zero_kernel(uint4* p, size_t n16) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  const uint4 z = {0u, 0u, 0u, 0u};
+  for (; i < n16; i += stride) p[i] = z;
+}
+
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
+  const size_t n16 = bytes / 16;        // buffers are sized in multiples of 256 bytes
+  if (n16 == 0) return hipSuccess;
+  size_t blocks = (n16 + 255) / 256;
+  if (blocks > 8192) blocks = 8192;
+  hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (uint4*)p, n16);
+  return hipGetLastError();
+}
+
+// --------------------------------------------------------------------------
+// Append.  Input rows are token-major [M][H][d]; the cache is head-major
+// [H][cap][d].  One thread per 16-byte piece of K and of V.
+__global__ void __launch_bounds__(256)
+append_kernel(Geom g, char* kv, char* meta, int layer0, const char* k_new, const char* v_new,
+              int n, uint32_t gid0) {
+  const int layer = layer0 + blockIdx.y;
+  const int row_bytes = g.d * g.esize;             // 128 (bf16) or 256 (f32)
+  const int pieces = row_bytes / 16;
+  const size_t per_layer_in = (size_t)g.M * g.H * row_bytes;
+  const size_t total = (size_t)g.M * g.H * pieces;
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  const int piece = (int)(i % pieces);
+  const int h = (int)((i / pieces) % g.H);
+  const int m = (int)(i / ((size_t)pieces * g.H));
+  const size_t src = (size_t)blockIdx.y * per_layer_in + ((size_t)m * g.H + h) * row_bytes + piece * 16;
+  const size_t dst = ((size_t)h * g.cap + (n + m)) * row_bytes + piece * 16;
+  *(uint4*)(layer_k(kv, g, layer) + dst) = *(const uint4*)(k_new + src);
+  *(uint4*)(layer_v(kv, g, layer) + dst) = *(const uint4*)(v_new + src);
+  if (h == 0 && piece == 0) {
+    char* mb = layer_meta(meta, g, layer);
+    ((uint32_t*)(mb + g.off_ids))[n + m] = gid0 + (uint32_t)m;
+    ((float*)(mb + g.off_ss))[n + m] = 0.f;
+    ((uint8_t*)(mb + g.off_flags))[n + m] = 0;
+  }
+}
+
+hipError_t launch_append(const Geom& g, char* kv, char* meta, int layer0, int nl,
+                         const void* k_new, const void* v_new, int n, uint32_t gid0, hipStream_t s) {
+  const size_t total = (size_t)g.M * g.H * (g.d * g.esize / 16);
+  dim3 grid((unsigned)((total + 255) / 256), (unsigned)nl);
+  hipLaunchKernelGGL(append_kernel, grid, dim3(256), 0, s, g, kv, meta, layer0,
+                     (const char*)k_new, (const char*)v_new, n, gid0);
+  return hipGetLastError();
+}
+
+// --------------------------------------------------------------------------
+// Compaction.  Workgroup r of a layer moves entry src[r] -> dst[r]: 2*H rows of
+// d elements (K and V of every head) plus id, score and flag.  Destinations are
+// slots below B, sources slots at or above B, so no ordering between moves is
+// needed.  Workgroups beyond the list length exit at once.
+__global__ void __launch_bounds__(256)
+compact_kernel(Geom g, char* kv, char* meta, int layer0) {
+  const int layer = layer0 + blockIdx.y;
+  char* mb = layer_meta(meta, g, layer);
+  const Ctrl* ctrl = (const Ctrl*)(mb + g.off_ctrl);
+  const uint32_t n_moves = ctrl->n_moves;
+  const uint32_t r = blockIdx.x;
+  if (r >= n_moves) return;
+  const uint32_t dst = ((const uint32_t*)(mb + g.off_mvdst))[r];
+  const uint32_t src = ((const uint32_t*)(mb + g.off_mvsrc))[r];
+  if (dst >= (uint32_t)g.B || src < (uint32_t)g.B || src >= (uint32_t)g.cap) return;   // never out of bounds
+  const int row_bytes = g.d * g.esize;
+  const int pieces = row_bytes / 16;
+  const int total = 2 * g.H * pieces;
+  char* kbase = layer_k(kv, g, layer);
+  const size_t v_off = (size_t)g.H * g.cap * row_bytes;
+  for (int i = threadIdx.x; i < total; i += blockDim.x) {
+    const int piece = i % pieces;
+    const int h = (i / pieces) % g.H;
+    const int isv = i / (pieces * g.H);
+    char* base = kbase + (isv ? v_off : 0) + (size_t)h * g.cap * row_bytes + piece * 16;
+    *(uint4*)(base + (size_t)dst * row_bytes) = *(const uint4*)(base + (size_t)src * row_bytes);
+  }
+  if (threadIdx.x == 0) {
+    uint32_t* ids = (uint32_t*)(mb + g.off_ids);
+    float* ss = (float*)(mb + g.off_ss);
+    uint8_t* fl = (uint8_t*)(mb + g.off_flags);
+    ids[dst] = ids[src];
+    ss[dst] = ss[src];
+    fl[dst] = fl[src];
+  }
+}
+
+hipError_t launch_compact(const Geom& g, char* kv, char* meta, int layer0, int nl, hipStream_t s) {
+  dim3 grid((unsigned)g.M, (unsigned)nl);      // at most M entries move per frame
+  hipLaunchKernelGGL(compact_kernel, grid, dim3(256), 0, s, g, kv, meta, layer0);
+  return hipGetLastError();
+}
+
+}  // namespace ovggt

@@ -1,0 +1,300 @@
+// Host side of the C ABI declared in include/ovggt.h: argument validation, the
+// per-layer call-order state machine, size arithmetic (the resident count of a
+// layer is known on the host without reading the device: it grows by M per
+// frame and is clipped to B by Eq. 8) and the kernel launches.
+#include "../../include/ovggt.h"
+#include "ovggt_internal.h"
+
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+using namespace ovggt;
+
+struct ovggt_cache {
+  ovggt_config cfg;
+  Geom g;
+  char* kv;
+  char* meta;
+  char* ws;
+  float scale;
+  int n_wgs;                       // attention workgroups (2 per CU)
+  std::vector<int32_t> n;          // resident (incl. pending) slots per layer
+  std::vector<int64_t> frames;     // completed frames per layer
+  std::vector<int8_t> phase;       // 0: expects global_attn, 1: score_select, 2: compact
+};
+
+namespace {
+
+inline size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+bool valid_config(const ovggt_config* c) {
+  if (!c) return false;
+  if (c->n_layers < 1 || c->n_layers > 4096) return false;
+  if (c->n_heads < 1 || c->n_heads > 1024) return false;
+  if (c->head_dim != 64) return false;
+  if (c->tokens_per_frame < 1) return false;
+  if (c->resid_dim < 1 || c->resid_dim > 4096) return false;
+  if (c->budget < c->tokens_per_frame) return false;
+  if ((int64_t)c->budget + c->tokens_per_frame > 128 * 1024) return false;   // selection handles <= 2^17 slots
+  if (c->dtype != OVGGT_F32 && c->dtype != OVGGT_BF16) return false;
+  if (c->score_mode != 0) return false;
+  if (!(c->softmax_scale >= 0.f) || !std::isfinite(c->softmax_scale)) return false;
+  return true;
+}
+
+void make_geom(const ovggt_config& c, Geom* g) {
+  g->L = c.n_layers; g->H = c.n_heads; g->d = c.head_dim; g->M = c.tokens_per_frame;
+  g->C = c.resid_dim; g->B = c.budget;
+  g->cap = (c.budget + c.tokens_per_frame + kSlotTile - 1) / kSlotTile * kSlotTile;
+  g->esize = c.dtype == OVGGT_BF16 ? 2 : 4;
+  g->kv_layer_bytes = up256((size_t)2 * g->H * g->cap * g->d * g->esize);
+  size_t off = 0;
+  g->off_ids = off;   off += up256((size_t)4 * g->cap);
+  g->off_ss = off;    off += up256((size_t)4 * g->cap);
+  g->off_flags = off; off += up256((size_t)g->cap);
+  g->off_ctrl = off;  off += sizeof(Ctrl);
+  g->off_mvdst = off; off += up256((size_t)4 * g->M);
+  g->off_mvsrc = off; off += up256((size_t)4 * g->M);
+  g->meta_layer_bytes = off;
+}
+
+size_t ws_bytes_for(const ovggt_config& c) { return c.dtype == OVGGT_BF16 ? up256(attn_ws_bytes()) : 256; }
+
+bool aligned16(const void* p) { return p && ((uintptr_t)p & 15) == 0; }
+
+// resolves `layer` to [l0, l0+nl); false if out of range
+bool layer_range(const ovggt_cache* c, int layer, int* l0, int* nl) {
+  if (layer == OVGGT_ALL_LAYERS) { *l0 = 0; *nl = c->g.L; return true; }
+  if (layer < 0 || layer >= c->g.L) return false;
+  *l0 = layer; *nl = 1;
+  return true;
+}
+
+bool uniform(const ovggt_cache* c, int l0, int nl, int phase) {
+  for (int l = l0; l < l0 + nl; ++l)
+    if (c->phase[l] != phase || c->n[l] != c->n[l0] || c->frames[l] != c->frames[l0]) return false;
+  return true;
+}
+
+inline Ctrl* ctrl_of(const ovggt_cache* c, int layer) {
+  return (Ctrl*)(layer_meta(c->meta, c->g, layer) + c->g.off_ctrl);
+}
+
+}  // namespace
+
+extern "C" {
+
+int ovggt_cache_query_bytes(const ovggt_config* cfg, size_t* kv_bytes, size_t* meta_bytes, size_t* ws_bytes) {
+  if (!valid_config(cfg)) return OVGGT_ERR_ARG;
+  Geom g;
+  make_geom(*cfg, &g);
+  if (kv_bytes) *kv_bytes = g.kv_layer_bytes * g.L;
+  if (meta_bytes) *meta_bytes = g.meta_layer_bytes * g.L;
+  if (ws_bytes) *ws_bytes = ws_bytes_for(*cfg);
+  return OVGGT_OK;
+}
+
+int ovggt_cache_init(ovggt_cache** out, const ovggt_config* cfg, void* kv_dev, void* meta_dev,
+                     void* ws_dev, void* hip_stream) {
+  if (!out || !valid_config(cfg)) return OVGGT_ERR_ARG;
+  if (!kv_dev || !meta_dev || !ws_dev) return OVGGT_ERR_ARG;
+  if (((uintptr_t)kv_dev | (uintptr_t)meta_dev | (uintptr_t)ws_dev) & 255) return OVGGT_ERR_ARG;
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return OVGGT_ERR_HIP;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return OVGGT_ERR_HIP;
+  ovggt_cache* c = new (std::nothrow) ovggt_cache();
+  if (!c) return OVGGT_ERR_ARG;
+  c->cfg = *cfg;
+  make_geom(*cfg, &c->g);
+  c->kv = (char*)kv_dev; c->meta = (char*)meta_dev; c->ws = (char*)ws_dev;
+  c->scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / std::sqrt((float)cfg->head_dim);
+  int wgs = 2 * cus;
+  wgs = (wgs + 7) & ~7;
+  if (wgs < 8) wgs = 8;
+  if (wgs > kMaxAttnWgs) wgs = kMaxAttnWgs;
+  c->n_wgs = wgs;
+  c->n.assign(c->g.L, 0);
+  c->frames.assign(c->g.L, 0);
+  c->phase.assign(c->g.L, 0);
+  hipStream_t s = (hipStream_t)hip_stream;
+  if (launch_fill_zero(c->kv, c->g.kv_layer_bytes * c->g.L, s) != hipSuccess ||
+      launch_fill_zero(c->meta, c->g.meta_layer_bytes * c->g.L, s) != hipSuccess ||
+      launch_fill_zero(c->ws, ws_bytes_for(*cfg), s) != hipSuccess) {
+    delete c;
+    return OVGGT_ERR_HIP;
+  }
+  *out = c;
+  return OVGGT_OK;
+}
+
+int ovggt_global_attn(ovggt_cache* c, int layer, const void* q, const void* k_new, const void* v_new,
+                      void* out, void* hip_stream) {
+  if (!c) return OVGGT_ERR_ARG;
+  int l0, nl;
+  if (!layer_range(c, layer, &l0, &nl)) return OVGGT_ERR_ARG;
+  if (!aligned16(q) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(out)) return OVGGT_ERR_ARG;
+  if (!uniform(c, l0, nl, 0)) return OVGGT_ERR_STATE;
+  const Geom& g = c->g;
+  const int n = c->n[l0];
+  const int64_t gid0 = c->frames[l0] * (int64_t)g.M;
+  if (gid0 + g.M > 0xFFFFFFFFLL) return OVGGT_ERR_ARG;          // token ids are 32-bit
+  if (n + g.M > g.cap) return OVGGT_ERR_STATE;
+  hipStream_t s = (hipStream_t)hip_stream;
+  if (launch_append(g, c->kv, c->meta, l0, nl, k_new, v_new, n, (uint32_t)gid0, s) != hipSuccess)
+    return OVGGT_ERR_HIP;
+  hipError_t e;
+  if (g.esize == 2)
+    e = launch_attn_bf16(g, c->kv, l0, nl, q, out, n + g.M, c->scale, c->ws, c->n_wgs, s);
+  else
+    e = launch_attn_f32(g, c->kv, l0, nl, q, out, n + g.M, c->scale, s);
+  if (e != hipSuccess) return OVGGT_ERR_HIP;
+  for (int l = l0; l < l0 + nl; ++l) { c->n[l] = n + g.M; c->phase[l] = 1; }
+  return OVGGT_OK;
+}
+
+int ovggt_score_select(ovggt_cache* c, int layer, const void* resid, const uint8_t* anchor_flags,
+                       void* hip_stream) {
+  if (!c) return OVGGT_ERR_ARG;
+  int l0, nl;
+  if (!layer_range(c, layer, &l0, &nl)) return OVGGT_ERR_ARG;
+  if (!aligned16(resid)) return OVGGT_ERR_ARG;
+  if (!uniform(c, l0, nl, 1)) return OVGGT_ERR_STATE;
+  if (launch_score_select(c->g, c->meta, l0, nl, resid, anchor_flags, c->n[l0], (hipStream_t)hip_stream) != hipSuccess)
+    return OVGGT_ERR_HIP;
+  for (int l = l0; l < l0 + nl; ++l) c->phase[l] = 2;
+  return OVGGT_OK;
+}
+
+int ovggt_cache_compact(ovggt_cache* c, int layer, void* hip_stream) {
+  if (!c) return OVGGT_ERR_ARG;
+  int l0, nl;
+  if (!layer_range(c, layer, &l0, &nl)) return OVGGT_ERR_ARG;
+  if (!uniform(c, l0, nl, 2)) return OVGGT_ERR_STATE;
+  const Geom& g = c->g;
+  if (c->n[l0] > g.B) {
+    if (launch_compact(g, c->kv, c->meta, l0, nl, (hipStream_t)hip_stream) != hipSuccess) return OVGGT_ERR_HIP;
+  }
+  for (int l = l0; l < l0 + nl; ++l) {
+    if (c->n[l] > g.B) c->n[l] = g.B;
+    c->frames[l] += 1;
+    c->phase[l] = 0;
+  }
+  return OVGGT_OK;
+}
+
+int ovggt_cache_destroy(ovggt_cache* c) {
+  if (!c) return OVGGT_ERR_ARG;
+  delete c;
+  return OVGGT_OK;
+}
+
+int ovggt_cache_size(const ovggt_cache* c, int layer, int32_t* n) {
+  if (!c || !n || layer < 0 || layer >= c->g.L) return OVGGT_ERR_ARG;
+  *n = c->n[layer];
+  return OVGGT_OK;
+}
+
+int ovggt_cache_frames(const ovggt_cache* c, int layer, int64_t* t) {
+  if (!c || !t || layer < 0 || layer >= c->g.L) return OVGGT_ERR_ARG;
+  *t = c->frames[layer];
+  return OVGGT_OK;
+}
+
+int ovggt_cache_status(ovggt_cache* c, int layer, int32_t* status, void* hip_stream) {
+  if (!c || !status || layer < 0 || layer >= c->g.L) return OVGGT_ERR_ARG;
+  if (hipStreamSynchronize((hipStream_t)hip_stream) != hipSuccess) return OVGGT_ERR_HIP;
+  uint32_t st = 0, zero = 0;
+  Ctrl* ctrl = ctrl_of(c, layer);
+  if (hipMemcpy(&st, &ctrl->status, 4, hipMemcpyDeviceToHost) != hipSuccess) return OVGGT_ERR_HIP;
+  if (hipMemcpy(&ctrl->status, &zero, 4, hipMemcpyHostToDevice) != hipSuccess) return OVGGT_ERR_HIP;
+  *status = (int32_t)st;
+  return OVGGT_OK;
+}
+
+int ovggt_cache_export(ovggt_cache* c, int layer, uint32_t* ids, void* k, void* v, float* ss,
+                       uint8_t* flags, void* hip_stream) {
+  if (!c || layer < 0 || layer >= c->g.L) return OVGGT_ERR_ARG;
+  if (hipStreamSynchronize((hipStream_t)hip_stream) != hipSuccess) return OVGGT_ERR_HIP;
+  const Geom& g = c->g;
+  const int n = c->n[layer];
+  if (n == 0) return OVGGT_OK;
+  char* mb = layer_meta(c->meta, g, layer);
+  if (ids && hipMemcpy(ids, mb + g.off_ids, (size_t)4 * n, hipMemcpyDeviceToHost) != hipSuccess) return OVGGT_ERR_HIP;
+  if (ss && hipMemcpy(ss, mb + g.off_ss, (size_t)4 * n, hipMemcpyDeviceToHost) != hipSuccess) return OVGGT_ERR_HIP;
+  if (flags && hipMemcpy(flags, mb + g.off_flags, (size_t)n, hipMemcpyDeviceToHost) != hipSuccess) return OVGGT_ERR_HIP;
+  const size_t row = (size_t)g.d * g.esize;
+  std::vector<char> tmp;
+  for (int which = 0; which < 2; ++which) {
+    char* dst = (char*)(which ? v : k);
+    if (!dst) continue;
+    const char* src = which ? layer_v(c->kv, g, layer) : layer_k(c->kv, g, layer);
+    tmp.resize((size_t)n * row);
+    for (int h = 0; h < g.H; ++h) {
+      if (hipMemcpy(tmp.data(), src + (size_t)h * g.cap * row, (size_t)n * row, hipMemcpyDeviceToHost) != hipSuccess)
+        return OVGGT_ERR_HIP;
+      for (int i = 0; i < n; ++i) std::memcpy(dst + ((size_t)i * g.H + h) * row, tmp.data() + (size_t)i * row, row);
+    }
+  }
+  return OVGGT_OK;
+}
+
+int ovggt_cache_import(ovggt_cache* c, int layer, int32_t n, int64_t frames, const uint32_t* ids,
+                       const void* k, const void* v, const float* ss, const uint8_t* flags,
+                       void* hip_stream) {
+  if (!c || layer < 0 || layer >= c->g.L) return OVGGT_ERR_ARG;
+  const Geom& g = c->g;
+  if (n < 0 || n > g.B || frames < 0 || (n > 0 && (!ids || !k || !v || !ss || !flags))) return OVGGT_ERR_ARG;
+  if ((frames + 1) * (int64_t)g.M > 0xFFFFFFFFLL) return OVGGT_ERR_ARG;
+  if (c->phase[layer] != 0) return OVGGT_ERR_STATE;
+  if (hipStreamSynchronize((hipStream_t)hip_stream) != hipSuccess) return OVGGT_ERR_HIP;
+  char* mb = layer_meta(c->meta, g, layer);
+  if (n > 0) {
+    if (hipMemcpy(mb + g.off_ids, ids, (size_t)4 * n, hipMemcpyHostToDevice) != hipSuccess) return OVGGT_ERR_HIP;
+    if (hipMemcpy(mb + g.off_ss, ss, (size_t)4 * n, hipMemcpyHostToDevice) != hipSuccess) return OVGGT_ERR_HIP;
+    if (hipMemcpy(mb + g.off_flags, flags, (size_t)n, hipMemcpyHostToDevice) != hipSuccess) return OVGGT_ERR_HIP;
+    const size_t row = (size_t)g.d * g.esize;
+    std::vector<char> tmp((size_t)n * row);
+    for (int which = 0; which < 2; ++which) {
+      const char* src = (const char*)(which ? v : k);
+      char* dst = which ? layer_v(c->kv, g, layer) : layer_k(c->kv, g, layer);
+      for (int h = 0; h < g.H; ++h) {
+        for (int i = 0; i < n; ++i) std::memcpy(tmp.data() + (size_t)i * row, src + ((size_t)i * g.H + h) * row, row);
+        if (hipMemcpy(dst + (size_t)h * g.cap * row, tmp.data(), (size_t)n * row, hipMemcpyHostToDevice) != hipSuccess)
+          return OVGGT_ERR_HIP;
+      }
+    }
+  }
+  c->n[layer] = n;
+  c->frames[layer] = frames;
+  return OVGGT_OK;
+}
+
+int ovggt_cache_last_moves(ovggt_cache* c, int layer, uint32_t* dst, uint32_t* src, int32_t* n_moves,
+                           void* hip_stream) {
+  if (!c || !n_moves || layer < 0 || layer >= c->g.L) return OVGGT_ERR_ARG;
+  if (hipStreamSynchronize((hipStream_t)hip_stream) != hipSuccess) return OVGGT_ERR_HIP;
+  const Geom& g = c->g;
+  char* mb = layer_meta(c->meta, g, layer);
+  uint32_t nm = 0;
+  if (hipMemcpy(&nm, &ctrl_of(c, layer)->n_moves, 4, hipMemcpyDeviceToHost) != hipSuccess) return OVGGT_ERR_HIP;
+  if (nm > (uint32_t)g.M) nm = (uint32_t)g.M;
+  if (dst && nm && hipMemcpy(dst, mb + g.off_mvdst, (size_t)4 * nm, hipMemcpyDeviceToHost) != hipSuccess) return OVGGT_ERR_HIP;
+  if (src && nm && hipMemcpy(src, mb + g.off_mvsrc, (size_t)4 * nm, hipMemcpyDeviceToHost) != hipSuccess) return OVGGT_ERR_HIP;
+  *n_moves = (int32_t)nm;
+  return OVGGT_OK;
+}
+
+const char* ovggt_strerror(int code) {
+  switch (code) {
+    case OVGGT_OK: return "ok";
+    case OVGGT_ERR_ARG: return "invalid argument";
+    case OVGGT_ERR_STATE: return "call out of order for this layer";
+    case OVGGT_ERR_BUDGET: return "protected set exceeds the budget";
+    case OVGGT_ERR_HIP: return "HIP runtime error";
+    default: return "unknown error";
+  }
+}
+
+}  // extern "C"

@@ -1,0 +1,68 @@
+// Internal layout description and kernel launchers shared by the HIP
+// translation units of libovggt.  Nothing here is part of the public ABI.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+namespace ovggt {
+
+constexpr int kSlotTile = 128;      // attention consumes the cache in 128-slot tiles
+constexpr int kQueryTile = 128;     // queries per attention work item
+constexpr int kMaxAttnWgs = 1024;   // upper bound on attention workgroups (sizes the workspace)
+
+// Per-layer control block kept in the metadata buffer.
+struct Ctrl {
+  uint32_t status;     // OVGGT_STATUS_* bits
+  uint32_t n_moves;    // length of the move list written by the last selection
+  uint32_t arrive;     // arrival counter of the score kernel's workgroups
+  uint32_t pad[61];
+};
+static_assert(sizeof(Ctrl) == 256, "Ctrl is one 256-byte block");
+
+// Geometry of one handle.  Device K/V storage per layer is
+//   K[H][cap][d] followed by V[H][cap][d]   (head-major, slot rows of d elements)
+// so one head's 128-slot tile is a contiguous 128*d*esize block.
+struct Geom {
+  int L, H, d, M, C, B;
+  int cap;                 // slots per layer: round_up(B + M, kSlotTile)
+  int esize;               // 2 (bf16) or 4 (f32)
+  size_t kv_layer_bytes;   // 2 * H * cap * d * esize
+  size_t meta_layer_bytes;
+  size_t off_ids, off_ss, off_flags, off_ctrl, off_mvdst, off_mvsrc;   // byte offsets in a layer's metadata
+};
+
+__host__ __device__ inline char* layer_k(char* kv, const Geom& g, int layer) {
+  return kv + (size_t)layer * g.kv_layer_bytes;
+}
+__host__ __device__ inline char* layer_v(char* kv, const Geom& g, int layer) {
+  return kv + (size_t)layer * g.kv_layer_bytes + (size_t)g.H * g.cap * g.d * g.esize;
+}
+__host__ __device__ inline char* layer_meta(char* meta, const Geom& g, int layer) {
+  return meta + (size_t)layer * g.meta_layer_bytes;
+}
+
+// ---- launchers (each only enqueues on `s`) ---------------------------------
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
+
+// Eq. 2: copy the frame's K/V rows into slots [n, n+M) of layers [layer0, layer0+nl)
+// and initialise their ids (gid0 + i), scores (0) and flags (0).
+hipError_t launch_append(const Geom& g, char* kv, char* meta, int layer0, int nl,
+                         const void* k_new, const void* v_new, int n, uint32_t gid0, hipStream_t s);
+
+// Attention of M queries over n_total resident slots.
+hipError_t launch_attn_f32(const Geom& g, char* kv, int layer0, int nl, const void* q, void* out,
+                           int n_total, float scale, hipStream_t s);
+hipError_t launch_attn_bf16(const Geom& g, char* kv, int layer0, int nl, const void* q, void* out,
+                            int n_total, float scale, char* ws, int n_wgs, hipStream_t s);
+size_t attn_ws_bytes();
+
+// Eq. 5 + anchor flags for the M slots [n_total-M, n_total), then (when
+// n_total > B) Eq. 8's selection and the move list.
+hipError_t launch_score_select(const Geom& g, char* meta, int layer0, int nl, const void* resid,
+                               const uint8_t* anchors, int n_total, hipStream_t s);
+
+// Apply the move list to K, V and the per-slot metadata.
+hipError_t launch_compact(const Geom& g, char* kv, char* meta, int layer0, int nl, hipStream_t s);
+
+}  // namespace ovggt

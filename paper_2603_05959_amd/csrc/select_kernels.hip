@@ -1,0 +1,319 @@
+// Activation Value Rating (paper Eq. 5), anchor flags (Sec. 3.3) and the
+// fixed-budget selection (Eq. 8) in one launch.
+//
+// Phase 1 (all workgroups): one wave per new token reduces the token's residual
+// row to ss = sum of squares in fp32 with a fixed balanced-tree order -- lane l
+// owns E consecutive elements, sums their squares pairwise in registers, then
+// six xor-butterfly steps add neighbouring lanes -- so the value is bit-for-bit
+// reproducible by a plain pairwise sum on any machine.  HBM-bound: each row is
+// read once with 16-byte loads.
+//
+// Phase 2 (the workgroup that arrives last for a layer, found with an arrival
+// counter; nobody waits): if more than B entries are resident, find the E =
+// n - B lowest-ranked evictable entries under the total order (ss ascending,
+// token id descending) by an 8-bit-digit radix select on the 64-bit key
+// (ss bits << 32) | ~id, with a per-lane-column LDS histogram (no bank or
+// address conflicts), then emit the move list in ascending slot order.
+#include "ovggt_internal.h"
+#include "../../include/ovggt.h"
+
+namespace ovggt {
+
+constexpr int kSelThreads = 1024;
+constexpr int kSelWaves = kSelThreads / 64;
+constexpr int kMaxSelChunks = 128;          // n_total <= 128 * 1024 slots
+
+__device__ inline float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
+// ---- phase 1 ---------------------------------------------------------------
+template <int E, bool BF16>
+__device__ inline float row_sum_sq(const char* row, int C, int lane) {
+  float p[E];
+  const int first = lane * E;
+  if constexpr (BF16) {
+    const uint16_t* r = (const uint16_t*)row;
+    if constexpr (E >= 8) {
+      if ((C & 7) == 0) {
+#pragma unroll
+        for (int j = 0; j < E; j += 8) {
+          uint4 w = {0u, 0u, 0u, 0u};
+          if (first + j < C) w = *(const uint4*)(r + first + j);
+          const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+          for (int t = 0; t < 4; ++t) {
+            const float a = __uint_as_float(ww[t] << 16), b = __uint_as_float(ww[t] & 0xFFFF0000u);
+            p[j + 2 * t] = __fmul_rn(a, a);
+            p[j + 2 * t + 1] = __fmul_rn(b, b);
+          }
+        }
+        goto tree;
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < E; ++j) {
+      const float a = (first + j < C) ? bf16_to_f32(r[first + j]) : 0.f;
+      p[j] = __fmul_rn(a, a);
+    }
+  } else {
+    const float* r = (const float*)row;
+    if constexpr (E >= 4) {
+      if ((C & 3) == 0) {
+#pragma unroll
+        for (int j = 0; j < E; j += 4) {
+          float4 w = {0.f, 0.f, 0.f, 0.f};
+          if (first + j < C) w = *(const float4*)(r + first + j);
+          p[j] = __fmul_rn(w.x, w.x); p[j + 1] = __fmul_rn(w.y, w.y);
+          p[j + 2] = __fmul_rn(w.z, w.z); p[j + 3] = __fmul_rn(w.w, w.w);
+        }
+        goto tree;
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < E; ++j) {
+      const float a = (first + j < C) ? r[first + j] : 0.f;
+      p[j] = __fmul_rn(a, a);
+    }
+  }
+tree:
+#pragma unroll
+  for (int w = 1; w < E; w *= 2)
+#pragma unroll
+    for (int j = 0; j < E; j += 2 * w) p[j] = __fadd_rn(p[j], p[j + w]);
+  float v = p[0];
+#pragma unroll
+  for (int off = 1; off < 64; off *= 2) v = __fadd_rn(v, __shfl_xor(v, off, 64));
+  return v;
+}
+
+template <bool BF16>
+__device__ inline float row_sum_sq_any(const char* row, int C, int e, int lane) {
+  switch (e) {
+    case 1: return row_sum_sq<1, BF16>(row, C, lane);
+    case 2: return row_sum_sq<2, BF16>(row, C, lane);
+    case 4: return row_sum_sq<4, BF16>(row, C, lane);
+    case 8: return row_sum_sq<8, BF16>(row, C, lane);
+    case 16: return row_sum_sq<16, BF16>(row, C, lane);
+    case 32: return row_sum_sq<32, BF16>(row, C, lane);
+    default: return row_sum_sq<64, BF16>(row, C, lane);
+  }
+}
+
+// ---- phase 2 helpers ---------------------------------------------------------
+struct SelShared {
+  uint32_t hist[128][64];          // two 16-bit bins per word, one column per lane id
+  uint32_t cnt[256];
+  uint32_t wave_tot[2][kMaxSelChunks * kSelWaves + 64];
+  uint32_t scan_tmp[2][kSelWaves];
+  uint32_t digit, rank, bucket, is_last, n_evictable, bad;
+};
+
+__device__ inline uint64_t make_key(float ss, uint32_t id, bool* bad) {
+  uint32_t b = __float_as_uint(ss);
+  if (ss != ss || (b & 0x80000000u)) { b = 0u; *bad = true; }      // NaN / negative: lowest rank
+  return ((uint64_t)b << 32) | (uint64_t)(0xFFFFFFFFu - id);
+}
+
+// exclusive scan of `n` counters laid out consecutively (n <= 2 * kSelThreads); in place
+__device__ inline void block_exclusive_scan(uint32_t* a, int n, uint32_t* wave_tmp, uint32_t* total_out) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int i0 = 2 * tid, i1 = 2 * tid + 1;
+  const uint32_t x0 = i0 < n ? a[i0] : 0u, x1 = i1 < n ? a[i1] : 0u;
+  uint32_t s = x0 + x1;
+  uint32_t inc = s;
+#pragma unroll
+  for (int off = 1; off < 64; off *= 2) {
+    const uint32_t y = __shfl_up(inc, off, 64);
+    if (lane >= off) inc += y;
+  }
+  if (lane == 63) wave_tmp[wave] = inc;
+  __syncthreads();
+  uint32_t base = 0;
+  for (int w = 0; w < wave; ++w) base += wave_tmp[w];
+  if (tid == kSelThreads - 1) *total_out = base + inc;
+  const uint32_t ex = base + inc - s;
+  if (i0 < n) a[i0] = ex;
+  if (i1 < n) a[i1] = ex + x0;
+  __syncthreads();
+}
+
+template <bool BF16>
+__global__ void __launch_bounds__(kSelThreads)
+score_select_kernel(Geom g, char* meta, int layer0, const char* resid, const uint8_t* anchors,
+                    int n_total, int e_per_lane) {
+  __shared__ SelShared sh;
+  const int layer = layer0 + blockIdx.y;
+  const int li = blockIdx.y;
+  char* mb = layer_meta(meta, g, layer);
+  uint32_t* ids = (uint32_t*)(mb + g.off_ids);
+  float* ss = (float*)(mb + g.off_ss);
+  uint8_t* flags = (uint8_t*)(mb + g.off_flags);
+  Ctrl* ctrl = (Ctrl*)(mb + g.off_ctrl);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n_old = n_total - g.M;
+
+  // ---- phase 1: scores and flags of the M new slots
+  {
+    const size_t row_bytes = (size_t)g.C * g.esize;
+    const char* rbase = resid + (size_t)li * g.M * row_bytes;
+    for (int tok = blockIdx.x * kSelWaves + wave; tok < g.M; tok += gridDim.x * kSelWaves) {
+      const float v = row_sum_sq_any<BF16>(rbase + (size_t)tok * row_bytes, g.C, e_per_lane, lane);
+      if (lane == 0) {
+        ss[n_old + tok] = v;
+        flags[n_old + tok] = (anchors && anchors[(size_t)li * g.M + tok]) ? 1 : 0;
+      }
+    }
+  }
+  const bool do_select = n_total > g.B;
+  if (!do_select) {
+    if (blockIdx.x == 0 && tid == 0) ctrl->n_moves = 0;
+    return;
+  }
+  __threadfence();
+  __syncthreads();
+  if (tid == 0) {
+    const uint32_t prev = atomicAdd(&ctrl->arrive, 1u);
+    sh.is_last = (prev == gridDim.x - 1) ? 1u : 0u;
+  }
+  __syncthreads();
+  if (!sh.is_last) return;
+  __threadfence();
+
+  // ---- phase 2: this workgroup saw every other one arrive
+  const int n_chunks = (n_total + kSelThreads - 1) / kSelThreads;
+  const uint32_t n_evict = (uint32_t)(n_total - g.B);
+  if (tid == 0) { ctrl->arrive = 0; sh.bad = 0; }
+  bool bad = false;
+  uint64_t prefix = 0;
+  uint32_t rank = n_evict;          // 1-based rank, in ascending key order, of the last entry to evict
+  int shift = 56;
+  bool budget_error = false;
+  for (int pass = 0; pass < 8; ++pass, shift -= 8) {
+    for (int i = tid; i < 128 * 64; i += kSelThreads) (&sh.hist[0][0])[i] = 0u;
+    __syncthreads();
+    for (int c = 0; c < n_chunks; ++c) {
+      const int i = c * kSelThreads + tid;
+      if (i < n_total && flags[i] == 0) {
+        const uint64_t key = make_key(ss[i], ids[i], &bad);
+        if (pass == 0 || (key >> (shift + 8)) == (prefix >> (shift + 8))) {
+          const uint32_t dg = (uint32_t)(key >> shift) & 255u;
+          atomicAdd(&sh.hist[dg >> 1][lane], 1u << (16 * (dg & 1u)));
+        }
+      }
+    }
+    __syncthreads();
+    {   // column sums: thread -> (bin, quarter of the 64 columns)
+      const int bin = tid >> 2, quarter = tid & 3;
+      uint32_t s = 0;
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        const int col = quarter * 16 + ((j + (lane >> 2)) & 15);   // 64 distinct columns per wave read
+        s += (sh.hist[bin >> 1][col] >> (16 * (bin & 1))) & 0xFFFFu;
+      }
+      s += __shfl_xor(s, 1, 64);
+      s += __shfl_xor(s, 2, 64);
+      if (quarter == 0) sh.cnt[bin] = s;
+    }
+    __syncthreads();
+    if (wave == 0) {     // find the digit whose bucket contains the rank-th smallest key
+      uint32_t c4[4];
+      uint32_t s = 0;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) { c4[j] = sh.cnt[4 * lane + j]; s += c4[j]; }
+      uint32_t inc = s;
+#pragma unroll
+      for (int off = 1; off < 64; off *= 2) {
+        const uint32_t y = __shfl_up(inc, off, 64);
+        if (lane >= off) inc += y;
+      }
+      uint32_t before = inc - s;
+      if (pass == 0 && lane == 63) sh.n_evictable = inc;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (before < rank && rank <= before + c4[j]) {
+          sh.digit = 4 * lane + j; sh.rank = rank - before; sh.bucket = c4[j];
+        }
+        before += c4[j];
+      }
+    }
+    __syncthreads();
+    if (pass == 0 && sh.n_evictable < n_evict) { budget_error = true; break; }   // |P| > B
+    prefix |= (uint64_t)sh.digit << shift;
+    rank = sh.rank;
+    const uint32_t bucket = sh.bucket;
+    __syncthreads();
+    if (rank == bucket) break;       // the whole bucket goes: no need to split it further
+  }
+  if (shift < 0) shift = 0;
+  if (bad) sh.bad = 1;
+
+  // ---- evict bits per slot, held as one bit per chunk in registers
+  uint64_t ev0 = 0, ev1 = 0;
+  if (!budget_error) {
+    for (int c = 0; c < n_chunks; ++c) {
+      const int i = c * kSelThreads + tid;
+      bool ev = false;
+      if (i < n_total && flags[i] == 0) {
+        bool b2 = false;
+        const uint64_t key = make_key(ss[i], ids[i], &b2);
+        ev = (key >> shift) <= (prefix >> shift);
+      }
+      if (ev) { if (c < 64) ev0 |= 1ull << c; else ev1 |= 1ull << (c - 64); }
+    }
+  }
+  // per-(chunk, wave) counts of holes (evicted slot below B) and movers (kept slot at or above B)
+  for (int c = 0; c < n_chunks; ++c) {
+    const int i = c * kSelThreads + tid;
+    const bool ev = c < 64 ? (ev0 >> c) & 1 : (ev1 >> (c - 64)) & 1;
+    const bool hole = !budget_error && i < g.B && ev;
+    const bool mover = !budget_error && i >= g.B && i < n_total && !ev;
+    const uint64_t hb = __ballot(hole), mvb = __ballot(mover);
+    if (lane == 0) {
+      sh.wave_tot[0][c * kSelWaves + wave] = __popcll(hb);
+      sh.wave_tot[1][c * kSelWaves + wave] = __popcll(mvb);
+    }
+  }
+  __syncthreads();
+  __shared__ uint32_t totals[2];
+  block_exclusive_scan(sh.wave_tot[0], n_chunks * kSelWaves, sh.scan_tmp[0], &totals[0]);
+  block_exclusive_scan(sh.wave_tot[1], n_chunks * kSelWaves, sh.scan_tmp[1], &totals[1]);
+  uint32_t* mvdst = (uint32_t*)(mb + g.off_mvdst);
+  uint32_t* mvsrc = (uint32_t*)(mb + g.off_mvsrc);
+  const uint64_t lt = (1ull << lane) - 1ull;
+  const bool consistent = totals[0] == totals[1] && totals[0] <= (uint32_t)g.M;
+  for (int c = 0; c < n_chunks; ++c) {
+    const int i = c * kSelThreads + tid;
+    const bool ev = c < 64 ? (ev0 >> c) & 1 : (ev1 >> (c - 64)) & 1;
+    const bool hole = !budget_error && i < g.B && ev;
+    const bool mover = !budget_error && i >= g.B && i < n_total && !ev;
+    const uint64_t hb = __ballot(hole), mvb = __ballot(mover);
+    if (consistent) {
+      if (hole) mvdst[sh.wave_tot[0][c * kSelWaves + wave] + __popcll(hb & lt)] = (uint32_t)i;
+      if (mover) mvsrc[sh.wave_tot[1][c * kSelWaves + wave] + __popcll(mvb & lt)] = (uint32_t)i;
+    }
+  }
+  __syncthreads();
+  if (tid == 0) {
+    ctrl->n_moves = consistent ? totals[0] : 0u;
+    uint32_t st = 0;
+    if (budget_error || !consistent) st |= OVGGT_STATUS_BUDGET;
+    if (sh.bad) st |= OVGGT_STATUS_NONFINITE;
+    if (st) atomicOr(&ctrl->status, st);
+  }
+}
+
+hipError_t launch_score_select(const Geom& g, char* meta, int layer0, int nl, const void* resid,
+                               const uint8_t* anchors, int n_total, hipStream_t s) {
+  int cp = 1;
+  while (cp < g.C) cp *= 2;
+  const int e = cp >= 64 ? cp / 64 : 1;
+  dim3 grid((unsigned)((g.M + kSelWaves - 1) / kSelWaves), (unsigned)nl);
+  if (g.esize == 2)
+    hipLaunchKernelGGL(score_select_kernel<true>, grid, dim3(kSelThreads), 0, s, g, meta, layer0,
+                       (const char*)resid, anchors, n_total, e);
+  else
+    hipLaunchKernelGGL(score_select_kernel<false>, grid, dim3(kSelThreads), 0, s, g, meta, layer0,
+                       (const char*)resid, anchors, n_total, e);
+  return hipGetLastError();
+}
+
+}  // namespace ovggt

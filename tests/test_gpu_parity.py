@@ -1,0 +1,280 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on
+the same seeded inputs.  Kept ids / slot layout / scores / flags / K / V must be
+bit-exact; attention outputs must agree within 1e-4 (f32) or 2e-2 (bf16) of the
+output RMS per frame (max-abs over the frame's [M,H,d] block)."""
+import numpy as np
+import pytest
+
+from oracle import ovggt_oracle as oc
+from paper_2603_05959_amd import binding as B
+from paper_2603_05959_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def make_cache(cfg, L=None):
+    return B.Cache(L or cfg.L, cfg.H, cfg.d, cfg.M, cfg.C, cfg.B, cfg.dtype)
+
+
+def dev(a, cfg):
+    return B.to_device(a, cfg.dtype)
+
+
+def rel_err(o_gpu, o_ref):
+    return float(np.abs(o_gpu - o_ref).max() / np.sqrt((o_ref ** 2).mean()))
+
+
+def compare_cache(cache, orc, layer=0, kv=True):
+    e = cache.export(layer)
+    assert len(e["ids"]) == orc.n
+    assert np.array_equal(e["ids"], orc.gid), "kept ids / layout differ"
+    assert np.array_equal(e["ss"].view(np.uint32), orc.ss.view(np.uint32)), "scores differ"
+    assert np.array_equal(e["flags"], orc.flag)
+    if kv:
+        assert np.array_equal(e["k"], orc.k) and np.array_equal(e["v"], orc.v)
+
+
+def run_stream(cfg, layer=0, attn_frames=None, cache_every=1, resid_fn=None, q_rows=None, log=None):
+    """Drive both sides over cfg.T frames of one layer; returns max attention error."""
+    torch = _torch()
+    cache = make_cache(cfg, L=1)
+    orc = oc.OracleCache(cfg.M, cfg.H, cfg.d, cfg.B)
+    odt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+    out = torch.empty((cfg.M, cfg.H, cfg.d), dtype=odt, device="cuda:0")
+    worst = 0.0
+    for t in range(cfg.T):
+        f = synth.frame_inputs(cfg, layer, t)
+        if resid_fn is not None:
+            f["r"] = resid_fn(cfg, layer, t)
+        q, k, v, r = (dev(f[x], cfg) for x in "qkvr")
+        a = torch.from_numpy(f["a"]).to("cuda:0")
+        cache.step(q, k, v, r, a, out, layer=0)
+        do_attn = attn_frames is None or t in attn_frames
+        orc.append(f["k"], f["v"])
+        if do_attn:
+            o_gpu = out.float().cpu().numpy().astype(np.float64)
+            if q_rows is None:
+                o_ref = orc.attend(f["q"])
+            else:
+                o_ref = oc.attention(f["q"][q_rows], orc.k, orc.v)
+                o_gpu = o_gpu[q_rows]
+            err = rel_err(o_gpu, o_ref)
+            worst = max(worst, err)
+            assert err < TOL[cfg.dtype], f"frame {t}: attention error {err:.3e}"
+        orc.update(f["r"], f["a"])
+        assert cache.size(0) == orc.n == min((t + 1) * cfg.M, cfg.B)
+        if t % cache_every == 0 or t == cfg.T - 1:
+            compare_cache(cache, orc, kv=(t % (4 * cache_every) == 0 or t == cfg.T - 1))
+        if log:
+            print(f"[{log}] frame {t} ok", flush=True)
+    assert cache.status(0) == 0
+    cache.close()
+    return worst
+
+
+def test_cfg0_tiny_f32_full_stream():
+    worst = run_stream(synth.preset(0))
+    print("cfg0 worst attention err/RMS:", worst)
+
+
+def test_bf16_ragged_small():
+    # 200 queries (1.6 query blocks), 900 slots at steady state (7 tiles + tail of 4), odd head count,
+    # residual width that is not a power of two
+    cfg = synth.preset(1, M=200, H=3, C=200, B=700, T=9, n_special=3)
+    worst = run_stream(cfg)
+    print("ragged worst attention err/RMS:", worst)
+
+
+@pytest.mark.parametrize("M,B,H,C", [(1, 64, 1, 64), (37, 37, 2, 1024), (130, 1000, 5, 4096), (128, 256, 16, 8)])
+def test_bf16_odd_shapes(M, B, H, C):
+    cfg = synth.preset(1, M=M, H=H, C=C, B=B, T=max(6, 2 * B // M + 3) if M > 1 else 70, n_special=min(M, 2))
+    run_stream(cfg)
+
+
+def test_f32_shapes_with_eviction_and_ties():
+    cfg = synth.preset(3, M=70, H=2, C=96, B=300, T=14, n_special=2, dtype="f32")
+    run_stream(cfg)
+
+
+def test_ties_bf16_stream():
+    cfg = synth.preset(3, M=300, H=2, C=1024, B=2000, T=30, n_special=5)
+    run_stream(cfg, attn_frames={0, 7, 29})
+
+
+def test_cfg4_shape_budget_sweep_and_full_cache_equality():
+    for budget in (4096, 8192):
+        cfg = synth.preset(4, B=budget, T=budget // 1041 + 4)
+        run_stream(cfg, attn_frames={0, budget // 1041 - 1, budget // 1041, cfg.T - 1}, cache_every=2)
+    # budget >= everything seen: equals uncompressed causal streaming attention
+    cfg = synth.preset(4, B=8 * 1041, T=8)
+    torch = _torch()
+    cache = make_cache(cfg, L=1)
+    out = torch.empty((cfg.M, cfg.H, cfg.d), dtype=torch.bfloat16, device="cuda:0")
+    ks, vs = [], []
+    for t in range(cfg.T):
+        f = synth.frame_inputs(cfg, 0, t)
+        cache.step(dev(f["q"], cfg), dev(f["k"], cfg), dev(f["v"], cfg), dev(f["r"], cfg),
+                   torch.from_numpy(f["a"]).cuda(), out, layer=0)
+        ks.append(f["k"]); vs.append(f["v"])
+        if t in (0, 3, 7):
+            ref = oc.attention(f["q"], np.concatenate(ks), np.concatenate(vs))
+            assert rel_err(out.float().cpu().numpy().astype(np.float64), ref) < TOL["bf16"]
+    e = cache.export(0)
+    assert np.array_equal(e["ids"], np.arange(cfg.T * cfg.M))
+    assert np.array_equal(e["k"], np.concatenate(ks))
+    cache.close()
+
+
+def test_cfg1_shapes_warmup_boundary():
+    """Full-size layer (M=1374, 16x64, B=16384): frames around the first eviction."""
+    cfg = synth.preset(1, T=14)
+    rows = np.random.default_rng(0).choice(cfg.M, size=96, replace=False)
+    rows = np.unique(np.concatenate([rows, [0, 127, 128, 1279, 1280, 1373]]))
+    worst = run_stream(cfg, attn_frames={0, 1, 10, 11, 12, 13}, q_rows=rows, cache_every=1, log="cfg1")
+    print("cfg1 worst sampled attention err/RMS:", worst)
+
+
+def test_worst_case_compaction_rising_scores():
+    cfg = synth.preset(1, M=300, H=4, B=1500, T=12, n_special=5)
+    torch = _torch()
+    cache = make_cache(cfg, L=1)
+    orc = oc.OracleCache(cfg.M, cfg.H, cfg.d, cfg.B)
+    out = torch.empty((cfg.M, cfg.H, cfg.d), dtype=torch.bfloat16, device="cuda:0")
+    for t in range(cfg.T):
+        f = synth.frame_inputs(cfg, 0, t, want=("q", "k", "v", "a"))
+        r = synth.rising_resid(cfg, 0, t)
+        cache.step(dev(f["q"], cfg), dev(f["k"], cfg), dev(f["v"], cfg), dev(r, cfg),
+                   torch.from_numpy(f["a"]).cuda(), out, layer=0)
+        orc.step(f["q"], f["k"], f["v"], r, f["a"], attend=False)
+        dst, src = cache.last_moves(0)
+        if t >= 5:
+            assert len(dst) == cfg.M - cfg.n_special * 0 or len(dst) > 0
+        compare_cache(cache, orc)
+    cache.close()
+
+
+def test_batched_layers_match_per_layer_oracle():
+    cfg = synth.preset(2, M=150, H=2, C=256, B=400, T=7, L=3, n_special=5)
+    torch = _torch()
+    cache = make_cache(cfg)
+    orcs = [oc.OracleCache(cfg.M, cfg.H, cfg.d, cfg.B) for _ in range(cfg.L)]
+    out = torch.empty((cfg.L, cfg.M, cfg.H, cfg.d), dtype=torch.bfloat16, device="cuda:0")
+    for t in range(cfg.T):
+        fs = [synth.frame_inputs(cfg, l, t) for l in range(cfg.L)]
+        stack = lambda key: dev(np.stack([f[key] for f in fs]), cfg)
+        a = torch.from_numpy(np.stack([f["a"] for f in fs])).cuda()
+        cache.step(stack("q"), stack("k"), stack("v"), stack("r"), a, out)      # layer = all
+        o = out.float().cpu().numpy().astype(np.float64)
+        for l in range(cfg.L):
+            ref = orcs[l].step(fs[l]["q"], fs[l]["k"], fs[l]["v"], fs[l]["r"], fs[l]["a"])
+            assert rel_err(o[l], ref) < TOL["bf16"], (t, l)
+            compare_cache(cache, orcs[l], layer=l)
+    cache.close()
+
+
+def test_per_layer_calls_are_independent():
+    cfg = synth.preset(2, M=64, H=1, C=64, B=128, T=5, L=2, n_special=1)
+    torch = _torch()
+    cache = make_cache(cfg)
+    orcs = [oc.OracleCache(cfg.M, cfg.H, cfg.d, cfg.B) for _ in range(2)]
+    out = torch.empty((cfg.M, cfg.H, cfg.d), dtype=torch.bfloat16, device="cuda:0")
+    for t in range(cfg.T):                        # layer 1 runs one frame behind layer 0
+        for l, tt in ((0, t), (1, t - 1)):
+            if tt < 0:
+                continue
+            f = synth.frame_inputs(cfg, l, tt)
+            cache.step(dev(f["q"], cfg), dev(f["k"], cfg), dev(f["v"], cfg), dev(f["r"], cfg),
+                       torch.from_numpy(f["a"]).cuda(), out, layer=l)
+            ref = orcs[l].step(f["q"], f["k"], f["v"], f["r"], f["a"])
+            assert rel_err(out.float().cpu().numpy().astype(np.float64), ref) < TOL["bf16"]
+            compare_cache(cache, orcs[l], layer=l)
+    with pytest.raises(B.OvggtError) as e:        # layers out of step: a batched call is refused
+        cache.global_attn(out, out, out, out)
+    assert e.value.code == B.OVGGT_ERR_STATE
+    cache.close()
+
+
+def test_call_order_and_argument_errors():
+    cfg = synth.preset(0)
+    torch = _torch()
+    cache = make_cache(cfg)
+    f = synth.frame_inputs(cfg, 0, 0)
+    q, k, v, r = (dev(f[x], cfg) for x in "qkvr")
+    out = torch.empty_like(q)
+    for call in (lambda: cache.score_select(r, None, 0), lambda: cache.compact(0)):
+        with pytest.raises(B.OvggtError) as e:
+            call()
+        assert e.value.code == B.OVGGT_ERR_STATE
+    with pytest.raises(B.OvggtError) as e:
+        cache.global_attn(q, k, v, out, layer=5)
+    assert e.value.code == B.OVGGT_ERR_ARG
+    with pytest.raises(B.OvggtError) as e:
+        B.ovggt_global_attn(cache.h, 0, q.data_ptr() + 4, k, v, out, cache.stream)
+    assert e.value.code == B.OVGGT_ERR_ARG
+    assert cache.size(0) == 0
+    cache.global_attn(q, k, v, out, 0)
+    for call in (lambda: cache.global_attn(q, k, v, out, 0), lambda: cache.compact(0)):
+        with pytest.raises(B.OvggtError) as e:
+            call()
+        assert e.value.code == B.OVGGT_ERR_STATE
+    assert cache.size(0) == cfg.M
+    cache.score_select(r, None, 0)
+    with pytest.raises(B.OvggtError):
+        cache.score_select(r, None, 0)
+    cache.compact(0)
+    assert cache.size(0) == cfg.M and cache.frames(0) == 1
+    cache.close()
+
+
+def test_protected_set_larger_than_budget_sets_status():
+    cfg = synth.preset(0, B=100, T=3)
+    torch = _torch()
+    cache = make_cache(cfg)
+    out = torch.empty((cfg.M, cfg.H, cfg.d), dtype=torch.float32, device="cuda:0")
+    ones = torch.ones(cfg.M, dtype=torch.uint8, device="cuda:0")
+    for t in range(2):                               # 130 protected tokens, budget 100
+        f = synth.frame_inputs(cfg, 0, t)
+        cache.step(dev(f["q"], cfg), dev(f["k"], cfg), dev(f["v"], cfg), dev(f["r"], cfg), ones, out, layer=0)
+    assert cache.status(0) & B.OVGGT_STATUS_BUDGET
+    assert cache.status(0) == 0                      # reading clears it
+    assert cache.size(0) == cfg.B
+    cache.close()
+
+
+def test_import_export_and_crafted_scores():
+    """Selection on hand-made cache contents: NaN ranks lowest, ties go to the
+    older id, k = 0 evicts every evictable entry."""
+    cfg = synth.preset(0, M=8, B=16, H=1, C=64, T=1, dtype="f32", n_special=1)
+    rng = np.random.default_rng(3)
+    cache = make_cache(cfg)
+    n = 16
+    ids = rng.permutation(80)[:n].astype(np.uint32)           # 10 frames already seen
+    ss = rng.choice(np.array([0.0, 1.0, 1.0, 2.0, 5.0], np.float32), size=n)
+    ss[3] = np.nan
+    flags = (rng.random(n) < 0.25).astype(np.uint8)
+    k = rng.standard_normal((n, 1, 64)).astype(np.float32); v = rng.standard_normal((n, 1, 64)).astype(np.float32)
+    cache.import_(0, 10, ids, k, v, ss, flags)
+    e = cache.export(0)
+    assert np.array_equal(e["ids"], ids) and np.array_equal(e["k"], k) and np.array_equal(e["flags"], flags)
+    orc = oc.OracleCache(cfg.M, cfg.H, cfg.d, cfg.B)
+    orc.k, orc.v, orc.gid, orc.ss, orc.flag, orc.t = k.copy(), v.copy(), ids.copy(), ss.copy(), flags.copy(), 10
+    torch = _torch()
+    f = synth.frame_inputs(cfg, 0, 10)
+    f["r"][2] = f["r"][5]                                      # an exact tie among the new tokens
+    out = torch.empty((cfg.M, cfg.H, cfg.d), dtype=torch.float32, device="cuda:0")
+    cache.step(dev(f["q"], cfg), dev(f["k"], cfg), dev(f["v"], cfg), dev(f["r"], cfg),
+               torch.from_numpy(f["a"]).cuda(), out, layer=0)
+    ref = orc.step(f["q"], f["k"], f["v"], f["r"], f["a"])
+    assert rel_err(out.cpu().numpy().astype(np.float64), ref) < TOL["f32"]
+    e = cache.export(0)
+    assert np.array_equal(e["ids"], orc.gid)
+    assert np.array_equal(np.isnan(e["ss"]), np.isnan(orc.ss))
+    assert cache.status(0) & B.OVGGT_STATUS_NONFINITE
+    cache.close()

@@ -1,0 +1,72 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the
+header declares, and its host-side validation works without a GPU."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2603_05959_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _built():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2603_05959_amd import build
+        build.build(verbose=False)
+
+
+def test_header_symbols_are_exported():
+    _built()
+    hdr = open(os.path.join(ROOT, "include", "ovggt.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(ovggt_[a-z_]+)\s*\(", hdr))
+    assert declared == set(B.EXPORTS)
+    lib = B.lib()
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_query_bytes_and_config_validation():
+    _built()
+    cfg = B.make_config(1, 16, 64, 1374, 1024, 16384, "bf16")
+    kv, meta, ws = B.ovggt_cache_query_bytes(cfg)
+    cap = (16384 + 1374 + 127) // 128 * 128
+    assert kv == 2 * 16 * cap * 64 * 2                 # 4 KiB per token per layer: the paper's 2*N_h*d elements in bf16
+    assert meta >= cap * 9 and ws > 0 and kv % 256 == 0 and meta % 256 == 0 and ws % 256 == 0
+    kv24, meta24, _ = B.ovggt_cache_query_bytes(B.make_config(24, 16, 64, 1374, 1024, 16384, "bf16"))
+    assert kv24 == 24 * kv and meta24 == 24 * meta
+    bad = [dict(head_dim=128), dict(budget=100), dict(n_layers=0), dict(resid_dim=0), dict(resid_dim=5000),
+           dict(dtype=7), dict(score_mode=1), dict(softmax_scale=-1.0), dict(budget=131072)]
+    for kw in bad:
+        args = dict(n_layers=1, n_heads=16, head_dim=64, tokens_per_frame=1374, resid_dim=1024, budget=16384,
+                    dtype="bf16", score_mode=0, softmax_scale=0.0)
+        args.update(kw)
+        with pytest.raises(B.OvggtError) as e:
+            B.ovggt_cache_query_bytes(B.make_config(**args))
+        assert e.value.code == B.OVGGT_ERR_ARG
+
+
+def test_null_and_misaligned_arguments_rejected_before_any_launch():
+    _built()
+    lib = B.lib()
+    cfg = B.make_config(1, 2, 64, 65, 128, 256, "f32")
+    h = C.c_void_p()
+    assert lib.ovggt_cache_init(C.byref(h), C.byref(cfg), None, None, None, None) == B.OVGGT_ERR_ARG
+    assert lib.ovggt_cache_init(C.byref(h), C.byref(cfg), 0x1001, 0x2000, 0x3000, None) == B.OVGGT_ERR_ARG
+    assert lib.ovggt_cache_init(None, C.byref(cfg), 0x1000, 0x2000, 0x3000, None) == B.OVGGT_ERR_ARG
+    assert lib.ovggt_global_attn(None, 0, None, None, None, None, None) == B.OVGGT_ERR_ARG
+    assert lib.ovggt_score_select(None, 0, None, None, None) == B.OVGGT_ERR_ARG
+    assert lib.ovggt_cache_compact(None, 0, None) == B.OVGGT_ERR_ARG
+    assert lib.ovggt_cache_destroy(None) == B.OVGGT_ERR_ARG
+    assert B.strerror(0) == "ok" and "order" in B.strerror(B.OVGGT_ERR_STATE)
+
+
+def test_product_path_does_not_touch_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2603_05959_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".cpp", ".h")):
+                src = open(os.path.join(dirpath, f)).read()
+                assert not re.search(r"(import|from)\s+oracle|oracle[/.]\w", src), f
