@@ -150,6 +150,18 @@ int ovggt_cache_import(ovggt_cache* c, int layer, int32_t n, int64_t frames, con
 int ovggt_cache_last_moves(ovggt_cache* c, int layer, uint32_t* dst, uint32_t* src, int32_t* n_moves,
                            void* hip_stream);
 
+/* Kernel timing for benchmarks (off by default; the hot path records nothing
+ * when off).  level 1: bracket the attention kernel of every `every`-th
+ * ovggt_global_attn call with HIP events on the call's stream; level 2: bracket
+ * every kernel of every call.  ovggt_profile_read synchronises `hip_stream`,
+ * returns per kernel class the summed elapsed milliseconds and the number of
+ * bracketed launches since the last read (host arrays of OVGGT_PROF_CLASSES
+ * entries), and resets them. */
+enum { OVGGT_PROF_APPEND = 0, OVGGT_PROF_ATTN = 1, OVGGT_PROF_COMBINE = 2, OVGGT_PROF_SELECT = 3,
+       OVGGT_PROF_COMPACT = 4, OVGGT_PROF_CLASSES = 5 };
+int ovggt_profile_enable(ovggt_cache* c, int level, int every);
+int ovggt_profile_read(ovggt_cache* c, double* ms_sum, int64_t* count, void* hip_stream);
+
 const char* ovggt_strerror(int code);
 
 #ifdef __cplusplus

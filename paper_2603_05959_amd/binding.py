@@ -22,8 +22,9 @@ EXPORTS = (
     "ovggt_cache_query_bytes", "ovggt_cache_init", "ovggt_global_attn", "ovggt_score_select",
     "ovggt_cache_compact", "ovggt_cache_destroy", "ovggt_cache_size", "ovggt_cache_frames",
     "ovggt_cache_status", "ovggt_cache_export", "ovggt_cache_import", "ovggt_cache_last_moves",
-    "ovggt_strerror",
+    "ovggt_profile_enable", "ovggt_profile_read", "ovggt_strerror",
 )
+PROF_CLASSES = ("append", "attn", "combine", "score_select", "compact")
 
 
 class ovggt_config(C.Structure):
@@ -65,6 +66,8 @@ def lib() -> C.CDLL:
     L.ovggt_cache_export.argtypes = [vp, C.c_int, u32p, vp, vp, vp, u8p, vp]
     L.ovggt_cache_import.argtypes = [vp, C.c_int, i32, i64, u32p, vp, vp, vp, u8p, vp]
     L.ovggt_cache_last_moves.argtypes = [vp, C.c_int, u32p, u32p, C.POINTER(i32), vp]
+    L.ovggt_profile_enable.argtypes = [vp, C.c_int, C.c_int]
+    L.ovggt_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64), vp]
     L.ovggt_strerror.argtypes = [C.c_int]
     L.ovggt_strerror.restype = C.c_char_p
     for name in EXPORTS:
@@ -166,6 +169,17 @@ def ovggt_cache_last_moves(h, layer, dst, src, stream: int = 0) -> int:
     _check(lib().ovggt_cache_last_moves(h, layer, _ptr(dst), _ptr(src), C.byref(n), stream),
            "ovggt_cache_last_moves")
     return n.value
+
+
+def ovggt_profile_enable(h, level: int, every: int = 1) -> None:
+    _check(lib().ovggt_profile_enable(h, level, every), "ovggt_profile_enable")
+
+
+def ovggt_profile_read(h, stream: int = 0) -> dict:
+    ms = (C.c_double * len(PROF_CLASSES))()
+    cnt = (C.c_int64 * len(PROF_CLASSES))()
+    _check(lib().ovggt_profile_read(h, ms, cnt, stream), "ovggt_profile_read")
+    return {name: (ms[i], cnt[i]) for i, name in enumerate(PROF_CLASSES)}
 
 
 # ---- convenience owner of the device buffers ---------------------------------

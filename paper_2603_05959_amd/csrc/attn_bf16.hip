@@ -381,7 +381,8 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(AttnParams p) {
 }
 
 hipError_t launch_attn_bf16(const Geom& g, char* kv, int layer0, int nl, const void* q, void* out,
-                            int n_total, float scale, char* ws, int n_wgs, hipStream_t s) {
+                            int n_total, float scale, char* ws, int n_wgs, hipStream_t s,
+                            hipEvent_t* ev) {
   AttnParams p;
   p.q = (const char*)q;
   p.out = (char*)out;
@@ -400,12 +401,17 @@ hipError_t launch_attn_bf16(const Geom& g, char* kv, int layer0, int nl, const v
   if (n_wgs < 8) n_wgs = 8;
   p.chunk = (int)((total + n_wgs - 1) / n_wgs);
   p.c = scale * 1.4426950408889634f;
+  if (ev && hipEventRecord(ev[0], s) != hipSuccess) return hipErrorUnknown;
   hipLaunchKernelGGL(attn_bf16_kernel, dim3((unsigned)n_wgs), dim3(256), 0, s, p);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  if (ev && hipEventRecord(ev[1], s) != hipSuccess) return hipErrorUnknown;
   const int items = nl * g.H * p.QB;
   hipLaunchKernelGGL(attn_combine_kernel, dim3((unsigned)items), dim3(256), 0, s, p);
-  return hipGetLastError();
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  if (ev && hipEventRecord(ev[2], s) != hipSuccess) return hipErrorUnknown;
+  return hipSuccess;
 }
 
 }  // namespace ovggt

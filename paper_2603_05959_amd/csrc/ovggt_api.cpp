@@ -23,6 +23,11 @@ struct ovggt_cache {
   std::vector<int32_t> n;          // resident (incl. pending) slots per layer
   std::vector<int64_t> frames;     // completed frames per layer
   std::vector<int8_t> phase;       // 0: expects global_attn, 1: score_select, 2: compact
+  // optional kernel timing (ovggt_profile_*): event pairs per kernel class
+  int prof_level = 0, prof_every = 1;
+  int64_t prof_calls = 0;
+  std::vector<hipEvent_t> prof_free;
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> prof_pending[OVGGT_PROF_CLASSES];
 };
 
 namespace {
@@ -77,6 +82,44 @@ bool uniform(const ovggt_cache* c, int l0, int nl, int phase) {
     if (c->phase[l] != phase || c->n[l] != c->n[l0] || c->frames[l] != c->frames[l0]) return false;
   return true;
 }
+
+hipEvent_t prof_event(ovggt_cache* c) {
+  if (!c->prof_free.empty()) { hipEvent_t e = c->prof_free.back(); c->prof_free.pop_back(); return e; }
+  hipEvent_t e = nullptr;
+  if (hipEventCreate(&e) != hipSuccess) return nullptr;
+  return e;
+}
+
+// Returns every pending event to the free list (an event shared by two
+// intervals is returned once).
+void prof_recycle(ovggt_cache* c) {
+  std::vector<hipEvent_t> seen;
+  for (int k = 0; k < OVGGT_PROF_CLASSES; ++k) {
+    for (auto& pr : c->prof_pending[k])
+      for (hipEvent_t e : {pr.first, pr.second}) {
+        bool dup = false;
+        for (hipEvent_t x : seen) if (x == e) { dup = true; break; }
+        if (!dup) seen.push_back(e);
+      }
+    c->prof_pending[k].clear();
+  }
+  for (hipEvent_t e : seen) c->prof_free.push_back(e);
+}
+
+// Brackets one launch with events when profiling asks for this kernel class.
+struct ProfScope {
+  ovggt_cache* c; int cls; hipStream_t s; hipEvent_t e0 = nullptr, e1 = nullptr;
+  ProfScope(ovggt_cache* c_, int cls_, hipStream_t s_, bool on) : c(c_), cls(cls_), s(s_) {
+    if (!on) return;
+    e0 = prof_event(c); e1 = prof_event(c);
+    if (e0 && e1) (void)hipEventRecord(e0, s); else e0 = e1 = nullptr;
+  }
+  ~ProfScope() {
+    if (!e0) return;
+    (void)hipEventRecord(e1, s);
+    c->prof_pending[cls].push_back({e0, e1});
+  }
+};
 
 inline Ctrl* ctrl_of(const ovggt_cache* c, int layer) {
   return (Ctrl*)(layer_meta(c->meta, c->g, layer) + c->g.off_ctrl);
@@ -142,13 +185,30 @@ int ovggt_global_attn(ovggt_cache* c, int layer, const void* q, const void* k_ne
   if (gid0 + g.M > 0xFFFFFFFFLL) return OVGGT_ERR_ARG;          // token ids are 32-bit
   if (n + g.M > g.cap) return OVGGT_ERR_STATE;
   hipStream_t s = (hipStream_t)hip_stream;
-  if (launch_append(g, c->kv, c->meta, l0, nl, k_new, v_new, n, (uint32_t)gid0, s) != hipSuccess)
-    return OVGGT_ERR_HIP;
+  const bool prof_attn = c->prof_level >= 1 && (c->prof_calls++ % c->prof_every) == 0;
+  const bool prof_all = c->prof_level >= 2;
+  {
+    ProfScope ps(c, OVGGT_PROF_APPEND, s, prof_all);
+    if (launch_append(g, c->kv, c->meta, l0, nl, k_new, v_new, n, (uint32_t)gid0, s) != hipSuccess)
+      return OVGGT_ERR_HIP;
+  }
   hipError_t e;
-  if (g.esize == 2)
-    e = launch_attn_bf16(g, c->kv, l0, nl, q, out, n + g.M, c->scale, c->ws, c->n_wgs, s);
-  else
+  if (g.esize == 2) {
+    hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
+    bool have = false;
+    if (prof_attn) {
+      for (auto& x : ev) x = prof_event(c);
+      have = ev[0] && ev[1] && ev[2];
+    }
+    e = launch_attn_bf16(g, c->kv, l0, nl, q, out, n + g.M, c->scale, c->ws, c->n_wgs, s, have ? ev : nullptr);
+    if (have) {
+      c->prof_pending[OVGGT_PROF_ATTN].push_back({ev[0], ev[1]});
+      c->prof_pending[OVGGT_PROF_COMBINE].push_back({ev[1], ev[2]});   // shares ev[1] as its start
+    }
+  } else {
+    ProfScope ps(c, OVGGT_PROF_ATTN, s, prof_attn);
     e = launch_attn_f32(g, c->kv, l0, nl, q, out, n + g.M, c->scale, s);
+  }
   if (e != hipSuccess) return OVGGT_ERR_HIP;
   for (int l = l0; l < l0 + nl; ++l) { c->n[l] = n + g.M; c->phase[l] = 1; }
   return OVGGT_OK;
@@ -161,8 +221,11 @@ int ovggt_score_select(ovggt_cache* c, int layer, const void* resid, const uint8
   if (!layer_range(c, layer, &l0, &nl)) return OVGGT_ERR_ARG;
   if (!aligned16(resid)) return OVGGT_ERR_ARG;
   if (!uniform(c, l0, nl, 1)) return OVGGT_ERR_STATE;
-  if (launch_score_select(c->g, c->meta, l0, nl, resid, anchor_flags, c->n[l0], (hipStream_t)hip_stream) != hipSuccess)
-    return OVGGT_ERR_HIP;
+  {
+    ProfScope ps(c, OVGGT_PROF_SELECT, (hipStream_t)hip_stream, c->prof_level >= 2);
+    if (launch_score_select(c->g, c->meta, l0, nl, resid, anchor_flags, c->n[l0], (hipStream_t)hip_stream) != hipSuccess)
+      return OVGGT_ERR_HIP;
+  }
   for (int l = l0; l < l0 + nl; ++l) c->phase[l] = 2;
   return OVGGT_OK;
 }
@@ -174,6 +237,7 @@ int ovggt_cache_compact(ovggt_cache* c, int layer, void* hip_stream) {
   if (!uniform(c, l0, nl, 2)) return OVGGT_ERR_STATE;
   const Geom& g = c->g;
   if (c->n[l0] > g.B) {
+    ProfScope ps(c, OVGGT_PROF_COMPACT, (hipStream_t)hip_stream, c->prof_level >= 2);
     if (launch_compact(g, c->kv, c->meta, l0, nl, (hipStream_t)hip_stream) != hipSuccess) return OVGGT_ERR_HIP;
   }
   for (int l = l0; l < l0 + nl; ++l) {
@@ -186,6 +250,8 @@ int ovggt_cache_compact(ovggt_cache* c, int layer, void* hip_stream) {
 
 int ovggt_cache_destroy(ovggt_cache* c) {
   if (!c) return OVGGT_ERR_ARG;
+  prof_recycle(c);
+  for (hipEvent_t e : c->prof_free) (void)hipEventDestroy(e);
   delete c;
   return OVGGT_OK;
 }
@@ -283,6 +349,29 @@ int ovggt_cache_last_moves(ovggt_cache* c, int layer, uint32_t* dst, uint32_t* s
   if (dst && nm && hipMemcpy(dst, mb + g.off_mvdst, (size_t)4 * nm, hipMemcpyDeviceToHost) != hipSuccess) return OVGGT_ERR_HIP;
   if (src && nm && hipMemcpy(src, mb + g.off_mvsrc, (size_t)4 * nm, hipMemcpyDeviceToHost) != hipSuccess) return OVGGT_ERR_HIP;
   *n_moves = (int32_t)nm;
+  return OVGGT_OK;
+}
+
+int ovggt_profile_enable(ovggt_cache* c, int level, int every) {
+  if (!c || level < 0 || level > 2 || every < 1) return OVGGT_ERR_ARG;
+  c->prof_level = level;
+  c->prof_every = every;
+  c->prof_calls = 0;
+  return OVGGT_OK;
+}
+
+int ovggt_profile_read(ovggt_cache* c, double* ms_sum, int64_t* count, void* hip_stream) {
+  if (!c || !ms_sum || !count) return OVGGT_ERR_ARG;
+  if (hipStreamSynchronize((hipStream_t)hip_stream) != hipSuccess) return OVGGT_ERR_HIP;
+  for (int k = 0; k < OVGGT_PROF_CLASSES; ++k) {
+    ms_sum[k] = 0.0; count[k] = 0;
+    for (auto& pr : c->prof_pending[k]) {
+      float ms = 0.f;
+      if (hipEventElapsedTime(&ms, pr.first, pr.second) != hipSuccess) return OVGGT_ERR_HIP;
+      ms_sum[k] += ms; count[k] += 1;
+    }
+  }
+  prof_recycle(c);
   return OVGGT_OK;
 }
 

@@ -53,8 +53,11 @@ hipError_t launch_append(const Geom& g, char* kv, char* meta, int layer0, int nl
 // Attention of M queries over n_total resident slots.
 hipError_t launch_attn_f32(const Geom& g, char* kv, int layer0, int nl, const void* q, void* out,
                            int n_total, float scale, hipStream_t s);
+// `ev` (optional, 3 events) are recorded before the main kernel, between it and
+// the combine kernel, and after the combine kernel.
 hipError_t launch_attn_bf16(const Geom& g, char* kv, int layer0, int nl, const void* q, void* out,
-                            int n_total, float scale, char* ws, int n_wgs, hipStream_t s);
+                            int n_total, float scale, char* ws, int n_wgs, hipStream_t s,
+                            hipEvent_t* ev = nullptr);
 size_t attn_ws_bytes();
 
 // Eq. 5 + anchor flags for the M slots [n_total-M, n_total), then (when

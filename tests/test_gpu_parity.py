@@ -92,9 +92,9 @@ def test_bf16_ragged_small():
     print("ragged worst attention err/RMS:", worst)
 
 
-@pytest.mark.parametrize("M,B,H,C", [(1, 64, 1, 64), (37, 37, 2, 1024), (130, 1000, 5, 4096), (128, 256, 16, 8)])
+@pytest.mark.parametrize("M,B,H,C", [(1, 64, 1, 64), (37, 74, 2, 1024), (130, 1000, 5, 4096), (128, 256, 16, 8)])
 def test_bf16_odd_shapes(M, B, H, C):
-    cfg = synth.preset(1, M=M, H=H, C=C, B=B, T=max(6, 2 * B // M + 3) if M > 1 else 70, n_special=min(M, 2))
+    cfg = synth.preset(1, M=M, H=H, C=C, B=B, T=max(6, 2 * B // M + 3) if M > 1 else 70, n_special=min(M - 1, 2))
     run_stream(cfg)
 
 
@@ -155,7 +155,7 @@ def test_worst_case_compaction_rising_scores():
         orc.step(f["q"], f["k"], f["v"], r, f["a"], attend=False)
         dst, src = cache.last_moves(0)
         if t >= 5:
-            assert len(dst) == cfg.M - cfg.n_special * 0 or len(dst) > 0
+            assert len(dst) == cfg.M              # every new token survives: M entries move per frame
         compare_cache(cache, orc)
     cache.close()
 
