@@ -70,6 +70,9 @@ typedef struct {
   int32_t dtype;             /* OVGGT_F32 or OVGGT_BF16: Q/K/V/O/residual and cache storage */
   int32_t score_mode;        /* 0 = every entry keeps the Eq. 5 score it entered with      */
   float   softmax_scale;     /* 0 => 1/sqrt(head_dim)                                      */
+  int32_t out_dtype;         /* type of the attention output O: OVGGT_F32, or OVGGT_BF16
+                                (bf16 handles only).  bf16 handles accumulate O in fp32
+                                either way; OVGGT_BF16 rounds it once (RNE) on store     */
 } ovggt_config;
 
 /* Sizes (bytes) of the three caller-allocated device buffers for `cfg`:
@@ -88,8 +91,8 @@ int ovggt_cache_init(ovggt_cache** out, const ovggt_config* cfg,
 /* Eq. 2 + Sec. 3.1's temporal causal attention.  Appends (k_new, v_new) as slots
  * [n, n+M) with token ids t*M+i, then out = softmax(q K^T * scale) V over all
  * n+M resident slots (frame-level causality: the frame sees itself entirely).
- * q, k_new, v_new: device, read-only, [M, N_h, d]; out: device, written,
- * [M, N_h, d].  bf16 runs use bf16 MFMA with fp32 accumulation and fp32 online
+ * q, k_new, v_new: device, read-only, [M, N_h, d] in the handle's dtype; out:
+ * device, written, [M, N_h, d] in the handle's out_dtype.  bf16 runs use bf16 MFMA with fp32 accumulation and fp32 online
  * softmax; f32 runs compute in fp32.  ERR_STATE unless the layer expects a new
  * frame. */
 int ovggt_global_attn(ovggt_cache* c, int layer, const void* q, const void* k_new, const void* v_new,

@@ -30,7 +30,8 @@ PROF_CLASSES = ("append", "attn", "combine", "score_select", "compact")
 class ovggt_config(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("n_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("tokens_per_frame", C.c_int32), ("resid_dim", C.c_int32), ("budget", C.c_int32),
-                ("dtype", C.c_int32), ("score_mode", C.c_int32), ("softmax_scale", C.c_float)]
+                ("dtype", C.c_int32), ("score_mode", C.c_int32), ("softmax_scale", C.c_float),
+                ("out_dtype", C.c_int32)]
 
 
 class OvggtError(RuntimeError):
@@ -98,10 +99,10 @@ def _ptr(t) -> int:
 
 
 def make_config(n_layers, n_heads, head_dim, tokens_per_frame, resid_dim, budget, dtype,
-                score_mode=0, softmax_scale=0.0) -> ovggt_config:
-    code = {"f32": OVGGT_F32, "bf16": OVGGT_BF16}.get(dtype, dtype)
-    return ovggt_config(n_layers, n_heads, head_dim, tokens_per_frame, resid_dim, budget, code,
-                        score_mode, softmax_scale)
+                score_mode=0, softmax_scale=0.0, out_dtype="f32") -> ovggt_config:
+    codes = {"f32": OVGGT_F32, "bf16": OVGGT_BF16}
+    return ovggt_config(n_layers, n_heads, head_dim, tokens_per_frame, resid_dim, budget,
+                        codes.get(dtype, dtype), score_mode, softmax_scale, codes.get(out_dtype, out_dtype))
 
 
 # ---- the C entry points, one wrapper each -----------------------------------
@@ -195,12 +196,13 @@ class Cache:
     Holds no logic of its own beyond marshalling."""
 
     def __init__(self, n_layers, n_heads, head_dim, tokens_per_frame, resid_dim, budget, dtype,
-                 softmax_scale=0.0, device="cuda:0"):
+                 softmax_scale=0.0, device="cuda:0", out_dtype="f32"):
         import torch
         self.torch = torch
         self.cfg = make_config(n_layers, n_heads, head_dim, tokens_per_frame, resid_dim, budget, dtype,
-                               0, softmax_scale)
+                               0, softmax_scale, out_dtype)
         self.dtype = dtype
+        self.out_dtype = out_dtype
         self.L, self.H, self.d, self.M, self.Cdim, self.B = n_layers, n_heads, head_dim, tokens_per_frame, resid_dim, budget
         kvb, mb, wsb = ovggt_cache_query_bytes(self.cfg)
         self.bytes = (kvb, mb, wsb)
@@ -227,6 +229,12 @@ class Cache:
         self.global_attn(q, k_new, v_new, out, layer)
         self.score_select(resid, anchor_flags, layer)
         self.compact(layer)
+
+    def new_output(self):
+        """Output tensor [L, M, H, d] of the handle's out_dtype."""
+        t = self.torch
+        return t.empty((self.L, self.M, self.H, self.d), device=self.device,
+                       dtype=t.float32 if self.out_dtype == "f32" else t.bfloat16)
 
     def size(self, layer=0) -> int:
         return ovggt_cache_size(self.h, layer)

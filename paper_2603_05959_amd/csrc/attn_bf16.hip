@@ -59,6 +59,7 @@ struct AttnParams {
   int chunk;                  // units per workgroup
   int total_units;
   float c;                    // softmax scale * log2(e)
+  int out_f32;                // output element type: 1 = fp32, 0 = bf16
 };
 
 // Lanes l and l+32 hold the two slot groups of the same query.  The swap
@@ -301,15 +302,22 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
           const int qrow = q0 + qhalf * 64 + qb * 32 + l32;
           if (qrow < p.M) {
             const float inv = 1.0f / lfin[qb];
-            char* op = p.out + ((((size_t)li * p.M + qrow) * p.H + h) * 64) * 2;
+            const size_t oel = (((size_t)li * p.M + qrow) * p.H + h) * 64;
 #pragma unroll
             for (int db = 0; db < 2; ++db)
 #pragma unroll
               for (int ig = 0; ig < 4; ++ig) {
-                bf16x4 w;
+                const int dcol = db * 32 + ig * 8 + 4 * g;
+                if (p.out_f32) {
+                  float4 w = {O[db][qb][ig * 4] * inv, O[db][qb][ig * 4 + 1] * inv,
+                              O[db][qb][ig * 4 + 2] * inv, O[db][qb][ig * 4 + 3] * inv};
+                  *(float4*)(p.out + (oel + dcol) * 4) = w;
+                } else {
+                  bf16x4 w;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) w[j] = (__bf16)(O[db][qb][ig * 4 + j] * inv);
-                *(bf16x4*)(op + (db * 32 + ig * 8 + 4 * g) * 2) = w;
+                  for (int j = 0; j < 4; ++j) w[j] = (__bf16)(O[db][qb][ig * 4 + j] * inv);
+                  *(bf16x4*)(p.out + (oel + dcol) * 2) = w;
+                }
               }
           }
         }
@@ -370,19 +378,27 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(AttnParams p) {
     }
   }
   const float inv = 1.0f / l;
-  char* op = p.out + ((((size_t)li * p.M + qrow) * p.H + h) * 64 + half * 32) * 2;
+  const size_t oel = (((size_t)li * p.M + qrow) * p.H + h) * 64 + half * 32;
+  if (p.out_f32) {
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    bf16x8 w;
+    for (int j = 0; j < 8; ++j) {
+      float4 w = {acc[4 * j] * inv, acc[4 * j + 1] * inv, acc[4 * j + 2] * inv, acc[4 * j + 3] * inv};
+      *(float4*)(p.out + (oel + 4 * j) * 4) = w;
+    }
+  } else {
 #pragma unroll
-    for (int e = 0; e < 8; ++e) w[e] = (__bf16)(acc[8 * j + e] * inv);
-    *(bf16x8*)(op + j * 16) = w;
+    for (int j = 0; j < 4; ++j) {
+      bf16x8 w;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) w[e] = (__bf16)(acc[8 * j + e] * inv);
+      *(bf16x8*)(p.out + (oel + 8 * j) * 2) = w;
+    }
   }
 }
 
 hipError_t launch_attn_bf16(const Geom& g, char* kv, int layer0, int nl, const void* q, void* out,
-                            int n_total, float scale, char* ws, int n_wgs, hipStream_t s,
-                            hipEvent_t* ev) {
+                            int n_total, float scale, char* ws, int n_wgs, bool out_f32,
+                            hipStream_t s, hipEvent_t* ev) {
   AttnParams p;
   p.q = (const char*)q;
   p.out = (char*)out;
@@ -401,6 +417,7 @@ hipError_t launch_attn_bf16(const Geom& g, char* kv, int layer0, int nl, const v
   if (n_wgs < 8) n_wgs = 8;
   p.chunk = (int)((total + n_wgs - 1) / n_wgs);
   p.c = scale * 1.4426950408889634f;
+  p.out_f32 = out_f32 ? 1 : 0;
   if (ev && hipEventRecord(ev[0], s) != hipSuccess) return hipErrorUnknown;
   hipLaunchKernelGGL(attn_bf16_kernel, dim3((unsigned)n_wgs), dim3(256), 0, s, p);
   hipError_t e = hipGetLastError();

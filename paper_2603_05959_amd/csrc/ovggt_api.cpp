@@ -45,6 +45,8 @@ bool valid_config(const ovggt_config* c) {
   if ((int64_t)c->budget + c->tokens_per_frame > 128 * 1024) return false;   // selection handles <= 2^17 slots
   if (c->dtype != OVGGT_F32 && c->dtype != OVGGT_BF16) return false;
   if (c->score_mode != 0) return false;
+  if (c->out_dtype != OVGGT_F32 && c->out_dtype != OVGGT_BF16) return false;
+  if (c->dtype == OVGGT_F32 && c->out_dtype != OVGGT_F32) return false;
   if (!(c->softmax_scale >= 0.f) || !std::isfinite(c->softmax_scale)) return false;
   return true;
 }
@@ -200,7 +202,8 @@ int ovggt_global_attn(ovggt_cache* c, int layer, const void* q, const void* k_ne
       for (auto& x : ev) x = prof_event(c);
       have = ev[0] && ev[1] && ev[2];
     }
-    e = launch_attn_bf16(g, c->kv, l0, nl, q, out, n + g.M, c->scale, c->ws, c->n_wgs, s, have ? ev : nullptr);
+    e = launch_attn_bf16(g, c->kv, l0, nl, q, out, n + g.M, c->scale, c->ws, c->n_wgs,
+                         c->cfg.out_dtype == OVGGT_F32, s, have ? ev : nullptr);
     if (have) {
       c->prof_pending[OVGGT_PROF_ATTN].push_back({ev[0], ev[1]});
       c->prof_pending[OVGGT_PROF_COMBINE].push_back({ev[1], ev[2]});   // shares ev[1] as its start

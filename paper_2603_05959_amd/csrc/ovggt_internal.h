@@ -56,8 +56,8 @@ hipError_t launch_attn_f32(const Geom& g, char* kv, int layer0, int nl, const vo
 // `ev` (optional, 3 events) are recorded before the main kernel, between it and
 // the combine kernel, and after the combine kernel.
 hipError_t launch_attn_bf16(const Geom& g, char* kv, int layer0, int nl, const void* q, void* out,
-                            int n_total, float scale, char* ws, int n_wgs, hipStream_t s,
-                            hipEvent_t* ev = nullptr);
+                            int n_total, float scale, char* ws, int n_wgs, bool out_f32,
+                            hipStream_t s, hipEvent_t* ev = nullptr);
 size_t attn_ws_bytes();
 
 // Eq. 5 + anchor flags for the M slots [n_total-M, n_total), then (when

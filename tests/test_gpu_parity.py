@@ -46,8 +46,7 @@ def run_stream(cfg, layer=0, attn_frames=None, cache_every=1, resid_fn=None, q_r
     torch = _torch()
     cache = make_cache(cfg, L=1)
     orc = oc.OracleCache(cfg.M, cfg.H, cfg.d, cfg.B)
-    odt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
-    out = torch.empty((cfg.M, cfg.H, cfg.d), dtype=odt, device="cuda:0")
+    out = cache.new_output()[0]
     worst = 0.0
     for t in range(cfg.T):
         f = synth.frame_inputs(cfg, layer, t)
@@ -116,7 +115,7 @@ def test_cfg4_shape_budget_sweep_and_full_cache_equality():
     cfg = synth.preset(4, B=8 * 1041, T=8)
     torch = _torch()
     cache = make_cache(cfg, L=1)
-    out = torch.empty((cfg.M, cfg.H, cfg.d), dtype=torch.bfloat16, device="cuda:0")
+    out = cache.new_output()[0]
     ks, vs = [], []
     for t in range(cfg.T):
         f = synth.frame_inputs(cfg, 0, t)
@@ -146,7 +145,7 @@ def test_worst_case_compaction_rising_scores():
     torch = _torch()
     cache = make_cache(cfg, L=1)
     orc = oc.OracleCache(cfg.M, cfg.H, cfg.d, cfg.B)
-    out = torch.empty((cfg.M, cfg.H, cfg.d), dtype=torch.bfloat16, device="cuda:0")
+    out = cache.new_output()[0]
     for t in range(cfg.T):
         f = synth.frame_inputs(cfg, 0, t, want=("q", "k", "v", "a"))
         r = synth.rising_resid(cfg, 0, t)
@@ -165,7 +164,7 @@ def test_batched_layers_match_per_layer_oracle():
     torch = _torch()
     cache = make_cache(cfg)
     orcs = [oc.OracleCache(cfg.M, cfg.H, cfg.d, cfg.B) for _ in range(cfg.L)]
-    out = torch.empty((cfg.L, cfg.M, cfg.H, cfg.d), dtype=torch.bfloat16, device="cuda:0")
+    out = cache.new_output()
     for t in range(cfg.T):
         fs = [synth.frame_inputs(cfg, l, t) for l in range(cfg.L)]
         stack = lambda key: dev(np.stack([f[key] for f in fs]), cfg)
@@ -184,7 +183,7 @@ def test_per_layer_calls_are_independent():
     torch = _torch()
     cache = make_cache(cfg)
     orcs = [oc.OracleCache(cfg.M, cfg.H, cfg.d, cfg.B) for _ in range(2)]
-    out = torch.empty((cfg.M, cfg.H, cfg.d), dtype=torch.bfloat16, device="cuda:0")
+    out = cache.new_output()[0]
     for t in range(cfg.T):                        # layer 1 runs one frame behind layer 0
         for l, tt in ((0, t), (1, t - 1)):
             if tt < 0:
@@ -207,7 +206,7 @@ def test_call_order_and_argument_errors():
     cache = make_cache(cfg)
     f = synth.frame_inputs(cfg, 0, 0)
     q, k, v, r = (dev(f[x], cfg) for x in "qkvr")
-    out = torch.empty_like(q)
+    out = cache.new_output()[0]
     for call in (lambda: cache.score_select(r, None, 0), lambda: cache.compact(0)):
         with pytest.raises(B.OvggtError) as e:
             call()
@@ -237,7 +236,7 @@ def test_protected_set_larger_than_budget_sets_status():
     cfg = synth.preset(0, B=100, T=3)
     torch = _torch()
     cache = make_cache(cfg)
-    out = torch.empty((cfg.M, cfg.H, cfg.d), dtype=torch.float32, device="cuda:0")
+    out = cache.new_output()[0]
     ones = torch.ones(cfg.M, dtype=torch.uint8, device="cuda:0")
     for t in range(2):                               # 130 protected tokens, budget 100
         f = synth.frame_inputs(cfg, 0, t)
@@ -268,7 +267,7 @@ def test_import_export_and_crafted_scores():
     torch = _torch()
     f = synth.frame_inputs(cfg, 0, 10)
     f["r"][2] = f["r"][5]                                      # an exact tie among the new tokens
-    out = torch.empty((cfg.M, cfg.H, cfg.d), dtype=torch.float32, device="cuda:0")
+    out = cache.new_output()[0]
     cache.step(dev(f["q"], cfg), dev(f["k"], cfg), dev(f["v"], cfg), dev(f["r"], cfg),
                torch.from_numpy(f["a"]).cuda(), out, layer=0)
     ref = orc.step(f["q"], f["k"], f["v"], f["r"], f["a"])
@@ -278,3 +277,20 @@ def test_import_export_and_crafted_scores():
     assert np.array_equal(np.isnan(e["ss"]), np.isnan(orc.ss))
     assert cache.status(0) & B.OVGGT_STATUS_NONFINITE
     cache.close()
+
+
+def test_bf16_output_is_the_rounded_fp32_output():
+    """out_dtype = bf16 stores RNE(bf16) of exactly the value the fp32-output run stores."""
+    cfg = synth.preset(1, M=200, H=3, C=64, B=500, T=5, n_special=3)
+    torch = _torch()
+    c32 = make_cache(cfg, L=1)
+    c16 = B.Cache(1, cfg.H, cfg.d, cfg.M, cfg.C, cfg.B, cfg.dtype, out_dtype="bf16")
+    o32, o16 = c32.new_output()[0], c16.new_output()[0]
+    assert o16.dtype == torch.bfloat16
+    for t in range(cfg.T):
+        f = synth.frame_inputs(cfg, 0, t)
+        args = [dev(f[x], cfg) for x in "qkvr"] + [torch.from_numpy(f["a"]).cuda()]
+        c32.step(*args, o32, layer=0)
+        c16.step(*args, o16, layer=0)
+        assert torch.equal(o32.to(torch.bfloat16), o16), t
+    c32.close(); c16.close()

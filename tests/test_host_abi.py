@@ -38,10 +38,11 @@ def test_query_bytes_and_config_validation():
     kv24, meta24, _ = B.ovggt_cache_query_bytes(B.make_config(24, 16, 64, 1374, 1024, 16384, "bf16"))
     assert kv24 == 24 * kv and meta24 == 24 * meta
     bad = [dict(head_dim=128), dict(budget=100), dict(n_layers=0), dict(resid_dim=0), dict(resid_dim=5000),
-           dict(dtype=7), dict(score_mode=1), dict(softmax_scale=-1.0), dict(budget=131072)]
+           dict(dtype=7), dict(score_mode=1), dict(softmax_scale=-1.0), dict(budget=131072), dict(out_dtype=3),
+           dict(dtype="f32", out_dtype="bf16")]
     for kw in bad:
         args = dict(n_layers=1, n_heads=16, head_dim=64, tokens_per_frame=1374, resid_dim=1024, budget=16384,
-                    dtype="bf16", score_mode=0, softmax_scale=0.0)
+                    dtype="bf16", score_mode=0, softmax_scale=0.0, out_dtype="f32")
         args.update(kw)
         with pytest.raises(B.OvggtError) as e:
             B.ovggt_cache_query_bytes(B.make_config(**args))
