@@ -74,11 +74,10 @@ __device__ inline float pair_sum(float x) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-__device__ inline bf16x8 pack8(const f32x16& s, int base) {
-  bf16x8 r;
-#pragma unroll
-  for (int j = 0; j < 8; ++j) r[j] = (__bf16)s[base + j];
-  return r;
+__device__ inline bf16x8 join4(const bf16x2* p) {
+  const __attribute__((ext_vector_type(4))) __bf16 a = __builtin_shufflevector(p[0], p[1], 0, 1, 2, 3);
+  const __attribute__((ext_vector_type(4))) __bf16 b = __builtin_shufflevector(p[2], p[3], 0, 1, 2, 3);
+  return __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
 __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
@@ -109,6 +108,9 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
     for (int db = 0; db < 2; ++db)
       voff[db] = (khalf * 64 + x) * 128 + ((((c0 ^ x) ^ (db << 2))) << 4) + inb;
   }
+  bf16x2 ones2;
+  ones2[0] = (__bf16)1.0f;
+  ones2[1] = (__bf16)1.0f;
   // direct-to-LDS load addressing: wave-instruction j covers LDS rows (wave*4+j)*8 .. +8
   const int ld_row = lane >> 3;
   const int ld_piece = ((lane & 7) ^ ld_row) << 4;
@@ -207,6 +209,7 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
       }
 
       // ---- online softmax; lane owns one query per qb
+      bf16x2 P[2][2][8];
 #pragma unroll
       for (int qb = 0; qb < 2; ++qb) {
         float mx = S[0][qb][0];
@@ -227,16 +230,23 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
             for (int i = 0; i < 16; ++i) O[db][qb][i] *= alpha;
         }
         const float mc = mrun[qb] * p.c;
-        float ls = 0.f;
+        // p = exp2(s*c - m*c), rounded to bf16 in pairs; the row sum is taken over the
+        // ROUNDED values (dot product with ones), so numerator and denominator of the
+        // softmax see the same weights and a dominant key's rounding error cancels
+        float ls[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(S[sb][qb][i], p.c, -mc));
-            S[sb][qb][i] = e;
-            ls += e;
+          for (int j = 0; j < 8; ++j) {
+            const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[sb][qb][2 * j], p.c, -mc));
+            const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[sb][qb][2 * j + 1], p.c, -mc));
+            bf16x2 pk;
+            pk[0] = (__bf16)e0;
+            pk[1] = (__bf16)e1;
+            ls[j & 3] = __builtin_amdgcn_fdot2_f32_bf16(pk, ones2, ls[j & 3], false);
+            P[sb][qb][j] = pk;
           }
-        lrun[qb] += ls;
+        lrun[qb] += (ls[0] + ls[1]) + (ls[2] + ls[3]);
       }
 
       // ---- O^T += V^T P^T
@@ -244,8 +254,8 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
       for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2) {
-          const bf16x8 pb0 = pack8(S[sb][0], 8 * s2);
-          const bf16x8 pb1 = pack8(S[sb][1], 8 * s2);
+          const bf16x8 pb0 = join4(P[sb][0] + 4 * s2);
+          const bf16x8 pb1 = join4(P[sb][1] + 4 * s2);
 #pragma unroll
           for (int db = 0; db < 2; ++db) {
             const int o = voff[db] + (sb * 32 + 16 * s2) * 128;
