@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_PKG, "libovggt.so")
 OVGGT_F32, OVGGT_BF16 = 0, 1
 OVGGT_ALL_LAYERS = -1
 OVGGT_OK, OVGGT_ERR_ARG, OVGGT_ERR_STATE, OVGGT_ERR_BUDGET, OVGGT_ERR_HIP = 0, -1, -2, -3, -4
-OVGGT_STATUS_BUDGET, OVGGT_STATUS_NONFINITE = 1, 2
+OVGGT_STATUS_BUDGET, OVGGT_STATUS_NONFINITE, OVGGT_STATUS_VRANGE = 1, 2, 4
 
 EXPORTS = (
     "ovggt_cache_query_bytes", "ovggt_cache_init", "ovggt_global_attn", "ovggt_score_select",

@@ -3,8 +3,22 @@
 // bound by HBM bandwidth; every lane moves 16-byte pieces of 128-byte-or-longer
 // contiguous rows.
 #include "ovggt_internal.h"
+#include "../../include/ovggt.h"
+#include <hip/hip_fp16.h>
 
 namespace ovggt {
+
+// bf16 handles keep V as IEEE binary16: the P*V product then runs on the f16
+// MFMA with 11-bit softmax weights instead of 8-bit ones.  Values beyond the
+// half range saturate (and are reported), values below 2^-14 round to the half
+// subnormal grid.
+__device__ inline uint32_t bf16pair_to_half(uint32_t w, bool* clipped) {
+  float a = __uint_as_float(w << 16), b = __uint_as_float(w & 0xFFFF0000u);
+  if (!(fabsf(a) <= 65504.f)) { *clipped = true; a = a != a ? a : copysignf(65504.f, a); }
+  if (!(fabsf(b) <= 65504.f)) { *clipped = true; b = b != b ? b : copysignf(65504.f, b); }
+  const __half2 h = __floats2half2_rn(a, b);
+  return *(const uint32_t*)&h;
+}
 
 // --------------------------------------------------------------------------
 __global__ void __launch_bounds__(256) fill_zero_kernel(uint4* p, size_t n16) {
@@ -42,9 +56,16 @@ append_kernel(Geom g, char* kv, char* meta, int layer0, const char* k_new, const
   const size_t src = (size_t)blockIdx.y * per_layer_in + ((size_t)m * g.H + h) * row_bytes + piece * 16;
   const size_t dst = ((size_t)h * g.cap + (n + m)) * row_bytes + piece * 16;
   *(uint4*)(layer_k(kv, g, layer) + dst) = *(const uint4*)(k_new + src);
-  *(uint4*)(layer_v(kv, g, layer) + dst) = *(const uint4*)(v_new + src);
+  uint4 vv = *(const uint4*)(v_new + src);
+  char* mb = layer_meta(meta, g, layer);
+  if (g.esize == 2) {
+    bool clipped = false;
+    vv.x = bf16pair_to_half(vv.x, &clipped); vv.y = bf16pair_to_half(vv.y, &clipped);
+    vv.z = bf16pair_to_half(vv.z, &clipped); vv.w = bf16pair_to_half(vv.w, &clipped);
+    if (clipped) atomicOr(&((Ctrl*)(mb + g.off_ctrl))->status, (uint32_t)OVGGT_STATUS_VRANGE);
+  }
+  *(uint4*)(layer_v(kv, g, layer) + dst) = vv;
   if (h == 0 && piece == 0) {
-    char* mb = layer_meta(meta, g, layer);
     ((uint32_t*)(mb + g.off_ids))[n + m] = gid0 + (uint32_t)m;
     ((float*)(mb + g.off_ss))[n + m] = 0.f;
     ((uint8_t*)(mb + g.off_flags))[n + m] = 0;

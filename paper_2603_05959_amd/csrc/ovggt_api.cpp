@@ -32,6 +32,42 @@ struct ovggt_cache {
 
 namespace {
 
+// ---- host conversions between the bf16 interface and the half V storage ----
+inline float bf16_bits_to_float(uint16_t b) { uint32_t u = (uint32_t)b << 16; float f; std::memcpy(&f, &u, 4); return f; }
+inline uint16_t float_to_bf16_bits(float f) {
+  uint32_t u; std::memcpy(&u, &f, 4);
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40);   // NaN stays NaN
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+inline float half_bits_to_float(uint16_t h) {
+  const uint32_t sign = (uint32_t)(h & 0x8000u) << 16, exp = (h >> 10) & 31u, man = h & 1023u;
+  float f;
+  if (exp == 0) f = std::ldexp((float)man, -24);
+  else if (exp == 31) f = man ? NAN : INFINITY;
+  else f = std::ldexp((float)(man | 1024u), (int)exp - 25);
+  uint32_t u; std::memcpy(&u, &f, 4); u |= sign; std::memcpy(&f, &u, 4);
+  return f;
+}
+// round-to-nearest-even float -> half, saturating at +-65504 like the append kernel
+inline uint16_t float_to_half_bits_sat(float f) {
+  if (f != f) return 0x7E00;
+  uint16_t sign = std::signbit(f) ? 0x8000 : 0;
+  float a = std::fabs(f);
+  if (a > 65504.f) a = 65504.f;
+  if (a < 5.9604645e-8f * 0.5f) return sign;                       // below half the smallest subnormal
+  int e; (void)std::frexp(a, &e);                                   // a = m * 2^e, m in [0.5, 1)
+  int shift = e - 1 < -14 ? -24 : e - 11;                           // exponent of one ulp
+  const float q = std::ldexp(a, -shift);                            // in ulps
+  float r = std::nearbyint(q);                                      // default rounding mode: nearest even
+  float v = std::ldexp(r, shift);
+  if (v >= 65520.f) v = 65504.f;
+  if (v < 6.1035156e-5f) return (uint16_t)(sign | (uint16_t)std::lround(std::ldexp(v, 24)));
+  int e2; const float m2 = std::frexp(v, &e2);                      // v = m2 * 2^e2
+  const uint32_t man = (uint32_t)std::lround(std::ldexp(m2, 11)) - 1024u;
+  return (uint16_t)(sign | (uint16_t)((e2 - 1 + 15) << 10) | (uint16_t)man);
+}
+
 inline size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 bool valid_config(const ovggt_config* c) {
@@ -303,6 +339,10 @@ int ovggt_cache_export(ovggt_cache* c, int layer, uint32_t* ids, void* k, void* 
     for (int h = 0; h < g.H; ++h) {
       if (hipMemcpy(tmp.data(), src + (size_t)h * g.cap * row, (size_t)n * row, hipMemcpyDeviceToHost) != hipSuccess)
         return OVGGT_ERR_HIP;
+      if (which == 1 && g.esize == 2) {        // V is stored as half: hand it back as bf16
+        uint16_t* t16 = (uint16_t*)tmp.data();
+        for (size_t j = 0; j < (size_t)n * g.d; ++j) t16[j] = float_to_bf16_bits(half_bits_to_float(t16[j]));
+      }
       for (int i = 0; i < n; ++i) std::memcpy(dst + ((size_t)i * g.H + h) * row, tmp.data() + (size_t)i * row, row);
     }
   }
@@ -330,6 +370,10 @@ int ovggt_cache_import(ovggt_cache* c, int layer, int32_t n, int64_t frames, con
       char* dst = which ? layer_v(c->kv, g, layer) : layer_k(c->kv, g, layer);
       for (int h = 0; h < g.H; ++h) {
         for (int i = 0; i < n; ++i) std::memcpy(tmp.data() + (size_t)i * row, src + ((size_t)i * g.H + h) * row, row);
+        if (which == 1 && g.esize == 2) {      // bf16 in, half stored
+          uint16_t* t16 = (uint16_t*)tmp.data();
+          for (size_t j = 0; j < (size_t)n * g.d; ++j) t16[j] = float_to_half_bits_sat(bf16_bits_to_float(t16[j]));
+        }
         if (hipMemcpy(dst + (size_t)h * g.cap * row, tmp.data(), (size_t)n * row, hipMemcpyHostToDevice) != hipSuccess)
           return OVGGT_ERR_HIP;
       }
