@@ -12,8 +12,10 @@
 // counter; nobody waits): if more than B entries are resident, find the E =
 // n - B lowest-ranked evictable entries under the total order (ss ascending,
 // token id descending) by an 8-bit-digit radix select on the 64-bit key
-// (ss bits << 32) | ~id, with a per-lane-column LDS histogram (no bank or
-// address conflicts), then emit the move list in ascending slot order.
+// (ss bits, ~id) held in registers, with a per-lane-column LDS histogram (no
+// bank or address conflicts); passes stop as soon as a whole bucket is evicted,
+// and the id half is only consulted when equal scores straddle the threshold.
+// Then emit the move list in ascending slot order.
 #include "ovggt_internal.h"
 #include "../../include/ovggt.h"
 
@@ -104,13 +106,18 @@ struct SelShared {
   uint32_t cnt[256];
   uint32_t wave_tot[2][kMaxSelChunks * kSelWaves + 64];
   uint32_t scan_tmp[2][kSelWaves];
+  uint32_t totals[2];
   uint32_t digit, rank, bucket, is_last, n_evictable, bad;
 };
 
-__device__ inline uint64_t make_key(float ss, uint32_t id, bool* bad) {
+constexpr uint32_t kNotEvictable = 0xFFFFFFFFu;   // score word of protected / absent slots (no real score maps to it)
+
+// Score word of a slot: the fp32 bit pattern of ss (order-preserving for ss >= 0);
+// NaN or negative values rank lowest (0) and are reported.
+__device__ inline uint32_t score_word(float ss, bool* bad) {
   uint32_t b = __float_as_uint(ss);
-  if (ss != ss || (b & 0x80000000u)) { b = 0u; *bad = true; }      // NaN / negative: lowest rank
-  return ((uint64_t)b << 32) | (uint64_t)(0xFFFFFFFFu - id);
+  if (ss != ss || (b & 0x80000000u)) { b = 0u; *bad = true; }
+  return b;
 }
 
 // exclusive scan of `n` counters laid out consecutively (n <= 2 * kSelThreads); in place
@@ -136,7 +143,196 @@ __device__ inline void block_exclusive_scan(uint32_t* a, int n, uint32_t* wave_t
   __syncthreads();
 }
 
-template <bool BF16>
+// One radix pass over the candidates: histogram of an 8-bit digit, then the
+// digit whose bucket holds the rank-th smallest candidate.  Results in sh.digit
+// / sh.rank / sh.bucket (and sh.n_evictable = number of candidates).
+template <int KPT, typename DigitOf>
+__device__ inline void radix_pass(SelShared& sh, int n_iter, uint32_t rank, DigitOf digit_of) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  for (int i = tid; i < 128 * 64; i += kSelThreads) (&sh.hist[0][0])[i] = 0u;
+  __syncthreads();
+  if constexpr (KPT > 0) {
+#pragma unroll
+    for (int c = 0; c < KPT; ++c) {
+      const int dg = digit_of(c);                     // < 0: not a candidate
+      if (dg >= 0) atomicAdd(&sh.hist[dg >> 1][lane], 1u << (16 * (dg & 1)));
+    }
+  } else {
+    // streaming: digits of 8 chunks are fetched together so their loads overlap
+    for (int c0 = 0; c0 < n_iter; c0 += 8) {
+      int dg[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) dg[j] = c0 + j < n_iter ? digit_of(c0 + j) : -1;
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        if (dg[j] >= 0) atomicAdd(&sh.hist[dg[j] >> 1][lane], 1u << (16 * (dg[j] & 1)));
+    }
+  }
+  __syncthreads();
+  {   // column sums: thread -> (bin, quarter of the 64 columns)
+    const int bin = tid >> 2, quarter = tid & 3;
+    uint32_t s = 0;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      const int col = quarter * 16 + ((j + (lane >> 2)) & 15);   // 64 distinct columns per wave read
+      s += (sh.hist[bin >> 1][col] >> (16 * (bin & 1))) & 0xFFFFu;
+    }
+    s += __shfl_xor(s, 1, 64);
+    s += __shfl_xor(s, 2, 64);
+    if (quarter == 0) sh.cnt[bin] = s;
+  }
+  __syncthreads();
+  if (wave == 0) {
+    uint32_t c4[4];
+    uint32_t s = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) { c4[j] = sh.cnt[4 * lane + j]; s += c4[j]; }
+    uint32_t inc = s;
+#pragma unroll
+    for (int off = 1; off < 64; off *= 2) {
+      const uint32_t y = __shfl_up(inc, off, 64);
+      if (lane >= off) inc += y;
+    }
+    uint32_t before = inc - s;
+    if (lane == 63) sh.n_evictable = inc;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (before < rank && rank <= before + c4[j]) {
+        sh.digit = 4 * lane + j; sh.rank = rank - before; sh.bucket = c4[j];
+      }
+      before += c4[j];
+    }
+  }
+  __syncthreads();
+}
+
+// Selection by one workgroup.  KPT > 0: the score words (and, if IDREG, the
+// inverted ids) of up to KPT*1024 slots live in registers, so the radix passes
+// touch LDS only.  KPT == 0: every pass re-reads them from memory (any size).
+template <int KPT, bool IDREG>
+__device__ inline void select_phase(SelShared& sh, const Geom& g, const float* ss, const uint32_t* ids,
+                                    const uint8_t* flags, Ctrl* ctrl, uint32_t* mvdst, uint32_t* mvsrc,
+                                    int n_total) {
+  constexpr int NREG = KPT > 0 ? KPT : 1;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n_chunks = (n_total + kSelThreads - 1) / kSelThreads;
+  const int n_iter = KPT > 0 ? KPT : n_chunks;
+  const uint32_t n_evict = (uint32_t)(n_total - g.B);
+  bool bad = false;
+  uint32_t kw[NREG], kid[(KPT > 0 && IDREG) ? KPT : 1];
+  auto load_word = [&](int c) -> uint32_t {          // branch-free so that loads of several chunks overlap
+    const int i = c * kSelThreads + tid;
+    const int ic = i < n_total ? i : n_total - 1;
+    const uint8_t f = flags[ic];
+    const uint32_t w = score_word(ss[ic], &bad);
+    return (i >= n_total || f != 0) ? kNotEvictable : w;
+  };
+  auto load_id = [&](int c) -> uint32_t {
+    const int i = c * kSelThreads + tid;
+    return 0xFFFFFFFFu - ids[i < n_total ? i : n_total - 1];
+  };
+  if constexpr (KPT > 0) {
+#pragma unroll
+    for (int c = 0; c < KPT; ++c) {
+      kw[c] = c < n_chunks ? load_word(c) : kNotEvictable;
+      if constexpr (IDREG) kid[c] = c < n_chunks ? load_id(c) : 0u;
+    }
+  }
+  auto word = [&](int c) -> uint32_t { if constexpr (KPT > 0) return kw[c]; else return load_word(c); };
+  auto idw = [&](int c) -> uint32_t { if constexpr (KPT > 0 && IDREG) return kid[c]; else return load_id(c); };
+  if (tid == 0) sh.bad = 0;
+
+  // radix select of the n_evict-th smallest (score word, inverted id) pair
+  uint32_t pre_hi = 0, pre_lo = 0, rank = n_evict;
+  int pass = 0;
+  bool budget_error = false, done = false;
+  for (; pass < 4 && !done; ++pass) {
+    const int shift = 24 - 8 * pass;
+    radix_pass<KPT>(sh, n_iter, rank, [&](int c) -> int {
+      const uint32_t w = word(c);
+      if (w == kNotEvictable) return -1;
+      if (pass > 0 && (w >> (shift + 8)) != (pre_hi >> (shift + 8))) return -1;
+      return (int)((w >> shift) & 255u);
+    });
+    if (pass == 0 && sh.n_evictable < n_evict) { budget_error = true; break; }   // |P| > B
+    pre_hi |= sh.digit << shift;
+    rank = sh.rank;
+    done = (rank == sh.bucket);          // the whole bucket goes
+    __syncthreads();
+  }
+  int lo_shift = 32;                      // 32: ids did not have to be consulted
+  if (!done && !budget_error) {
+    for (int p2 = 0; p2 < 4 && !done; ++p2) {
+      const int shift = 24 - 8 * p2;
+      radix_pass<KPT>(sh, n_iter, rank, [&](int c) -> int {
+        if (word(c) != pre_hi) return -1;
+        const uint32_t w = idw(c);
+        if (p2 > 0 && (w >> (shift + 8)) != (pre_lo >> (shift + 8))) return -1;
+        return (int)((w >> shift) & 255u);
+      });
+      pre_lo |= sh.digit << shift;
+      rank = sh.rank;
+      done = (rank == sh.bucket);
+      lo_shift = shift;
+      __syncthreads();
+    }
+  }
+  const int hi_shift = pass > 0 ? 24 - 8 * (pass - 1) : 24;
+  if (bad) sh.bad = 1;
+
+  // evict bit per slot (one bit per chunk, in registers)
+  uint64_t ev0 = 0, ev1 = 0;
+  if (!budget_error) {
+#pragma unroll
+    for (int c = 0; c < n_iter; ++c) {
+      const uint32_t w = word(c);
+      bool ev = false;
+      if (w != kNotEvictable) {
+        if (lo_shift == 32) ev = (w >> hi_shift) <= (pre_hi >> hi_shift);
+        else ev = w < pre_hi || (w == pre_hi && (idw(c) >> lo_shift) <= (pre_lo >> lo_shift));
+      }
+      if (ev) { if (c < 64) ev0 |= 1ull << c; else ev1 |= 1ull << (c - 64); }
+    }
+  }
+  // holes (evicted slot below B) and movers (kept slot at or above B), in slot order
+  for (int c = 0; c < n_chunks; ++c) {
+    const int i = c * kSelThreads + tid;
+    const bool ev = c < 64 ? (ev0 >> c) & 1 : (ev1 >> (c - 64)) & 1;
+    const bool hole = !budget_error && i < g.B && ev;
+    const bool mover = !budget_error && i >= g.B && i < n_total && !ev;
+    const uint64_t hb = __ballot(hole), mvb = __ballot(mover);
+    if (lane == 0) {
+      sh.wave_tot[0][c * kSelWaves + wave] = __popcll(hb);
+      sh.wave_tot[1][c * kSelWaves + wave] = __popcll(mvb);
+    }
+  }
+  __syncthreads();
+  block_exclusive_scan(sh.wave_tot[0], n_chunks * kSelWaves, sh.scan_tmp[0], &sh.totals[0]);
+  block_exclusive_scan(sh.wave_tot[1], n_chunks * kSelWaves, sh.scan_tmp[1], &sh.totals[1]);
+  const uint64_t lt = (1ull << lane) - 1ull;
+  const bool consistent = sh.totals[0] == sh.totals[1] && sh.totals[0] <= (uint32_t)g.M;
+  for (int c = 0; c < n_chunks; ++c) {
+    const int i = c * kSelThreads + tid;
+    const bool ev = c < 64 ? (ev0 >> c) & 1 : (ev1 >> (c - 64)) & 1;
+    const bool hole = !budget_error && i < g.B && ev;
+    const bool mover = !budget_error && i >= g.B && i < n_total && !ev;
+    const uint64_t hb = __ballot(hole), mvb = __ballot(mover);
+    if (consistent) {
+      if (hole) mvdst[sh.wave_tot[0][c * kSelWaves + wave] + __popcll(hb & lt)] = (uint32_t)i;
+      if (mover) mvsrc[sh.wave_tot[1][c * kSelWaves + wave] + __popcll(mvb & lt)] = (uint32_t)i;
+    }
+  }
+  __syncthreads();
+  if (tid == 0) {
+    ctrl->n_moves = consistent ? sh.totals[0] : 0u;
+    uint32_t st = 0;
+    if (budget_error || !consistent) st |= OVGGT_STATUS_BUDGET;
+    if (sh.bad) st |= OVGGT_STATUS_NONFINITE;
+    if (st) atomicOr(&ctrl->status, st);
+  }
+}
+
+template <bool BF16, int KPT, bool IDREG>
 __global__ void __launch_bounds__(kSelThreads)
 score_select_kernel(Geom g, char* meta, int layer0, const char* resid, const uint8_t* anchors,
                     int n_total, int e_per_lane) {
@@ -163,8 +359,7 @@ score_select_kernel(Geom g, char* meta, int layer0, const char* resid, const uin
       }
     }
   }
-  const bool do_select = n_total > g.B;
-  if (!do_select) {
+  if (n_total <= g.B) {                      // under budget: nothing to select
     if (blockIdx.x == 0 && tid == 0) ctrl->n_moves = 0;
     return;
   }
@@ -177,128 +372,28 @@ score_select_kernel(Geom g, char* meta, int layer0, const char* resid, const uin
   __syncthreads();
   if (!sh.is_last) return;
   __threadfence();
+  if (tid == 0) ctrl->arrive = 0;
 
   // ---- phase 2: this workgroup saw every other one arrive
-  const int n_chunks = (n_total + kSelThreads - 1) / kSelThreads;
-  const uint32_t n_evict = (uint32_t)(n_total - g.B);
-  if (tid == 0) { ctrl->arrive = 0; sh.bad = 0; }
-  bool bad = false;
-  uint64_t prefix = 0;
-  uint32_t rank = n_evict;          // 1-based rank, in ascending key order, of the last entry to evict
-  int shift = 56;
-  bool budget_error = false;
-  for (int pass = 0; pass < 8; ++pass, shift -= 8) {
-    for (int i = tid; i < 128 * 64; i += kSelThreads) (&sh.hist[0][0])[i] = 0u;
-    __syncthreads();
-    for (int c = 0; c < n_chunks; ++c) {
-      const int i = c * kSelThreads + tid;
-      if (i < n_total && flags[i] == 0) {
-        const uint64_t key = make_key(ss[i], ids[i], &bad);
-        if (pass == 0 || (key >> (shift + 8)) == (prefix >> (shift + 8))) {
-          const uint32_t dg = (uint32_t)(key >> shift) & 255u;
-          atomicAdd(&sh.hist[dg >> 1][lane], 1u << (16 * (dg & 1u)));
-        }
-      }
-    }
-    __syncthreads();
-    {   // column sums: thread -> (bin, quarter of the 64 columns)
-      const int bin = tid >> 2, quarter = tid & 3;
-      uint32_t s = 0;
-#pragma unroll
-      for (int j = 0; j < 16; ++j) {
-        const int col = quarter * 16 + ((j + (lane >> 2)) & 15);   // 64 distinct columns per wave read
-        s += (sh.hist[bin >> 1][col] >> (16 * (bin & 1))) & 0xFFFFu;
-      }
-      s += __shfl_xor(s, 1, 64);
-      s += __shfl_xor(s, 2, 64);
-      if (quarter == 0) sh.cnt[bin] = s;
-    }
-    __syncthreads();
-    if (wave == 0) {     // find the digit whose bucket contains the rank-th smallest key
-      uint32_t c4[4];
-      uint32_t s = 0;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) { c4[j] = sh.cnt[4 * lane + j]; s += c4[j]; }
-      uint32_t inc = s;
-#pragma unroll
-      for (int off = 1; off < 64; off *= 2) {
-        const uint32_t y = __shfl_up(inc, off, 64);
-        if (lane >= off) inc += y;
-      }
-      uint32_t before = inc - s;
-      if (pass == 0 && lane == 63) sh.n_evictable = inc;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        if (before < rank && rank <= before + c4[j]) {
-          sh.digit = 4 * lane + j; sh.rank = rank - before; sh.bucket = c4[j];
-        }
-        before += c4[j];
-      }
-    }
-    __syncthreads();
-    if (pass == 0 && sh.n_evictable < n_evict) { budget_error = true; break; }   // |P| > B
-    prefix |= (uint64_t)sh.digit << shift;
-    rank = sh.rank;
-    const uint32_t bucket = sh.bucket;
-    __syncthreads();
-    if (rank == bucket) break;       // the whole bucket goes: no need to split it further
-  }
-  if (shift < 0) shift = 0;
-  if (bad) sh.bad = 1;
-
-  // ---- evict bits per slot, held as one bit per chunk in registers
-  uint64_t ev0 = 0, ev1 = 0;
-  if (!budget_error) {
-    for (int c = 0; c < n_chunks; ++c) {
-      const int i = c * kSelThreads + tid;
-      bool ev = false;
-      if (i < n_total && flags[i] == 0) {
-        bool b2 = false;
-        const uint64_t key = make_key(ss[i], ids[i], &b2);
-        ev = (key >> shift) <= (prefix >> shift);
-      }
-      if (ev) { if (c < 64) ev0 |= 1ull << c; else ev1 |= 1ull << (c - 64); }
-    }
-  }
-  // per-(chunk, wave) counts of holes (evicted slot below B) and movers (kept slot at or above B)
-  for (int c = 0; c < n_chunks; ++c) {
-    const int i = c * kSelThreads + tid;
-    const bool ev = c < 64 ? (ev0 >> c) & 1 : (ev1 >> (c - 64)) & 1;
-    const bool hole = !budget_error && i < g.B && ev;
-    const bool mover = !budget_error && i >= g.B && i < n_total && !ev;
-    const uint64_t hb = __ballot(hole), mvb = __ballot(mover);
-    if (lane == 0) {
-      sh.wave_tot[0][c * kSelWaves + wave] = __popcll(hb);
-      sh.wave_tot[1][c * kSelWaves + wave] = __popcll(mvb);
-    }
-  }
-  __syncthreads();
-  __shared__ uint32_t totals[2];
-  block_exclusive_scan(sh.wave_tot[0], n_chunks * kSelWaves, sh.scan_tmp[0], &totals[0]);
-  block_exclusive_scan(sh.wave_tot[1], n_chunks * kSelWaves, sh.scan_tmp[1], &totals[1]);
   uint32_t* mvdst = (uint32_t*)(mb + g.off_mvdst);
   uint32_t* mvsrc = (uint32_t*)(mb + g.off_mvsrc);
-  const uint64_t lt = (1ull << lane) - 1ull;
-  const bool consistent = totals[0] == totals[1] && totals[0] <= (uint32_t)g.M;
-  for (int c = 0; c < n_chunks; ++c) {
-    const int i = c * kSelThreads + tid;
-    const bool ev = c < 64 ? (ev0 >> c) & 1 : (ev1 >> (c - 64)) & 1;
-    const bool hole = !budget_error && i < g.B && ev;
-    const bool mover = !budget_error && i >= g.B && i < n_total && !ev;
-    const uint64_t hb = __ballot(hole), mvb = __ballot(mover);
-    if (consistent) {
-      if (hole) mvdst[sh.wave_tot[0][c * kSelWaves + wave] + __popcll(hb & lt)] = (uint32_t)i;
-      if (mover) mvsrc[sh.wave_tot[1][c * kSelWaves + wave] + __popcll(mvb & lt)] = (uint32_t)i;
-    }
-  }
-  __syncthreads();
-  if (tid == 0) {
-    ctrl->n_moves = consistent ? totals[0] : 0u;
-    uint32_t st = 0;
-    if (budget_error || !consistent) st |= OVGGT_STATUS_BUDGET;
-    if (sh.bad) st |= OVGGT_STATUS_NONFINITE;
-    if (st) atomicOr(&ctrl->status, st);
-  }
+  select_phase<KPT, IDREG>(sh, g, ss, ids, flags, ctrl, mvdst, mvsrc, n_total);
+}
+
+template <bool BF16>
+static void launch_variant(const Geom& g, char* meta, int layer0, int nl, const void* resid,
+                           const uint8_t* anchors, int n_total, int e, hipStream_t s) {
+  dim3 grid((unsigned)((g.M + kSelWaves - 1) / kSelWaves), (unsigned)nl);
+  const int n_chunks = (n_total + kSelThreads - 1) / kSelThreads;
+#define OVGGT_SEL_LAUNCH(KPT, IDREG)                                                                  \
+  hipLaunchKernelGGL((score_select_kernel<BF16, KPT, IDREG>), grid, dim3(kSelThreads), 0, s, g, meta, \
+                     layer0, (const char*)resid, anchors, n_total, e)
+  // the variant only matters when a selection will run (n_total > B)
+  if (n_total <= g.B || n_chunks <= 8) OVGGT_SEL_LAUNCH(8, true);
+  else if (n_chunks <= 20) OVGGT_SEL_LAUNCH(20, true);
+  else if (n_chunks <= 36) OVGGT_SEL_LAUNCH(36, true);
+  else OVGGT_SEL_LAUNCH(0, false);
+#undef OVGGT_SEL_LAUNCH
 }
 
 hipError_t launch_score_select(const Geom& g, char* meta, int layer0, int nl, const void* resid,
@@ -306,13 +401,8 @@ hipError_t launch_score_select(const Geom& g, char* meta, int layer0, int nl, co
   int cp = 1;
   while (cp < g.C) cp *= 2;
   const int e = cp >= 64 ? cp / 64 : 1;
-  dim3 grid((unsigned)((g.M + kSelWaves - 1) / kSelWaves), (unsigned)nl);
-  if (g.esize == 2)
-    hipLaunchKernelGGL(score_select_kernel<true>, grid, dim3(kSelThreads), 0, s, g, meta, layer0,
-                       (const char*)resid, anchors, n_total, e);
-  else
-    hipLaunchKernelGGL(score_select_kernel<false>, grid, dim3(kSelThreads), 0, s, g, meta, layer0,
-                       (const char*)resid, anchors, n_total, e);
+  if (g.esize == 2) launch_variant<true>(g, meta, layer0, nl, resid, anchors, n_total, e, s);
+  else launch_variant<false>(g, meta, layer0, nl, resid, anchors, n_total, e, s);
   return hipGetLastError();
 }
 
