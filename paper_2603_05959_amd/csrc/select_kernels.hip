@@ -147,10 +147,11 @@ __device__ inline void block_exclusive_scan(uint32_t* a, int n, uint32_t* wave_t
 // digit whose bucket holds the rank-th smallest candidate.  Results in sh.digit
 // / sh.rank / sh.bucket (and sh.n_evictable = number of candidates).
 template <int KPT, typename DigitOf>
-__device__ inline void radix_pass(SelShared& sh, int n_iter, uint32_t rank, DigitOf digit_of) {
+__device__ inline void radix_pass(SelShared& sh, int n_iter, uint32_t rank, DigitOf digit_of, uint32_t* ts = nullptr) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   for (int i = tid; i < 128 * 64; i += kSelThreads) (&sh.hist[0][0])[i] = 0u;
   __syncthreads();
+  if (ts && tid == 0) ts[0] = (uint32_t)wall_clock64();
   if constexpr (KPT > 0) {
 #pragma unroll
     for (int c = 0; c < KPT; ++c) {
@@ -169,6 +170,7 @@ __device__ inline void radix_pass(SelShared& sh, int n_iter, uint32_t rank, Digi
     }
   }
   __syncthreads();
+  if (ts && tid == 0) ts[1] = (uint32_t)wall_clock64();
   {   // column sums: thread -> (bin, quarter of the 64 columns)
     const int bin = tid >> 2, quarter = tid & 3;
     uint32_t s = 0;
@@ -182,6 +184,7 @@ __device__ inline void radix_pass(SelShared& sh, int n_iter, uint32_t rank, Digi
     if (quarter == 0) sh.cnt[bin] = s;
   }
   __syncthreads();
+  if (ts && tid == 0) ts[2] = (uint32_t)wall_clock64();
   if (wave == 0) {
     uint32_t c4[4];
     uint32_t s = 0;
@@ -232,20 +235,36 @@ __device__ inline void select_phase(SelShared& sh, const Geom& g, const float* s
     return 0xFFFFFFFFu - ids[i < n_total ? i : n_total - 1];
   };
   if constexpr (KPT > 0) {
+    // every load is unconditional (indices are clamped), so all of them are in flight together
+    uint8_t fl[KPT];
+    float sv[KPT];
 #pragma unroll
     for (int c = 0; c < KPT; ++c) {
-      kw[c] = c < n_chunks ? load_word(c) : kNotEvictable;
-      if constexpr (IDREG) kid[c] = c < n_chunks ? load_id(c) : 0u;
+      const int i = c * kSelThreads + tid;
+      const int ic = i < n_total ? i : n_total - 1;
+      fl[c] = flags[ic];
+      sv[c] = ss[ic];
+      if constexpr (IDREG) kid[c] = ids[ic];
+    }
+#pragma unroll
+    for (int c = 0; c < KPT; ++c) {
+      const int i = c * kSelThreads + tid;
+      const uint32_t w = score_word(sv[c], &bad);
+      kw[c] = (i >= n_total || fl[c] != 0) ? kNotEvictable : w;
+      if constexpr (IDREG) kid[c] = 0xFFFFFFFFu - kid[c];
     }
   }
   auto word = [&](int c) -> uint32_t { if constexpr (KPT > 0) return kw[c]; else return load_word(c); };
   auto idw = [&](int c) -> uint32_t { if constexpr (KPT > 0 && IDREG) return kid[c]; else return load_id(c); };
   if (tid == 0) sh.bad = 0;
+#define TSTAMP(k) do { if (tid == 0) ctrl->pad[k] = (uint32_t)wall_clock64(); } while (0)
+  TSTAMP(1);
 
   // radix select of the n_evict-th smallest (score word, inverted id) pair
   uint32_t pre_hi = 0, pre_lo = 0, rank = n_evict;
   int pass = 0;
   bool budget_error = false, done = false;
+#pragma nounroll
   for (; pass < 4 && !done; ++pass) {
     const int shift = 24 - 8 * pass;
     radix_pass<KPT>(sh, n_iter, rank, [&](int c) -> int {
@@ -253,15 +272,17 @@ __device__ inline void select_phase(SelShared& sh, const Geom& g, const float* s
       if (w == kNotEvictable) return -1;
       if (pass > 0 && (w >> (shift + 8)) != (pre_hi >> (shift + 8))) return -1;
       return (int)((w >> shift) & 255u);
-    });
+    }, pass == 0 ? &ctrl->pad[20] : nullptr);
     if (pass == 0 && sh.n_evictable < n_evict) { budget_error = true; break; }   // |P| > B
     pre_hi |= sh.digit << shift;
     rank = sh.rank;
     done = (rank == sh.bucket);          // the whole bucket goes
     __syncthreads();
+    TSTAMP(2 + pass);
   }
   int lo_shift = 32;                      // 32: ids did not have to be consulted
   if (!done && !budget_error) {
+#pragma nounroll
     for (int p2 = 0; p2 < 4 && !done; ++p2) {
       const int shift = 24 - 8 * p2;
       radix_pass<KPT>(sh, n_iter, rank, [&](int c) -> int {
@@ -279,6 +300,7 @@ __device__ inline void select_phase(SelShared& sh, const Geom& g, const float* s
   }
   const int hi_shift = pass > 0 ? 24 - 8 * (pass - 1) : 24;
   if (bad) sh.bad = 1;
+  TSTAMP(10);
 
   // evict bit per slot (one bit per chunk, in registers)
   uint64_t ev0 = 0, ev1 = 0;
@@ -307,6 +329,7 @@ __device__ inline void select_phase(SelShared& sh, const Geom& g, const float* s
     }
   }
   __syncthreads();
+  TSTAMP(11);
   block_exclusive_scan(sh.wave_tot[0], n_chunks * kSelWaves, sh.scan_tmp[0], &sh.totals[0]);
   block_exclusive_scan(sh.wave_tot[1], n_chunks * kSelWaves, sh.scan_tmp[1], &sh.totals[1]);
   const uint64_t lt = (1ull << lane) - 1ull;
@@ -329,6 +352,8 @@ __device__ inline void select_phase(SelShared& sh, const Geom& g, const float* s
     if (budget_error || !consistent) st |= OVGGT_STATUS_BUDGET;
     if (sh.bad) st |= OVGGT_STATUS_NONFINITE;
     if (st) atomicOr(&ctrl->status, st);
+    ctrl->pad[12] = (uint32_t)wall_clock64();
+    ctrl->pad[13] = (uint32_t)pass;
   }
 }
 
@@ -347,6 +372,7 @@ score_select_kernel(Geom g, char* meta, int layer0, const char* resid, const uin
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n_old = n_total - g.M;
 
+  if (blockIdx.x == 0 && tid == 0) ctrl->pad[15] = (uint32_t)wall_clock64();
   // ---- phase 1: scores and flags of the M new slots
   {
     const size_t row_bytes = (size_t)g.C * g.esize;
@@ -363,16 +389,21 @@ score_select_kernel(Geom g, char* meta, int layer0, const char* resid, const uin
     if (blockIdx.x == 0 && tid == 0) ctrl->n_moves = 0;
     return;
   }
-  __threadfence();
+  // Publish this workgroup's scores and count its arrival.  Every wave first
+  // waits for its own stores to reach L2; one thread then performs the
+  // device-scope release / acquire (they act on the whole cache, not on one
+  // wave's data), so the cache maintenance runs once per workgroup.
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   if (tid == 0) {
+    __threadfence();
     const uint32_t prev = atomicAdd(&ctrl->arrive, 1u);
-    sh.is_last = (prev == gridDim.x - 1) ? 1u : 0u;
+    const bool last = prev == gridDim.x - 1;
+    if (last) { __threadfence(); ctrl->arrive = 0; ctrl->pad[0] = (uint32_t)wall_clock64(); }
+    sh.is_last = last ? 1u : 0u;
   }
   __syncthreads();
   if (!sh.is_last) return;
-  __threadfence();
-  if (tid == 0) ctrl->arrive = 0;
 
   // ---- phase 2: this workgroup saw every other one arrive
   uint32_t* mvdst = (uint32_t*)(mb + g.off_mvdst);
