@@ -74,6 +74,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-frames", type=int, default=3)
     ap.add_argument("--detail-steps", type=int, default=40, help="extra untimed steps with per-kernel events")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy (reference dispatch for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (no collectives, no sharding); run with --gpus 1",
@@ -114,6 +116,14 @@ def main():
             del host
     torch.cuda.synchronize()
     gen_s = time.perf_counter() - t_gen
+
+    if args.calibrate_copy:                              # known traffic: reads 256 MiB, writes 256 MiB
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     cache = B.Cache(L, cfg.H, cfg.d, cfg.M, cfg.C, cfg.B, cfg.dtype)
     out = cache.new_output()                             # fp32 outputs (fp32 accumulators stored unrounded)

@@ -11,7 +11,7 @@ from dataclasses import dataclass
 import numpy as np
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libovggt.so")
+LIB_PATH = os.environ.get("OVGGT_LIB") or os.path.join(_PKG, "libovggt.so")   # OVGGT_LIB: alternate build
 
 OVGGT_F32, OVGGT_BF16 = 0, 1
 OVGGT_ALL_LAYERS = -1

@@ -48,10 +48,29 @@ typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
 #define GLB_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
 
+// XOR swizzle of the 16-byte piece index within a 128-byte LDS row, as a function of the row.
+#ifndef OVGGT_SWZ
+#define OVGGT_SWZ 0
+#endif
+__device__ __forceinline__ int swz(int row) {
+#if OVGGT_SWZ == 0
+  return row & 7;
+#elif OVGGT_SWZ == 1
+  return (row >> 1) & 7;
+#else
+  const int t = (row >> 1) & 7;
+  return ((t & 1) << 2) | (t & 2) | ((t >> 2) & 1);
+#endif
+}
+
+#ifndef OVGGT_ABLATE
+#define OVGGT_ABLATE 0          // timing experiments only: bit 0 no exp, 1 no softmax, 2 no PV, 3 no QK, 4 no loads, 5 no barrier
+#endif
+
 constexpr int kTileBytes = kSlotTile * 128;            // one K (or V) tile: 128 slots x 64 bf16
 constexpr int kPartialFloats = kQueryTile * 64 + 2 * kQueryTile;
-constexpr float kRescaleThreshold = 8.0f;              // log2 units
-constexpr float kWeightBias = 7.0f;                    // weights are stored as 2^7 * p <= 2^15 (half max 65504)
+constexpr float kWeightBias = 7.0f;                    // weights are stored as 2^7 * p (half max 65504)
+constexpr float kWeightSumLimit = 32768.0f;            // a lane's weight sum below 2^15 proves no weight overflowed
 
 size_t attn_ws_bytes() { return (size_t)kMaxAttnWgs * 2 * kPartialFloats * sizeof(float); }
 
@@ -89,6 +108,162 @@ __device__ inline f16x8 join4(const f16x2* p) {
   return __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
+// One 64-slot x 64-query tile of one wave: S^T = K Q^T, online softmax, O^T += V^T P^T.
+// tail: the tile extends past n_total (only the last tile can); weights of the
+// absent slots are cleared after the softmax (their rows hold zeros or stale but
+// finite keys, so their scores are finite and merely move the reference maximum).
+//
+// Softmax fast path: weights are formed against the running reference maximum
+// m without looking for this tile's maximum; p = 2^7 * exp2((s - m) * c) is
+// rounded to half and summed.  If the lane's sum stays below 2^15 no weight can
+// have overflowed half.  Otherwise (first tile, or the maximum grew by about 2^8)
+// the wave takes the slow path: true tile maximum, rescale O and l, redo the
+// weights.  The reference maximum therefore lags the true one by < 2^8, which
+// costs no accuracy in fp32/half arithmetic.
+__device__ __forceinline__ void process_tile(const char* ldsK, const int (&koff)[4], const int (&voff)[2][2],
+                                             const bf16x8 (&qf)[2][4], f32x16 (&O)[2][2], float (&mrun)[2],
+                                             float (&lrun)[2], float c, int sbase, int n_total, bool tail) {
+  const char* ldsV = ldsK + kTileBytes;
+  f16x2 ones2;
+  ones2[0] = (_Float16)1.0f;
+  ones2[1] = (_Float16)1.0f;
+  f32x16 S[2][2];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) S[a][b][i] = 0.f;
+#if OVGGT_ABLATE & 8
+  for (int a = 0; a < 2; ++a) for (int b = 0; b < 2; ++b) for (int i = 0; i < 16; ++i) S[a][b][i] = mrun[b] + i * 0.01f + (float)qf[a][b][0];
+#else
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) {
+    const bf16x8 k0 = *LDS_PTR(const bf16x8, ldsK + koff[ks]);
+    const bf16x8 k1 = *LDS_PTR(const bf16x8, ldsK + koff[ks] + 32 * 128);
+    S[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0, qf[0][ks], S[0][0], 0, 0, 0);
+    S[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0, qf[1][ks], S[0][1], 0, 0, 0);
+    S[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1, qf[0][ks], S[1][0], 0, 0, 0);
+    S[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1, qf[1][ks], S[1][1], 0, 0, 0);
+  }
+#endif
+  f16x2 P[2][2][8];
+#pragma unroll
+  for (int qb = 0; qb < 2; ++qb) {
+    float lsum;
+    {
+      const float mcb = mrun[qb] * c - kWeightBias;
+      float ls[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+#if OVGGT_ABLATE & 2
+          const float e0 = S[sb][qb][2 * j], e1 = S[sb][qb][2 * j + 1];
+          if (j > 0) { P[sb][qb][j] = P[sb][qb][0]; continue; }
+#elif OVGGT_ABLATE & 1
+          const float e0 = __builtin_fmaf(S[sb][qb][2 * j], c, -mcb);
+          const float e1 = __builtin_fmaf(S[sb][qb][2 * j + 1], c, -mcb);
+#else
+          const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[sb][qb][2 * j], c, -mcb));
+          const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[sb][qb][2 * j + 1], c, -mcb));
+#endif
+          f16x2 pk;
+          pk[0] = (_Float16)e0;
+          pk[1] = (_Float16)e1;
+          ls[j & 3] = __builtin_amdgcn_fdot2(pk, ones2, ls[j & 3], false);
+          P[sb][qb][j] = pk;
+        }
+      lsum = (ls[0] + ls[1]) + (ls[2] + ls[3]);
+    }
+#if OVGGT_ABLATE & 3
+    if (false) {
+#else
+    if (__builtin_amdgcn_ballot_w64(!(lsum <= kWeightSumLimit)) != 0ull) {
+#endif
+      // rare: recompute this query block's scores (cheaper than keeping them live past the fast path)
+      f32x16 R[2];
+#pragma unroll
+      for (int sb = 0; sb < 2; ++sb) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) R[sb][i] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+          R[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*LDS_PTR(const bf16x8, ldsK + koff[ks] + sb * 32 * 128),
+                                                          qf[qb][ks], R[sb], 0, 0, 0);
+      }
+      float mx = R[0][0];
+#pragma unroll
+      for (int i = 1; i < 16; ++i) mx = fmaxf(mx, R[0][i]);
+#pragma unroll
+      for (int i = 0; i < 16; ++i) mx = fmaxf(mx, R[1][i]);
+      mx = pair_max(mx);
+      const float mnew = fmaxf(mrun[qb], mx);
+      const float alpha = __builtin_amdgcn_exp2f((mrun[qb] - mnew) * c);
+      mrun[qb] = mnew;
+      lrun[qb] *= alpha;
+#pragma unroll
+      for (int db = 0; db < 2; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) O[db][qb][i] *= alpha;
+      const float mcb = mnew * c - kWeightBias;
+      float ls[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(R[sb][2 * j], c, -mcb));
+          const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(R[sb][2 * j + 1], c, -mcb));
+          f16x2 pk;
+          pk[0] = (_Float16)e0;
+          pk[1] = (_Float16)e1;
+          ls[j & 3] = __builtin_amdgcn_fdot2(pk, ones2, ls[j & 3], false);
+          P[sb][qb][j] = pk;
+        }
+      lsum = (ls[0] + ls[1]) + (ls[2] + ls[3]);
+    }
+    if (tail) {
+      asm volatile("; tail tile: clear absent slots" ::: "memory");   // keeps this block a real branch (never if-converted)
+      float ls = 0.f;
+#pragma unroll
+      for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const int slot = sbase + sb * 32 + (j >> 1) * 8 + (j & 1) * 2;      // slots of accumulators 2j, 2j+1
+          uint32_t w = __builtin_bit_cast(uint32_t, P[sb][qb][j]);
+          w &= (slot < n_total ? 0x0000FFFFu : 0u) | (slot + 1 < n_total ? 0xFFFF0000u : 0u);
+          P[sb][qb][j] = __builtin_bit_cast(f16x2, w);
+          ls = __builtin_amdgcn_fdot2(P[sb][qb][j], ones2, ls, false);
+        }
+      lsum = ls;
+    }
+    lrun[qb] += lsum;
+  }
+
+  // O^T += V^T P^T; each V^T fragment feeds both query blocks
+#pragma unroll
+  for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2) {
+      const f16x8 pb0 = join4(P[sb][0] + 4 * s2);
+      const f16x8 pb1 = join4(P[sb][1] + 4 * s2);
+#pragma unroll
+      for (int db = 0; db < 2; ++db) {
+        const int o = (sb * 32 + 16 * s2) * 128;
+        const s16x4 va = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, ldsV + voff[db][0] + o));
+        const s16x4 vb = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, ldsV + voff[db][1] + o));
+        const __attribute__((ext_vector_type(8))) short v8 = __builtin_shufflevector(va, vb, 0, 1, 2, 3, 4, 5, 6, 7);
+        const f16x8 vf = __builtin_bit_cast(f16x8, v8);
+#if OVGGT_ABLATE & 4
+        O[db][0][0] += (float)vf[0] * (float)pb0[0]; O[db][1][1] += (float)vf[1] * (float)pb1[1];
+#else
+        O[db][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pb0, O[db][0], 0, 0, 0);
+        O[db][1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pb1, O[db][1], 0, 0, 0);
+#endif
+      }
+    }
+}
+
 __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
   __shared__ __attribute__((aligned(1024))) char lds[4 * kTileBytes];     // [buf][K|V]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -106,23 +281,22 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
   int koff[4];
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks)
-    koff[ks] = (khalf * 64 + l32) * 128 + ((((2 * ks + g) ^ (l32 & 7))) << 4);
-  int voff[2];
+    koff[ks] = (khalf * 64 + l32) * 128 + ((((2 * ks + g) ^ swz(l32))) << 4);
+  int voff[2][2];                                        // [db][second group of four slots]
   {
     const int i = lane & 15;
-    const int x = 4 * g + (i >> 2);
+    const int x = 4 * g + (i >> 2);                    // row within an 8-row group (row offsets added later are multiples of 8)
     const int c0 = 2 * ((lane >> 4) & 1) + ((i & 3) >> 1);
     const int inb = (i & 1) * 8;
 #pragma unroll
     for (int db = 0; db < 2; ++db)
-      voff[db] = (khalf * 64 + x) * 128 + ((((c0 ^ x) ^ (db << 2))) << 4) + inb;
+#pragma unroll
+      for (int hh = 0; hh < 2; ++hh)
+        voff[db][hh] = (khalf * 64 + 8 * hh + x) * 128 + ((((c0 + 4 * db) ^ swz(8 * hh + x))) << 4) + inb;
   }
-  f16x2 ones2;
-  ones2[0] = (_Float16)1.0f;
-  ones2[1] = (_Float16)1.0f;
   // direct-to-LDS load addressing: wave-instruction j covers LDS rows (wave*4+j)*8 .. +8
   const int ld_row = lane >> 3;
-  const int ld_piece = ((lane & 7) ^ ld_row) << 4;
+  const int ld_piece[2] = {((lane & 7) ^ swz(ld_row)) << 4, ((lane & 7) ^ swz(8 + ld_row)) << 4};
 
   while (u < u_end) {
     const int item = u / p.T;
@@ -164,7 +338,7 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const int r8 = (wave * 4 + j) * 8;
-        const size_t goff = (trow + r8 + ld_row) * 128 + ld_piece;
+        const size_t goff = (trow + r8 + ld_row) * 128 + ld_piece[j & 1];
         __builtin_amdgcn_global_load_lds(GLB_PTR(kbase + goff), LDS_PTR(void, lds + r8 * 128), 16, 0, 0);
         __builtin_amdgcn_global_load_lds(GLB_PTR(vbase + goff), LDS_PTR(void, lds + kTileBytes + r8 * 128), 16, 0, 0);
       }
@@ -173,110 +347,24 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
     for (int tt = t0; tt < t1; ++tt) {
       const int cur = (tt - t0) & 1;
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#if !(OVGGT_ABLATE & 32)
       __syncthreads();
-      if (tt + 1 < t1) {
-        const size_t trow = (size_t)(tt + 1) * kSlotTile;
+#endif
+      if (tt + 1 < t1 && !(OVGGT_ABLATE & 16)) {
+        const size_t trow = (size_t)((OVGGT_ABLATE & 64) ? ((tt + 1) & 7) : (tt + 1)) * kSlotTile;
         char* nb = lds + (cur ^ 1) * 2 * kTileBytes;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           const int r8 = (wave * 4 + j) * 8;
-          const size_t goff = (trow + r8 + ld_row) * 128 + ld_piece;
+          const size_t goff = (trow + r8 + ld_row) * 128 + ld_piece[j & 1];
           __builtin_amdgcn_global_load_lds(GLB_PTR(kbase + goff), LDS_PTR(void, nb + r8 * 128), 16, 0, 0);
           __builtin_amdgcn_global_load_lds(GLB_PTR(vbase + goff), LDS_PTR(void, nb + kTileBytes + r8 * 128), 16, 0, 0);
         }
       }
       const char* ldsK = lds + cur * 2 * kTileBytes;
-      const char* ldsV = ldsK + kTileBytes;
-
-      // ---- S^T = K Q^T for this wave's 64 slots x 64 queries
-      f32x16 S[2][2];
-#pragma unroll
-      for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) S[a][b][i] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        const bf16x8 k0 = *LDS_PTR(const bf16x8, ldsK + koff[ks]);
-        const bf16x8 k1 = *LDS_PTR(const bf16x8, ldsK + koff[ks] + 32 * 128);
-        S[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0, qf[0][ks], S[0][0], 0, 0, 0);
-        S[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0, qf[1][ks], S[0][1], 0, 0, 0);
-        S[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1, qf[0][ks], S[1][0], 0, 0, 0);
-        S[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1, qf[1][ks], S[1][1], 0, 0, 0);
-      }
-      // slots past the resident count only exist in the last tile
-      if (tt == p.T - 1 && (p.n_total & (kSlotTile - 1))) {
-        const int sbase = tt * kSlotTile + khalf * 64 + 4 * g;
-#pragma unroll
-        for (int sb = 0; sb < 2; ++sb)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const int slot = sbase + sb * 32 + (i >> 2) * 8 + (i & 3);
-            if (slot >= p.n_total) { S[sb][0][i] = -INFINITY; S[sb][1][i] = -INFINITY; }
-          }
-      }
-
-      // ---- online softmax; lane owns one query per qb
-      f16x2 P[2][2][8];
-#pragma unroll
-      for (int qb = 0; qb < 2; ++qb) {
-        float mx = S[0][qb][0];
-#pragma unroll
-        for (int i = 1; i < 16; ++i) mx = fmaxf(mx, S[0][qb][i]);
-#pragma unroll
-        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, S[1][qb][i]);
-        mx = pair_max(mx);
-        const float mnew = fmaxf(mrun[qb], mx);
-        const bool need = (mnew - mrun[qb]) * p.c > kRescaleThreshold;
-        if (__builtin_amdgcn_ballot_w64(need) != 0ull) {
-          const float alpha = __builtin_amdgcn_exp2f((mrun[qb] - mnew) * p.c);
-          mrun[qb] = mnew;
-          lrun[qb] *= alpha;
-#pragma unroll
-          for (int db = 0; db < 2; ++db)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) O[db][qb][i] *= alpha;
-        }
-        const float mc = mrun[qb] * p.c - kWeightBias;
-        // p = 2^7 exp2(s*c - m*c), rounded to half in pairs; the row sum is taken over the
-        // ROUNDED values (dot product with ones), so numerator and denominator of the
-        // softmax see the same weights and a dominant key's rounding error cancels
-        float ls[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int sb = 0; sb < 2; ++sb)
-#pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[sb][qb][2 * j], p.c, -mc));
-            const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[sb][qb][2 * j + 1], p.c, -mc));
-            f16x2 pk;
-            pk[0] = (_Float16)e0;
-            pk[1] = (_Float16)e1;
-            ls[j & 3] = __builtin_amdgcn_fdot2(pk, ones2, ls[j & 3], false);
-            P[sb][qb][j] = pk;
-          }
-        lrun[qb] += (ls[0] + ls[1]) + (ls[2] + ls[3]);
-      }
-
-      // ---- O^T += V^T P^T
-#pragma unroll
-      for (int sb = 0; sb < 2; ++sb)
-#pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2) {
-          const f16x8 pb0 = join4(P[sb][0] + 4 * s2);
-          const f16x8 pb1 = join4(P[sb][1] + 4 * s2);
-#pragma unroll
-          for (int db = 0; db < 2; ++db) {
-            const int o = voff[db] + (sb * 32 + 16 * s2) * 128;
-            const s16x4 va = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, ldsV + o));
-            const s16x4 vb = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, ldsV + o + 8 * 128));
-            const __attribute__((ext_vector_type(8))) short v8 =
-                __builtin_shufflevector(va, vb, 0, 1, 2, 3, 4, 5, 6, 7);
-            const f16x8 vf = __builtin_bit_cast(f16x8, v8);
-            O[db][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pb0, O[db][0], 0, 0, 0);
-            O[db][1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pb1, O[db][1], 0, 0, 0);
-          }
-        }
+      const int sbase = tt * kSlotTile + khalf * 64 + 4 * g;      // first slot of this lane's accumulator rows
+      process_tile(ldsK, koff, voff, qf, O, mrun, lrun, p.c, sbase, p.n_total,
+                   tt == p.T - 1 && (p.n_total & (kSlotTile - 1)) != 0);
     }
 
     // ---- merge the two slot halves through LDS
