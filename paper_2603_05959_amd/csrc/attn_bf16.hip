@@ -108,6 +108,38 @@ __device__ inline f16x8 join4(const f16x2* p) {
   return __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
+// Softmax weights of one query block of a tile: p = exp2(s*c - mcb) for the 32 scores a lane
+// holds (two 32-slot accumulators), rounded to half in pairs; returns the lane's fp32 sum of the
+// weights.
+__device__ __forceinline__ float tile_weights(const f32x16& s0, const f32x16& s1, float c, float mcb,
+                                              f16x2 (&p0)[8], f16x2 (&p1)[8]) {
+  float ls[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const float a = sb ? s1[2 * j] : s0[2 * j], b = sb ? s1[2 * j + 1] : s0[2 * j + 1];
+#if OVGGT_ABLATE & 2
+      const float e0 = a, e1 = b;
+      if (j > 0) { (sb ? p1 : p0)[j] = (sb ? p1 : p0)[0]; continue; }
+#elif OVGGT_ABLATE & 1
+      const float e0 = __builtin_fmaf(a, c, -mcb), e1 = __builtin_fmaf(b, c, -mcb);
+#else
+      const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(a, c, -mcb));
+      const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(b, c, -mcb));
+#endif
+      f16x2 pk;
+      pk[0] = (_Float16)e0;
+      pk[1] = (_Float16)e1;
+      // plain fp32 adds: v_dot2c_f32_f16 runs on the matrix pipe and serialises with the other
+      // wave's MFMAs (measured), v_add_f32 co-executes with them
+      ls[j & 3] += e0;
+      ls[(j + 2) & 3] += e1;
+      (sb ? p1 : p0)[j] = pk;
+    }
+  return (ls[0] + ls[1]) + (ls[2] + ls[3]);
+}
+
 // One 64-slot x 64-query tile of one wave: S^T = K Q^T, online softmax, O^T += V^T P^T.
 // tail: the tile extends past n_total (only the last tile can); weights of the
 // absent slots are cleared after the softmax (their rows hold zeros or stale but
@@ -124,9 +156,6 @@ __device__ __forceinline__ void process_tile(const char* ldsK, const int (&koff)
                                              const bf16x8 (&qf)[2][4], f32x16 (&O)[2][2], float (&mrun)[2],
                                              float (&lrun)[2], float c, int sbase, int n_total, bool tail) {
   const char* ldsV = ldsK + kTileBytes;
-  f16x2 ones2;
-  ones2[0] = (_Float16)1.0f;
-  ones2[1] = (_Float16)1.0f;
   f32x16 S[2][2];
 #pragma unroll
   for (int a = 0; a < 2; ++a)
@@ -148,40 +177,21 @@ __device__ __forceinline__ void process_tile(const char* ldsK, const int (&koff)
   }
 #endif
   f16x2 P[2][2][8];
+  float lsum[2];
 #pragma unroll
-  for (int qb = 0; qb < 2; ++qb) {
-    float lsum;
-    {
-      const float mcb = mrun[qb] * c - kWeightBias;
-      float ls[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int sb = 0; sb < 2; ++sb)
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-#if OVGGT_ABLATE & 2
-          const float e0 = S[sb][qb][2 * j], e1 = S[sb][qb][2 * j + 1];
-          if (j > 0) { P[sb][qb][j] = P[sb][qb][0]; continue; }
-#elif OVGGT_ABLATE & 1
-          const float e0 = __builtin_fmaf(S[sb][qb][2 * j], c, -mcb);
-          const float e1 = __builtin_fmaf(S[sb][qb][2 * j + 1], c, -mcb);
+  for (int qb = 0; qb < 2; ++qb)
+    lsum[qb] = tile_weights(S[0][qb], S[1][qb], c, mrun[qb] * c - kWeightBias, P[0][qb], P[1][qb]);
+
+  // one overflow test for both query blocks, after all fast-path work has been issued
+#if OVGGT_ABLATE & (3 | 256)
+  if (false) {
 #else
-          const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[sb][qb][2 * j], c, -mcb));
-          const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[sb][qb][2 * j + 1], c, -mcb));
+  if (__builtin_amdgcn_ballot_w64(!(lsum[0] <= kWeightSumLimit) || !(lsum[1] <= kWeightSumLimit)) != 0ull) {
 #endif
-          f16x2 pk;
-          pk[0] = (_Float16)e0;
-          pk[1] = (_Float16)e1;
-          ls[j & 3] = __builtin_amdgcn_fdot2(pk, ones2, ls[j & 3], false);
-          P[sb][qb][j] = pk;
-        }
-      lsum = (ls[0] + ls[1]) + (ls[2] + ls[3]);
-    }
-#if OVGGT_ABLATE & 3
-    if (false) {
-#else
-    if (__builtin_amdgcn_ballot_w64(!(lsum <= kWeightSumLimit)) != 0ull) {
-#endif
-      // rare: recompute this query block's scores (cheaper than keeping them live past the fast path)
+    // rare: recompute the scores (cheaper than keeping them live past the fast path), take the
+    // true maximum, rescale the accumulators and redo the weights
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
       f32x16 R[2];
 #pragma unroll
       for (int sb = 0; sb < 2; ++sb) {
@@ -206,24 +216,13 @@ __device__ __forceinline__ void process_tile(const char* ldsK, const int (&koff)
       for (int db = 0; db < 2; ++db)
 #pragma unroll
         for (int i = 0; i < 16; ++i) O[db][qb][i] *= alpha;
-      const float mcb = mnew * c - kWeightBias;
-      float ls[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int sb = 0; sb < 2; ++sb)
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(R[sb][2 * j], c, -mcb));
-          const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(R[sb][2 * j + 1], c, -mcb));
-          f16x2 pk;
-          pk[0] = (_Float16)e0;
-          pk[1] = (_Float16)e1;
-          ls[j & 3] = __builtin_amdgcn_fdot2(pk, ones2, ls[j & 3], false);
-          P[sb][qb][j] = pk;
-        }
-      lsum = (ls[0] + ls[1]) + (ls[2] + ls[3]);
+      lsum[qb] = tile_weights(R[0], R[1], c, mnew * c - kWeightBias, P[0][qb], P[1][qb]);
     }
-    if (tail) {
-      asm volatile("; tail tile: clear absent slots" ::: "memory");   // keeps this block a real branch (never if-converted)
+  }
+  if (tail) {
+    asm volatile("; tail tile: clear absent slots" ::: "memory");   // keeps this block a real branch (never if-converted)
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
       float ls = 0.f;
 #pragma unroll
       for (int sb = 0; sb < 2; ++sb)
@@ -233,12 +232,13 @@ __device__ __forceinline__ void process_tile(const char* ldsK, const int (&koff)
           uint32_t w = __builtin_bit_cast(uint32_t, P[sb][qb][j]);
           w &= (slot < n_total ? 0x0000FFFFu : 0u) | (slot + 1 < n_total ? 0xFFFF0000u : 0u);
           P[sb][qb][j] = __builtin_bit_cast(f16x2, w);
-          ls = __builtin_amdgcn_fdot2(P[sb][qb][j], ones2, ls, false);
+          ls += (float)P[sb][qb][j][0] + (float)P[sb][qb][j][1];
         }
-      lsum = ls;
+      lsum[qb] = ls;
     }
-    lrun[qb] += lsum;
   }
+  lrun[0] += lsum[0];
+  lrun[1] += lsum[1];
 
   // O^T += V^T P^T; each V^T fragment feeds both query blocks
 #pragma unroll
@@ -276,6 +276,9 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
   const int u_end = min(u + p.chunk, p.total_units);
   if (u >= u_end) return;
   const int u_begin = u;
+#ifdef OVGGT_DEPHASE
+  if ((int)blockIdx.x >= (G >> 1)) { for (int r = 0; r < OVGGT_DEPHASE; ++r) __builtin_amdgcn_s_sleep(16); }
+#endif
 
   // per-lane LDS offsets
   int koff[4];

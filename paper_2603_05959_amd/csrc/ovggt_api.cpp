@@ -6,6 +6,7 @@
 #include "ovggt_internal.h"
 
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -194,6 +195,10 @@ int ovggt_cache_init(ovggt_cache** out, const ovggt_config* cfg, void* kv_dev, v
   int wgs = 2 * cus;
   wgs = (wgs + 7) & ~7;
   if (wgs < 8) wgs = 8;
+  if (const char* e = std::getenv("OVGGT_ATTN_WGS")) {          // tuning knob: attention workgroups per launch
+    const int v = std::atoi(e);
+    if (v >= 8) wgs = (v + 7) & ~7;
+  }
   if (wgs > kMaxAttnWgs) wgs = kMaxAttnWgs;
   c->n_wgs = wgs;
   c->n.assign(c->g.L, 0);
