@@ -48,26 +48,47 @@ typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
 #define GLB_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
 
-// XOR swizzle of the 16-byte piece index within a 128-byte LDS row, as a function of the row.
-#ifndef OVGGT_SWZ
-#define OVGGT_SWZ 0
-#endif
-__device__ __forceinline__ int swz(int row) {
-#if OVGGT_SWZ == 0
-  return row & 7;
-#elif OVGGT_SWZ == 1
-  return (row >> 1) & 7;
-#else
-  const int t = (row >> 1) & 7;
-  return ((t & 1) << 2) | (t & 2) | ((t >> 2) & 1);
-#endif
-}
+// XOR swizzle of the 16-byte piece index within a 128-byte LDS row (measured against
+// variants keyed on higher row bits: this one has the fewest bank conflicts).
+__device__ __forceinline__ int swz(int row) { return row & 7; }
 
 #ifndef OVGGT_ABLATE
 #define OVGGT_ABLATE 0          // timing experiments only: bit 0 no exp, 1 no softmax, 2 no PV, 3 no QK, 4 no loads, 5 no barrier
 #endif
 
-constexpr int kTileBytes = kSlotTile * 128;            // one K (or V) tile: 128 slots x 64 bf16
+constexpr int kTileBytes = kSlotTile * 128;
+
+// 16-byte direct-to-LDS load: lane i's 16 bytes land at lds_base + 16*i.  Issued as inline
+// assembly on purpose: the compiler cannot tell which LDS bytes an LDS-DMA load writes and
+// would make every later LDS read wait for ALL outstanding loads (vmcnt(0)), i.e. for the
+// prefetch of the next tile.  The kernel orders these loads itself: one explicit
+// s_waitcnt vmcnt(0) in front of the barrier that publishes a tile.
+template <int IMM>
+__device__ __forceinline__ void load16_to_lds(const char* base, uint32_t lane_off, const char* lds_base) {
+  const uint32_t m0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)LDS_PTR(const char, lds_base));
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2 offset:%3"
+               : : "s"(m0), "v"(lane_off), "s"(base), "n"(IMM) : "memory", "m0");
+}
+
+// One 128-slot K tile and V tile, global -> LDS: wave w fills rows [32w, 32w+32) of both with
+// four loads each (8 rows of 128 bytes per load); piece p of row r goes to LDS piece p ^ swz(r).
+// The instruction's immediate offset advances the memory address and the LDS address alike.
+__device__ __forceinline__ void issue_tile_loads(const char* kbase, const char* vbase, int tile, char* buf,
+                                                 int wave, int lane) {
+  const int ld_row = lane >> 3;
+  const uint32_t off = (uint32_t)((tile * kSlotTile + wave * 32 + ld_row) * 128 + (((lane & 7) ^ swz(ld_row)) << 4));
+  char* lk = buf + wave * 4096;
+  char* lv = lk + kTileBytes;
+  load16_to_lds<0>(kbase, off, lk);
+  load16_to_lds<0>(vbase, off, lv);
+  load16_to_lds<1024>(kbase, off, lk);
+  load16_to_lds<1024>(vbase, off, lv);
+  load16_to_lds<2048>(kbase, off, lk);
+  load16_to_lds<2048>(vbase, off, lv);
+  load16_to_lds<3072>(kbase, off, lk);
+  load16_to_lds<3072>(vbase, off, lv);
+}
+
 constexpr int kPartialFloats = kQueryTile * 64 + 2 * kQueryTile;
 constexpr float kWeightBias = 7.0f;                    // weights are stored as 2^7 * p (half max 65504)
 constexpr float kWeightSumLimit = 32768.0f;            // a lane's weight sum below 2^15 proves no weight overflowed
@@ -168,8 +189,12 @@ __device__ __forceinline__ void process_tile(const char* ldsK, const int (&koff)
 #else
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks) {
+#if OVGGT_ABLATE & 512
+    const bf16x8 k0 = qf[1][ks], k1 = qf[0][(ks + 1) & 3];
+#else
     const bf16x8 k0 = *LDS_PTR(const bf16x8, ldsK + koff[ks]);
     const bf16x8 k1 = *LDS_PTR(const bf16x8, ldsK + koff[ks] + 32 * 128);
+#endif
     S[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0, qf[0][ks], S[0][0], 0, 0, 0);
     S[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0, qf[1][ks], S[0][1], 0, 0, 0);
     S[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1, qf[0][ks], S[1][0], 0, 0, 0);
@@ -250,8 +275,13 @@ __device__ __forceinline__ void process_tile(const char* ldsK, const int (&koff)
 #pragma unroll
       for (int db = 0; db < 2; ++db) {
         const int o = (sb * 32 + 16 * s2) * 128;
+#if OVGGT_ABLATE & 1024
+        const s16x4 va = __builtin_bit_cast(s16x4, __builtin_shufflevector(pb0, pb0, 0, 1, 2, 3));
+        const s16x4 vb = __builtin_bit_cast(s16x4, __builtin_shufflevector(pb1, pb1, 4, 5, 6, 7));
+#else
         const s16x4 va = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, ldsV + voff[db][0] + o));
         const s16x4 vb = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, ldsV + voff[db][1] + o));
+#endif
         const __attribute__((ext_vector_type(8))) short v8 = __builtin_shufflevector(va, vb, 0, 1, 2, 3, 4, 5, 6, 7);
         const f16x8 vf = __builtin_bit_cast(f16x8, v8);
 #if OVGGT_ABLATE & 4
@@ -297,10 +327,6 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
       for (int hh = 0; hh < 2; ++hh)
         voff[db][hh] = (khalf * 64 + 8 * hh + x) * 128 + ((((c0 + 4 * db) ^ swz(8 * hh + x))) << 4) + inb;
   }
-  // direct-to-LDS load addressing: wave-instruction j covers LDS rows (wave*4+j)*8 .. +8
-  const int ld_row = lane >> 3;
-  const int ld_piece[2] = {((lane & 7) ^ swz(ld_row)) << 4, ((lane & 7) ^ swz(8 + ld_row)) << 4};
-
   while (u < u_end) {
     const int item = u / p.T;
     const int t0 = u - item * p.T;
@@ -336,35 +362,18 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
     float lrun[2] = {0.f, 0.f};
 
     // prologue: first tile into buffer 0
-    {
-      const size_t trow = (size_t)t0 * kSlotTile;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int r8 = (wave * 4 + j) * 8;
-        const size_t goff = (trow + r8 + ld_row) * 128 + ld_piece[j & 1];
-        __builtin_amdgcn_global_load_lds(GLB_PTR(kbase + goff), LDS_PTR(void, lds + r8 * 128), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds(GLB_PTR(vbase + goff), LDS_PTR(void, lds + kTileBytes + r8 * 128), 16, 0, 0);
-      }
-    }
+    issue_tile_loads(kbase, vbase, t0, lds, wave, lane);
 
-    for (int tt = t0; tt < t1; ++tt) {
+    for (int tt = t0; tt < ((OVGGT_ABLATE & 2048) ? t0 : t1); ++tt) {
       const int cur = (tt - t0) & 1;
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #if !(OVGGT_ABLATE & 32)
       __syncthreads();
 #endif
-      if (tt + 1 < t1 && !(OVGGT_ABLATE & 16)) {
-        const size_t trow = (size_t)((OVGGT_ABLATE & 64) ? ((tt + 1) & 7) : (tt + 1)) * kSlotTile;
-        char* nb = lds + (cur ^ 1) * 2 * kTileBytes;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const int r8 = (wave * 4 + j) * 8;
-          const size_t goff = (trow + r8 + ld_row) * 128 + ld_piece[j & 1];
-          __builtin_amdgcn_global_load_lds(GLB_PTR(kbase + goff), LDS_PTR(void, nb + r8 * 128), 16, 0, 0);
-          __builtin_amdgcn_global_load_lds(GLB_PTR(vbase + goff), LDS_PTR(void, nb + kTileBytes + r8 * 128), 16, 0, 0);
-        }
-      }
-      const char* ldsK = lds + cur * 2 * kTileBytes;
+      if (tt + 1 < t1 && !(OVGGT_ABLATE & 16))
+        issue_tile_loads(kbase, vbase, (OVGGT_ABLATE & 64) ? ((tt + 1) & 7) : (tt + 1),
+                         lds + (cur ^ 1) * 2 * kTileBytes, wave, lane);
+      const char* ldsK = lds + ((OVGGT_ABLATE & 16) ? 0 : cur) * 2 * kTileBytes;
       const int sbase = tt * kSlotTile + khalf * 64 + 4 * g;      // first slot of this lane's accumulator rows
       process_tile(ldsK, koff, voff, qf, O, mrun, lrun, p.c, sbase, p.n_total,
                    tt == p.T - 1 && (p.n_total & (kSlotTile - 1)) != 0);
