@@ -366,7 +366,10 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
 
     for (int tt = t0; tt < ((OVGGT_ABLATE & 2048) ? t0 : t1); ++tt) {
       const int cur = (tt - t0) & 1;
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      // vmcnt(0): this tile's loads have landed.  Issued through the builtin (not inline asm) so the
+      // compiler also knows that every load it tracks itself (the Q fragments) is complete and puts
+      // no vmcnt wait of its own inside the loop, where it would wait on the prefetch instead.
+      __builtin_amdgcn_s_waitcnt(0x0F70);
 #if !(OVGGT_ABLATE & 32)
       __syncthreads();
 #endif
