@@ -16,18 +16,33 @@
 // maximum grows by more than 2^8) and weights biased by 2^7 to sit in the middle
 // of the half range.
 //
-// Work split.  An item is (layer, head, 128-query block); its work is T =
-// ceil(n/128) slot tiles.  The flat list of item x tile units is cut into equal
-// chunks, one per workgroup (persistent, stream-K style), so all CUs finish
-// together whatever M, n and H are.  A workgroup that covers an item completely
-// writes the output; otherwise it writes an unnormalised partial (O, m, l) that
-// attn_combine_kernel merges.  Chunks are handed to workgroups so that each
-// XCD's L2 sees as few heads as possible.
+// Schedule.  On this chip the softmax of a tile (64 x {fma, exp, add} + 32
+// conversions per lane) costs more VALU time than the tile's 32 MFMAs cost matrix
+// time, a wave never overlaps its own MFMAs with its own VALU work, and two free
+// running waves on a SIMD starve the younger one.  So a workgroup is 8 waves =
+// two sets of 4, one wave of each set per SIMD, and the sets alternate between a
+// matrix phase (P V of the previous tile, then Q K^T of the current one; LDS
+// reads, no VALU instruction) and a vector phase (the softmax; no MFMA), with one
+// workgroup barrier per phase.  Set B starts one barrier late, so while one set
+// is in its matrix phase the other is in its vector phase and both pipes stay
+// busy.  Every wave executes the same sequence of barriers.
 //
-// A workgroup is 4 waves: wave = (query half, slot half) of the 128x128 tile;
-// the two slot halves are merged through LDS at the end of an item.  K and V
-// tiles are streamed global->LDS with 16-byte direct-to-LDS loads, double
-// buffered, one barrier per tile.  LDS rows are 128 bytes; 16-byte pieces are
+// Work split.  The two sets work on two different (layer, head) pairs of the same
+// 128-query block, each with its own K/V tile buffers, so they share control flow
+// (same tile range) but no data.  A pair item is (layer-head pair, query block);
+// its work is T = ceil(n/128) slot tiles.  The flat list of pair item x tile
+// units is cut into equal chunks, one per workgroup (one workgroup per CU,
+// persistent, stream-K style).  A set that covers its item completely writes the
+// output; otherwise it writes an unnormalised partial (O, m, l) that
+// attn_combine_kernel merges.  Chunks are handed to workgroups so that each XCD's
+// L2 sees as few heads as possible.
+//
+// Inside a set, wave = (query half, slot half) of the 128x128 tile; the two slot
+// halves are merged through LDS at the end of an item.  K and V tiles stream
+// global->LDS with 16-byte direct-to-LDS loads, double buffered: K of tile t+1 is
+// requested at the start of the matrix phase of tile t, V of tile t+1 at the
+// start of its vector phase, and both are awaited (vmcnt) just before the barrier
+// that precedes their first use.  LDS rows are 128 bytes; 16-byte pieces are
 // XOR-swizzled with the row index so both the K operand reads and the V
 // transpose reads are bank-conflict free.
 #include "ovggt_internal.h"
@@ -36,64 +51,35 @@ namespace ovggt {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
-typedef __attribute__((ext_vector_type(4))) _Float16 f16x4;
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
-typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(p))
-#define GLB_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
 
 // XOR swizzle of the 16-byte piece index within a 128-byte LDS row (measured against
 // variants keyed on higher row bits: this one has the fewest bank conflicts).
 __device__ __forceinline__ int swz(int row) { return row & 7; }
 
 #ifndef OVGGT_ABLATE
-#define OVGGT_ABLATE 0          // timing experiments only: bit 0 no exp, 1 no softmax, 2 no PV, 3 no QK, 4 no loads, 5 no barrier
+#define OVGGT_ABLATE 0          // timing experiments only: bit 0 no MFMA, bit 1 no LDS operand reads, bit 2 no tile loads, bit 3 no fma, bit 4 no row-sum adds, bit 5 no overflow branch
 #endif
 
-constexpr int kTileBytes = kSlotTile * 128;
-
-// 16-byte direct-to-LDS load: lane i's 16 bytes land at lds_base + 16*i.  Issued as inline
-// assembly on purpose: the compiler cannot tell which LDS bytes an LDS-DMA load writes and
-// would make every later LDS read wait for ALL outstanding loads (vmcnt(0)), i.e. for the
-// prefetch of the next tile.  The kernel orders these loads itself: one explicit
-// s_waitcnt vmcnt(0) in front of the barrier that publishes a tile.
-template <int IMM>
-__device__ __forceinline__ void load16_to_lds(const char* base, uint32_t lane_off, const char* lds_base) {
-  const uint32_t m0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)LDS_PTR(const char, lds_base));
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2 offset:%3"
-               : : "s"(m0), "v"(lane_off), "s"(base), "n"(IMM) : "memory", "m0");
-}
-
-// One 128-slot K tile and V tile, global -> LDS: wave w fills rows [32w, 32w+32) of both with
-// four loads each (8 rows of 128 bytes per load); piece p of row r goes to LDS piece p ^ swz(r).
-// The instruction's immediate offset advances the memory address and the LDS address alike.
-__device__ __forceinline__ void issue_tile_loads(const char* kbase, const char* vbase, int tile, char* buf,
-                                                 int wave, int lane) {
-  const int ld_row = lane >> 3;
-  const uint32_t off = (uint32_t)((tile * kSlotTile + wave * 32 + ld_row) * 128 + (((lane & 7) ^ swz(ld_row)) << 4));
-  char* lk = buf + wave * 4096;
-  char* lv = lk + kTileBytes;
-  load16_to_lds<0>(kbase, off, lk);
-  load16_to_lds<0>(vbase, off, lv);
-  load16_to_lds<1024>(kbase, off, lk);
-  load16_to_lds<1024>(vbase, off, lv);
-  load16_to_lds<2048>(kbase, off, lk);
-  load16_to_lds<2048>(vbase, off, lv);
-  load16_to_lds<3072>(kbase, off, lk);
-  load16_to_lds<3072>(vbase, off, lv);
-}
-
+constexpr int kTileBytes = kSlotTile * 128;            // one K (or V) tile: 128 slots x 64 16-bit elements
+constexpr int kSetBytes = 4 * kTileBytes;              // LDS of one wave set: [parity][K | V]
+constexpr int kAttnThreads = 512;
 constexpr int kPartialFloats = kQueryTile * 64 + 2 * kQueryTile;
 constexpr float kWeightBias = 7.0f;                    // weights are stored as 2^7 * p (half max 65504)
 constexpr float kWeightSumLimit = 32768.0f;            // a lane's weight sum below 2^15 proves no weight overflowed
 
-size_t attn_ws_bytes() { return (size_t)kMaxAttnWgs * 2 * kPartialFloats * sizeof(float); }
+// s_waitcnt immediates (gfx9 encoding: vmcnt [3:0] and [15:14], expcnt [6:4], lgkmcnt [11:8])
+constexpr int kWaitVm0 = 0x0F70;                       // vmcnt(0), nothing else
+constexpr int kWaitVm4 = 0x0F74;                       // vmcnt(4)
+
+size_t attn_ws_bytes() { return (size_t)kMaxAttnWgs * 4 * kPartialFloats * sizeof(float); }
 
 struct AttnParams {
   const char* q;
@@ -102,14 +88,41 @@ struct AttnParams {
   size_t kv_layer_bytes;
   size_t v_off;               // bytes from a layer's K to its V
   float* ws;
-  int H, M, cap, n_total, nl;
+  int H, M, cap, n_total;
+  int LH;                     // (layer, head) count of this launch
   int QB;                     // query blocks per (layer, head)
   int T;                      // slot tiles
   int chunk;                  // units per workgroup
-  int total_units;
+  int total_units;            // ceil(LH / 2) * QB * T
   float c;                    // softmax scale * log2(e)
   int out_f32;                // output element type: 1 = fp32, 0 = bf16
 };
+
+// Half a tile pair, global -> LDS: the calling wave fills 32 rows (4 KiB) of a K or V tile with four
+// 16-byte-per-lane direct-to-LDS loads (8 rows of 128 bytes each); lane i's 16 bytes land at
+// lds_addr + 16*i, and the immediate offset advances the memory address and the LDS address alike.
+// Inline assembly on purpose: the compiler cannot tell which LDS bytes an LDS-DMA load writes and
+// would make every later LDS read wait for all outstanding loads.  The kernel orders these loads
+// itself with explicit vmcnt waits in front of the barrier that publishes a tile.
+__device__ __forceinline__ void load_rows_to_lds(const char* gtile, uint32_t lane_off, uint32_t lds_addr) {
+#if OVGGT_ABLATE & 4
+  return;
+#endif
+  asm volatile("s_mov_b32 m0, %0\n\t"
+               "s_nop 0\n\t"
+               "global_load_lds_dwordx4 %1, %2 offset:0\n\t"
+               "global_load_lds_dwordx4 %1, %2 offset:1024\n\t"
+               "global_load_lds_dwordx4 %1, %2 offset:2048\n\t"
+               "global_load_lds_dwordx4 %1, %2 offset:3072"
+               : : "s"(lds_addr), "v"(lane_off), "s"(gtile) : "memory", "m0");
+}
+
+// Workgroup barrier that neither memory accesses nor ALU work may be moved across.
+__device__ __forceinline__ void phase_barrier() {
+  __builtin_amdgcn_sched_barrier(0);
+  asm volatile("s_barrier" ::: "memory");
+  __builtin_amdgcn_sched_barrier(0);
+}
 
 // Lanes l and l+32 hold the two slot groups of the same query.  The swap
 // instruction leaves each lane with both values in (r[0], r[1]) in some order,
@@ -123,149 +136,55 @@ __device__ inline float pair_sum(float x) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-__device__ inline f16x8 join4(const f16x2* p) {
-  const f16x4 a = __builtin_shufflevector(p[0], p[1], 0, 1, 2, 3);
-  const f16x4 b = __builtin_shufflevector(p[2], p[3], 0, 1, 2, 3);
-  return __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
+__device__ inline f16x8 join4(const uint32_t* p) {
+  const u32x4 v = {p[0], p[1], p[2], p[3]};
+  return __builtin_bit_cast(f16x8, v);
 }
 
 // Softmax weights of one query block of a tile: p = exp2(s*c - mcb) for the 32 scores a lane
-// holds (two 32-slot accumulators), rounded to half in pairs; returns the lane's fp32 sum of the
-// weights.
+// holds (two 32-slot accumulators), rounded to half in pairs (kept as the 32-bit pattern of the
+// pair); returns the lane's fp32 sum of the weights.
+//
+// Issued in batches of 16 (all fma, then all exp, then conversions and adds) with scheduling
+// fences between them: an instruction that consumes the result of the one issued just before it
+// stalls about four cycles (measured for fma -> exp and exp -> add), and left to itself the
+// scheduler emits exactly such dependent pairs to save registers.
 __device__ __forceinline__ float tile_weights(const f32x16& s0, const f32x16& s1, float c, float mcb,
-                                              f16x2 (&p0)[8], f16x2 (&p1)[8]) {
+                                              uint32_t (&p0)[8], uint32_t (&p1)[8]) {
   float ls[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-  for (int sb = 0; sb < 2; ++sb)
+  for (int sb = 0; sb < 2; ++sb) {
+    float e[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) e[i] = (OVGGT_ABLATE & 8) ? (sb ? s1[i] : s0[i]) : __builtin_fmaf(sb ? s1[i] : s0[i], c, -mcb);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) e[i] = __builtin_amdgcn_exp2f(e[i]);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      const float a = sb ? s1[2 * j] : s0[2 * j], b = sb ? s1[2 * j + 1] : s0[2 * j + 1];
-#if OVGGT_ABLATE & 2
-      const float e0 = a, e1 = b;
-      if (j > 0) { (sb ? p1 : p0)[j] = (sb ? p1 : p0)[0]; continue; }
-#elif OVGGT_ABLATE & 1
-      const float e0 = __builtin_fmaf(a, c, -mcb), e1 = __builtin_fmaf(b, c, -mcb);
-#else
-      const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(a, c, -mcb));
-      const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(b, c, -mcb));
-#endif
       f16x2 pk;
-      pk[0] = (_Float16)e0;
-      pk[1] = (_Float16)e1;
+      pk[0] = (_Float16)e[2 * j];
+      pk[1] = (_Float16)e[2 * j + 1];
       // plain fp32 adds: v_dot2c_f32_f16 runs on the matrix pipe and serialises with the other
-      // wave's MFMAs (measured), v_add_f32 co-executes with them
-      ls[j & 3] += e0;
-      ls[(j + 2) & 3] += e1;
-      (sb ? p1 : p0)[j] = pk;
+      // set's MFMAs (measured), v_add_f32 co-executes with them
+      if (!(OVGGT_ABLATE & 16)) {
+        ls[j & 3] += e[2 * j];
+        ls[(j + 2) & 3] += e[2 * j + 1];
+      }
+      (sb ? p1 : p0)[j] = __builtin_bit_cast(uint32_t, pk);
     }
+    __builtin_amdgcn_sched_barrier(0);
+  }
   return (ls[0] + ls[1]) + (ls[2] + ls[3]);
 }
 
-// One 64-slot x 64-query tile of one wave: S^T = K Q^T, online softmax, O^T += V^T P^T.
-// tail: the tile extends past n_total (only the last tile can); weights of the
-// absent slots are cleared after the softmax (their rows hold zeros or stale but
-// finite keys, so their scores are finite and merely move the reference maximum).
-//
-// Softmax fast path: weights are formed against the running reference maximum
-// m without looking for this tile's maximum; p = 2^7 * exp2((s - m) * c) is
-// rounded to half and summed.  If the lane's sum stays below 2^15 no weight can
-// have overflowed half.  Otherwise (first tile, or the maximum grew by about 2^8)
-// the wave takes the slow path: true tile maximum, rescale O and l, redo the
-// weights.  The reference maximum therefore lags the true one by < 2^8, which
-// costs no accuracy in fp32/half arithmetic.
-__device__ __forceinline__ void process_tile(const char* ldsK, const int (&koff)[4], const int (&voff)[2][2],
-                                             const bf16x8 (&qf)[2][4], f32x16 (&O)[2][2], float (&mrun)[2],
-                                             float (&lrun)[2], float c, int sbase, int n_total, bool tail) {
-  const char* ldsV = ldsK + kTileBytes;
-  f32x16 S[2][2];
-#pragma unroll
-  for (int a = 0; a < 2; ++a)
-#pragma unroll
-    for (int b = 0; b < 2; ++b)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) S[a][b][i] = 0.f;
-#if OVGGT_ABLATE & 8
-  for (int a = 0; a < 2; ++a) for (int b = 0; b < 2; ++b) for (int i = 0; i < 16; ++i) S[a][b][i] = mrun[b] + i * 0.01f + (float)qf[a][b][0];
-#else
-#pragma unroll
-  for (int ks = 0; ks < 4; ++ks) {
-#if OVGGT_ABLATE & 512
-    const bf16x8 k0 = qf[1][ks], k1 = qf[0][(ks + 1) & 3];
-#else
-    const bf16x8 k0 = *LDS_PTR(const bf16x8, ldsK + koff[ks]);
-    const bf16x8 k1 = *LDS_PTR(const bf16x8, ldsK + koff[ks] + 32 * 128);
-#endif
-    S[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0, qf[0][ks], S[0][0], 0, 0, 0);
-    S[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0, qf[1][ks], S[0][1], 0, 0, 0);
-    S[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1, qf[0][ks], S[1][0], 0, 0, 0);
-    S[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1, qf[1][ks], S[1][1], 0, 0, 0);
-  }
-#endif
-  f16x2 P[2][2][8];
-  float lsum[2];
-#pragma unroll
-  for (int qb = 0; qb < 2; ++qb)
-    lsum[qb] = tile_weights(S[0][qb], S[1][qb], c, mrun[qb] * c - kWeightBias, P[0][qb], P[1][qb]);
-
-  // one overflow test for both query blocks, after all fast-path work has been issued
-#if OVGGT_ABLATE & (3 | 256)
-  if (false) {
-#else
-  if (__builtin_amdgcn_ballot_w64(!(lsum[0] <= kWeightSumLimit) || !(lsum[1] <= kWeightSumLimit)) != 0ull) {
-#endif
-    // rare: recompute the scores (cheaper than keeping them live past the fast path), take the
-    // true maximum, rescale the accumulators and redo the weights
-#pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-      f32x16 R[2];
-#pragma unroll
-      for (int sb = 0; sb < 2; ++sb) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) R[sb][i] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
-          R[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*LDS_PTR(const bf16x8, ldsK + koff[ks] + sb * 32 * 128),
-                                                          qf[qb][ks], R[sb], 0, 0, 0);
-      }
-      float mx = R[0][0];
-#pragma unroll
-      for (int i = 1; i < 16; ++i) mx = fmaxf(mx, R[0][i]);
-#pragma unroll
-      for (int i = 0; i < 16; ++i) mx = fmaxf(mx, R[1][i]);
-      mx = pair_max(mx);
-      const float mnew = fmaxf(mrun[qb], mx);
-      const float alpha = __builtin_amdgcn_exp2f((mrun[qb] - mnew) * c);
-      mrun[qb] = mnew;
-      lrun[qb] *= alpha;
-#pragma unroll
-      for (int db = 0; db < 2; ++db)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) O[db][qb][i] *= alpha;
-      lsum[qb] = tile_weights(R[0], R[1], c, mnew * c - kWeightBias, P[0][qb], P[1][qb]);
-    }
-  }
-  if (tail) {
-    asm volatile("; tail tile: clear absent slots" ::: "memory");   // keeps this block a real branch (never if-converted)
-#pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-      float ls = 0.f;
-#pragma unroll
-      for (int sb = 0; sb < 2; ++sb)
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          const int slot = sbase + sb * 32 + (j >> 1) * 8 + (j & 1) * 2;      // slots of accumulators 2j, 2j+1
-          uint32_t w = __builtin_bit_cast(uint32_t, P[sb][qb][j]);
-          w &= (slot < n_total ? 0x0000FFFFu : 0u) | (slot + 1 < n_total ? 0xFFFF0000u : 0u);
-          P[sb][qb][j] = __builtin_bit_cast(f16x2, w);
-          ls += (float)P[sb][qb][j][0] + (float)P[sb][qb][j][1];
-        }
-      lsum[qb] = ls;
-    }
-  }
-  lrun[0] += lsum[0];
-  lrun[1] += lsum[1];
-
-  // O^T += V^T P^T; each V^T fragment feeds both query blocks
+// Matrix phase, first part: O^T += V^T P^T for one 64-slot x 64-query tile of one wave; each V^T
+// fragment feeds both query blocks.  P is indexed [slot block][query block][pair].
+template <int PAR>
+__device__ __forceinline__ void pv_tile(const char* lds, const int (&voff)[2][2], const uint32_t (&P)[2][2][8],
+                                        f32x16 (&O)[2][2]) {
+  const char* ldsV = lds + PAR * 2 * kTileBytes + kTileBytes;
 #pragma unroll
   for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
@@ -275,17 +194,16 @@ __device__ __forceinline__ void process_tile(const char* ldsK, const int (&koff)
 #pragma unroll
       for (int db = 0; db < 2; ++db) {
         const int o = (sb * 32 + 16 * s2) * 128;
-#if OVGGT_ABLATE & 1024
-        const s16x4 va = __builtin_bit_cast(s16x4, __builtin_shufflevector(pb0, pb0, 0, 1, 2, 3));
-        const s16x4 vb = __builtin_bit_cast(s16x4, __builtin_shufflevector(pb1, pb1, 4, 5, 6, 7));
+#if OVGGT_ABLATE & 2
+        const f16x8 vf = db ? pb1 : pb0;
 #else
         const s16x4 va = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, ldsV + voff[db][0] + o));
         const s16x4 vb = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, ldsV + voff[db][1] + o));
-#endif
         const __attribute__((ext_vector_type(8))) short v8 = __builtin_shufflevector(va, vb, 0, 1, 2, 3, 4, 5, 6, 7);
         const f16x8 vf = __builtin_bit_cast(f16x8, v8);
-#if OVGGT_ABLATE & 4
-        O[db][0][0] += (float)vf[0] * (float)pb0[0]; O[db][1][1] += (float)vf[1] * (float)pb1[1];
+#endif
+#if OVGGT_ABLATE & 1
+        asm volatile("" :: "v"(vf));
 #else
         O[db][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pb0, O[db][0], 0, 0, 0);
         O[db][1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pb1, O[db][1], 0, 0, 0);
@@ -294,27 +212,252 @@ __device__ __forceinline__ void process_tile(const char* ldsK, const int (&koff)
     }
 }
 
-__global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
-  __shared__ __attribute__((aligned(1024))) char lds[4 * kTileBytes];     // [buf][K|V]
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int qhalf = wave & 1, khalf = wave >> 1;
+// Matrix phase, second part: S^T = K Q^T, S indexed [slot block][query block].
+template <int PAR>
+__device__ __forceinline__ void qk_tile(const char* lds, const int (&koff)[4], const bf16x8 (&qf)[2][4],
+                                        f32x16 (&S)[2][2]) {
+  const char* ldsK = lds + PAR * 2 * kTileBytes;
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) S[a][b][i] = 0.f;
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) {
+#if OVGGT_ABLATE & 2
+    const bf16x8 k0 = qf[1][ks], k1 = qf[0][(ks + 1) & 3];
+#else
+    const bf16x8 k0 = *LDS_PTR(const bf16x8, ldsK + koff[ks]);
+    const bf16x8 k1 = *LDS_PTR(const bf16x8, ldsK + koff[ks] + 32 * 128);
+#endif
+#if OVGGT_ABLATE & 1
+    asm volatile("" :: "v"(k0), "v"(k1));
+    continue;
+#endif
+    S[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0, qf[0][ks], S[0][0], 0, 0, 0);
+    S[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0, qf[1][ks], S[0][1], 0, 0, 0);
+    S[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1, qf[0][ks], S[1][0], 0, 0, 0);
+    S[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1, qf[1][ks], S[1][1], 0, 0, 0);
+  }
+}
+
+// Vector phase: online softmax of one 64-slot x 64-query tile of one wave.
+// tail: the tile extends past n_total (only the last tile can); weights of the
+// absent slots are cleared after the softmax (their rows hold zeros or stale but
+// finite keys, so their scores are finite and merely move the reference maximum).
+//
+// Fast path: weights are formed against the running reference maximum m without
+// looking for this tile's maximum; p = 2^7 * exp2((s - m) * c) is rounded to half
+// and summed.  If the lane's sum stays below 2^15 no weight can have overflowed
+// half.  Otherwise (first tile, or the maximum grew by about 2^8) the wave takes
+// the slow path: true tile maximum, rescale O and l, redo the weights.  The
+// reference maximum therefore lags the true one by < 2^8, which costs no accuracy
+// in fp32/half arithmetic.  O holds the tiles before this one (their P V products
+// were issued in the preceding matrix phase), so rescaling it here is consistent.
+__device__ __forceinline__ void softmax_tile(const f32x16 (&S)[2][2], uint32_t (&P)[2][2][8], f32x16 (&O)[2][2],
+                                             float (&mrun)[2], float (&lrun)[2], float c, int sbase, int n_total,
+                                             bool tail, unsigned long long* trs = nullptr) {
+  float lsum[2];
+#ifdef OVGGT_TRACE
+  __builtin_amdgcn_sched_barrier(0);
+  trs[0] = clock64();
+  __builtin_amdgcn_sched_barrier(0);
+#endif
+  lsum[0] = tile_weights(S[0][0], S[1][0], c, mrun[0] * c - kWeightBias, P[0][0], P[1][0]);
+#ifdef OVGGT_TRACE
+  __builtin_amdgcn_sched_barrier(0);
+  trs[1] = clock64();
+  __builtin_amdgcn_sched_barrier(0);
+#endif
+  lsum[1] = tile_weights(S[0][1], S[1][1], c, mrun[1] * c - kWeightBias, P[0][1], P[1][1]);
+#ifdef OVGGT_TRACE
+  __builtin_amdgcn_sched_barrier(0);
+  trs[2] = clock64();
+  __builtin_amdgcn_sched_barrier(0);
+#endif
+
+  // one overflow test for both query blocks; the compare is issued before the conversions to half
+  // are forced out, so the branch does not wait for the VALU pipeline to drain
+  const bool overflow =
+      __builtin_amdgcn_ballot_w64(!(lsum[0] <= kWeightSumLimit) || !(lsum[1] <= kWeightSumLimit)) != 0ull;
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) asm volatile("" : "+v"(P[a][b][j]));
+  if (__builtin_expect(overflow, 0)) {
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      float mx = S[0][qb][0];
+#pragma unroll
+      for (int i = 1; i < 16; ++i) mx = fmaxf(mx, S[0][qb][i]);
+#pragma unroll
+      for (int i = 0; i < 16; ++i) mx = fmaxf(mx, S[1][qb][i]);
+      mx = pair_max(mx);
+      const float mnew = fmaxf(mrun[qb], mx);
+      const float alpha = __builtin_amdgcn_exp2f((mrun[qb] - mnew) * c);
+      mrun[qb] = mnew;
+      lrun[qb] *= alpha;
+#pragma unroll
+      for (int db = 0; db < 2; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) O[db][qb][i] *= alpha;
+      lsum[qb] = tile_weights(S[0][qb], S[1][qb], c, mnew * c - kWeightBias, P[0][qb], P[1][qb]);
+    }
+  }
+  if (__builtin_expect(tail, 0)) {
+    asm volatile("; tail tile: clear absent slots" ::: "memory");   // keeps this block a real branch (never if-converted)
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      float ls = 0.f;
+#pragma unroll
+      for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const int slot = sbase + sb * 32 + (j >> 1) * 8 + (j & 1) * 2;      // slots of accumulators 2j, 2j+1
+          uint32_t w = P[sb][qb][j];
+          w &= (slot < n_total ? 0x0000FFFFu : 0u) | (slot + 1 < n_total ? 0xFFFF0000u : 0u);
+          P[sb][qb][j] = w;
+          const f16x2 h = __builtin_bit_cast(f16x2, w);
+          ls += (float)h[0] + (float)h[1];
+        }
+      lsum[qb] = ls;
+    }
+  }
+  lrun[0] += lsum[0];
+  lrun[1] += lsum[1];
+#ifdef OVGGT_TRACE
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) asm volatile("" : "+v"(P[a][b][j]));
+  __builtin_amdgcn_sched_barrier(0);
+  trs[3] = clock64();
+  __builtin_amdgcn_sched_barrier(0);
+#endif
+}
+
+// State a wave carries through one segment (a run of tiles of one item).
+struct TileCtx {
+  const char* lds;            // base of the LDS array
+  const char* kbase;          // K rows of this set's (layer, head)
+  const char* vbase;
+  uint32_t lane_off;          // this lane's byte offset inside a tile for the direct-to-LDS loads
+  uint32_t lds_ld;            // LDS byte address of this wave's 32 rows in K buffer 0 of its set
+  int t1, T, n_total, slot0;  // slot0: first slot of this lane's accumulator rows within a tile
+  float c;
+  bool active;
+#ifdef OVGGT_TRACE
+  unsigned long long tr_m, tr_x, tr_v, tr_y, tr_w, tr_s[4];   // cycles in matrix phase, at its barrier, in vector phase, at its barrier
+#endif
+};
+
+// One tile: matrix phase, barrier, vector phase, barrier.  PAR is the parity of the tile within the
+// segment and selects the LDS buffers at compile time (no address arithmetic on the VALU).
+template <int PAR>
+__device__ __forceinline__ void tile_step(TileCtx& x, int tt, bool first, const int (&koff)[4],
+                                          const int (&voff)[2][2], const bf16x8 (&qf)[2][4], f32x16 (&S)[2][2],
+                                          uint32_t (&P)[2][2][8], f32x16 (&O)[2][2], float (&mrun)[2],
+                                          float (&lrun)[2]) {
+  const bool more = tt + 1 < x.t1;
+#ifdef OVGGT_TRACE
+  const unsigned long long tr0 = clock64();
+  __builtin_amdgcn_sched_barrier(0);
+#endif
+  // ---- matrix phase
+  __builtin_amdgcn_s_setprio(1);
+  if (x.active) {
+    if (more)
+      load_rows_to_lds(x.kbase + (size_t)(tt + 1) * kTileBytes, x.lane_off, x.lds_ld + (PAR ^ 1) * 2 * kTileBytes);
+    if (!first) pv_tile<PAR ^ 1>(x.lds, voff, P, O);
+    qk_tile<PAR>(x.lds, koff, qf, S);
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int b = 0; b < 2; ++b) asm volatile("" : "+v"(S[a][b]));      // issued before the barrier
+  }
+  __builtin_amdgcn_s_setprio(0);
+#ifdef OVGGT_TRACE
+  __builtin_amdgcn_sched_barrier(0);
+  const unsigned long long tr1 = clock64();
+#endif
+  phase_barrier();
+#ifdef OVGGT_TRACE
+  const unsigned long long tr2 = clock64();
+  __builtin_amdgcn_sched_barrier(0);
+#endif
+  // ---- vector phase
+  if (x.active) {
+    if (more)
+      load_rows_to_lds(x.vbase + (size_t)(tt + 1) * kTileBytes, x.lane_off,
+                       x.lds_ld + (PAR ^ 1) * 2 * kTileBytes + kTileBytes);
+#if OVGGT_ABLATE & 64
+    if (x.n_total < 0)
+#endif
+#ifdef OVGGT_TRACE
+    unsigned long long trs[4];
+    softmax_tile(S, P, O, mrun, lrun, x.c, tt * kSlotTile + x.slot0, x.n_total,
+                 tt == x.T - 1 && (x.n_total & (kSlotTile - 1)) != 0, trs);
+    x.tr_s[0] += trs[0] - tr2; x.tr_s[1] += trs[1] - trs[0]; x.tr_s[2] += trs[2] - trs[1]; x.tr_s[3] += trs[3] - trs[2];
+#else
+    softmax_tile(S, P, O, mrun, lrun, x.c, tt * kSlotTile + x.slot0, x.n_total,
+                 tt == x.T - 1 && (x.n_total & (kSlotTile - 1)) != 0);
+#endif
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) asm volatile("" : "+v"(P[a][b][j]));   // computed before the barrier
+  }
+#ifdef OVGGT_TRACE
+  __builtin_amdgcn_sched_barrier(0);
+  const unsigned long long tr2b = clock64();
+  __builtin_amdgcn_sched_barrier(0);
+#endif
+  // K of tile tt+1 (and everything older) has landed; only V of tile tt+1 may still be in flight
+  if (more) __builtin_amdgcn_s_waitcnt(kWaitVm4);
+  else __builtin_amdgcn_s_waitcnt(kWaitVm0);
+#ifdef OVGGT_TRACE
+  __builtin_amdgcn_sched_barrier(0);
+  const unsigned long long tr3 = clock64();
+#endif
+  phase_barrier();
+#ifdef OVGGT_TRACE
+  const unsigned long long tr4 = clock64();
+  x.tr_m += tr1 - tr0; x.tr_x += tr2 - tr1; x.tr_v += tr2b - tr2; x.tr_y += tr4 - tr3; x.tr_w += tr3 - tr2b;
+#endif
+}
+
+__global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p) {
+  __shared__ __attribute__((aligned(1024))) char lds[2 * kSetBytes];      // [set][parity][K | V]
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int set = wave >> 2, wv = wave & 3;
+  const int qhalf = wv & 1, khalf = wv >> 1;
   const int l32 = lane & 31, g = lane >> 5;
 
   const int G = gridDim.x;
   const int cidx = (blockIdx.x & 7) * (G >> 3) + (blockIdx.x >> 3);
   int u = cidx * p.chunk;
   const int u_end = min(u + p.chunk, p.total_units);
-  if (u >= u_end) return;
+  if (u >= u_end) return;                                // whole workgroup: no barrier has been executed yet
   const int u_begin = u;
-#ifdef OVGGT_DEPHASE
-  if ((int)blockIdx.x >= (G >> 1)) { for (int r = 0; r < OVGGT_DEPHASE; ++r) __builtin_amdgcn_s_sleep(16); }
+#ifdef OVGGT_TRACE
+  const unsigned long long tr_w0 = wall_clock64(), tr_c0 = clock64();
+  unsigned long long tr_n = 0;
 #endif
 
-  // per-lane LDS offsets
+  // per-lane LDS offsets (the set's region included)
+  char* const lset = lds + set * kSetBytes;
   int koff[4];
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks)
-    koff[ks] = (khalf * 64 + l32) * 128 + ((((2 * ks + g) ^ swz(l32))) << 4);
+    koff[ks] = set * kSetBytes + (khalf * 64 + l32) * 128 + ((((2 * ks + g) ^ swz(l32))) << 4);
   int voff[2][2];                                        // [db][second group of four slots]
   {
     const int i = lane & 15;
@@ -325,19 +468,42 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
     for (int db = 0; db < 2; ++db)
 #pragma unroll
       for (int hh = 0; hh < 2; ++hh)
-        voff[db][hh] = (khalf * 64 + 8 * hh + x) * 128 + ((((c0 + 4 * db) ^ swz(8 * hh + x))) << 4) + inb;
+        voff[db][hh] = set * kSetBytes + (khalf * 64 + 8 * hh + x) * 128 + ((((c0 + 4 * db) ^ swz(8 * hh + x))) << 4) + inb;
   }
+
+  TileCtx x;
+#ifdef OVGGT_TRACE
+  x.tr_m = x.tr_x = x.tr_v = x.tr_y = x.tr_w = 0; x.tr_s[0] = x.tr_s[1] = x.tr_s[2] = x.tr_s[3] = 0;
+#endif
+  x.lds = lds;
+  x.T = p.T;
+  x.n_total = p.n_total;
+  x.c = p.c;
+  x.slot0 = khalf * 64 + 4 * g;
+  {
+    const int ld_row = lane >> 3;
+    x.lane_off = (uint32_t)((wv * 32 + ld_row) * 128 + (((lane & 7) ^ swz(ld_row)) << 4));
+    x.lds_ld = (uint32_t)(uintptr_t)LDS_PTR(char, lds) + (uint32_t)(set * kSetBytes + wv * 4096);
+  }
+
+  // set B runs one barrier behind set A: its matrix phases coincide with A's vector phases
+  if (set == 1) phase_barrier();
+
   while (u < u_end) {
-    const int item = u / p.T;
+    const int item = u / p.T;                            // pair item
     const int t0 = u - item * p.T;
     const int t1 = min(p.T, t0 + (u_end - u));
     const bool first_seg = (u == u_begin);
     const bool full = (t0 == 0 && t1 == p.T);
     const int qb_idx = item % p.QB;
-    const int h = (item / p.QB) % p.H;
-    const int li = item / (p.QB * p.H);
-    const char* kbase = p.kv0 + (size_t)li * p.kv_layer_bytes + (size_t)h * p.cap * 128;
-    const char* vbase = kbase + p.v_off;
+    const int lh = 2 * (item / p.QB) + set;              // this set's (layer, head)
+    const bool active = lh < p.LH;
+    const int li = active ? lh / p.H : 0;
+    const int h = active ? lh - li * p.H : 0;
+    x.active = active;
+    x.t1 = t1;
+    x.kbase = p.kv0 + (size_t)li * p.kv_layer_bytes + (size_t)h * p.cap * 128;
+    x.vbase = x.kbase + p.v_off;
     const int q0 = qb_idx * kQueryTile;
 
     // Q^T fragments: lane holds query (q0 + qhalf*64 + qb*32 + l32), d = ks*16 + 8g .. +8
@@ -351,45 +517,56 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
       for (int ks = 0; ks < 4; ++ks) qf[qb][ks] = *(const bf16x8*)(qp + (ks * 16 + 8 * g) * 2);
     }
 
-    f32x16 O[2][2];
+    f32x16 O[2][2], S[2][2];
+    uint32_t P[2][2][8];
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
-      for (int b = 0; b < 2; ++b)
+      for (int b = 0; b < 2; ++b) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) O[a][b][i] = 0.f;
+        for (int i = 0; i < 16; ++i) { O[a][b][i] = 0.f; S[a][b][i] = 0.f; }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) P[a][b][j] = 0u;
+      }
     float mrun[2] = {-1e30f, -1e30f};
     float lrun[2] = {0.f, 0.f};
 
-    // prologue: first tile into buffer 0
-    issue_tile_loads(kbase, vbase, t0, lds, wave, lane);
+    // prologue: first tile of the segment into the parity-0 buffers; the builtin wait also tells the
+    // compiler that the loads it tracks itself (Q) are complete, so it adds no vmcnt waits of its own
+    if (active) {
+      load_rows_to_lds(x.kbase + (size_t)t0 * kTileBytes, x.lane_off, x.lds_ld);
+      load_rows_to_lds(x.vbase + (size_t)t0 * kTileBytes, x.lane_off, x.lds_ld + kTileBytes);
+    }
+    __builtin_amdgcn_s_waitcnt(kWaitVm0);
+    phase_barrier();
 
-    for (int tt = t0; tt < ((OVGGT_ABLATE & 2048) ? t0 : t1); ++tt) {
-      const int cur = (tt - t0) & 1;
-      // vmcnt(0): this tile's loads have landed.  Issued through the builtin (not inline asm) so the
-      // compiler also knows that every load it tracks itself (the Q fragments) is complete and puts
-      // no vmcnt wait of its own inside the loop, where it would wait on the prefetch instead.
-      __builtin_amdgcn_s_waitcnt(0x0F70);
-#if !(OVGGT_ABLATE & 32)
-      __syncthreads();
+    int tt = t0;
+    bool first = true;
+    for (; tt + 1 < t1; tt += 2) {
+      tile_step<0>(x, tt, first, koff, voff, qf, S, P, O, mrun, lrun);
+      tile_step<1>(x, tt + 1, false, koff, voff, qf, S, P, O, mrun, lrun);
+      first = false;
+    }
+    const bool odd = tt < t1;                            // an odd number of tiles: one more on parity 0
+    if (odd) tile_step<0>(x, tt, first, koff, voff, qf, S, P, O, mrun, lrun);
+#ifdef OVGGT_TRACE
+    tr_n += t1 - t0;
 #endif
-      if (tt + 1 < t1 && !(OVGGT_ABLATE & 16))
-        issue_tile_loads(kbase, vbase, (OVGGT_ABLATE & 64) ? ((tt + 1) & 7) : (tt + 1),
-                         lds + (cur ^ 1) * 2 * kTileBytes, wave, lane);
-      const char* ldsK = lds + ((OVGGT_ABLATE & 16) ? 0 : cur) * 2 * kTileBytes;
-      const int sbase = tt * kSlotTile + khalf * 64 + 4 * g;      // first slot of this lane's accumulator rows
-      process_tile(ldsK, koff, voff, qf, O, mrun, lrun, p.c, sbase, p.n_total,
-                   tt == p.T - 1 && (p.n_total & (kSlotTile - 1)) != 0);
+
+    // P V of the last tile
+    if (active) {
+      if (odd) pv_tile<0>(lds, voff, P, O);
+      else pv_tile<1>(lds, voff, P, O);
     }
 
-    // ---- merge the two slot halves through LDS
+    // ---- merge the two slot halves through the set's LDS
     float ltot[2];
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) ltot[qb] = pair_sum(lrun[qb]);
-    __syncthreads();                                  // all tile reads done; LDS is free
-    float* mO = (float*)lds + qhalf * (64 * 64);       // [reg][lane]
-    float* mML = (float*)lds + 2 * 64 * 64 + qhalf * (4 * 64);
-    if (khalf == 1) {
+    __syncthreads();                                  // all tile reads done; the set's LDS is free
+    float* mO = (float*)lset + qhalf * (64 * 64);      // [reg][lane]
+    float* mML = (float*)lset + 2 * 64 * 64 + qhalf * (4 * 64);
+    if (active && khalf == 1) {
 #pragma unroll
       for (int db = 0; db < 2; ++db)
 #pragma unroll
@@ -403,7 +580,7 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
       }
     }
     __syncthreads();
-    if (khalf == 0) {
+    if (active && khalf == 0) {
       float mfin[2], lfin[2];
 #pragma unroll
       for (int qb = 0; qb < 2; ++qb) {
@@ -444,7 +621,7 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
           }
         }
       } else {
-        float* rec = p.ws + (size_t)(2 * cidx + (first_seg ? 0 : 1)) * kPartialFloats;
+        float* rec = p.ws + (size_t)((2 * cidx + (first_seg ? 0 : 1)) * 2 + set) * kPartialFloats;
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
           const int r = qhalf * 64 + qb * 32 + l32;
@@ -465,23 +642,33 @@ __global__ void __launch_bounds__(256, 2) attn_bf16_kernel(AttnParams p) {
     __syncthreads();                                  // merge scratch is reused as tile buffers
     u += t1 - t0;
   }
+  if (set == 0) phase_barrier();                       // set A: the barrier set B executed up front
+#ifdef OVGGT_TRACE
+  if (lane == 0) {
+    unsigned long long* tr = (unsigned long long*)(p.ws + (size_t)4 * kMaxAttnWgs * kPartialFloats) - (size_t)(cidx * 8 + wave + 1) * 8;
+    tr[0] = x.tr_w; tr[1] = wall_clock64() - tr_w0; tr[2] = clock64() - tr_c0; tr[5] = tr_n;
+    if (OVGGT_TRACE == 2) { tr[3] = x.tr_s[0]; tr[4] = x.tr_s[1]; tr[6] = x.tr_s[2]; tr[7] = x.tr_s[3]; } else { tr[3] = x.tr_m; tr[4] = x.tr_x; tr[6] = x.tr_v; tr[7] = x.tr_y; }
+  }
+#endif
 }
 
 // Merge the partials of every item that was split across workgroups.
 __global__ void __launch_bounds__(256) attn_combine_kernel(AttnParams p) {
-  const int item = blockIdx.x;
-  const long ua = (long)item * p.T, ub = ua + p.T - 1;
+  const int item = blockIdx.x;                         // (layer-head, query block)
+  const int qb_idx = item % p.QB;
+  const int lh = item / p.QB;
+  const int set = lh & 1;
+  const long ua = ((long)(lh >> 1) * p.QB + qb_idx) * p.T, ub = ua + p.T - 1;
   const int cf = (int)(ua / p.chunk), cl = (int)(ub / p.chunk);
   if (cf == cl) return;                                // one workgroup did the whole item
   const int row = threadIdx.x >> 1, half = threadIdx.x & 1;
-  const int qb_idx = item % p.QB;
-  const int h = (item / p.QB) % p.H;
-  const int li = item / (p.QB * p.H);
+  const int li = lh / p.H;
+  const int h = lh - li * p.H;
   const int qrow = qb_idx * kQueryTile + row;
   if (qrow >= p.M) return;
   float mt = -INFINITY;
   for (int c = cf; c <= cl; ++c) {
-    const float* rec = p.ws + (size_t)(2 * c + ((long)c * p.chunk < ua ? 1 : 0)) * kPartialFloats;
+    const float* rec = p.ws + (size_t)((2 * c + ((long)c * p.chunk < ua ? 1 : 0)) * 2 + set) * kPartialFloats;
     mt = fmaxf(mt, rec[kQueryTile * 64 + row]);
   }
   float acc[32];
@@ -489,7 +676,7 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(AttnParams p) {
   for (int j = 0; j < 32; ++j) acc[j] = 0.f;
   float l = 0.f;
   for (int c = cf; c <= cl; ++c) {
-    const float* rec = p.ws + (size_t)(2 * c + ((long)c * p.chunk < ua ? 1 : 0)) * kPartialFloats;
+    const float* rec = p.ws + (size_t)((2 * c + ((long)c * p.chunk < ua ? 1 : 0)) * 2 + set) * kPartialFloats;
     const float w = __builtin_amdgcn_exp2f(rec[kQueryTile * 64 + row] - mt);
     l += rec[kQueryTile * 64 + kQueryTile + row] * w;
     const float4* o4 = (const float4*)(rec + row * 64 + half * 32);
@@ -528,10 +715,11 @@ hipError_t launch_attn_bf16(const Geom& g, char* kv, int layer0, int nl, const v
   p.kv_layer_bytes = g.kv_layer_bytes;
   p.v_off = (size_t)g.H * g.cap * g.d * g.esize;
   p.ws = (float*)ws;
-  p.H = g.H; p.M = g.M; p.cap = g.cap; p.n_total = n_total; p.nl = nl;
+  p.H = g.H; p.M = g.M; p.cap = g.cap; p.n_total = n_total;
+  p.LH = nl * g.H;
   p.QB = (g.M + kQueryTile - 1) / kQueryTile;
   p.T = (n_total + kSlotTile - 1) / kSlotTile;
-  const long total = (long)nl * g.H * p.QB * p.T;
+  const long total = (long)((p.LH + 1) / 2) * p.QB * p.T;
   if (total > 0x7FFFFFFFL) return hipErrorInvalidValue;
   p.total_units = (int)total;
   if (n_wgs > kMaxAttnWgs) n_wgs = kMaxAttnWgs;
@@ -541,11 +729,11 @@ hipError_t launch_attn_bf16(const Geom& g, char* kv, int layer0, int nl, const v
   p.c = scale * 1.4426950408889634f;
   p.out_f32 = out_f32 ? 1 : 0;
   if (ev && hipEventRecord(ev[0], s) != hipSuccess) return hipErrorUnknown;
-  hipLaunchKernelGGL(attn_bf16_kernel, dim3((unsigned)n_wgs), dim3(256), 0, s, p);
+  hipLaunchKernelGGL(attn_bf16_kernel, dim3((unsigned)n_wgs), dim3(kAttnThreads), 0, s, p);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (ev && hipEventRecord(ev[1], s) != hipSuccess) return hipErrorUnknown;
-  const int items = nl * g.H * p.QB;
+  const int items = p.LH * p.QB;
   hipLaunchKernelGGL(attn_combine_kernel, dim3((unsigned)items), dim3(256), 0, s, p);
   e = hipGetLastError();
   if (e != hipSuccess) return e;

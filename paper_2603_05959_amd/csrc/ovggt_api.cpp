@@ -20,7 +20,7 @@ struct ovggt_cache {
   char* meta;
   char* ws;
   float scale;
-  int n_wgs;                       // attention workgroups (2 per CU)
+  int n_wgs;                       // attention workgroups (1 per CU, 8 waves each)
   std::vector<int32_t> n;          // resident (incl. pending) slots per layer
   std::vector<int64_t> frames;     // completed frames per layer
   std::vector<int8_t> phase;       // 0: expects global_attn, 1: score_select, 2: compact
@@ -192,7 +192,7 @@ int ovggt_cache_init(ovggt_cache** out, const ovggt_config* cfg, void* kv_dev, v
   make_geom(*cfg, &c->g);
   c->kv = (char*)kv_dev; c->meta = (char*)meta_dev; c->ws = (char*)ws_dev;
   c->scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / std::sqrt((float)cfg->head_dim);
-  int wgs = 2 * cus;
+  int wgs = cus;
   wgs = (wgs + 7) & ~7;
   if (wgs < 8) wgs = 8;
   if (const char* e = std::getenv("OVGGT_ATTN_WGS")) {          // tuning knob: attention workgroups per launch

@@ -9,7 +9,7 @@ namespace ovggt {
 
 constexpr int kSlotTile = 128;      // attention consumes the cache in 128-slot tiles
 constexpr int kQueryTile = 128;     // queries per attention work item
-constexpr int kMaxAttnWgs = 1024;   // upper bound on attention workgroups (sizes the workspace)
+constexpr int kMaxAttnWgs = 512;    // upper bound on attention workgroups (sizes the workspace: 4 partials each)
 
 // Per-layer control block kept in the metadata buffer.
 struct Ctrl {
