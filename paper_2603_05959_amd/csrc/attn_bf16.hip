@@ -652,56 +652,63 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
 #endif
 }
 
-// Merge the partials of every item that was split across workgroups.
+// Merge the partials of every item that was split across workgroups.  A workgroup takes 16 query
+// rows of one item; a thread owns four output columns of one row, so every load is one 16-byte
+// piece of a 256-byte row and the few loads a thread issues (one per partial) are all in flight
+// together.
+constexpr int kCombineRows = 16;
 __global__ void __launch_bounds__(256) attn_combine_kernel(AttnParams p) {
-  const int item = blockIdx.x;                         // (layer-head, query block)
+  const int item = blockIdx.x / (kQueryTile / kCombineRows);     // (layer-head, query block)
+  const int rgrp = blockIdx.x % (kQueryTile / kCombineRows);
   const int qb_idx = item % p.QB;
   const int lh = item / p.QB;
   const int set = lh & 1;
   const long ua = ((long)(lh >> 1) * p.QB + qb_idx) * p.T, ub = ua + p.T - 1;
   const int cf = (int)(ua / p.chunk), cl = (int)(ub / p.chunk);
   if (cf == cl) return;                                // one workgroup did the whole item
-  const int row = threadIdx.x >> 1, half = threadIdx.x & 1;
+  const int row = rgrp * kCombineRows + (threadIdx.x >> 4), piece = threadIdx.x & 15;
   const int li = lh / p.H;
   const int h = lh - li * p.H;
   const int qrow = qb_idx * kQueryTile + row;
   if (qrow >= p.M) return;
-  float mt = -INFINITY;
-  for (int c = cf; c <= cl; ++c) {
-    const float* rec = p.ws + (size_t)((2 * c + ((long)c * p.chunk < ua ? 1 : 0)) * 2 + set) * kPartialFloats;
-    mt = fmaxf(mt, rec[kQueryTile * 64 + row]);
-  }
-  float acc[32];
+  constexpr int kMaxParts = 8;                         // partials fetched per round
+  float4 acc = {0.f, 0.f, 0.f, 0.f};
+  float l = 0.f, mt = -INFINITY;
+  for (int c0 = cf; c0 <= cl; c0 += kMaxParts) {
+    float m[kMaxParts], lp[kMaxParts];
+    float4 o[kMaxParts];
 #pragma unroll
-  for (int j = 0; j < 32; ++j) acc[j] = 0.f;
-  float l = 0.f;
-  for (int c = cf; c <= cl; ++c) {
-    const float* rec = p.ws + (size_t)((2 * c + ((long)c * p.chunk < ua ? 1 : 0)) * 2 + set) * kPartialFloats;
-    const float w = __builtin_amdgcn_exp2f(rec[kQueryTile * 64 + row] - mt);
-    l += rec[kQueryTile * 64 + kQueryTile + row] * w;
-    const float4* o4 = (const float4*)(rec + row * 64 + half * 32);
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const float4 v = o4[j];
-      acc[4 * j] += v.x * w; acc[4 * j + 1] += v.y * w; acc[4 * j + 2] += v.z * w; acc[4 * j + 3] += v.w * w;
+    for (int j = 0; j < kMaxParts; ++j) {
+      const int c = min(c0 + j, cl);
+      const float* rec = p.ws + (size_t)((2 * c + ((long)c * p.chunk < ua ? 1 : 0)) * 2 + set) * kPartialFloats;
+      m[j] = rec[kQueryTile * 64 + row];
+      lp[j] = rec[kQueryTile * 64 + kQueryTile + row];
+      o[j] = *(const float4*)(rec + row * 64 + piece * 4);
     }
+    float mn = mt;
+#pragma unroll
+    for (int j = 0; j < kMaxParts; ++j)
+      if (c0 + j <= cl) mn = fmaxf(mn, m[j]);
+    const float rs = __builtin_amdgcn_exp2f(mt - mn);  // 0 in the first round (mt = -inf)
+    acc.x *= rs; acc.y *= rs; acc.z *= rs; acc.w *= rs;
+    l *= rs;
+    mt = mn;
+#pragma unroll
+    for (int j = 0; j < kMaxParts; ++j)
+      if (c0 + j <= cl) {
+        const float w = __builtin_amdgcn_exp2f(m[j] - mt);
+        l += lp[j] * w;
+        acc.x += o[j].x * w; acc.y += o[j].y * w; acc.z += o[j].z * w; acc.w += o[j].w * w;
+      }
   }
   const float inv = 1.0f / l;
-  const size_t oel = (((size_t)li * p.M + qrow) * p.H + h) * 64 + half * 32;
+  const size_t oel = (((size_t)li * p.M + qrow) * p.H + h) * 64 + piece * 4;
   if (p.out_f32) {
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      float4 w = {acc[4 * j] * inv, acc[4 * j + 1] * inv, acc[4 * j + 2] * inv, acc[4 * j + 3] * inv};
-      *(float4*)(p.out + (oel + 4 * j) * 4) = w;
-    }
+    float4 w = {acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv};
+    *(float4*)(p.out + oel * 4) = w;
   } else {
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      bf16x8 w;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) w[e] = (__bf16)(acc[8 * j + e] * inv);
-      *(bf16x8*)(p.out + (oel + 8 * j) * 2) = w;
-    }
+    bf16x4 w = {(__bf16)(acc.x * inv), (__bf16)(acc.y * inv), (__bf16)(acc.z * inv), (__bf16)(acc.w * inv)};
+    *(bf16x4*)(p.out + oel * 2) = w;
   }
 }
 
@@ -734,7 +741,7 @@ hipError_t launch_attn_bf16(const Geom& g, char* kv, int layer0, int nl, const v
   if (e != hipSuccess) return e;
   if (ev && hipEventRecord(ev[1], s) != hipSuccess) return hipErrorUnknown;
   const int items = p.LH * p.QB;
-  hipLaunchKernelGGL(attn_combine_kernel, dim3((unsigned)items), dim3(256), 0, s, p);
+  hipLaunchKernelGGL(attn_combine_kernel, dim3((unsigned)(items * (kQueryTile / kCombineRows))), dim3(256), 0, s, p);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (ev && hipEventRecord(ev[2], s) != hipSuccess) return hipErrorUnknown;

@@ -104,7 +104,7 @@ __device__ inline float row_sum_sq_any(const char* row, int C, int e, int lane) 
 struct SelShared {
   uint32_t hist[128][64];          // two 16-bit bins per word, one column per lane id
   uint32_t cnt[256];
-  uint32_t wave_tot[2][kMaxSelChunks * kSelWaves + 64];
+  uint32_t evmap[kMaxSelChunks * kSelThreads / 32];   // evict bit per slot, slot order
   uint32_t scan_tmp[2][kSelWaves];
   uint32_t totals[2];
   uint32_t digit, rank, bucket, is_last, n_evictable, bad;
@@ -118,29 +118,6 @@ __device__ inline uint32_t score_word(float ss, bool* bad) {
   uint32_t b = __float_as_uint(ss);
   if (ss != ss || (b & 0x80000000u)) { b = 0u; *bad = true; }
   return b;
-}
-
-// exclusive scan of `n` counters laid out consecutively (n <= 2 * kSelThreads); in place
-__device__ inline void block_exclusive_scan(uint32_t* a, int n, uint32_t* wave_tmp, uint32_t* total_out) {
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int i0 = 2 * tid, i1 = 2 * tid + 1;
-  const uint32_t x0 = i0 < n ? a[i0] : 0u, x1 = i1 < n ? a[i1] : 0u;
-  uint32_t s = x0 + x1;
-  uint32_t inc = s;
-#pragma unroll
-  for (int off = 1; off < 64; off *= 2) {
-    const uint32_t y = __shfl_up(inc, off, 64);
-    if (lane >= off) inc += y;
-  }
-  if (lane == 63) wave_tmp[wave] = inc;
-  __syncthreads();
-  uint32_t base = 0;
-  for (int w = 0; w < wave; ++w) base += wave_tmp[w];
-  if (tid == kSelThreads - 1) *total_out = base + inc;
-  const uint32_t ex = base + inc - s;
-  if (i0 < n) a[i0] = ex;
-  if (i1 < n) a[i1] = ex + x0;
-  __syncthreads();
 }
 
 // One radix pass over the candidates: histogram of an 8-bit digit, then the
@@ -280,6 +257,7 @@ __device__ inline void select_phase(SelShared& sh, const Geom& g, const float* s
     __syncthreads();
     TSTAMP(2 + pass);
   }
+  const int hi_shift = pass > 0 ? 24 - 8 * (pass - 1) : 24;
   int lo_shift = 32;                      // 32: ids did not have to be consulted
   if (!done && !budget_error) {
 #pragma nounroll
@@ -298,51 +276,86 @@ __device__ inline void select_phase(SelShared& sh, const Geom& g, const float* s
       __syncthreads();
     }
   }
-  const int hi_shift = pass > 0 ? 24 - 8 * (pass - 1) : 24;
   if (bad) sh.bad = 1;
   TSTAMP(10);
 
-  // evict bit per slot (one bit per chunk, in registers)
-  uint64_t ev0 = 0, ev1 = 0;
-  if (!budget_error) {
-#pragma unroll
-    for (int c = 0; c < n_iter; ++c) {
+  // evict bit per slot, published in slot order: the ballot of one chunk over one wave covers 64
+  // consecutive slots
+  auto publish = [&](int c) {
+    bool ev = false;
+    if (!budget_error) {
       const uint32_t w = word(c);
-      bool ev = false;
       if (w != kNotEvictable) {
         if (lo_shift == 32) ev = (w >> hi_shift) <= (pre_hi >> hi_shift);
         else ev = w < pre_hi || (w == pre_hi && (idw(c) >> lo_shift) <= (pre_lo >> lo_shift));
       }
-      if (ev) { if (c < 64) ev0 |= 1ull << c; else ev1 |= 1ull << (c - 64); }
     }
-  }
-  // holes (evicted slot below B) and movers (kept slot at or above B), in slot order
-  for (int c = 0; c < n_chunks; ++c) {
-    const int i = c * kSelThreads + tid;
-    const bool ev = c < 64 ? (ev0 >> c) & 1 : (ev1 >> (c - 64)) & 1;
-    const bool hole = !budget_error && i < g.B && ev;
-    const bool mover = !budget_error && i >= g.B && i < n_total && !ev;
-    const uint64_t hb = __ballot(hole), mvb = __ballot(mover);
+    const uint64_t b = __ballot(ev);
     if (lane == 0) {
-      sh.wave_tot[0][c * kSelWaves + wave] = __popcll(hb);
-      sh.wave_tot[1][c * kSelWaves + wave] = __popcll(mvb);
+      sh.evmap[(c * kSelThreads >> 5) + 2 * wave] = (uint32_t)b;
+      sh.evmap[(c * kSelThreads >> 5) + 2 * wave + 1] = (uint32_t)(b >> 32);
     }
+  };
+  if constexpr (KPT > 0) {
+#pragma unroll
+    for (int c = 0; c < KPT; ++c)
+      if (c < n_chunks) publish(c);
+  } else {
+    for (int c = 0; c < n_chunks; ++c) publish(c);
   }
   __syncthreads();
   TSTAMP(11);
-  block_exclusive_scan(sh.wave_tot[0], n_chunks * kSelWaves, sh.scan_tmp[0], &sh.totals[0]);
-  block_exclusive_scan(sh.wave_tot[1], n_chunks * kSelWaves, sh.scan_tmp[1], &sh.totals[1]);
-  const uint64_t lt = (1ull << lane) - 1ull;
-  const bool consistent = sh.totals[0] == sh.totals[1] && sh.totals[0] <= (uint32_t)g.M;
-  for (int c = 0; c < n_chunks; ++c) {
-    const int i = c * kSelThreads + tid;
-    const bool ev = c < 64 ? (ev0 >> c) & 1 : (ev1 >> (c - 64)) & 1;
-    const bool hole = !budget_error && i < g.B && ev;
-    const bool mover = !budget_error && i >= g.B && i < n_total && !ev;
-    const uint64_t hb = __ballot(hole), mvb = __ballot(mover);
+  // holes (evicted slot below B) and movers (kept slot at or above B), in slot order: a thread
+  // takes PP consecutive 32-slot words of the bitmap, one scan over the per-thread (holes, movers)
+  // counts gives it the list position of its first hole and first mover
+  const int n_words = (n_total + 31) >> 5;
+  const int PP = (n_words + kSelThreads - 1) / kSelThreads;      // <= 4
+  uint32_t hw[4], mw[4];
+  uint32_t nh = 0, nm = 0;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    hw[j] = mw[j] = 0u;
+    const int wi = tid * PP + j;
+    if (j < PP && wi < n_words) {
+      const int s0 = wi << 5;
+      const uint32_t e = sh.evmap[wi];
+      const uint32_t below_b = s0 + 32 <= g.B ? 0xFFFFFFFFu : (s0 >= g.B ? 0u : ((1u << (g.B - s0)) - 1u));
+      const uint32_t below_n = s0 + 32 <= n_total ? 0xFFFFFFFFu : ((1u << (n_total - s0)) - 1u);
+      hw[j] = e & below_b;
+      mw[j] = ~e & ~below_b & below_n;
+      nh += __popc(hw[j]);
+      nm += __popc(mw[j]);
+    }
+  }
+  bool consistent;
+  {
+    uint32_t inc_h = nh, inc_m = nm;
+#pragma unroll
+    for (int off = 1; off < 64; off *= 2) {
+      const uint32_t yh = __shfl_up(inc_h, off, 64), ym = __shfl_up(inc_m, off, 64);
+      if (lane >= off) { inc_h += yh; inc_m += ym; }
+    }
+    if (lane == 63) { sh.scan_tmp[0][wave] = inc_h; sh.scan_tmp[1][wave] = inc_m; }
+    __syncthreads();
+    uint32_t base_h = 0, base_m = 0, tot_h = 0, tot_m = 0;
+#pragma unroll
+    for (int w = 0; w < kSelWaves; ++w) {
+      const uint32_t th = sh.scan_tmp[0][w], tm = sh.scan_tmp[1][w];
+      if (w < wave) { base_h += th; base_m += tm; }
+      tot_h += th; tot_m += tm;
+    }
+    consistent = !budget_error && tot_h == tot_m && tot_h <= (uint32_t)g.M;
+    if (tid == 0) sh.totals[0] = tot_h;
     if (consistent) {
-      if (hole) mvdst[sh.wave_tot[0][c * kSelWaves + wave] + __popcll(hb & lt)] = (uint32_t)i;
-      if (mover) mvsrc[sh.wave_tot[1][c * kSelWaves + wave] + __popcll(mvb & lt)] = (uint32_t)i;
+      uint32_t hp = base_h + inc_h - nh, mp = base_m + inc_m - nm;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const uint32_t s0 = (uint32_t)(tid * PP + j) << 5;
+        uint32_t b = hw[j];
+        while (b) { mvdst[hp++] = s0 + (uint32_t)__builtin_ctz(b); b &= b - 1; }
+        b = mw[j];
+        while (b) { mvsrc[mp++] = s0 + (uint32_t)__builtin_ctz(b); b &= b - 1; }
+      }
     }
   }
   __syncthreads();
