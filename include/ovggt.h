@@ -58,8 +58,8 @@ enum {
   OVGGT_STATUS_BUDGET = 1, /* |P| > B at a selection: Eq. 8's k would be negative; the
                               frame's surplus slots were dropped instead (cache invalid) */
   OVGGT_STATUS_NONFINITE = 2, /* a NaN (or negative) score was seen; it ranks lowest     */
-  OVGGT_STATUS_VRANGE = 4  /* bf16 handle: a V element was NaN or beyond +-65504 (V is
-                              cached as IEEE half; such values were saturated)           */
+  OVGGT_STATUS_VRANGE = 4  /* bf16 handle: a K or V element was NaN or beyond +-65504 (both
+                              are cached as IEEE half; such values were saturated)       */
 };
 
 typedef struct {
@@ -94,10 +94,11 @@ int ovggt_cache_init(ovggt_cache** out, const ovggt_config* cfg,
  * [n, n+M) with token ids t*M+i, then out = softmax(q K^T * scale) V over all
  * n+M resident slots (frame-level causality: the frame sees itself entirely).
  * q, k_new, v_new: device, read-only, [M, N_h, d] in the handle's dtype; out:
- * device, written, [M, N_h, d] in the handle's out_dtype.  bf16 runs compute Q K^T on the bf16 MFMA and
- * P V on the f16 MFMA (V is cached as IEEE half, softmax weights are rounded to
- * half), both with fp32 accumulation, and an fp32 online softmax; f32 runs
- * compute in fp32.  ERR_STATE unless the layer expects a new
+ * device, written, [M, N_h, d] in the handle's out_dtype.  bf16 runs compute both
+ * Q K^T and P V on the f16 MFMA with fp32 accumulation (K and V are cached as IEEE
+ * half, the queries are multiplied by scale*log2(e) and rounded to half, softmax
+ * weights are rounded to half) and an fp32 online softmax; f32 runs compute in
+ * fp32.  ERR_STATE unless the layer expects a new
  * frame. */
 int ovggt_global_attn(ovggt_cache* c, int layer, const void* q, const void* k_new, const void* v_new,
                       void* out, void* hip_stream);
@@ -141,8 +142,8 @@ int ovggt_cache_status(ovggt_cache* c, int layer, int32_t* status, void* hip_str
 /* Synchronises `hip_stream` and copies the layer's n resident entries to host
  * buffers in slot order: ids uint32[n], k and v [n, N_h, d] in the handle's
  * dtype, ss float[n], flags uint8[n].  Any output pointer may be NULL.  Serves
- * tests and checkpointing.  For bf16 handles V comes back as bf16(half(v)): equal
- * to the appended value whenever that is a normal half number. */
+ * tests and checkpointing.  For bf16 handles K and V come back as bf16(half(x)):
+ * equal to the appended value whenever that is a normal half number. */
 int ovggt_cache_export(ovggt_cache* c, int layer, uint32_t* ids, void* k, void* v, float* ss,
                        uint8_t* flags, void* hip_stream);
 

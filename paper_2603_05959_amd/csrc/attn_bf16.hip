@@ -7,16 +7,20 @@
 //   O^T = V^T P^T    A = V^T via LDS transpose reads, B = P^T straight from the
 //                    S^T accumulators (the contraction index may be permuted
 //                    freely as long as both operands agree)
-// S^T uses v_mfma_f32_32x32x16_bf16 on the bf16 Q and K.  The cache holds V as
-// IEEE half and the softmax weights are rounded to half, so O^T uses
-// v_mfma_f32_32x32x16_f16: 11-bit weights keep the output within 1e-3 of its RMS
-// where 8-bit (bf16) weights reach 4e-2 on rows with one dominant key.  Both
-// accumulate in fp32; the online softmax runs in fp32 in the exp2 domain with a
-// lazily applied running maximum (accumulators are rescaled only when the
-// maximum grows by more than 2^8) and weights biased by 2^7 to sit in the middle
-// of the half range.
+// Both products run on v_mfma_f32_32x32x16_f16 with fp32 accumulation.  The cache
+// holds K and V as IEEE half (exact images of the bf16 inputs inside the half
+// range) and the softmax weights are rounded to half: 11-bit weights keep the
+// output within 1e-3 of its RMS where 8-bit (bf16) weights reach 4e-2 on rows with
+// one dominant key.  The queries are scaled by c = scale * log2(e) and rounded to
+// half when a work item starts (relative error 2^-12 per element, below the
+// weights' own rounding), and the running reference of every query enters S^T as
+// a fifth contraction step, so the accumulators leave the matrix pipe as the
+// exponents x = s*c - ref and the softmax is exp2, convert, add and nothing else.
+// The reference is applied lazily (accumulators are rescaled only when the
+// maximum grows by more than 2^8) and sits 7 below the maximum, so weights are
+// stored as 2^7 * p in the middle of the half range.
 //
-// Schedule.  On this chip the softmax of a tile (64 x {fma, exp, add} + 32
+// Schedule.  On this chip the softmax of a tile (64 x {exp, add} + 32
 // conversions per lane) costs more VALU time than the tile's 32 MFMAs cost matrix
 // time, a wave never overlaps its own MFMAs with its own VALU work, and two free
 // running waves on a SIMD starve the younger one.  So a workgroup is 8 waves =
@@ -141,25 +145,28 @@ __device__ inline f16x8 join4(const uint32_t* p) {
   return __builtin_bit_cast(f16x8, v);
 }
 
-// Softmax weights of one query block of a tile: p = exp2(s*c - mcb) for the 32 scores a lane
-// holds (two 32-slot accumulators), rounded to half in pairs (kept as the 32-bit pattern of the
-// pair); returns the lane's fp32 sum of the weights.
+// Softmax weights of one query block of a tile: p = exp2(x + d) for the 32 exponents a lane holds
+// (two 32-slot accumulators; the matrix phase already delivered x = s*c - reference), rounded to
+// half in pairs (kept as the 32-bit pattern of the pair); returns the lane's fp32 sum of the
+// weights.  SHIFT: d is added first (slow path only; the fast path has d = 0 and no instruction
+// for it).
 //
-// Issued in batches of 16 (all fma, then all exp, then conversions and adds) with scheduling
-// fences between them: an instruction that consumes the result of the one issued just before it
-// stalls about four cycles (measured for fma -> exp and exp -> add), and left to itself the
-// scheduler emits exactly such dependent pairs to save registers.
-__device__ __forceinline__ float tile_weights(const f32x16& s0, const f32x16& s1, float c, float mcb,
+// Issued in batches of 16 (all exp, then conversions and adds) with scheduling fences between
+// them: an instruction that consumes the result of the one issued just before it stalls about four
+// cycles (measured for exp -> add), and left to itself the scheduler emits exactly such dependent
+// pairs to save registers.
+template <bool SHIFT>
+__device__ __forceinline__ float tile_weights(const f32x16& s0, const f32x16& s1, float d,
                                               uint32_t (&p0)[8], uint32_t (&p1)[8]) {
   float ls[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int sb = 0; sb < 2; ++sb) {
     float e[16];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) e[i] = (OVGGT_ABLATE & 8) ? (sb ? s1[i] : s0[i]) : __builtin_fmaf(sb ? s1[i] : s0[i], c, -mcb);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int i = 0; i < 16; ++i) e[i] = __builtin_amdgcn_exp2f(e[i]);
+    for (int i = 0; i < 16; ++i) {
+      const float x = sb ? s1[i] : s0[i];
+      e[i] = __builtin_amdgcn_exp2f(SHIFT ? x + d : x);
+    }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
@@ -168,15 +175,21 @@ __device__ __forceinline__ float tile_weights(const f32x16& s0, const f32x16& s1
       pk[1] = (_Float16)e[2 * j + 1];
       // plain fp32 adds: v_dot2c_f32_f16 runs on the matrix pipe and serialises with the other
       // set's MFMAs (measured), v_add_f32 co-executes with them
-      if (!(OVGGT_ABLATE & 16)) {
-        ls[j & 3] += e[2 * j];
-        ls[(j + 2) & 3] += e[2 * j + 1];
-      }
+      ls[j & 3] += e[2 * j];
+      ls[(j + 2) & 3] += e[2 * j + 1];
       (sb ? p1 : p0)[j] = __builtin_bit_cast(uint32_t, pk);
     }
     __builtin_amdgcn_sched_barrier(0);
   }
   return (ls[0] + ls[1]) + (ls[2] + ls[3]);
+}
+
+// The reference of a query block as the B operand of the bias step of S^T: -ref (exact in half) at
+// contraction index 0, which only the lanes of the first 8-index group hold.
+__device__ __forceinline__ f16x8 bias_operand(float ref, int g) {
+  const f16x2 h = {(_Float16)(-ref), (_Float16)0.f};
+  const u32x4 v = {g == 0 ? __builtin_bit_cast(uint32_t, h) : 0u, 0u, 0u, 0u};
+  return __builtin_bit_cast(f16x8, v);
 }
 
 // Matrix phase, first part: O^T += V^T P^T for one 64-slot x 64-query tile of one wave; each V^T
@@ -212,70 +225,59 @@ __device__ __forceinline__ void pv_tile(const char* lds, const int (&voff)[2][2]
     }
 }
 
-// Matrix phase, second part: S^T = K Q^T, S indexed [slot block][query block].
+// Matrix phase, second part: S^T = K Q'^T - ref, S indexed [slot block][query block].  Q' is the
+// query scaled by c = scale * log2(e) and rounded to half, K is cached as half, and the reference of
+// each query enters as one more step of the contraction (a column of ones on the K side times a
+// row holding -ref on the Q side), so the accumulators leave the matrix pipe as the exponents the
+// softmax needs and the vector phase spends no instruction on scaling or subtracting.  The bias
+// step goes first: it needs no LDS operand and covers the latency of the first K reads.
 template <int PAR>
-__device__ __forceinline__ void qk_tile(const char* lds, const int (&koff)[4], const bf16x8 (&qf)[2][4],
-                                        f32x16 (&S)[2][2]) {
+__device__ __forceinline__ void qk_tile(const char* lds, const int (&koff)[4], const f16x8 (&qf)[2][4],
+                                        const f16x8 (&qbias)[2], f16x8 kones, f32x16 (&S)[2][2]) {
   const char* ldsK = lds + PAR * 2 * kTileBytes;
+  f32x16 zero;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) zero[i] = 0.f;
 #pragma unroll
   for (int a = 0; a < 2; ++a)
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) S[a][b][i] = 0.f;
+    for (int b = 0; b < 2; ++b) S[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kones, qbias[b], zero, 0, 0, 0);
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks) {
-#if OVGGT_ABLATE & 2
-    const bf16x8 k0 = qf[1][ks], k1 = qf[0][(ks + 1) & 3];
-#else
-    const bf16x8 k0 = *LDS_PTR(const bf16x8, ldsK + koff[ks]);
-    const bf16x8 k1 = *LDS_PTR(const bf16x8, ldsK + koff[ks] + 32 * 128);
-#endif
-#if OVGGT_ABLATE & 1
-    asm volatile("" :: "v"(k0), "v"(k1));
-    continue;
-#endif
-    S[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0, qf[0][ks], S[0][0], 0, 0, 0);
-    S[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0, qf[1][ks], S[0][1], 0, 0, 0);
-    S[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1, qf[0][ks], S[1][0], 0, 0, 0);
-    S[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1, qf[1][ks], S[1][1], 0, 0, 0);
+    const f16x8 k0 = *LDS_PTR(const f16x8, ldsK + koff[ks]);
+    const f16x8 k1 = *LDS_PTR(const f16x8, ldsK + koff[ks] + 32 * 128);
+    S[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(k0, qf[0][ks], S[0][0], 0, 0, 0);
+    S[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(k0, qf[1][ks], S[0][1], 0, 0, 0);
+    S[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(k1, qf[0][ks], S[1][0], 0, 0, 0);
+    S[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(k1, qf[1][ks], S[1][1], 0, 0, 0);
   }
 }
 
 // Vector phase: online softmax of one 64-slot x 64-query tile of one wave.
-// tail: the tile extends past n_total (only the last tile can); weights of the
-// absent slots are cleared after the softmax (their rows hold zeros or stale but
-// finite keys, so their scores are finite and merely move the reference maximum).
+// S holds x = s*c - ref for the reference ref the query block had when the matrix phase ran; ref
+// is (a half-representable value near) the running maximum of s*c minus 7, so weights are stored
+// as 2^7 * p and sit in the middle of the half range.
+// tail: the tile extends past n_total (only the last tile can); weights of the absent slots are
+// cleared after the softmax (their rows hold zeros or stale but finite keys, so their exponents
+// are finite and merely move the reference).
 //
-// Fast path: weights are formed against the running reference maximum m without
-// looking for this tile's maximum; p = 2^7 * exp2((s - m) * c) is rounded to half
-// and summed.  If the lane's sum stays below 2^15 no weight can have overflowed
-// half.  Otherwise (first tile, or the maximum grew by about 2^8) the wave takes
-// the slow path: true tile maximum, rescale O and l, redo the weights.  The
-// reference maximum therefore lags the true one by < 2^8, which costs no accuracy
-// in fp32/half arithmetic.  O holds the tiles before this one (their P V products
-// were issued in the preceding matrix phase), so rescaling it here is consistent.
+// Fast path: weights are formed against the current reference without looking for this tile's
+// maximum; p = exp2(x) is rounded to half and summed.  If the lane's sum stays below 2^15 no
+// weight can have overflowed half.  Otherwise (the maximum grew by about 2^8), and always on the
+// first tile of a segment (force: the reference starts at 0 and must be set from real scores so
+// that small weights do not underflow), the wave takes the slow path: true tile maximum, new
+// reference, rescale O and l, redo the weights.  The reference therefore lags the true maximum
+// by < 2^8, which costs no accuracy in fp32/half arithmetic; any value of it is consistent as long
+// as every weight since the last rescale used the same one, which the exact half value guarantees.
+// O holds the tiles before this one (their P V products were issued in the preceding matrix
+// phase), so rescaling it here is consistent.
 __device__ __forceinline__ void softmax_tile(const f32x16 (&S)[2][2], uint32_t (&P)[2][2][8], f32x16 (&O)[2][2],
-                                             float (&mrun)[2], float (&lrun)[2], float c, int sbase, int n_total,
-                                             bool tail, unsigned long long* trs = nullptr) {
+                                             float (&ref)[2], f16x8 (&qbias)[2], float (&lrun)[2], int g,
+                                             int sbase, int n_total, bool tail, bool force) {
   float lsum[2];
-#ifdef OVGGT_TRACE
-  __builtin_amdgcn_sched_barrier(0);
-  trs[0] = clock64();
-  __builtin_amdgcn_sched_barrier(0);
-#endif
-  lsum[0] = tile_weights(S[0][0], S[1][0], c, mrun[0] * c - kWeightBias, P[0][0], P[1][0]);
-#ifdef OVGGT_TRACE
-  __builtin_amdgcn_sched_barrier(0);
-  trs[1] = clock64();
-  __builtin_amdgcn_sched_barrier(0);
-#endif
-  lsum[1] = tile_weights(S[0][1], S[1][1], c, mrun[1] * c - kWeightBias, P[0][1], P[1][1]);
-#ifdef OVGGT_TRACE
-  __builtin_amdgcn_sched_barrier(0);
-  trs[2] = clock64();
-  __builtin_amdgcn_sched_barrier(0);
-#endif
+#pragma unroll
+  for (int qb = 0; qb < 2; ++qb)
+    lsum[qb] = tile_weights<false>(S[0][qb], S[1][qb], 0.f, P[0][qb], P[1][qb]);
 
   // one overflow test for both query blocks; the compare is issued before the conversions to half
   // are forced out, so the branch does not wait for the VALU pipeline to drain
@@ -287,7 +289,7 @@ __device__ __forceinline__ void softmax_tile(const f32x16 (&S)[2][2], uint32_t (
     for (int b = 0; b < 2; ++b)
 #pragma unroll
       for (int j = 0; j < 8; ++j) asm volatile("" : "+v"(P[a][b][j]));
-  if (__builtin_expect(overflow, 0)) {
+  if (__builtin_expect(overflow || force, 0)) {
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
       float mx = S[0][qb][0];
@@ -296,15 +298,20 @@ __device__ __forceinline__ void softmax_tile(const f32x16 (&S)[2][2], uint32_t (
 #pragma unroll
       for (int i = 0; i < 16; ++i) mx = fmaxf(mx, S[1][qb][i]);
       mx = pair_max(mx);
-      const float mnew = fmaxf(mrun[qb], mx);
-      const float alpha = __builtin_amdgcn_exp2f((mrun[qb] - mnew) * c);
-      mrun[qb] = mnew;
+      // the tile's maximum of s*c is mx + ref; the new reference is that minus 7, rounded to half
+      const float want = fminf(fmaxf(mx + ref[qb] - kWeightBias, -65504.f), 65504.f);
+      const float cand = (float)(_Float16)want;
+      const float rnew = force ? cand : fmaxf(ref[qb], cand);
+      const float d = ref[qb] - rnew;
+      const float alpha = force ? 1.f : __builtin_amdgcn_exp2f(d);     // nothing accumulated yet when forced
+      ref[qb] = rnew;
+      qbias[qb] = bias_operand(rnew, g);
       lrun[qb] *= alpha;
 #pragma unroll
       for (int db = 0; db < 2; ++db)
 #pragma unroll
         for (int i = 0; i < 16; ++i) O[db][qb][i] *= alpha;
-      lsum[qb] = tile_weights(S[0][qb], S[1][qb], c, mnew * c - kWeightBias, P[0][qb], P[1][qb]);
+      lsum[qb] = tile_weights<true>(S[0][qb], S[1][qb], d, P[0][qb], P[1][qb]);
     }
   }
   if (__builtin_expect(tail, 0)) {
@@ -328,17 +335,6 @@ __device__ __forceinline__ void softmax_tile(const f32x16 (&S)[2][2], uint32_t (
   }
   lrun[0] += lsum[0];
   lrun[1] += lsum[1];
-#ifdef OVGGT_TRACE
-#pragma unroll
-  for (int a = 0; a < 2; ++a)
-#pragma unroll
-    for (int b = 0; b < 2; ++b)
-#pragma unroll
-      for (int j = 0; j < 8; ++j) asm volatile("" : "+v"(P[a][b][j]));
-  __builtin_amdgcn_sched_barrier(0);
-  trs[3] = clock64();
-  __builtin_amdgcn_sched_barrier(0);
-#endif
 }
 
 // State a wave carries through one segment (a run of tiles of one item).
@@ -349,20 +345,28 @@ struct TileCtx {
   uint32_t lane_off;          // this lane's byte offset inside a tile for the direct-to-LDS loads
   uint32_t lds_ld;            // LDS byte address of this wave's 32 rows in K buffer 0 of its set
   int t1, T, n_total, slot0;  // slot0: first slot of this lane's accumulator rows within a tile
-  float c;
+  int g;                      // which 8-index group of the contraction this lane holds
   bool active;
 #ifdef OVGGT_TRACE
-  unsigned long long tr_m, tr_x, tr_v, tr_y, tr_w, tr_s[4];   // cycles in matrix phase, at its barrier, in vector phase, at its barrier
+  unsigned long long tr_m, tr_x, tr_v, tr_y, tr_w;   // cycles in matrix phase, at its barrier, in vector phase, at its barrier
 #endif
+};
+
+// Per-wave attention state of one segment.
+struct SegState {
+  f16x8 qf[2][4];             // Q'^T fragments: c * q rounded to half
+  f16x8 qbias[2];             // bias operand of each query block (-ref at contraction index 0)
+  f16x8 kones;                // K-side operand of the bias step (1 at contraction index 0)
+  f32x16 S[2][2], O[2][2];
+  uint32_t P[2][2][8];
+  float ref[2], lrun[2];
 };
 
 // One tile: matrix phase, barrier, vector phase, barrier.  PAR is the parity of the tile within the
 // segment and selects the LDS buffers at compile time (no address arithmetic on the VALU).
 template <int PAR>
 __device__ __forceinline__ void tile_step(TileCtx& x, int tt, bool first, const int (&koff)[4],
-                                          const int (&voff)[2][2], const bf16x8 (&qf)[2][4], f32x16 (&S)[2][2],
-                                          uint32_t (&P)[2][2][8], f32x16 (&O)[2][2], float (&mrun)[2],
-                                          float (&lrun)[2]) {
+                                          const int (&voff)[2][2], SegState& z) {
   const bool more = tt + 1 < x.t1;
 #ifdef OVGGT_TRACE
   const unsigned long long tr0 = clock64();
@@ -373,12 +377,12 @@ __device__ __forceinline__ void tile_step(TileCtx& x, int tt, bool first, const 
   if (x.active) {
     if (more)
       load_rows_to_lds(x.kbase + (size_t)(tt + 1) * kTileBytes, x.lane_off, x.lds_ld + (PAR ^ 1) * 2 * kTileBytes);
-    if (!first) pv_tile<PAR ^ 1>(x.lds, voff, P, O);
-    qk_tile<PAR>(x.lds, koff, qf, S);
+    if (!first) pv_tile<PAR ^ 1>(x.lds, voff, z.P, z.O);
+    qk_tile<PAR>(x.lds, koff, z.qf, z.qbias, z.kones, z.S);
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
-      for (int b = 0; b < 2; ++b) asm volatile("" : "+v"(S[a][b]));      // issued before the barrier
+      for (int b = 0; b < 2; ++b) asm volatile("" : "+v"(z.S[a][b]));      // issued before the barrier
   }
   __builtin_amdgcn_s_setprio(0);
 #ifdef OVGGT_TRACE
@@ -395,24 +399,14 @@ __device__ __forceinline__ void tile_step(TileCtx& x, int tt, bool first, const 
     if (more)
       load_rows_to_lds(x.vbase + (size_t)(tt + 1) * kTileBytes, x.lane_off,
                        x.lds_ld + (PAR ^ 1) * 2 * kTileBytes + kTileBytes);
-#if OVGGT_ABLATE & 64
-    if (x.n_total < 0)
-#endif
-#ifdef OVGGT_TRACE
-    unsigned long long trs[4];
-    softmax_tile(S, P, O, mrun, lrun, x.c, tt * kSlotTile + x.slot0, x.n_total,
-                 tt == x.T - 1 && (x.n_total & (kSlotTile - 1)) != 0, trs);
-    x.tr_s[0] += trs[0] - tr2; x.tr_s[1] += trs[1] - trs[0]; x.tr_s[2] += trs[2] - trs[1]; x.tr_s[3] += trs[3] - trs[2];
-#else
-    softmax_tile(S, P, O, mrun, lrun, x.c, tt * kSlotTile + x.slot0, x.n_total,
-                 tt == x.T - 1 && (x.n_total & (kSlotTile - 1)) != 0);
-#endif
+    softmax_tile(z.S, z.P, z.O, z.ref, z.qbias, z.lrun, x.g, tt * kSlotTile + x.slot0, x.n_total,
+                 tt == x.T - 1 && (x.n_total & (kSlotTile - 1)) != 0, first);
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
       for (int b = 0; b < 2; ++b)
 #pragma unroll
-        for (int j = 0; j < 8; ++j) asm volatile("" : "+v"(P[a][b][j]));   // computed before the barrier
+        for (int j = 0; j < 8; ++j) asm volatile("" : "+v"(z.P[a][b][j]));   // computed before the barrier
   }
 #ifdef OVGGT_TRACE
   __builtin_amdgcn_sched_barrier(0);
@@ -473,12 +467,12 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
 
   TileCtx x;
 #ifdef OVGGT_TRACE
-  x.tr_m = x.tr_x = x.tr_v = x.tr_y = x.tr_w = 0; x.tr_s[0] = x.tr_s[1] = x.tr_s[2] = x.tr_s[3] = 0;
+  x.tr_m = x.tr_x = x.tr_v = x.tr_y = x.tr_w = 0;
 #endif
   x.lds = lds;
   x.T = p.T;
   x.n_total = p.n_total;
-  x.c = p.c;
+  x.g = g;
   x.slot0 = khalf * 64 + 4 * g;
   {
     const int ld_row = lane >> 3;
@@ -506,58 +500,77 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
     x.vbase = x.kbase + p.v_off;
     const int q0 = qb_idx * kQueryTile;
 
-    // Q^T fragments: lane holds query (q0 + qhalf*64 + qb*32 + l32), d = ks*16 + 8g .. +8
-    bf16x8 qf[2][4];
+    // prologue: first tile of the segment into the parity-0 buffers
+    if (active) {
+      load_rows_to_lds(x.kbase + (size_t)t0 * kTileBytes, x.lane_off, x.lds_ld);
+      load_rows_to_lds(x.vbase + (size_t)t0 * kTileBytes, x.lane_off, x.lds_ld + kTileBytes);
+    }
+
+    // Q'^T fragments: lane holds query (q0 + qhalf*64 + qb*32 + l32), d = ks*16 + 8g .. +8, as
+    // half(c * q): the scores then leave the matrix pipe already in the exp2 domain
+    SegState z;
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
       int qrow = q0 + qhalf * 64 + qb * 32 + l32;
       if (qrow > p.M - 1) qrow = p.M - 1;
       const char* qp = p.q + ((((size_t)li * p.M + qrow) * p.H + h) * 64) * 2;
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) qf[qb][ks] = *(const bf16x8*)(qp + (ks * 16 + 8 * g) * 2);
-    }
-
-    f32x16 O[2][2], S[2][2];
-    uint32_t P[2][2][8];
+      for (int ks = 0; ks < 4; ++ks) {
+        const u32x4 w = *(const u32x4*)(qp + (ks * 16 + 8 * g) * 2);
+        u32x4 r;
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+        for (int e = 0; e < 4; ++e) {
+          f16x2 hh;
+          hh[0] = (_Float16)(__uint_as_float(w[e] << 16) * p.c);
+          hh[1] = (_Float16)(__uint_as_float(w[e] & 0xFFFF0000u) * p.c);
+          r[e] = __builtin_bit_cast(uint32_t, hh);
+        }
+        z.qf[qb][ks] = __builtin_bit_cast(f16x8, r);
+      }
+    }
+    {
+      const u32x4 one = {g == 0 ? 0x00003C00u : 0u, 0u, 0u, 0u};          // half 1.0 at contraction index 0
+      z.kones = __builtin_bit_cast(f16x8, one);
+    }
+#pragma unroll
+    for (int a = 0; a < 2; ++a) {
+      z.ref[a] = 0.f;                                    // replaced on the first tile (forced slow path)
+      z.lrun[a] = 0.f;
+      z.qbias[a] = bias_operand(0.f, g);
 #pragma unroll
       for (int b = 0; b < 2; ++b) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) { O[a][b][i] = 0.f; S[a][b][i] = 0.f; }
+        for (int i = 0; i < 16; ++i) { z.O[a][b][i] = 0.f; z.S[a][b][i] = 0.f; }
 #pragma unroll
-        for (int j = 0; j < 8; ++j) P[a][b][j] = 0u;
+        for (int j = 0; j < 8; ++j) z.P[a][b][j] = 0u;
       }
-    float mrun[2] = {-1e30f, -1e30f};
-    float lrun[2] = {0.f, 0.f};
-
-    // prologue: first tile of the segment into the parity-0 buffers; the builtin wait also tells the
-    // compiler that the loads it tracks itself (Q) are complete, so it adds no vmcnt waits of its own
-    if (active) {
-      load_rows_to_lds(x.kbase + (size_t)t0 * kTileBytes, x.lane_off, x.lds_ld);
-      load_rows_to_lds(x.vbase + (size_t)t0 * kTileBytes, x.lane_off, x.lds_ld + kTileBytes);
     }
+
+    // the builtin wait also tells the compiler that the loads it tracks itself (Q) are complete, so
+    // it adds no vmcnt waits of its own inside the tile loop
     __builtin_amdgcn_s_waitcnt(kWaitVm0);
     phase_barrier();
 
     int tt = t0;
     bool first = true;
     for (; tt + 1 < t1; tt += 2) {
-      tile_step<0>(x, tt, first, koff, voff, qf, S, P, O, mrun, lrun);
-      tile_step<1>(x, tt + 1, false, koff, voff, qf, S, P, O, mrun, lrun);
+      tile_step<0>(x, tt, first, koff, voff, z);
+      tile_step<1>(x, tt + 1, false, koff, voff, z);
       first = false;
     }
     const bool odd = tt < t1;                            // an odd number of tiles: one more on parity 0
-    if (odd) tile_step<0>(x, tt, first, koff, voff, qf, S, P, O, mrun, lrun);
+    if (odd) tile_step<0>(x, tt, first, koff, voff, z);
 #ifdef OVGGT_TRACE
     tr_n += t1 - t0;
 #endif
 
     // P V of the last tile
     if (active) {
-      if (odd) pv_tile<0>(lds, voff, P, O);
-      else pv_tile<1>(lds, voff, P, O);
+      if (odd) pv_tile<0>(lds, voff, z.P, z.O);
+      else pv_tile<1>(lds, voff, z.P, z.O);
     }
+    f32x16 (&O)[2][2] = z.O;
+    float (&lrun)[2] = z.lrun;
 
     // ---- merge the two slot halves through the set's LDS
     float ltot[2];
@@ -575,7 +588,7 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
           for (int i = 0; i < 16; ++i) mO[((db * 2 + qb) * 16 + i) * 64 + lane] = O[db][qb][i];
 #pragma unroll
       for (int qb = 0; qb < 2; ++qb) {
-        mML[qb * 64 + lane] = mrun[qb] * p.c;
+        mML[qb * 64 + lane] = z.ref[qb];
         mML[(2 + qb) * 64 + lane] = ltot[qb];
       }
     }
@@ -584,7 +597,7 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
       float mfin[2], lfin[2];
 #pragma unroll
       for (int qb = 0; qb < 2; ++qb) {
-        const float m0 = mrun[qb] * p.c, m1 = mML[qb * 64 + lane];
+        const float m0 = z.ref[qb], m1 = mML[qb * 64 + lane];
         const float mt = fmaxf(m0, m1);
         const float a0 = __builtin_amdgcn_exp2f(m0 - mt), a1 = __builtin_amdgcn_exp2f(m1 - mt);
         mfin[qb] = mt;
@@ -647,7 +660,7 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
   if (lane == 0) {
     unsigned long long* tr = (unsigned long long*)(p.ws + (size_t)4 * kMaxAttnWgs * kPartialFloats) - (size_t)(cidx * 8 + wave + 1) * 8;
     tr[0] = x.tr_w; tr[1] = wall_clock64() - tr_w0; tr[2] = clock64() - tr_c0; tr[5] = tr_n;
-    if (OVGGT_TRACE == 2) { tr[3] = x.tr_s[0]; tr[4] = x.tr_s[1]; tr[6] = x.tr_s[2]; tr[7] = x.tr_s[3]; } else { tr[3] = x.tr_m; tr[4] = x.tr_x; tr[6] = x.tr_v; tr[7] = x.tr_y; }
+    tr[3] = x.tr_m; tr[4] = x.tr_x; tr[6] = x.tr_v; tr[7] = x.tr_y;
   }
 #endif
 }

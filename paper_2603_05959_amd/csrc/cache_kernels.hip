@@ -8,8 +8,9 @@
 
 namespace ovggt {
 
-// bf16 handles keep V as IEEE binary16: the P*V product then runs on the f16
-// MFMA with 11-bit softmax weights instead of 8-bit ones.  Values beyond the
+// bf16 handles keep K and V as IEEE binary16: both attention products then run
+// on the f16 MFMA, P*V with 11-bit softmax weights instead of 8-bit ones and
+// Q*K^T with queries that carry the softmax scale at 11 bits.  Values beyond the
 // half range saturate (and are reported), values below 2^-14 round to the half
 // subnormal grid.
 __device__ inline uint32_t bf16pair_to_half(uint32_t w, bool* clipped) {
@@ -55,15 +56,18 @@ append_kernel(Geom g, char* kv, char* meta, int layer0, const char* k_new, const
   const int m = (int)(i / ((size_t)pieces * g.H));
   const size_t src = (size_t)blockIdx.y * per_layer_in + ((size_t)m * g.H + h) * row_bytes + piece * 16;
   const size_t dst = ((size_t)h * g.cap + (n + m)) * row_bytes + piece * 16;
-  *(uint4*)(layer_k(kv, g, layer) + dst) = *(const uint4*)(k_new + src);
+  uint4 kk = *(const uint4*)(k_new + src);
   uint4 vv = *(const uint4*)(v_new + src);
   char* mb = layer_meta(meta, g, layer);
   if (g.esize == 2) {
     bool clipped = false;
+    kk.x = bf16pair_to_half(kk.x, &clipped); kk.y = bf16pair_to_half(kk.y, &clipped);
+    kk.z = bf16pair_to_half(kk.z, &clipped); kk.w = bf16pair_to_half(kk.w, &clipped);
     vv.x = bf16pair_to_half(vv.x, &clipped); vv.y = bf16pair_to_half(vv.y, &clipped);
     vv.z = bf16pair_to_half(vv.z, &clipped); vv.w = bf16pair_to_half(vv.w, &clipped);
     if (clipped) atomicOr(&((Ctrl*)(mb + g.off_ctrl))->status, (uint32_t)OVGGT_STATUS_VRANGE);
   }
+  *(uint4*)(layer_k(kv, g, layer) + dst) = kk;
   *(uint4*)(layer_v(kv, g, layer) + dst) = vv;
   if (h == 0 && piece == 0) {
     ((uint32_t*)(mb + g.off_ids))[n + m] = gid0 + (uint32_t)m;

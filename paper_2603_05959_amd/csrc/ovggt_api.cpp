@@ -33,7 +33,7 @@ struct ovggt_cache {
 
 namespace {
 
-// ---- host conversions between the bf16 interface and the half V storage ----
+// ---- host conversions between the bf16 interface and the half K/V storage ----
 inline float bf16_bits_to_float(uint16_t b) { uint32_t u = (uint32_t)b << 16; float f; std::memcpy(&f, &u, 4); return f; }
 inline uint16_t float_to_bf16_bits(float f) {
   uint32_t u; std::memcpy(&u, &f, 4);
@@ -344,7 +344,7 @@ int ovggt_cache_export(ovggt_cache* c, int layer, uint32_t* ids, void* k, void* 
     for (int h = 0; h < g.H; ++h) {
       if (hipMemcpy(tmp.data(), src + (size_t)h * g.cap * row, (size_t)n * row, hipMemcpyDeviceToHost) != hipSuccess)
         return OVGGT_ERR_HIP;
-      if (which == 1 && g.esize == 2) {        // V is stored as half: hand it back as bf16
+      if (g.esize == 2) {                      // K and V are stored as half: hand them back as bf16
         uint16_t* t16 = (uint16_t*)tmp.data();
         for (size_t j = 0; j < (size_t)n * g.d; ++j) t16[j] = float_to_bf16_bits(half_bits_to_float(t16[j]));
       }
@@ -375,7 +375,7 @@ int ovggt_cache_import(ovggt_cache* c, int layer, int32_t n, int64_t frames, con
       char* dst = which ? layer_v(c->kv, g, layer) : layer_k(c->kv, g, layer);
       for (int h = 0; h < g.H; ++h) {
         for (int i = 0; i < n; ++i) std::memcpy(tmp.data() + (size_t)i * row, src + ((size_t)i * g.H + h) * row, row);
-        if (which == 1 && g.esize == 2) {      // bf16 in, half stored
+        if (g.esize == 2) {                    // bf16 in, half stored
           uint16_t* t16 = (uint16_t*)tmp.data();
           for (size_t j = 0; j < (size_t)n * g.d; ++j) t16[j] = float_to_half_bits_sat(bf16_bits_to_float(t16[j]));
         }

@@ -32,8 +32,8 @@ def rel_err(o_gpu, o_ref):
 
 
 def stored_v(v, dtype):
-    """What export returns for V: bf16 handles keep V as IEEE half (exact for every
-    normal half value, 2^-24 grid below 2^-14) and hand it back as bf16."""
+    """What export returns for K and V: bf16 handles keep both as IEEE half (exact for
+    every normal half value, 2^-24 grid below 2^-14) and hand them back as bf16."""
     if dtype != "bf16":
         return v
     with np.errstate(over="ignore"):
@@ -48,7 +48,7 @@ def compare_cache(cache, orc, layer=0, kv=True):
     assert np.array_equal(e["ss"].view(np.uint32), orc.ss.view(np.uint32)), "scores differ"
     assert np.array_equal(e["flags"], orc.flag)
     if kv:
-        assert np.array_equal(e["k"], orc.k)
+        assert np.array_equal(e["k"], stored_v(orc.k, cache.dtype))
         assert np.array_equal(e["v"], stored_v(orc.v, cache.dtype))
 
 
@@ -138,7 +138,7 @@ def test_cfg4_shape_budget_sweep_and_full_cache_equality():
             assert rel_err(out.float().cpu().numpy().astype(np.float64), ref) < TOL["bf16"]
     e = cache.export(0)
     assert np.array_equal(e["ids"], np.arange(cfg.T * cfg.M))
-    assert np.array_equal(e["k"], np.concatenate(ks))
+    assert np.array_equal(e["k"], stored_v(np.concatenate(ks), "bf16"))
     assert np.array_equal(e["v"], stored_v(np.concatenate(vs), "bf16"))
     cache.close()
 
