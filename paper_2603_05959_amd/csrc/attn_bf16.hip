@@ -72,6 +72,13 @@ __device__ __forceinline__ int swz(int row) { return row & 7; }
 #define OVGGT_ABLATE 0          // timing experiments only: bit 0 no MFMA, bit 1 no LDS operand reads, bit 2 no tile loads, bit 3 no fma, bit 4 no row-sum adds, bit 5 no overflow branch
 #endif
 
+// Wave priority in the two phases.  The vector phase is the longer one and its VALU stream loses
+// issue slots to the other set's MFMAs; giving it the higher priority shortens the younger set's
+// vector phase by a tenth (measured) at no cost to the matrix phase that runs beside it.
+#ifndef OVGGT_PRIO_M
+#define OVGGT_PRIO_M 0
+#define OVGGT_PRIO_V 3
+#endif
 constexpr int kTileBytes = kSlotTile * 128;            // one K (or V) tile: 128 slots x 64 16-bit elements
 constexpr int kSetBytes = 4 * kTileBytes;              // LDS of one wave set: [parity][K | V]
 constexpr int kAttnThreads = 512;
@@ -184,12 +191,14 @@ __device__ __forceinline__ float tile_weights(const f32x16& s0, const f32x16& s1
   return (ls[0] + ls[1]) + (ls[2] + ls[3]);
 }
 
-// The reference of a query block as the B operand of the bias step of S^T: -ref (exact in half) at
-// contraction index 0, which only the lanes of the first 8-index group hold.
-__device__ __forceinline__ f16x8 bias_operand(float ref, int g) {
+// The reference of a query block as the B operand of the bias step of S^T (a 32x32x8 MFMA, whose
+// operands are four halves per lane): -ref (exact in half) at contraction index 0, which only the
+// lanes of the first 4-index group hold.
+typedef __attribute__((ext_vector_type(4))) _Float16 f16x4;
+__device__ __forceinline__ f16x4 bias_operand(float ref, int g) {
   const f16x2 h = {(_Float16)(-ref), (_Float16)0.f};
-  const u32x4 v = {g == 0 ? __builtin_bit_cast(uint32_t, h) : 0u, 0u, 0u, 0u};
-  return __builtin_bit_cast(f16x8, v);
+  const u32x2 v = {g == 0 ? __builtin_bit_cast(uint32_t, h) : 0u, 0u};
+  return __builtin_bit_cast(f16x4, v);
 }
 
 // Matrix phase, first part: O^T += V^T P^T for one 64-slot x 64-query tile of one wave; each V^T
@@ -232,24 +241,29 @@ __device__ __forceinline__ void pv_tile(const char* lds, const int (&voff)[2][2]
 // softmax needs and the vector phase spends no instruction on scaling or subtracting.  The bias
 // step goes first: it needs no LDS operand and covers the latency of the first K reads.
 template <int PAR>
-__device__ __forceinline__ void qk_tile(const char* lds, const int (&koff)[4], const f16x8 (&qf)[2][4],
-                                        const f16x8 (&qbias)[2], f16x8 kones, f32x16 (&S)[2][2]) {
+__device__ __forceinline__ void k_frags(const char* lds, const int (&koff)[4], f16x8 (&kf)[4][2]) {
   const char* ldsK = lds + PAR * 2 * kTileBytes;
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) {
+    kf[ks][0] = *LDS_PTR(const f16x8, ldsK + koff[ks]);
+    kf[ks][1] = *LDS_PTR(const f16x8, ldsK + koff[ks] + 32 * 128);
+  }
+}
+__device__ __forceinline__ void qk_tile(const f16x8 (&kf)[4][2], const f16x8 (&qf)[2][4], const f16x4 (&qbias)[2],
+                                        f16x4 kones, f32x16 (&S)[2][2]) {
   f32x16 zero;
 #pragma unroll
   for (int i = 0; i < 16; ++i) zero[i] = 0.f;
 #pragma unroll
   for (int a = 0; a < 2; ++a)
 #pragma unroll
-    for (int b = 0; b < 2; ++b) S[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kones, qbias[b], zero, 0, 0, 0);
+    for (int b = 0; b < 2; ++b) S[a][b] = __builtin_amdgcn_mfma_f32_32x32x8f16(kones, qbias[b], zero, 0, 0, 0);
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks) {
-    const f16x8 k0 = *LDS_PTR(const f16x8, ldsK + koff[ks]);
-    const f16x8 k1 = *LDS_PTR(const f16x8, ldsK + koff[ks] + 32 * 128);
-    S[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(k0, qf[0][ks], S[0][0], 0, 0, 0);
-    S[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(k0, qf[1][ks], S[0][1], 0, 0, 0);
-    S[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(k1, qf[0][ks], S[1][0], 0, 0, 0);
-    S[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(k1, qf[1][ks], S[1][1], 0, 0, 0);
+    S[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[ks][0], qf[0][ks], S[0][0], 0, 0, 0);
+    S[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[ks][0], qf[1][ks], S[0][1], 0, 0, 0);
+    S[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[ks][1], qf[0][ks], S[1][0], 0, 0, 0);
+    S[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[ks][1], qf[1][ks], S[1][1], 0, 0, 0);
   }
 }
 
@@ -265,15 +279,17 @@ __device__ __forceinline__ void qk_tile(const char* lds, const int (&koff)[4], c
 // maximum; p = exp2(x) is rounded to half and summed.  If the lane's sum stays below 2^15 no
 // weight can have overflowed half.  Otherwise (the maximum grew by about 2^8), and always on the
 // first tile of a segment (force: the reference starts at 0 and must be set from real scores so
-// that small weights do not underflow), the wave takes the slow path: true tile maximum, new
+// that small weights do not underflow), the wave takes the slow path: exponents again, true tile maximum, new
 // reference, rescale O and l, redo the weights.  The reference therefore lags the true maximum
 // by < 2^8, which costs no accuracy in fp32/half arithmetic; any value of it is consistent as long
 // as every weight since the last rescale used the same one, which the exact half value guarantees.
 // O holds the tiles before this one (their P V products were issued in the preceding matrix
 // phase), so rescaling it here is consistent.
-__device__ __forceinline__ void softmax_tile(const f32x16 (&S)[2][2], uint32_t (&P)[2][2][8], f32x16 (&O)[2][2],
-                                             float (&ref)[2], f16x8 (&qbias)[2], float (&lrun)[2], int g,
-                                             int sbase, int n_total, bool tail, bool force) {
+template <int PAR>
+__device__ __forceinline__ void softmax_tile(f32x16 (&S)[2][2], uint32_t (&P)[2][2][8], f32x16 (&O)[2][2],
+                                             float (&ref)[2], f16x4 (&qbias)[2], float (&lrun)[2], int g,
+                                             int sbase, int n_total, bool tail, bool force, const char* lds,
+                                             const int (&koff)[4], const f16x8 (&qf)[2][4], f16x4 kones) {
   float lsum[2];
 #pragma unroll
   for (int qb = 0; qb < 2; ++qb)
@@ -290,6 +306,13 @@ __device__ __forceinline__ void softmax_tile(const f32x16 (&S)[2][2], uint32_t (
 #pragma unroll
       for (int j = 0; j < 8; ++j) asm volatile("" : "+v"(P[a][b][j]));
   if (__builtin_expect(overflow || force, 0)) {
+    // rare: the exponents are recomputed from the K tile (still resident in this phase) rather than
+    // kept alive through the fast path, which frees their registers for the weights
+    {
+      f16x8 kf[4][2];
+      k_frags<PAR>(lds, koff, kf);
+      qk_tile(kf, qf, qbias, kones, S);
+    }
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
       float mx = S[0][qb][0];
@@ -355,8 +378,8 @@ struct TileCtx {
 // Per-wave attention state of one segment.
 struct SegState {
   f16x8 qf[2][4];             // Q'^T fragments: c * q rounded to half
-  f16x8 qbias[2];             // bias operand of each query block (-ref at contraction index 0)
-  f16x8 kones;                // K-side operand of the bias step (1 at contraction index 0)
+  f16x4 qbias[2];             // bias operand of each query block (-ref at contraction index 0)
+  f16x4 kones;                // K-side operand of the bias step (1 at contraction index 0)
   f32x16 S[2][2], O[2][2];
   uint32_t P[2][2][8];
   float ref[2], lrun[2];
@@ -364,8 +387,8 @@ struct SegState {
 
 // One tile: matrix phase, barrier, vector phase, barrier.  PAR is the parity of the tile within the
 // segment and selects the LDS buffers at compile time (no address arithmetic on the VALU).
-template <int PAR>
-__device__ __forceinline__ void tile_step(TileCtx& x, int tt, bool first, const int (&koff)[4],
+template <int PAR, bool FIRST>
+__device__ __forceinline__ void tile_step(TileCtx& x, int tt, const int (&koff)[4],
                                           const int (&voff)[2][2], SegState& z) {
   const bool more = tt + 1 < x.t1;
 #ifdef OVGGT_TRACE
@@ -373,18 +396,36 @@ __device__ __forceinline__ void tile_step(TileCtx& x, int tt, bool first, const 
   __builtin_amdgcn_sched_barrier(0);
 #endif
   // ---- matrix phase
-  __builtin_amdgcn_s_setprio(1);
+  __builtin_amdgcn_s_setprio(OVGGT_PRIO_M);
   if (x.active) {
     if (more)
       load_rows_to_lds(x.kbase + (size_t)(tt + 1) * kTileBytes, x.lane_off, x.lds_ld + (PAR ^ 1) * 2 * kTileBytes);
-    if (!first) pv_tile<PAR ^ 1>(x.lds, voff, z.P, z.O);
-    qk_tile<PAR>(x.lds, koff, z.qf, z.qbias, z.kones, z.S);
+    f16x8 kf[4][2];
+    if (!FIRST) pv_tile<PAR ^ 1>(x.lds, voff, z.P, z.O);
+    k_frags<PAR>(x.lds, koff, kf);
+    qk_tile(kf, z.qf, z.qbias, z.kones, z.S);
+    if (!FIRST) {
+      // Issue order of this phase (one scheduling region: 24 LDS reads, 34 MFMAs).  Left alone the
+      // scheduler saves registers by reading each operand right before the MFMA that needs it and
+      // exposes the LDS latency every time; instead: two V^T fragment groups up front, then each
+      // group of four P V MFMAs is followed by the four reads the MFMAs two groups later need
+      // (the rest of V^T, then K in two halves), so the Q K^T MFMAs find their operands in registers.
+      __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+#pragma unroll
+      for (int grp = 0; grp < 3; ++grp) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, 6, 0);      // last P V group and the two bias steps
+      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);      // second half of K
+      __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
+    }
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
       for (int b = 0; b < 2; ++b) asm volatile("" : "+v"(z.S[a][b]));      // issued before the barrier
   }
-  __builtin_amdgcn_s_setprio(0);
+  __builtin_amdgcn_s_setprio(OVGGT_PRIO_V);
 #ifdef OVGGT_TRACE
   __builtin_amdgcn_sched_barrier(0);
   const unsigned long long tr1 = clock64();
@@ -399,8 +440,8 @@ __device__ __forceinline__ void tile_step(TileCtx& x, int tt, bool first, const 
     if (more)
       load_rows_to_lds(x.vbase + (size_t)(tt + 1) * kTileBytes, x.lane_off,
                        x.lds_ld + (PAR ^ 1) * 2 * kTileBytes + kTileBytes);
-    softmax_tile(z.S, z.P, z.O, z.ref, z.qbias, z.lrun, x.g, tt * kSlotTile + x.slot0, x.n_total,
-                 tt == x.T - 1 && (x.n_total & (kSlotTile - 1)) != 0, first);
+    softmax_tile<PAR>(z.S, z.P, z.O, z.ref, z.qbias, z.lrun, x.g, tt * kSlotTile + x.slot0, x.n_total,
+                      tt == x.T - 1 && (x.n_total & (kSlotTile - 1)) != 0, FIRST, x.lds, koff, z.qf, z.kones);
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
@@ -529,8 +570,8 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
       }
     }
     {
-      const u32x4 one = {g == 0 ? 0x00003C00u : 0u, 0u, 0u, 0u};          // half 1.0 at contraction index 0
-      z.kones = __builtin_bit_cast(f16x8, one);
+      const u32x2 one = {g == 0 ? 0x00003C00u : 0u, 0u};                  // half 1.0 at contraction index 0
+      z.kones = __builtin_bit_cast(f16x4, one);
     }
 #pragma unroll
     for (int a = 0; a < 2; ++a) {
@@ -551,15 +592,15 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
     __builtin_amdgcn_s_waitcnt(kWaitVm0);
     phase_barrier();
 
-    int tt = t0;
-    bool first = true;
+    // the first tile has no predecessor to multiply by V and always sets the reference
+    tile_step<0, true>(x, t0, koff, voff, z);
+    int tt = t0 + 1;
     for (; tt + 1 < t1; tt += 2) {
-      tile_step<0>(x, tt, first, koff, voff, z);
-      tile_step<1>(x, tt + 1, false, koff, voff, z);
-      first = false;
+      tile_step<1, false>(x, tt, koff, voff, z);
+      tile_step<0, false>(x, tt + 1, koff, voff, z);
     }
-    const bool odd = tt < t1;                            // an odd number of tiles: one more on parity 0
-    if (odd) tile_step<0>(x, tt, first, koff, voff, z);
+    const bool odd = tt >= t1;                           // an odd number of tiles: the last one had parity 0
+    if (!odd) tile_step<1, false>(x, tt, koff, voff, z);
 #ifdef OVGGT_TRACE
     tr_n += t1 - t0;
 #endif
