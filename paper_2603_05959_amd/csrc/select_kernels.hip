@@ -23,6 +23,7 @@ namespace ovggt {
 
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / 64;
+constexpr int kRowsPerWave = 4;             // tokens scored per wave and round when many layers are batched
 constexpr int kMaxSelChunks = 128;          // n_total <= 128 * 1024 slots
 
 __device__ inline float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
@@ -87,16 +88,30 @@ tree:
   return v;
 }
 
-template <bool BF16>
-__device__ inline float row_sum_sq_any(const char* row, int C, int e, int lane) {
-  switch (e) {
-    case 1: return row_sum_sq<1, BF16>(row, C, lane);
-    case 2: return row_sum_sq<2, BF16>(row, C, lane);
-    case 4: return row_sum_sq<4, BF16>(row, C, lane);
-    case 8: return row_sum_sq<8, BF16>(row, C, lane);
-    case 16: return row_sum_sq<16, BF16>(row, C, lane);
-    case 32: return row_sum_sq<32, BF16>(row, C, lane);
-    default: return row_sum_sq<64, BF16>(row, C, lane);
+// Phase 1 of one workgroup for a compile-time E.  A wave takes R consecutive tokens per round;
+// their loads are independent, so all of them are in flight before the first reduction.  R = 1
+// spreads a single layer's rows over as many CUs as possible, R = kRowsPerWave amortises the
+// per-workgroup arrival when the launch covers many layers.
+template <int E, bool BF16, int R>
+__device__ inline void score_rows(const char* rbase, size_t row_bytes, int C, int M, const uint8_t* anchors_layer,
+                                  float* ss_new, uint8_t* flags_new) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int tok0 = (blockIdx.x * kSelWaves + wave) * R; tok0 < M; tok0 += gridDim.x * kSelWaves * R) {
+    float v[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+      v[r] = row_sum_sq<E, BF16>(rbase + (size_t)min(tok0 + r, M - 1) * row_bytes, C, lane);
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int tok = tok0 + r;
+      if (lane == 0 && tok < M) {
+        // device-coherent (write-through) stores: the selection may run on another XCD, and a
+        // device-scope release fence per workgroup (an L2 write-back each) would cost far more
+        __hip_atomic_store(&ss_new[tok], v[r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&flags_new[tok], (uint8_t)((anchors_layer && anchors_layer[tok]) ? 1 : 0),
+                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
   }
 }
 
@@ -382,7 +397,7 @@ score_select_kernel(Geom g, char* meta, int layer0, const char* resid, const uin
   float* ss = (float*)(mb + g.off_ss);
   uint8_t* flags = (uint8_t*)(mb + g.off_flags);
   Ctrl* ctrl = (Ctrl*)(mb + g.off_ctrl);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x;
   const int n_old = n_total - g.M;
 
   if (blockIdx.x == 0 && tid == 0) ctrl->pad[15] = (uint32_t)wall_clock64();
@@ -390,29 +405,38 @@ score_select_kernel(Geom g, char* meta, int layer0, const char* resid, const uin
   {
     const size_t row_bytes = (size_t)g.C * g.esize;
     const char* rbase = resid + (size_t)li * g.M * row_bytes;
-    for (int tok = blockIdx.x * kSelWaves + wave; tok < g.M; tok += gridDim.x * kSelWaves) {
-      const float v = row_sum_sq_any<BF16>(rbase + (size_t)tok * row_bytes, g.C, e_per_lane, lane);
-      if (lane == 0) {
-        ss[n_old + tok] = v;
-        flags[n_old + tok] = (anchors && anchors[(size_t)li * g.M + tok]) ? 1 : 0;
-      }
+    const uint8_t* al = anchors ? anchors + (size_t)li * g.M : nullptr;
+    float* sn = ss + n_old;
+    uint8_t* fn = flags + n_old;
+    const bool many = gridDim.x * kSelWaves < (unsigned)g.M;       // the launch packs several tokens per wave
+    switch (e_per_lane) {
+      case 1: if (many) score_rows<1, BF16, kRowsPerWave>(rbase, row_bytes, g.C, g.M, al, sn, fn); else score_rows<1, BF16, 1>(rbase, row_bytes, g.C, g.M, al, sn, fn); break;
+      case 2: if (many) score_rows<2, BF16, kRowsPerWave>(rbase, row_bytes, g.C, g.M, al, sn, fn); else score_rows<2, BF16, 1>(rbase, row_bytes, g.C, g.M, al, sn, fn); break;
+      case 4: if (many) score_rows<4, BF16, kRowsPerWave>(rbase, row_bytes, g.C, g.M, al, sn, fn); else score_rows<4, BF16, 1>(rbase, row_bytes, g.C, g.M, al, sn, fn); break;
+      case 8: if (many) score_rows<8, BF16, kRowsPerWave>(rbase, row_bytes, g.C, g.M, al, sn, fn); else score_rows<8, BF16, 1>(rbase, row_bytes, g.C, g.M, al, sn, fn); break;
+      case 16: if (many) score_rows<16, BF16, kRowsPerWave>(rbase, row_bytes, g.C, g.M, al, sn, fn); else score_rows<16, BF16, 1>(rbase, row_bytes, g.C, g.M, al, sn, fn); break;
+      case 32: if (many) score_rows<32, BF16, kRowsPerWave>(rbase, row_bytes, g.C, g.M, al, sn, fn); else score_rows<32, BF16, 1>(rbase, row_bytes, g.C, g.M, al, sn, fn); break;
+      default: if (many) score_rows<64, BF16, kRowsPerWave>(rbase, row_bytes, g.C, g.M, al, sn, fn); else score_rows<64, BF16, 1>(rbase, row_bytes, g.C, g.M, al, sn, fn); break;
     }
   }
   if (n_total <= g.B) {                      // under budget: nothing to select
     if (blockIdx.x == 0 && tid == 0) ctrl->n_moves = 0;
     return;
   }
-  // Publish this workgroup's scores and count its arrival.  Every wave first
-  // waits for its own stores to reach L2; one thread then performs the
-  // device-scope release / acquire (they act on the whole cache, not on one
-  // wave's data), so the cache maintenance runs once per workgroup.
+  // Publish this workgroup's scores and count its arrival.  The scores were written through to
+  // device-coherent memory, so every wave only waits for its own stores to be acknowledged; the
+  // arrival counter is a relaxed device-scope atomic, and the one workgroup that arrives last
+  // invalidates its caches (acquire) before it reads what the others wrote.
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   if (tid == 0) {
-    __threadfence();
-    const uint32_t prev = atomicAdd(&ctrl->arrive, 1u);
+    const uint32_t prev = __hip_atomic_fetch_add(&ctrl->arrive, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     const bool last = prev == gridDim.x - 1;
-    if (last) { __threadfence(); ctrl->arrive = 0; ctrl->pad[0] = (uint32_t)wall_clock64(); }
+    if (last) {
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+      __hip_atomic_store(&ctrl->arrive, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      ctrl->pad[0] = (uint32_t)wall_clock64();
+    }
     sh.is_last = last ? 1u : 0u;
   }
   __syncthreads();
@@ -427,7 +451,21 @@ score_select_kernel(Geom g, char* meta, int layer0, const char* resid, const uin
 template <bool BF16>
 static void launch_variant(const Geom& g, char* meta, int layer0, int nl, const void* resid,
                            const uint8_t* anchors, int n_total, int e, hipStream_t s) {
-  dim3 grid((unsigned)((g.M + kSelWaves - 1) / kSelWaves), (unsigned)nl);
+  // One workgroup fits a CU (the selection's register-resident keys set the footprint), so the
+  // launch stays within one round of the chip: a single layer spreads its rows one per wave, a
+  // batch of layers gives each workgroup several rounds of kRowsPerWave rows per wave.
+  static int n_cus = 0;
+  if (n_cus == 0) {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+      n_cus = v;
+    else
+      n_cus = 256;
+  }
+  int gx = (g.M + kSelWaves - 1) / kSelWaves;
+  if ((long)gx * nl > n_cus) gx = n_cus / nl > 0 ? n_cus / nl : 1;
+  dim3 grid((unsigned)gx, (unsigned)nl);
   const int n_chunks = (n_total + kSelThreads - 1) / kSelThreads;
 #define OVGGT_SEL_LAUNCH(KPT, IDREG)                                                                  \
   hipLaunchKernelGGL((score_select_kernel<BF16, KPT, IDREG>), grid, dim3(kSelThreads), 0, s, g, meta, \
