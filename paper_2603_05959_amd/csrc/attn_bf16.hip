@@ -69,7 +69,7 @@ typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 __device__ __forceinline__ int swz(int row) { return row & 7; }
 
 #ifndef OVGGT_ABLATE
-#define OVGGT_ABLATE 0          // timing experiments only: bit 0 no MFMA, bit 1 no LDS operand reads, bit 2 no tile loads, bit 3 no fma, bit 4 no row-sum adds, bit 5 no overflow branch
+#define OVGGT_ABLATE 0          // timing experiments only: bit 0 no MFMA, bit 1 no LDS operand reads, bit 2 no tile loads, bit 3 no fma, bit 4 no row-sum adds, bit 5 no overflow branch, bit 7 prefetches hit the L2 (eight tiles reused)
 #endif
 
 // Wave priority in the two phases.  The vector phase is the longer one and its VALU stream loses
@@ -90,7 +90,8 @@ constexpr float kWeightSumLimit = 32768.0f;            // a lane's weight sum be
 constexpr int kWaitVm0 = 0x0F70;                       // vmcnt(0), nothing else
 constexpr int kWaitVm4 = 0x0F74;                       // vmcnt(4)
 
-size_t attn_ws_bytes() { return (size_t)kMaxAttnWgs * 4 * kPartialFloats * sizeof(float); }
+constexpr int kSegRecs = 3;                            // partial records per workgroup and wave set
+size_t attn_ws_bytes() { return (size_t)kMaxAttnWgs * kSegRecs * 2 * kPartialFloats * sizeof(float); }
 
 struct AttnParams {
   const char* q;
@@ -104,10 +105,44 @@ struct AttnParams {
   int QB;                     // query blocks per (layer, head)
   int T;                      // slot tiles
   int chunk;                  // units per workgroup
-  int total_units;            // ceil(LH / 2) * QB * T
+  int NS, L0;                 // tile segments per item and their length (the last one takes the rest)
+  int PP;                     // unit slots per head pair: QB * T, or that rounded up to whole chunks
+  int total_units;            // ceil(LH / 2) * PP
   float c;                    // softmax scale * log2(e)
   int out_f32;                // output element type: 1 = fp32, 0 = bf16
 };
+
+// Order of the work units.  Inside one (layer, head) pair the T tiles of every query block are cut
+// into NS segments (L0 tiles each, the last one takes the rest), and the units run segment by
+// segment, query block by query block, tile by tile.  With L0 equal to a workgroup's chunk,
+// neighbouring workgroups (same XCD, same L2) start on the same tile of neighbouring query blocks
+// and walk the same K/V tiles side by side, so a tile is fetched into the L2 once instead of once
+// per query block.  NS = 1 is the plain order (query block, tile).  A head pair's units may be
+// followed by empty slots up to a whole number of chunks, which keeps chunk and segment boundaries
+// aligned in every head pair (one piece per workgroup in all but the last segment).
+struct UnitPos {
+  bool valid;                 // false: an empty slot behind the head pair's last unit
+  int hp, s, qb;              // head pair, segment, query block
+  int tile;                   // first tile of the unit's run
+  int seg_end;                // end of the segment (exclusive)
+  int combo;                  // running index of (hp, s, qb)
+};
+__host__ __device__ inline UnitPos decode_unit(long u, int T, int QB, int NS, int L0, int PP) {
+  UnitPos r;
+  r.hp = (int)(u / PP);
+  int rem = (int)(u - (long)r.hp * PP);
+  r.valid = rem < QB * T;
+  if (!r.valid) rem = QB * T - 1;
+  r.s = NS == 1 ? 0 : min(rem / (QB * L0), NS - 1);
+  const int seg0 = r.s * L0;
+  r.seg_end = r.s == NS - 1 ? T : seg0 + L0;
+  const int len = r.seg_end - seg0;
+  const int r2 = rem - QB * seg0;
+  r.qb = r2 / len;
+  r.tile = seg0 + r2 - r.qb * len;
+  r.combo = (r.hp * NS + r.s) * QB + r.qb;
+  return r;
+}
 
 // Half a tile pair, global -> LDS: the calling wave fills 32 rows (4 KiB) of a K or V tile with four
 // 16-byte-per-lane direct-to-LDS loads (8 rows of 128 bytes each); lane i's 16 bytes land at
@@ -399,7 +434,7 @@ __device__ __forceinline__ void tile_step(TileCtx& x, int tt, const int (&koff)[
   __builtin_amdgcn_s_setprio(OVGGT_PRIO_M);
   if (x.active) {
     if (more)
-      load_rows_to_lds(x.kbase + (size_t)(tt + 1) * kTileBytes, x.lane_off, x.lds_ld + (PAR ^ 1) * 2 * kTileBytes);
+      load_rows_to_lds(x.kbase + (size_t)((OVGGT_ABLATE & 128) ? ((tt + 1) & 7) : (tt + 1)) * kTileBytes, x.lane_off, x.lds_ld + (PAR ^ 1) * 2 * kTileBytes);
     f16x8 kf[4][2];
     if (!FIRST) pv_tile<PAR ^ 1>(x.lds, voff, z.P, z.O);
     k_frags<PAR>(x.lds, koff, kf);
@@ -438,7 +473,7 @@ __device__ __forceinline__ void tile_step(TileCtx& x, int tt, const int (&koff)[
   // ---- vector phase
   if (x.active) {
     if (more)
-      load_rows_to_lds(x.vbase + (size_t)(tt + 1) * kTileBytes, x.lane_off,
+      load_rows_to_lds(x.vbase + (size_t)((OVGGT_ABLATE & 128) ? ((tt + 1) & 7) : (tt + 1)) * kTileBytes, x.lane_off,
                        x.lds_ld + (PAR ^ 1) * 2 * kTileBytes + kTileBytes);
     softmax_tile<PAR>(z.S, z.P, z.O, z.ref, z.qbias, z.lrun, x.g, tt * kSlotTile + x.slot0, x.n_total,
                       tt == x.T - 1 && (x.n_total & (kSlotTile - 1)) != 0, FIRST, x.lds, koff, z.qf, z.kones);
@@ -482,6 +517,7 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
   const int u_end = min(u + p.chunk, p.total_units);
   if (u >= u_end) return;                                // whole workgroup: no barrier has been executed yet
   const int u_begin = u;
+  int n_piece = 0;
 #ifdef OVGGT_TRACE
   const unsigned long long tr_w0 = wall_clock64(), tr_c0 = clock64();
   unsigned long long tr_n = 0;
@@ -525,13 +561,17 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
   if (set == 1) phase_barrier();
 
   while (u < u_end) {
-    const int item = u / p.T;                            // pair item
-    const int t0 = u - item * p.T;
-    const int t1 = min(p.T, t0 + (u_end - u));
-    const bool first_seg = (u == u_begin);
-    const bool full = (t0 == 0 && t1 == p.T);
-    const int qb_idx = item % p.QB;
-    const int lh = 2 * (item / p.QB) + set;              // this set's (layer, head)
+    const UnitPos up = decode_unit(u, p.T, p.QB, p.NS, p.L0, p.PP);
+    if (!up.valid) break;                                // the rest of the chunk is empty slots
+    const int t0 = up.tile;
+    const int t1 = min(up.seg_end, t0 + (u_end - u));
+    // plain order: only the first and the last piece of a chunk can be partial (records 0 and 1);
+    // segmented order: every piece is partial and takes the next record
+    const int rec_ord = p.NS == 1 ? (u == u_begin ? 0 : 1) : n_piece;
+    ++n_piece;
+    const bool full = (p.NS == 1 && t0 == 0 && t1 == p.T);
+    const int qb_idx = up.qb;
+    const int lh = 2 * up.hp + set;                      // this set's (layer, head)
     const bool active = lh < p.LH;
     const int li = active ? lh / p.H : 0;
     const int h = active ? lh - li * p.H : 0;
@@ -675,7 +715,7 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
           }
         }
       } else {
-        float* rec = p.ws + (size_t)((2 * cidx + (first_seg ? 0 : 1)) * 2 + set) * kPartialFloats;
+        float* rec = p.ws + (size_t)((kSegRecs * cidx + rec_ord) * 2 + set) * kPartialFloats;
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
           const int r = qhalf * 64 + qb * 32 + l32;
@@ -699,7 +739,7 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
   if (set == 0) phase_barrier();                       // set A: the barrier set B executed up front
 #ifdef OVGGT_TRACE
   if (lane == 0) {
-    unsigned long long* tr = (unsigned long long*)(p.ws + (size_t)4 * kMaxAttnWgs * kPartialFloats) - (size_t)(cidx * 8 + wave + 1) * 8;
+    unsigned long long* tr = (unsigned long long*)(p.ws + (size_t)2 * kSegRecs * kMaxAttnWgs * kPartialFloats) - (size_t)(cidx * 8 + wave + 1) * 8;
     tr[0] = x.tr_w; tr[1] = wall_clock64() - tr_w0; tr[2] = clock64() - tr_c0; tr[5] = tr_n;
     tr[3] = x.tr_m; tr[4] = x.tr_x; tr[6] = x.tr_v; tr[7] = x.tr_y;
   }
@@ -717,44 +757,74 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(AttnParams p) {
   const int qb_idx = item % p.QB;
   const int lh = item / p.QB;
   const int set = lh & 1;
-  const long ua = ((long)(lh >> 1) * p.QB + qb_idx) * p.T, ub = ua + p.T - 1;
-  const int cf = (int)(ua / p.chunk), cl = (int)(ub / p.chunk);
-  if (cf == cl) return;                                // one workgroup did the whole item
+  const int hp = lh >> 1;
+  if (p.NS == 1) {
+    const long ua = (long)hp * p.PP + (long)qb_idx * p.T;
+    if (ua / p.chunk == (ua + p.T - 1) / p.chunk) return;   // one workgroup did the whole item
+  }
   const int row = rgrp * kCombineRows + (threadIdx.x >> 4), piece = threadIdx.x & 15;
   const int li = lh / p.H;
   const int h = lh - li * p.H;
   const int qrow = qb_idx * kQueryTile + row;
-  if (qrow >= p.M) return;
-  constexpr int kMaxParts = 8;                         // partials fetched per round
+  constexpr int kMaxParts = 4;                         // partials fetched per round
+  constexpr int kSegGroup = 64;                        // segments whose records are listed at a time
+  __shared__ uint32_t rec_list[kSegGroup * kSegRecs];
+  __shared__ int n_list;
   float4 acc = {0.f, 0.f, 0.f, 0.f};
   float l = 0.f, mt = -INFINITY;
-  for (int c0 = cf; c0 <= cl; c0 += kMaxParts) {
-    float m[kMaxParts], lp[kMaxParts];
-    float4 o[kMaxParts];
-#pragma unroll
-    for (int j = 0; j < kMaxParts; ++j) {
-      const int c = min(c0 + j, cl);
-      const float* rec = p.ws + (size_t)((2 * c + ((long)c * p.chunk < ua ? 1 : 0)) * 2 + set) * kPartialFloats;
-      m[j] = rec[kQueryTile * 64 + row];
-      lp[j] = rec[kQueryTile * 64 + kQueryTile + row];
-      o[j] = *(const float4*)(rec + row * 64 + piece * 4);
-    }
-    float mn = mt;
-#pragma unroll
-    for (int j = 0; j < kMaxParts; ++j)
-      if (c0 + j <= cl) mn = fmaxf(mn, m[j]);
-    const float rs = __builtin_amdgcn_exp2f(mt - mn);  // 0 in the first round (mt = -inf)
-    acc.x *= rs; acc.y *= rs; acc.z *= rs; acc.w *= rs;
-    l *= rs;
-    mt = mn;
-#pragma unroll
-    for (int j = 0; j < kMaxParts; ++j)
-      if (c0 + j <= cl) {
-        const float w = __builtin_amdgcn_exp2f(m[j] - mt);
-        l += lp[j] * w;
-        acc.x += o[j].x * w; acc.y += o[j].y * w; acc.z += o[j].z * w; acc.w += o[j].w * w;
+  for (int sg0 = 0; sg0 < p.NS; sg0 += kSegGroup) {
+    // one thread lists the records that hold pieces of this item (integer divisions, done once)
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      int n = 0;
+      for (int sg = sg0; sg < min(sg0 + kSegGroup, p.NS); ++sg) {
+        const int seg0 = sg * p.L0;
+        const int len = (sg == p.NS - 1 ? p.T : seg0 + p.L0) - seg0;
+        const long ua = (long)hp * p.PP + (long)p.QB * seg0 + (long)qb_idx * len, ub = ua + len - 1;
+        const int cf = (int)(ua / p.chunk), cl = (int)(ub / p.chunk);
+        const int combo = (hp * p.NS + sg) * p.QB + qb_idx;
+        for (int c = cf; c <= cl && n < kSegGroup * kSegRecs; ++c) {
+          // which of the chunk's records: plain order, 0 if the chunk starts with this item, else
+          // 1; segmented order, the pieces of a chunk are numbered in unit order
+          int ord;
+          if (p.NS == 1) ord = (long)c * p.chunk < ua ? 1 : 0;
+          else ord = combo - decode_unit((long)c * p.chunk, p.T, p.QB, p.NS, p.L0, p.PP).combo;
+          rec_list[n++] = (uint32_t)((kSegRecs * c + ord) * 2 + set);
+        }
       }
+      n_list = n;
+    }
+    __syncthreads();
+    const int n = n_list;
+    if (qrow < p.M)
+    for (int i0 = 0; i0 < n; i0 += kMaxParts) {
+      float m[kMaxParts], lp[kMaxParts];
+      float4 o[kMaxParts];
+#pragma unroll
+      for (int j = 0; j < kMaxParts; ++j) {
+        const float* rec = p.ws + (size_t)rec_list[min(i0 + j, n - 1)] * kPartialFloats;
+        m[j] = rec[kQueryTile * 64 + row];
+        lp[j] = rec[kQueryTile * 64 + kQueryTile + row];
+        o[j] = *(const float4*)(rec + row * 64 + piece * 4);
+      }
+      float mn = mt;
+#pragma unroll
+      for (int j = 0; j < kMaxParts; ++j)
+        if (i0 + j < n) mn = fmaxf(mn, m[j]);
+      const float rs = __builtin_amdgcn_exp2f(mt - mn);  // 0 in the first round (mt = -inf)
+      acc.x *= rs; acc.y *= rs; acc.z *= rs; acc.w *= rs;
+      l *= rs;
+      mt = mn;
+#pragma unroll
+      for (int j = 0; j < kMaxParts; ++j)
+        if (i0 + j < n) {
+          const float w = __builtin_amdgcn_exp2f(m[j] - mt);
+          l += lp[j] * w;
+          acc.x += o[j].x * w; acc.y += o[j].y * w; acc.z += o[j].z * w; acc.w += o[j].w * w;
+        }
+    }
   }
+  if (qrow >= p.M) return;
   const float inv = 1.0f / l;
   const size_t oel = (((size_t)li * p.M + qrow) * p.H + h) * 64 + piece * 4;
   if (p.out_f32) {
@@ -787,6 +857,19 @@ hipError_t launch_attn_bf16(const Geom& g, char* kv, int layer0, int nl, const v
   n_wgs &= ~7;
   if (n_wgs < 8) n_wgs = 8;
   p.chunk = (int)((total + n_wgs - 1) / n_wgs);
+  // Tile segments of the chunk's length, so that neighbouring workgroups walk the same tiles of
+  // neighbouring query blocks together; a short remainder joins the segment before it, which
+  // bounds the pieces of a chunk by kSegRecs (chunk - 1 <= 2 * shortest segment).
+  p.NS = (p.T + p.chunk - 1) / p.chunk;
+  p.L0 = p.chunk;
+  if (p.NS > 1 && p.T - (p.NS - 1) * p.L0 < (p.chunk + 1) / 2) --p.NS;
+  if (p.NS <= 1) { p.NS = 1; p.L0 = p.T; }
+  p.PP = p.QB * p.T;
+  if (p.NS > 1) {                                        // whole chunks per head pair, if the grid has room
+    const long padded = (long)((p.PP + p.chunk - 1) / p.chunk) * p.chunk;
+    if ((long)((p.LH + 1) / 2) * padded <= (long)n_wgs * p.chunk) p.PP = (int)padded;
+  }
+  p.total_units = ((p.LH + 1) / 2) * p.PP;
   p.c = scale * 1.4426950408889634f;
   p.out_f32 = out_f32 ? 1 : 0;
   if (ev && hipEventRecord(ev[0], s) != hipSuccess) return hipErrorUnknown;
