@@ -91,7 +91,14 @@ constexpr int kWaitVm0 = 0x0F70;                       // vmcnt(0), nothing else
 constexpr int kWaitVm4 = 0x0F74;                       // vmcnt(4)
 
 constexpr int kSegRecs = 3;                            // partial records per workgroup and wave set
-size_t attn_ws_bytes() { return (size_t)kMaxAttnWgs * kSegRecs * 2 * kPartialFloats * sizeof(float); }
+// Workspace: kSegRecs partial records per chunk and wave set.  A launch over few (layer, head)
+// pairs has one chunk per workgroup; a launch whose head pairs are dealt out to the XCDs round by
+// round has kMaxAttnWgs / 8 chunks per head pair.
+size_t attn_ws_bytes(int layer_heads) {
+  const long pairs = (layer_heads + 1) / 2;
+  const long chunks = pairs * (kMaxAttnWgs / 8) > kMaxAttnWgs ? pairs * (kMaxAttnWgs / 8) : kMaxAttnWgs;
+  return (size_t)chunks * kSegRecs * 2 * kPartialFloats * sizeof(float);
+}
 
 struct AttnParams {
   const char* q;
@@ -107,6 +114,8 @@ struct AttnParams {
   int chunk;                  // units per workgroup
   int NS, L0;                 // tile segments per item and their length (the last one takes the rest)
   int PP;                     // unit slots per head pair: QB * T, or that rounded up to whole chunks
+  int rounds;                 // chunks per workgroup (chunk index = round * workgroups + workgroup's index)
+  size_t trace_off;           // floats from ws to the end of the record area (timing builds)
   int total_units;            // ceil(LH / 2) * PP
   float c;                    // softmax scale * log2(e)
   int out_f32;                // output element type: 1 = fp32, 0 = bf16
@@ -513,11 +522,7 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
 
   const int G = gridDim.x;
   const int cidx = (blockIdx.x & 7) * (G >> 3) + (blockIdx.x >> 3);
-  int u = cidx * p.chunk;
-  const int u_end = min(u + p.chunk, p.total_units);
-  if (u >= u_end) return;                                // whole workgroup: no barrier has been executed yet
-  const int u_begin = u;
-  int n_piece = 0;
+  if (cidx * p.chunk >= p.total_units) return;           // whole workgroup: no barrier has been executed yet
 #ifdef OVGGT_TRACE
   const unsigned long long tr_w0 = wall_clock64(), tr_c0 = clock64();
   unsigned long long tr_n = 0;
@@ -560,6 +565,14 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
   // set B runs one barrier behind set A: its matrix phases coincide with A's vector phases
   if (set == 1) phase_barrier();
 
+  // Head pairs are dealt out round by round: in every round an XCD's workgroups share one head
+  // pair (its K/V tiles then live in that XCD's L2 while all its query blocks pass over them).
+  for (int rnd = 0; rnd < p.rounds; ++rnd) {
+  const int chunk_idx = rnd * G + cidx;
+  int u = chunk_idx * p.chunk;
+  const int u_end = min(u + p.chunk, p.total_units);
+  const int u_begin = u;
+  int n_piece = 0;
   while (u < u_end) {
     const UnitPos up = decode_unit(u, p.T, p.QB, p.NS, p.L0, p.PP);
     if (!up.valid) break;                                // the rest of the chunk is empty slots
@@ -715,7 +728,7 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
           }
         }
       } else {
-        float* rec = p.ws + (size_t)((kSegRecs * cidx + rec_ord) * 2 + set) * kPartialFloats;
+        float* rec = p.ws + (size_t)((kSegRecs * chunk_idx + rec_ord) * 2 + set) * kPartialFloats;
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
           const int r = qhalf * 64 + qb * 32 + l32;
@@ -736,10 +749,11 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
     __syncthreads();                                  // merge scratch is reused as tile buffers
     u += t1 - t0;
   }
+  }
   if (set == 0) phase_barrier();                       // set A: the barrier set B executed up front
 #ifdef OVGGT_TRACE
   if (lane == 0) {
-    unsigned long long* tr = (unsigned long long*)(p.ws + (size_t)2 * kSegRecs * kMaxAttnWgs * kPartialFloats) - (size_t)(cidx * 8 + wave + 1) * 8;
+    unsigned long long* tr = (unsigned long long*)(p.ws + p.trace_off) - (size_t)(cidx * 8 + wave + 1) * 8;
     tr[0] = x.tr_w; tr[1] = wall_clock64() - tr_w0; tr[2] = clock64() - tr_c0; tr[5] = tr_n;
     tr[3] = x.tr_m; tr[4] = x.tr_x; tr[6] = x.tr_v; tr[7] = x.tr_y;
   }
@@ -837,7 +851,7 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(AttnParams p) {
 }
 
 hipError_t launch_attn_bf16(const Geom& g, char* kv, int layer0, int nl, const void* q, void* out,
-                            int n_total, float scale, char* ws, int n_wgs, bool out_f32,
+                            int n_total, float scale, char* ws, size_t ws_bytes, int n_wgs, bool out_f32,
                             hipStream_t s, hipEvent_t* ev) {
   AttnParams p;
   p.q = (const char*)q;
@@ -870,6 +884,27 @@ hipError_t launch_attn_bf16(const Geom& g, char* kv, int layer0, int nl, const v
     if ((long)((p.LH + 1) / 2) * padded <= (long)n_wgs * p.chunk) p.PP = (int)padded;
   }
   p.total_units = ((p.LH + 1) / 2) * p.PP;
+  p.rounds = 1;
+  // Many head pairs: deal them out to the XCDs round by round, one head pair per XCD and round, cut
+  // into as many chunks as the XCD has workgroups.  The plain split above would hand a workgroup a
+  // run of whole items, and the query blocks of a head would re-read its K/V from memory one after
+  // the other.
+  {
+    const int pairs = (p.LH + 1) / 2, per_xcd = n_wgs / 8;
+    const long chunks = (long)pairs * per_xcd;
+    if (pairs > 8 && pairs % 8 == 0 && p.QB * p.T >= per_xcd &&
+        (size_t)chunks * kSegRecs * 2 * kPartialFloats * sizeof(float) <= ws_bytes) {
+      p.chunk = (p.QB * p.T + per_xcd - 1) / per_xcd;
+      p.NS = (p.T + p.chunk - 1) / p.chunk;
+      p.L0 = p.chunk;
+      if (p.NS > 1 && p.T - (p.NS - 1) * p.L0 < (p.chunk + 1) / 2) --p.NS;
+      if (p.NS <= 1) { p.NS = 1; p.L0 = p.T; }
+      p.PP = per_xcd * p.chunk;
+      p.total_units = pairs * p.PP;
+      p.rounds = pairs / 8;
+    }
+  }
+  p.trace_off = ws_bytes / sizeof(float);
   p.c = scale * 1.4426950408889634f;
   p.out_f32 = out_f32 ? 1 : 0;
   if (ev && hipEventRecord(ev[0], s) != hipSuccess) return hipErrorUnknown;

@@ -104,7 +104,9 @@ void make_geom(const ovggt_config& c, Geom* g) {
   g->meta_layer_bytes = off;
 }
 
-size_t ws_bytes_for(const ovggt_config& c) { return c.dtype == OVGGT_BF16 ? up256(attn_ws_bytes()) : 256; }
+size_t ws_bytes_for(const ovggt_config& c) {
+  return c.dtype == OVGGT_BF16 ? up256(attn_ws_bytes(c.n_layers * c.n_heads)) : 256;
+}
 
 bool aligned16(const void* p) { return p && ((uintptr_t)p & 15) == 0; }
 
@@ -243,7 +245,7 @@ int ovggt_global_attn(ovggt_cache* c, int layer, const void* q, const void* k_ne
       for (auto& x : ev) x = prof_event(c);
       have = ev[0] && ev[1] && ev[2];
     }
-    e = launch_attn_bf16(g, c->kv, l0, nl, q, out, n + g.M, c->scale, c->ws, c->n_wgs,
+    e = launch_attn_bf16(g, c->kv, l0, nl, q, out, n + g.M, c->scale, c->ws, ws_bytes_for(c->cfg), c->n_wgs,
                          c->cfg.out_dtype == OVGGT_F32, s, have ? ev : nullptr);
     if (have) {
       c->prof_pending[OVGGT_PROF_ATTN].push_back({ev[0], ev[1]});

@@ -9,7 +9,7 @@ namespace ovggt {
 
 constexpr int kSlotTile = 128;      // attention consumes the cache in 128-slot tiles
 constexpr int kQueryTile = 128;     // queries per attention work item
-constexpr int kMaxAttnWgs = 512;    // upper bound on attention workgroups (sizes the workspace: 4 partials each)
+constexpr int kMaxAttnWgs = 256;    // upper bound on attention workgroups (one per CU; sizes the workspace)
 
 // Per-layer control block kept in the metadata buffer.
 struct Ctrl {
@@ -56,9 +56,9 @@ hipError_t launch_attn_f32(const Geom& g, char* kv, int layer0, int nl, const vo
 // `ev` (optional, 3 events) are recorded before the main kernel, between it and
 // the combine kernel, and after the combine kernel.
 hipError_t launch_attn_bf16(const Geom& g, char* kv, int layer0, int nl, const void* q, void* out,
-                            int n_total, float scale, char* ws, int n_wgs, bool out_f32,
+                            int n_total, float scale, char* ws, size_t ws_bytes, int n_wgs, bool out_f32,
                             hipStream_t s, hipEvent_t* ev = nullptr);
-size_t attn_ws_bytes();
+size_t attn_ws_bytes(int layer_heads);
 
 // Eq. 5 + anchor flags for the M slots [n_total-M, n_total), then (when
 // n_total > B) Eq. 8's selection and the move list.

@@ -171,8 +171,13 @@ def test_worst_case_compaction_rising_scores():
     cache.close()
 
 
-def test_batched_layers_match_per_layer_oracle():
-    cfg = synth.preset(2, M=150, H=2, C=256, B=400, T=7, L=3, n_special=5)
+@pytest.mark.parametrize("shape", [
+    dict(M=150, H=2, C=256, B=400, T=7, L=3),          # 3 head pairs: one chunk per workgroup
+    dict(M=300, H=8, C=64, B=5000, T=5, L=4),          # 16 head pairs: two rounds per XCD, tile segments
+    dict(M=130, H=16, C=64, B=300, T=4, L=3),          # 24 head pairs: three rounds, short caches
+])
+def test_batched_layers_match_per_layer_oracle(shape):
+    cfg = synth.preset(2, n_special=5, **shape)
     torch = _torch()
     cache = make_cache(cfg)
     orcs = [oc.OracleCache(cfg.M, cfg.H, cfg.d, cfg.B) for _ in range(cfg.L)]
