@@ -37,6 +37,21 @@ def gen_frames(cfg, frames, layers, pool):
     return dict(zip(jobs, pool.map(lambda lt: synth.frame_inputs(cfg, lt[0], lt[1]), jobs)))
 
 
+def profiled_traffic(kernel, workload, layers):
+    """HBM-side bytes per launch of `kernel` from the committed rocprofv3 --pmc summary of this
+    workload (FETCH_SIZE + WRITE_SIZE, calibrated there against a plain copy), or None."""
+    path = os.path.join(ROOT, "profiles", "bench_%s_kernels_and_traffic.md" % workload)
+    tag = "traffic_bytes_per_launch %s %s layers=%d:" % (kernel, workload, layers)
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith(tag):
+                    return int(line[len(tag):].split()[0])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(cfg, warm_frames, timed_frames):
     """The oracle as it stands: attention-free warm-up to reach the steady-state
     cache, then whole steps (fp64 attention + score + select + compact) timed."""
@@ -144,6 +159,8 @@ def main():
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     prof = B.ovggt_profile_read(cache.h, cache.stream)
+    # what an event bracket reports beyond the bracketed kernel's own execution (empty launch)
+    bracket_overhead_ms = B.ovggt_profile_overhead(cache.h, 64, cache.stream)
     status = [cache.status(l) for l in range(L)]
     assert not any(status), f"device status {status}"
     n_res = cache.size(0)
@@ -165,11 +182,14 @@ def main():
     n_keys = min(cfg.B, T * cfg.M) + cfg.M if T * cfg.M > cfg.B else T * cfg.M
     attn_ms, attn_cnt = prof["attn"]
     flop = 4.0 * cfg.M * n_keys * cfg.H * cfg.d * L
-    attn_avg_ms = attn_ms / max(attn_cnt, 1)
+    bracket_ms = attn_ms / max(attn_cnt, 1)
+    attn_avg_ms = max(bracket_ms - bracket_overhead_ms, 1e-6)
     achieved = flop / (attn_avg_ms * 1e-3) / 1e12 if attn_cnt else 0.0
     roofline = {"bound": "mfma", "kernel": "attn_bf16_kernel", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS,
-                "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
-                "avg_kernel_ms": attn_avg_ms, "launches_timed": int(attn_cnt),
+                "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
+                "traffic": profiled_traffic("attn_bf16_kernel", cfg.name.split("-")[0], L),
+                "avg_kernel_ms": attn_avg_ms, "event_bracket_ms": bracket_ms,
+                "event_bracket_of_empty_launch_ms": bracket_overhead_ms, "launches_timed": int(attn_cnt),
                 "flop_per_launch": flop, "keys_per_launch": int(n_keys)}
 
     kernels = {}

@@ -22,7 +22,7 @@ EXPORTS = (
     "ovggt_cache_query_bytes", "ovggt_cache_init", "ovggt_global_attn", "ovggt_score_select",
     "ovggt_cache_compact", "ovggt_cache_destroy", "ovggt_cache_size", "ovggt_cache_frames",
     "ovggt_cache_status", "ovggt_cache_export", "ovggt_cache_import", "ovggt_cache_last_moves",
-    "ovggt_profile_enable", "ovggt_profile_read", "ovggt_strerror",
+    "ovggt_profile_enable", "ovggt_profile_read", "ovggt_profile_overhead", "ovggt_strerror",
 )
 PROF_CLASSES = ("append", "attn", "combine", "score_select", "compact")
 
@@ -69,6 +69,7 @@ def lib() -> C.CDLL:
     L.ovggt_cache_last_moves.argtypes = [vp, C.c_int, u32p, u32p, C.POINTER(i32), vp]
     L.ovggt_profile_enable.argtypes = [vp, C.c_int, C.c_int]
     L.ovggt_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64), vp]
+    L.ovggt_profile_overhead.argtypes = [vp, C.c_int, C.POINTER(C.c_double), vp]
     L.ovggt_strerror.argtypes = [C.c_int]
     L.ovggt_strerror.restype = C.c_char_p
     for name in EXPORTS:
@@ -181,6 +182,12 @@ def ovggt_profile_read(h, stream: int = 0) -> dict:
     cnt = (C.c_int64 * len(PROF_CLASSES))()
     _check(lib().ovggt_profile_read(h, ms, cnt, stream), "ovggt_profile_read")
     return {name: (ms[i], cnt[i]) for i, name in enumerate(PROF_CLASSES)}
+
+
+def ovggt_profile_overhead(h, reps: int = 64, stream: int = 0) -> float:
+    ms = C.c_double()
+    _check(lib().ovggt_profile_overhead(h, reps, C.byref(ms), stream), "ovggt_profile_overhead")
+    return ms.value
 
 
 # ---- convenience owner of the device buffers ---------------------------------

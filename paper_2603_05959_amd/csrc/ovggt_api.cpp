@@ -429,6 +429,32 @@ int ovggt_profile_read(ovggt_cache* c, double* ms_sum, int64_t* count, void* hip
   return OVGGT_OK;
 }
 
+int ovggt_profile_overhead(ovggt_cache* c, int reps, double* ms_mean, void* hip_stream) {
+  if (!c || !ms_mean || reps < 1 || reps > 1024) return OVGGT_ERR_ARG;
+  hipStream_t s = (hipStream_t)hip_stream;
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> ev;
+  for (int i = 0; i < reps; ++i) {
+    hipEvent_t e0 = prof_event(c), e1 = prof_event(c);
+    if (!e0 || !e1) return OVGGT_ERR_HIP;
+    // the same bracket as around a timed kernel, around a launch that does next to nothing
+    if (hipEventRecord(e0, s) != hipSuccess || launch_fill_zero(c->ws, 256, s) != hipSuccess ||
+        hipEventRecord(e1, s) != hipSuccess)
+      return OVGGT_ERR_HIP;
+    ev.push_back({e0, e1});
+  }
+  if (hipStreamSynchronize(s) != hipSuccess) return OVGGT_ERR_HIP;
+  double sum = 0.0;
+  for (auto& pr : ev) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, pr.first, pr.second) != hipSuccess) return OVGGT_ERR_HIP;
+    sum += ms;
+    c->prof_free.push_back(pr.first);
+    c->prof_free.push_back(pr.second);
+  }
+  *ms_mean = sum / reps;
+  return OVGGT_OK;
+}
+
 const char* ovggt_strerror(int code) {
   switch (code) {
     case OVGGT_OK: return "ok";
