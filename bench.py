@@ -89,6 +89,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-frames", type=int, default=3)
     ap.add_argument("--detail-steps", type=int, default=40, help="extra untimed steps with per-kernel events")
+    ap.add_argument("--flatness", action="store_true",
+                    help="also bracket every 8th timed step with events and report the slope of step latency over the stream")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (reference dispatch for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -153,9 +155,17 @@ def main():
         step(t)
     torch.cuda.synchronize()
     B.ovggt_profile_enable(cache.h, 1, 4)                # attention kernel of every 4th step
+    flat_ev = []
     t0 = time.perf_counter()
     for t in range(W, T):
-        step(t)
+        if args.flatness and (t - W) % 8 == 0:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            step(t)
+            e1.record()
+            flat_ev.append((t, e0, e1))
+        else:
+            step(t)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     prof = B.ovggt_profile_read(cache.h, cache.stream)
@@ -227,6 +237,20 @@ def main():
         "cache_bytes": {"kv": cache.bytes[0], "meta": cache.bytes[1], "workspace": cache.bytes[2]},
         "input_staging_s": gen_s,
     }
+    if flat_ev:
+        # steady state only: the resident key count is constant once the cache is full
+        full_from = cfg.B // cfg.M + 1
+        pts = [(t, a.elapsed_time(b)) for t, a, b in flat_ev if t >= full_from]
+        if len(pts) >= 8:
+            tt = np.array([p[0] for p in pts], dtype=np.float64)
+            ms = np.array([p[1] for p in pts], dtype=np.float64)
+            slope, icpt = np.polyfit(tt, ms, 1)
+            q = len(pts) // 4
+            res["flatness"] = {"samples": len(pts), "first_frame": int(tt[0]), "last_frame": int(tt[-1]),
+                               "mean_ms": float(ms.mean()), "mean_ms_first_quarter": float(ms[:q].mean()),
+                               "mean_ms_last_quarter": float(ms[-q:].mean()),
+                               "slope_us_per_1000_frames": float(slope * 1e6),
+                               "note": "event-bracketed whole steps, every 8th timed step, frames with a full cache"}
     cache.close()
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(cfg, warm_frames=max(cfg.B // cfg.M + 2, 2), timed_frames=args.cpu_frames)
