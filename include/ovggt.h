@@ -75,6 +75,19 @@ typedef struct {
   int32_t out_dtype;         /* type of the attention output O: OVGGT_F32, or OVGGT_BF16
                                 (bf16 handles only).  bf16 handles accumulate O in fp32
                                 either way; OVGGT_BF16 rounds it once (RNE) on store     */
+  /* Activation smoothing (Eq. 6).  smooth_alpha = 0 turns it off and every field below is
+   * ignored; the rank key of a token is then ss = s^2.  With 0 < alpha <= 1 a frame is
+   * n_special aux tokens followed by a patch_h x patch_w map in row-major order
+   * (n_special + patch_h*patch_w = M), s = sqrt(ss) in fp32 (correctly rounded), the patch
+   * scores are replaced by alpha*(G*S) + (1-alpha)*S and the aux tokens keep s; that value is
+   * the token's rank key (what `ss` of export then holds).  G is the 3x3 kernel below, row-major,
+   * applied with the border replicated; the paper fixes neither its size nor its width, so the
+   * caller supplies the weights (they should sum to 1).  All of it in fp32 without fused
+   * multiply-adds: products g*s are rounded, added left to right in kernel order starting from
+   * the first product, then fl(fl(alpha*conv) + fl(fl(1-alpha)*s)).                           */
+  float   smooth_alpha;
+  int32_t patch_h, patch_w, n_special;
+  float   smooth_kernel[9];
 } ovggt_config;
 
 /* Sizes (bytes) of the three caller-allocated device buffers for `cfg`:

@@ -38,7 +38,8 @@ tree order from left-to-right order; Eq. 9's bound on |P|; the 2 L T M N_h d
 footprint with the paper's "~10 GB at 100 frames" example.
 Parity unpinned by the paper: the slot layout after eviction (our definition,
 pinned only by exhaustive tiny cases and by permutation invariance of
-attention) and `hybrid_rank`/`smooth_scores` beyond their degenerate cases.
+attention), `hybrid_rank` beyond its degenerate cases, and the kernel size, width and
+padding of the activation smoothing (`smoothed_keys_f32`, `smooth_scores`).
 """
 from __future__ import annotations
 
@@ -150,11 +151,14 @@ def hole_fill_moves(keep: np.ndarray, budget: int) -> tuple[np.ndarray, np.ndarr
 class OracleCache:
     """One layer's KV cache with scores, ids and protection flags per slot."""
 
-    def __init__(self, M: int, H: int, d: int, budget: int, scale: float | None = None):
+    def __init__(self, M: int, H: int, d: int, budget: int, scale: float | None = None, smooth=None):
+        """smooth: None (rank key = ss), or (alpha, patch_h, patch_w, n_special, kernel 3x3) to rank
+        by the smoothed activation map of Eq. 6 (see `smoothed_keys_f32`)."""
         if budget < M:
             raise ValueError("budget must hold at least one frame")
         self.M, self.H, self.d, self.B = M, H, d, budget
         self.scale = scale
+        self.smooth = smooth
         self.k = np.zeros((0, H, d), np.float32)
         self.v = np.zeros((0, H, d), np.float32)
         self.gid = np.zeros(0, np.uint32)
@@ -188,6 +192,8 @@ class OracleCache:
         M, n = self.M, self.n
         ss_new = tree_sum_sq_f32(resid_t)
         assert ss_new.shape == (M,)
+        if self.smooth is not None:
+            ss_new = smoothed_keys_f32(ss_new, *self.smooth)
         flag_new = np.zeros(M, np.uint8) if anchor_t is None else (np.asarray(anchor_t) != 0).astype(np.uint8)
         ss = self.ss.copy(); ss[n - M:] = ss_new
         flag = self.flag.copy(); flag[n - M:] = flag_new
@@ -238,10 +244,42 @@ def hybrid_rank(k_hist: np.ndarray, s_new: np.ndarray, beta: float) -> tuple[np.
     return (1.0 - beta) * minmax01(d), beta * minmax01(s_new)
 
 
+def smoothed_keys_f32(ss_new: np.ndarray, alpha: float, ph: int, pw: int, n_special: int, g) -> np.ndarray:
+    """Rank keys of one frame's tokens under activation smoothing (Eq. 6).
+
+    s = sqrt(ss) (Eq. 5's score) in fp32; the last ph*pw tokens are the patch map S in row-major
+    order and become alpha*(G*S) + (1-alpha)*S; the first n_special (aux) tokens keep s, as the
+    paper says.  G is a 3x3 kernel given by the caller (the paper fixes neither size nor width),
+    applied with the border replicated: tap (a, b) weighs S[y+a-1, x+b-1], which is the
+    convolution for the symmetric kernels Eq. 6 means.  Every operation is a separate fp32
+    operation, taps added left to right in kernel order, so a GPU thread can repeat it bit for
+    bit: the smoothed value decides which tokens survive.  Pinned against `smooth_scores` (the
+    same formula in fp64), alpha = 0, a constant map, an impulse and a hand-computed 2x2 case;
+    kernel size, width and padding remain this build's reading (parity unpinned by the paper)."""
+    f32 = np.float32
+    ss_new = np.asarray(ss_new, dtype=f32)
+    assert n_special + ph * pw == len(ss_new)
+    g = np.asarray(g, dtype=f32).reshape(3, 3)
+    a = f32(alpha)
+    with np.errstate(invalid="ignore"):
+        s = np.sqrt(ss_new)                                   # correctly rounded in fp32
+    S = s[n_special:].reshape(ph, pw)
+    pad = np.pad(S, 1, mode="edge")
+    conv = None
+    for dy in range(3):
+        for dx in range(3):
+            prod = g[dy, dx] * pad[dy:dy + ph, dx:dx + pw]    # fp32 product, rounded
+            conv = prod if conv is None else conv + prod      # fp32 add, rounded
+    out = s.copy()
+    out[n_special:] = (a * conv + (f32(1.0) - a) * S).reshape(-1)
+    return out
+
+
 def smooth_scores(s_patch: np.ndarray, alpha: float, g: np.ndarray) -> np.ndarray:
     """Eq. 6: S~ = alpha (G * S) + (1-alpha) S on the H_p x W_p patch map, with
-    an explicit normalised kernel `g` and replicate padding.  PARITY UNPINNED
-    (kernel size, sigma and padding are not given) beyond alpha = 0."""
+    an explicit normalised kernel `g` and replicate padding, in fp64.  Pinned by
+    alpha = 0 and a constant map; kernel size, sigma and padding are this
+    build's reading (parity unpinned by the paper)."""
     s = np.asarray(s_patch, dtype=np.float64)
     g = np.asarray(g, dtype=np.float64)
     ry, rx = g.shape[0] // 2, g.shape[1] // 2

@@ -31,7 +31,8 @@ class ovggt_config(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("n_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("tokens_per_frame", C.c_int32), ("resid_dim", C.c_int32), ("budget", C.c_int32),
                 ("dtype", C.c_int32), ("score_mode", C.c_int32), ("softmax_scale", C.c_float),
-                ("out_dtype", C.c_int32)]
+                ("out_dtype", C.c_int32), ("smooth_alpha", C.c_float), ("patch_h", C.c_int32),
+                ("patch_w", C.c_int32), ("n_special", C.c_int32), ("smooth_kernel", C.c_float * 9)]
 
 
 class OvggtError(RuntimeError):
@@ -100,10 +101,16 @@ def _ptr(t) -> int:
 
 
 def make_config(n_layers, n_heads, head_dim, tokens_per_frame, resid_dim, budget, dtype,
-                score_mode=0, softmax_scale=0.0, out_dtype="f32") -> ovggt_config:
+                score_mode=0, softmax_scale=0.0, out_dtype="f32", smooth=None) -> ovggt_config:
+    """smooth: None, or (alpha, patch_h, patch_w, n_special, kernel) with kernel nine floats, row-major."""
     codes = {"f32": OVGGT_F32, "bf16": OVGGT_BF16}
-    return ovggt_config(n_layers, n_heads, head_dim, tokens_per_frame, resid_dim, budget,
-                        codes.get(dtype, dtype), score_mode, softmax_scale, codes.get(out_dtype, out_dtype))
+    cfg = ovggt_config(n_layers, n_heads, head_dim, tokens_per_frame, resid_dim, budget,
+                       codes.get(dtype, dtype), score_mode, softmax_scale, codes.get(out_dtype, out_dtype))
+    if smooth is not None:
+        alpha, ph, pw, ns, kern = smooth
+        cfg.smooth_alpha, cfg.patch_h, cfg.patch_w, cfg.n_special = float(alpha), int(ph), int(pw), int(ns)
+        cfg.smooth_kernel = (C.c_float * 9)(*[float(x) for x in np.asarray(kern, dtype=np.float32).reshape(9)])
+    return cfg
 
 
 # ---- the C entry points, one wrapper each -----------------------------------
@@ -203,11 +210,11 @@ class Cache:
     Holds no logic of its own beyond marshalling."""
 
     def __init__(self, n_layers, n_heads, head_dim, tokens_per_frame, resid_dim, budget, dtype,
-                 softmax_scale=0.0, device="cuda:0", out_dtype="f32"):
+                 softmax_scale=0.0, device="cuda:0", out_dtype="f32", smooth=None):
         import torch
         self.torch = torch
         self.cfg = make_config(n_layers, n_heads, head_dim, tokens_per_frame, resid_dim, budget, dtype,
-                               0, softmax_scale, out_dtype)
+                               0, softmax_scale, out_dtype, smooth)
         self.dtype = dtype
         self.out_dtype = out_dtype
         self.L, self.H, self.d, self.M, self.Cdim, self.B = n_layers, n_heads, head_dim, tokens_per_frame, resid_dim, budget

@@ -21,6 +21,7 @@ struct ovggt_cache {
   char* ws;
   float scale;
   int n_wgs;                       // attention workgroups (1 per CU, 8 waves each)
+  SmoothParams smooth;             // Eq. 6 parameters (alpha = 0: off)
   std::vector<int32_t> n;          // resident (incl. pending) slots per layer
   std::vector<int64_t> frames;     // completed frames per layer
   std::vector<int8_t> phase;       // 0: expects global_attn, 1: score_select, 2: compact
@@ -85,6 +86,13 @@ bool valid_config(const ovggt_config* c) {
   if (c->out_dtype != OVGGT_F32 && c->out_dtype != OVGGT_BF16) return false;
   if (c->dtype == OVGGT_F32 && c->out_dtype != OVGGT_F32) return false;
   if (!(c->softmax_scale >= 0.f) || !std::isfinite(c->softmax_scale)) return false;
+  if (!(c->smooth_alpha >= 0.f && c->smooth_alpha <= 1.f)) return false;
+  if (c->smooth_alpha > 0.f) {
+    if (c->patch_h < 1 || c->patch_w < 1 || c->n_special < 0) return false;
+    if ((int64_t)c->n_special + (int64_t)c->patch_h * c->patch_w != c->tokens_per_frame) return false;
+    for (float w : c->smooth_kernel)
+      if (!std::isfinite(w)) return false;
+  }
   return true;
 }
 
@@ -192,6 +200,9 @@ int ovggt_cache_init(ovggt_cache** out, const ovggt_config* cfg, void* kv_dev, v
   if (!c) return OVGGT_ERR_ARG;
   c->cfg = *cfg;
   make_geom(*cfg, &c->g);
+  c->smooth.alpha = cfg->smooth_alpha;
+  c->smooth.ph = cfg->patch_h; c->smooth.pw = cfg->patch_w; c->smooth.n_special = cfg->n_special;
+  for (int i = 0; i < 9; ++i) c->smooth.g[i] = cfg->smooth_kernel[i];
   c->kv = (char*)kv_dev; c->meta = (char*)meta_dev; c->ws = (char*)ws_dev;
   c->scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / std::sqrt((float)cfg->head_dim);
   int wgs = cus;
@@ -269,7 +280,7 @@ int ovggt_score_select(ovggt_cache* c, int layer, const void* resid, const uint8
   if (!uniform(c, l0, nl, 1)) return OVGGT_ERR_STATE;
   {
     ProfScope ps(c, OVGGT_PROF_SELECT, (hipStream_t)hip_stream, c->prof_level >= 2);
-    if (launch_score_select(c->g, c->meta, l0, nl, resid, anchor_flags, c->n[l0], (hipStream_t)hip_stream) != hipSuccess)
+    if (launch_score_select(c->g, c->smooth, c->meta, l0, nl, resid, anchor_flags, c->n[l0], (hipStream_t)hip_stream) != hipSuccess)
       return OVGGT_ERR_HIP;
   }
   for (int l = l0; l < l0 + nl; ++l) c->phase[l] = 2;

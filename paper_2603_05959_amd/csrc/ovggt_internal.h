@@ -60,9 +60,17 @@ hipError_t launch_attn_bf16(const Geom& g, char* kv, int layer0, int nl, const v
                             hipStream_t s, hipEvent_t* ev = nullptr);
 size_t attn_ws_bytes(int layer_heads);
 
-// Eq. 5 + anchor flags for the M slots [n_total-M, n_total), then (when
-// n_total > B) Eq. 8's selection and the move list.
-hipError_t launch_score_select(const Geom& g, char* meta, int layer0, int nl, const void* resid,
+// Eq. 6: activation smoothing of a frame's patch scores (alpha = 0: off).
+struct SmoothParams {
+  float alpha;
+  int ph, pw, n_special;
+  float g[9];
+};
+
+// Eq. 5 + anchor flags for the M slots [n_total-M, n_total), Eq. 6's smoothing of
+// their scores when enabled, then (when n_total > B) Eq. 8's selection and the
+// move list.
+hipError_t launch_score_select(const Geom& g, const SmoothParams& sm, char* meta, int layer0, int nl, const void* resid,
                                const uint8_t* anchors, int n_total, hipStream_t s);
 
 // Apply the move list to K, V and the per-slot metadata.

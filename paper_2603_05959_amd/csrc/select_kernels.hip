@@ -1,5 +1,5 @@
-// Activation Value Rating (paper Eq. 5), anchor flags (Sec. 3.3) and the
-// fixed-budget selection (Eq. 8) in one launch.
+// Activation Value Rating (paper Eq. 5), activation smoothing (Eq. 6, optional),
+// anchor flags (Sec. 3.3) and the fixed-budget selection (Eq. 8) in one launch.
 //
 // Phase 1 (all workgroups): one wave per new token reduces the token's residual
 // row to ss = sum of squares in fp32 with a fixed balanced-tree order -- lane l
@@ -113,6 +113,37 @@ __device__ inline void score_rows(const char* rbase, size_t row_bytes, int C, in
       }
     }
   }
+}
+
+// ---- activation smoothing (Eq. 6), by the workgroup that saw all scores arrive -------------
+// s = sqrt(ss) for every new token; patch tokens (row-major ph x pw map behind the n_special aux
+// tokens) become alpha * (G * S) + (1 - alpha) * S with the border replicated, aux tokens keep s.
+// The result replaces ss as the token's rank key.  fp32 throughout, every operation rounded on its
+// own (contraction off, sqrtf is the correctly rounded one: the hardware's approximate square root
+// is a unit in the last place off now and then), taps added left to right in kernel order: the CPU
+// reference repeats exactly this sequence.  `raw` is scratch for M floats.
+__device__ inline void smooth_new_scores(const SmoothParams& sm, int M, float* key, float* raw) {
+#pragma clang fp contract(off)
+  for (int i = threadIdx.x; i < M; i += kSelThreads) raw[i] = __builtin_sqrtf(key[i]);
+  __syncthreads();
+  const float one_minus = 1.0f - sm.alpha;
+  for (int i = threadIdx.x; i < M; i += kSelThreads) {
+    float v = raw[i];
+    if (i >= sm.n_special) {
+      const int p = i - sm.n_special, y = p / sm.pw, x = p - y * sm.pw;
+      float conv = 0.f;
+#pragma unroll
+      for (int t = 0; t < 9; ++t) {
+        const int yy = min(max(y + t / 3 - 1, 0), sm.ph - 1), xx = min(max(x + t % 3 - 1, 0), sm.pw - 1);
+        const float prod = sm.g[t] * raw[sm.n_special + yy * sm.pw + xx];
+        conv = t == 0 ? prod : conv + prod;
+      }
+      const float blur = sm.alpha * conv, keep = one_minus * v;
+      v = blur + keep;
+    }
+    key[i] = v;
+  }
+  __syncthreads();
 }
 
 // ---- phase 2 helpers ---------------------------------------------------------
@@ -387,7 +418,7 @@ __device__ inline void select_phase(SelShared& sh, const Geom& g, const float* s
 
 template <bool BF16, int KPT, bool IDREG>
 __global__ void __launch_bounds__(kSelThreads)
-score_select_kernel(Geom g, char* meta, int layer0, const char* resid, const uint8_t* anchors,
+score_select_kernel(Geom g, SmoothParams sm, char* meta, int layer0, const char* resid, const uint8_t* anchors,
                     int n_total, int e_per_lane) {
   __shared__ SelShared sh;
   const int layer = layer0 + blockIdx.y;
@@ -419,7 +450,8 @@ score_select_kernel(Geom g, char* meta, int layer0, const char* resid, const uin
       default: if (many) score_rows<64, BF16, kRowsPerWave>(rbase, row_bytes, g.C, g.M, al, sn, fn); else score_rows<64, BF16, 1>(rbase, row_bytes, g.C, g.M, al, sn, fn); break;
     }
   }
-  if (n_total <= g.B) {                      // under budget: nothing to select
+  const bool smoothing = sm.alpha > 0.f;
+  if (n_total <= g.B && !smoothing) {        // under budget and no smoothing: nothing needs the whole frame
     if (blockIdx.x == 0 && tid == 0) ctrl->n_moves = 0;
     return;
   }
@@ -445,11 +477,18 @@ score_select_kernel(Geom g, char* meta, int layer0, const char* resid, const uin
   // ---- phase 2: this workgroup saw every other one arrive
   uint32_t* mvdst = (uint32_t*)(mb + g.off_mvdst);
   uint32_t* mvsrc = (uint32_t*)(mb + g.off_mvsrc);
+  if (smoothing) {
+    smooth_new_scores(sm, g.M, ss + n_old, (float*)mvdst);     // the move list is not written yet: scratch
+    if (n_total <= g.B) {
+      if (tid == 0) ctrl->n_moves = 0;
+      return;
+    }
+  }
   select_phase<KPT, IDREG>(sh, g, ss, ids, flags, ctrl, mvdst, mvsrc, n_total);
 }
 
 template <bool BF16>
-static void launch_variant(const Geom& g, char* meta, int layer0, int nl, const void* resid,
+static void launch_variant(const Geom& g, const SmoothParams& sm, char* meta, int layer0, int nl, const void* resid,
                            const uint8_t* anchors, int n_total, int e, hipStream_t s) {
   // One workgroup fits a CU (the selection's register-resident keys set the footprint), so the
   // launch stays within one round of the chip: a single layer spreads its rows one per wave, a
@@ -468,7 +507,7 @@ static void launch_variant(const Geom& g, char* meta, int layer0, int nl, const 
   dim3 grid((unsigned)gx, (unsigned)nl);
   const int n_chunks = (n_total + kSelThreads - 1) / kSelThreads;
 #define OVGGT_SEL_LAUNCH(KPT, IDREG)                                                                  \
-  hipLaunchKernelGGL((score_select_kernel<BF16, KPT, IDREG>), grid, dim3(kSelThreads), 0, s, g, meta, \
+  hipLaunchKernelGGL((score_select_kernel<BF16, KPT, IDREG>), grid, dim3(kSelThreads), 0, s, g, sm, meta, \
                      layer0, (const char*)resid, anchors, n_total, e)
   // the variant only matters when a selection will run (n_total > B)
   if (n_total <= g.B || n_chunks <= 8) OVGGT_SEL_LAUNCH(8, true);
@@ -478,13 +517,13 @@ static void launch_variant(const Geom& g, char* meta, int layer0, int nl, const 
 #undef OVGGT_SEL_LAUNCH
 }
 
-hipError_t launch_score_select(const Geom& g, char* meta, int layer0, int nl, const void* resid,
+hipError_t launch_score_select(const Geom& g, const SmoothParams& sm, char* meta, int layer0, int nl, const void* resid,
                                const uint8_t* anchors, int n_total, hipStream_t s) {
   int cp = 1;
   while (cp < g.C) cp *= 2;
   const int e = cp >= 64 ? cp / 64 : 1;
-  if (g.esize == 2) launch_variant<true>(g, meta, layer0, nl, resid, anchors, n_total, e, s);
-  else launch_variant<false>(g, meta, layer0, nl, resid, anchors, n_total, e, s);
+  if (g.esize == 2) launch_variant<true>(g, sm, meta, layer0, nl, resid, anchors, n_total, e, s);
+  else launch_variant<false>(g, sm, meta, layer0, nl, resid, anchors, n_total, e, s);
   return hipGetLastError();
 }
 

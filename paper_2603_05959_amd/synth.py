@@ -71,6 +71,14 @@ def preset(k: int, **overrides) -> StreamConfig:
 CFG4_BUDGETS = (4096, 8192, 32768, 65536)
 
 
+def gaussian_kernel3(sigma: float = 1.0) -> np.ndarray:
+    """A normalised 3x3 Gaussian as float32 [3, 3]: the smoothing kernel handed to both the library
+    and the oracle as a workload parameter (the paper gives no size or width for its G)."""
+    w = np.exp(-0.5 * (np.array([-1.0, 0.0, 1.0]) / sigma) ** 2)
+    k = np.outer(w, w)
+    return (k / k.sum()).astype(np.float32)
+
+
 # --------------------------------------------------------------------------- #
 # number formats
 # --------------------------------------------------------------------------- #

@@ -19,8 +19,8 @@ def _torch():
     return torch
 
 
-def make_cache(cfg, L=None):
-    return B.Cache(L or cfg.L, cfg.H, cfg.d, cfg.M, cfg.C, cfg.B, cfg.dtype)
+def make_cache(cfg, L=None, smooth=None):
+    return B.Cache(L or cfg.L, cfg.H, cfg.d, cfg.M, cfg.C, cfg.B, cfg.dtype, smooth=smooth)
 
 
 def dev(a, cfg):
@@ -52,11 +52,11 @@ def compare_cache(cache, orc, layer=0, kv=True):
         assert np.array_equal(e["v"], stored_v(orc.v, cache.dtype))
 
 
-def run_stream(cfg, layer=0, attn_frames=None, cache_every=1, resid_fn=None, q_rows=None, log=None):
+def run_stream(cfg, layer=0, attn_frames=None, cache_every=1, resid_fn=None, q_rows=None, log=None, smooth=None):
     """Drive both sides over cfg.T frames of one layer; returns max attention error."""
     torch = _torch()
-    cache = make_cache(cfg, L=1)
-    orc = oc.OracleCache(cfg.M, cfg.H, cfg.d, cfg.B)
+    cache = make_cache(cfg, L=1, smooth=smooth)
+    orc = oc.OracleCache(cfg.M, cfg.H, cfg.d, cfg.B, smooth=smooth)
     out = cache.new_output()[0]
     worst = 0.0
     for t in range(cfg.T):
@@ -294,6 +294,43 @@ def test_import_export_and_crafted_scores():
     assert np.array_equal(np.isnan(e["ss"]), np.isnan(orc.ss))
     assert cache.status(0) & B.OVGGT_STATUS_NONFINITE
     cache.close()
+
+
+@pytest.mark.parametrize("dtype,ph,pw,ns,H,C,B_,alpha", [
+    ("bf16", 9, 13, 5, 2, 256, 500, 0.5),       # budget not a multiple of the frame, eviction from frame 4 on
+    ("f32", 6, 7, 2, 2, 96, 130, 0.25),
+    ("bf16", 1, 40, 0, 1, 64, 100, 1.0),        # one-row map, no aux tokens, pure convolution
+    ("bf16", 37, 37, 5, 4, 1024, 4200, 0.5),    # the paper's patch grid (518 px / 14) at a small budget
+])
+def test_activation_smoothing_matches_oracle(dtype, ph, pw, ns, H, C, B_, alpha):
+    M = ns + ph * pw
+    cfg = synth.preset(1, M=M, H=H, C=C, B=B_, T=2 * (B_ // M) + 5, n_special=ns, dtype=dtype)
+    sm = (alpha, ph, pw, ns, synth.gaussian_kernel3(1.0))
+    run_stream(cfg, smooth=sm, attn_frames={0, cfg.T - 1})
+
+
+def test_activation_smoothing_batched_layers_and_bad_configs():
+    torch = _torch()
+    ph, pw, ns = 8, 10, 3
+    cfg = synth.preset(1, M=ns + ph * pw, H=2, C=128, B=300, T=8, n_special=ns, L=3)
+    sm = (0.5, ph, pw, ns, synth.gaussian_kernel3(0.8))
+    cache = make_cache(cfg, smooth=sm)
+    orcs = [oc.OracleCache(cfg.M, cfg.H, cfg.d, cfg.B, smooth=sm) for _ in range(cfg.L)]
+    out = cache.new_output()
+    for t in range(cfg.T):
+        fs = [synth.frame_inputs(cfg, l, t) for l in range(cfg.L)]
+        q, k, v, r = (dev(np.stack([f[x] for f in fs]), cfg) for x in "qkvr")
+        a = torch.from_numpy(np.stack([f["a"] for f in fs])).cuda()
+        cache.step(q, k, v, r, a, out)                                         # layer = all
+        for l, (f, o) in enumerate(zip(fs, orcs)):
+            o.append(f["k"], f["v"]); o.update(f["r"], f["a"])
+            compare_cache(cache, o, layer=l, kv=(t == cfg.T - 1))
+    cache.close()
+    g = synth.gaussian_kernel3(1.0)
+    for bad in [(0.5, 8, 10, 2, g), (1.5, 8, 10, 3, g), (-0.1, 8, 10, 3, g), (0.5, 0, 83, 0, g), (float("nan"), 8, 10, 3, g),
+                (0.5, 8, 10, 3, np.full((3, 3), np.nan, np.float32))]:
+        with pytest.raises(B.OvggtError):
+            make_cache(cfg, smooth=bad)
 
 
 def test_bf16_output_is_the_rounded_fp32_output():

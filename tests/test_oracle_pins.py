@@ -395,3 +395,81 @@ def test_hybrid_and_smoothing_degenerate_cases():
     m = rng.random((5, 6))
     assert np.array_equal(oc.smooth_scores(m, 0.0, g), m)
     assert np.allclose(oc.smooth_scores(np.full((5, 6), 3.0), 0.5, g), 3.0)
+
+
+# ----------------------------------------------------------------- activation smoothing (Eq. 6), fp32 rank keys
+def _binomial3():
+    g = np.array([[1, 2, 1], [2, 4, 2], [1, 2, 1]], np.float32)
+    return g / np.float32(16)          # exact in binary: every tap and every partial sum below is exact
+
+
+def test_smoothed_keys_agree_with_the_fp64_map():
+    rng = np.random.default_rng(61)
+    ph, pw, ns = 7, 9, 5
+    ss = (rng.random(ns + ph * pw) * 40).astype(np.float32)
+    g = synth.gaussian_kernel3(1.0)
+    for alpha in (0.25, 0.5, 1.0):
+        got = oc.smoothed_keys_f32(ss, alpha, ph, pw, ns, g)
+        s = np.sqrt(ss.astype(np.float64))
+        want = oc.smooth_scores(s[ns:].reshape(ph, pw), float(np.float32(alpha)), g.astype(np.float64)).reshape(-1)
+        assert got.dtype == np.float32
+        assert np.array_equal(got[:ns], np.sqrt(ss[:ns]))            # aux tokens keep their raw score
+        assert np.max(np.abs(got[ns:] - want) / want) < 2e-6          # 11 fp32 roundings at most
+
+
+def test_smoothed_keys_alpha_zero_and_constant_map():
+    rng = np.random.default_rng(62)
+    ss = (rng.random(3 + 4 * 6) * 9).astype(np.float32)
+    g = _binomial3()
+    assert np.array_equal(oc.smoothed_keys_f32(ss, 0.0, 4, 6, 3, g)[3:], np.sqrt(ss[3:]))
+    flat = np.full(2 + 5 * 5, 49.0, np.float32)                       # s = 7 everywhere: weights sum to 1
+    assert np.array_equal(oc.smoothed_keys_f32(flat, 0.5, 5, 5, 2, g), np.full(27, 7.0, np.float32))
+
+
+def test_smoothed_keys_impulse_interior_and_replicated_border():
+    g = _binomial3()
+    ph, pw, ns = 5, 6, 1
+    # interior impulse of s = 16 (ss = 256): response is alpha*16*g around it, plus (1-alpha)*16 at the centre
+    ss = np.zeros(ns + ph * pw, np.float32); ss[ns + 2 * pw + 3] = 256.0
+    out = oc.smoothed_keys_f32(ss, 0.5, ph, pw, ns, g)[ns:].reshape(ph, pw)
+    want = np.zeros((ph, pw)); want[1:4, 2:5] = 0.5 * 16.0 * np.array([[1, 2, 1], [2, 4, 2], [1, 2, 1]]) / 16.0
+    want[2, 3] += 0.5 * 16.0
+    assert np.array_equal(out.astype(np.float64), want)
+    # corner impulse: the replicated border folds the taps that fall outside back onto the corner
+    ss = np.zeros(ns + ph * pw, np.float32); ss[ns] = 256.0
+    out = oc.smoothed_keys_f32(ss, 1.0, ph, pw, ns, g)[ns:].reshape(ph, pw)
+    want = np.zeros((ph, pw)); want[0, 0] = 9.0; want[0, 1] = want[1, 0] = 3.0; want[1, 1] = 1.0
+    assert np.array_equal(out.astype(np.float64), want)
+    # an asymmetric kernel tells the tap orientation: tap (a, b) weighs S[y+a-1, x+b-1]
+    e = np.zeros((3, 3), np.float32); e[0, 2] = 1.0                   # up-right neighbour only
+    ss = np.zeros(ns + ph * pw, np.float32); ss[ns + 1 * pw + 4] = 4.0
+    out = oc.smoothed_keys_f32(ss, 1.0, ph, pw, ns, e)[ns:].reshape(ph, pw)
+    assert out[2, 3] == 2.0 and out.sum() == 2.0
+
+
+def test_smoothed_keys_hand_computed_2x2():
+    # S = [[1, 2], [3, 4]], binomial kernel, replicate border, alpha = 1/2, done by hand:
+    # G*S at (0,0): (1*1+2*1+1*2 + 2*1+4*1+2*2 + 1*3+2*3+1*4)/16 = 28/16
+    # G*S at (0,1): (1*1+2*2+1*2 + 2*1+4*2+2*2 + 1*3+2*4+1*4)/16 = 36/16; (1,0): 44/16; (1,1): 52/16
+    ss = np.array([100.0, 1.0, 4.0, 9.0, 16.0], np.float32)          # one aux token with s = 10
+    out = oc.smoothed_keys_f32(ss, 0.5, 2, 2, 1, _binomial3())
+    conv = np.array([28, 36, 44, 52]) / 16.0
+    assert np.array_equal(out.astype(np.float64), np.concatenate([[10.0], 0.5 * conv + 0.5 * np.array([1, 2, 3, 4.0])]))
+
+
+def test_smoothed_stream_keeps_invariants_and_changes_the_choice():
+    cfg = synth.preset(0, M=2 + 4 * 5, n_special=2, B=60, T=9)
+    sm = (0.5, 4, 5, 2, synth.gaussian_kernel3(1.0))
+    a = oc.OracleCache(cfg.M, cfg.H, cfg.d, cfg.B, smooth=sm)
+    b = oc.OracleCache(cfg.M, cfg.H, cfg.d, cfg.B)
+    differs = False
+    for t in range(cfg.T):
+        f = synth.frame_inputs(cfg, 0, t)
+        for c in (a, b):
+            c.append(f["k"], f["v"]); c.update(f["r"], f["a"])
+        assert a.n == min((t + 1) * cfg.M, cfg.B)
+        anchors = t * cfg.M + np.flatnonzero(f["a"])
+        assert np.isin(anchors, a.gid).all() and np.isin(np.arange(cfg.M)[synth.frame_inputs(cfg, 0, 0)["a"] != 0], a.gid).all()
+        assert len(np.unique(a.gid)) == a.n
+        differs |= not np.array_equal(a.gid, b.gid)
+    assert differs                                                     # smoothing is not a no-op on the selection
