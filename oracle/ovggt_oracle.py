@@ -63,7 +63,12 @@ def tree_sum_sq_f32(r: np.ndarray) -> np.ndarray:
     r = np.asarray(r, dtype=np.float32)
     if r.ndim == 1:
         r = r[None, :]
-    p = r * r                                     # fp32 x fp32 -> fp32, one rounding
+    return tree_sum_f32(r * r)                    # fp32 x fp32 -> fp32, one rounding
+
+
+def tree_sum_f32(p: np.ndarray) -> np.ndarray:
+    """Row sums of fp32 terms `p` [n, C] in the balanced-tree order described above."""
+    p = np.asarray(p, dtype=np.float32)
     width = 1
     while width < p.shape[1]:
         width *= 2
@@ -151,14 +156,19 @@ def hole_fill_moves(keep: np.ndarray, budget: int) -> tuple[np.ndarray, np.ndarr
 class OracleCache:
     """One layer's KV cache with scores, ids and protection flags per slot."""
 
-    def __init__(self, M: int, H: int, d: int, budget: int, scale: float | None = None, smooth=None):
+    def __init__(self, M: int, H: int, d: int, budget: int, scale: float | None = None, smooth=None,
+                 hybrid_beta: float | None = None):
         """smooth: None (rank key = ss), or (alpha, patch_h, patch_w, n_special, kernel 3x3) to rank
-        by the smoothed activation map of Eq. 6 (see `smoothed_keys_f32`)."""
+        by the smoothed activation map of Eq. 6 (see `smoothed_keys_f32`).
+        hybrid_beta: None ranks every entry by the score it entered with; a value in [0, 1]
+        ranks by Eq. 7 (see `hybrid_keys_f32`) whenever something has to be evicted, and the
+        rank value r replaces the stored score of every evictable entry."""
         if budget < M:
             raise ValueError("budget must hold at least one frame")
         self.M, self.H, self.d, self.B = M, H, d, budget
         self.scale = scale
         self.smooth = smooth
+        self.hybrid_beta = hybrid_beta
         self.k = np.zeros((0, H, d), np.float32)
         self.v = np.zeros((0, H, d), np.float32)
         self.gid = np.zeros(0, np.uint32)
@@ -197,6 +207,10 @@ class OracleCache:
         flag_new = np.zeros(M, np.uint8) if anchor_t is None else (np.asarray(anchor_t) != 0).astype(np.uint8)
         ss = self.ss.copy(); ss[n - M:] = ss_new
         flag = self.flag.copy(); flag[n - M:] = flag_new
+        if self.hybrid_beta is not None and n > self.B:
+            s_new = ss_new if self.smooth is not None else np.sqrt(ss_new)       # fp32, correctly rounded
+            r = hybrid_keys_f32(cached_half(self.k), flag, M, s_new, self.hybrid_beta)
+            ss = np.where(flag != 0, ss, r).astype(np.float32)
         keep = select_keep(ss, self.gid, flag, self.B)     # raises before any state change
         self.ss, self.flag = ss, flag
         if np.isnan(ss_new).any():
@@ -242,6 +256,68 @@ def hybrid_rank(k_hist: np.ndarray, s_new: np.ndarray, beta: float) -> tuple[np.
     else:
         d = np.zeros(0)
     return (1.0 - beta) * minmax01(d), beta * minmax01(s_new)
+
+
+def cached_half(k: np.ndarray) -> np.ndarray:
+    """The keys as a bf16 cache holds them: the IEEE half nearest each given value (ties to
+    even, 2^-24 grid below 2^-14), saturated at +-65504; returned as fp32."""
+    with np.errstate(over="ignore"):
+        return np.clip(np.asarray(k, np.float32), -65504.0, 65504.0).astype(np.float16).astype(np.float32)
+
+
+def hybrid_keys_f32(k_half: np.ndarray, flag: np.ndarray, n_new: int, s_new: np.ndarray, beta: float) -> np.ndarray:
+    """Eq. 7 rank values r for every resident entry, as one fixed fp32 operation sequence.
+
+    k_half [n, H, d] (or [n, H*d]): half-representable key values; a token's key vector is the
+    concatenation over heads.  The last n_new entries are the current frame, whose scores
+    (s of Eq. 5, or Eq. 6's smoothed s) are `s_new`; the others are history.  Flagged entries
+    are in P and get r = NaN here (callers ignore them).
+
+    Centroid: the sum of the evictable history keys, accumulated exactly (every half is an
+    integer multiple of 2^-24, the integer sum cannot overflow 64 bits below 2^17 entries),
+    then rounded integer -> fp64 -> fp32 and scaled by 2^-24.  The cosine does not depend on
+    the centroid's length, so the sum stands for the mean.  Per history token, in fp32:
+    dot = tree(k_j * c_j), nk = tree(k_j^2), nc = tree(c_j^2) (the balanced tree of
+    `tree_sum_f32`), cos = dot / (sqrt(nk) * sqrt(nc)) (0 when that product is 0), d = 1 - cos.
+    Min-max: x^ = (x - min) / (max - min) over the evictable set of each source, all zeros when
+    max = min; r = (1 - beta) * d^ for history, beta * s^ for the current frame.
+    Which tokens form the centroid, whether keys are taken per head, and the degenerate
+    cases are this build's reading (parity unpinned by the paper)."""
+    f32 = np.float32
+    k = np.asarray(k_half, dtype=np.float32)
+    n = len(k)
+    k = k.reshape(n, -1)
+    flag = np.asarray(flag) != 0
+    idx = np.arange(n)
+    hist = (idx < n - n_new) & ~flag
+    new = (idx >= n - n_new) & ~flag
+    r = np.full(n, np.nan, np.float32)
+    b = f32(beta)
+    if hist.any():
+        fixed = k[hist].astype(np.float64) * 2.0 ** 24
+        assert np.array_equal(fixed, np.rint(fixed)) and np.abs(fixed).max(initial=0) < 2.0 ** 41 and hist.sum() < 2 ** 17
+        csum = fixed.astype(np.int64).sum(axis=0)                       # exact
+        c = csum.astype(np.float64).astype(np.float32) * f32(2.0 ** -24)  # two roundings, then an exact scaling
+        kh = k[hist]
+        nc = tree_sum_f32((c * c)[None, :])[0]
+        nk = tree_sum_f32(kh * kh)
+        dot = tree_sum_f32(kh * c[None, :])
+        den = np.sqrt(nk) * np.sqrt(nc)
+        with np.errstate(divide="ignore", invalid="ignore"):
+            cos = np.where(den == 0, f32(0), dot / den).astype(np.float32)
+        d = f32(1) - cos
+        r[hist] = (f32(1) - b) * _minmax01_f32(d)
+    if new.any():
+        sn = np.asarray(s_new, dtype=np.float32)[new[n - n_new:]]
+        r[new] = b * _minmax01_f32(sn)
+    return r
+
+
+def _minmax01_f32(x: np.ndarray) -> np.ndarray:
+    lo, hi = x.min(), x.max()
+    if hi == lo:
+        return np.zeros_like(x)
+    return (x - lo) / (hi - lo)
 
 
 def smoothed_keys_f32(ss_new: np.ndarray, alpha: float, ph: int, pw: int, n_special: int, g) -> np.ndarray:

@@ -473,3 +473,99 @@ def test_smoothed_stream_keeps_invariants_and_changes_the_choice():
         assert len(np.unique(a.gid)) == a.n
         differs |= not np.array_equal(a.gid, b.gid)
     assert differs                                                     # smoothing is not a no-op on the selection
+
+
+# ----------------------------------------------------------------- hybrid scoring (Eq. 7), fp32 rank values
+def _half_keys(rng, n, H, d, scale=1.0):
+    return oc.cached_half(synth.quantise((rng.standard_normal((n, H, d)) * scale).astype(np.float32), "bf16"))
+
+
+def test_hybrid_keys_agree_with_the_fp64_formula():
+    rng = np.random.default_rng(71)
+    n, m, H, d = 300, 40, 3, 64
+    k = _half_keys(rng, n, H, d) + np.float32(0.25)          # off-centre cloud: cosines spread over a wide range
+    k = oc.cached_half(k)
+    flag = (rng.random(n) < 0.1).astype(np.uint8)
+    s_new = rng.random(m).astype(np.float32) * 30
+    for beta in (0.3, 0.5):
+        r = oc.hybrid_keys_f32(k, flag, m, s_new, beta)
+        hist = (np.arange(n) < n - m) & (flag == 0); new = (np.arange(n) >= n - m) & (flag == 0)
+        d64, s64 = oc.hybrid_rank(k[hist].reshape(hist.sum(), -1), s_new[new[n - m:]].astype(np.float64), float(np.float32(beta)))
+        assert r.dtype == np.float32 and np.isnan(r[flag != 0]).all()
+        assert np.max(np.abs(r[hist] - d64)) < 2e-5 and np.max(np.abs(r[new] - s64)) < 1e-6
+        assert r[hist].min() == 0 and r[hist].max() == np.float32(1) - np.float32(beta)
+        assert r[new].min() == 0 and r[new].max() == np.float32(beta)
+
+
+def test_hybrid_keys_exact_centroid_makes_slot_order_and_scale_irrelevant():
+    rng = np.random.default_rng(72)
+    n, m = 500, 30
+    k = _half_keys(rng, n, 2, 64)
+    flag = (rng.random(n) < 0.05).astype(np.uint8)
+    s_new = rng.random(m).astype(np.float32)
+    r = oc.hybrid_keys_f32(k, flag, m, s_new, 0.5)
+    perm = np.concatenate([rng.permutation(n - m), np.arange(n - m, n)])
+    rp = oc.hybrid_keys_f32(k[perm], flag[perm], m, s_new, 0.5)
+    assert np.array_equal(rp.view(np.uint32), r[perm].view(np.uint32))          # bit for bit
+    r4 = oc.hybrid_keys_f32(k * np.float32(4), flag, m, s_new, 0.5)             # exact in half, cosines unchanged
+    assert np.array_equal(r4.view(np.uint32), r.view(np.uint32))
+    # protected entries take no part: deleting them changes nothing for the others
+    keep = flag == 0
+    rd = oc.hybrid_keys_f32(k[keep], flag[keep], int(keep[n - m:].sum()), s_new[keep[n - m:]], 0.5)
+    assert np.array_equal(rd.view(np.uint32), r[keep].view(np.uint32))
+
+
+def test_hybrid_keys_closed_forms():
+    H, d = 2, 64
+    a = np.zeros((H, d), np.float32); a[0, 0] = 3; a[1, 5] = 4             # |a| = 5, spread over both heads
+    k = np.stack([a, a, a, -a, a])                                          # last entry is the current frame
+    r = oc.hybrid_keys_f32(k, np.zeros(5, np.uint8), 1, np.array([7.0], np.float32), 0.25)
+    # centroid 2a: cos = +1, +1, +1, -1 -> d = 0, 0, 0, 2 -> min-max 0, 0, 0, 1; a single new token: max = min -> 0
+    assert np.array_equal(r, np.array([0, 0, 0, 0.75, 0], np.float32))
+    e1 = np.zeros((H, d), np.float32); e1[0, 1] = 3
+    e2 = np.zeros((H, d), np.float32); e2[1, 2] = 3
+    k = np.stack([e1, e2, (e1 + e2) * 2, e1, e2])
+    r = oc.hybrid_keys_f32(k, np.zeros(5, np.uint8), 2, np.array([1.0, 3.0], np.float32), 0.5)
+    # centroid (5, 5): e1 and e2 sit at 45 degrees (equal d, the maximum), the diagonal key at 0 degrees
+    assert np.array_equal(r, np.array([0.5, 0.5, 0, 0, 0.5], np.float32))
+    # two history tokens at the same angle only: max = min -> all zeros
+    r = oc.hybrid_keys_f32(np.stack([e1, e2, e1]), np.zeros(3, np.uint8), 1, np.array([2.0], np.float32), 0.5)
+    assert np.array_equal(r, np.zeros(3, np.float32))
+    # an all-zero key has no direction: cos = 0, d = 1
+    z = np.zeros((H, d), np.float32)
+    r = oc.hybrid_keys_f32(np.stack([a, a, -a, z, a]), np.zeros(5, np.uint8), 1, np.array([2.0], np.float32), 0.0)
+    assert np.array_equal(r, np.array([0, 0, 1, 0.5, 0], np.float32))     # centroid a: d = 0, 0, 2, 1
+
+
+def test_hybrid_beta_extremes():
+    rng = np.random.default_rng(73)
+    k = _half_keys(rng, 60, 2, 64); s_new = rng.random(10).astype(np.float32)
+    r0 = oc.hybrid_keys_f32(k, np.zeros(60, np.uint8), 10, s_new, 0.0)
+    r1 = oc.hybrid_keys_f32(k, np.zeros(60, np.uint8), 10, s_new, 1.0)
+    assert np.all(r0[50:] == 0) and r0[:50].max() == 1 and np.all(r1[:50] == 0) and r1[50:].max() == 1
+    assert np.argmax(r1[50:]) == np.argmax(s_new)
+
+
+def test_hybrid_stream_invariants_and_threshold():
+    cfg = synth.preset(1, M=40, H=2, C=64, B=150, T=12, n_special=2)
+    c = oc.OracleCache(cfg.M, cfg.H, cfg.d, cfg.B, hybrid_beta=0.5)
+    plain = oc.OracleCache(cfg.M, cfg.H, cfg.d, cfg.B)
+    differs = False
+    for t in range(cfg.T):
+        f = synth.frame_inputs(cfg, 0, t)
+        c.append(f["k"], f["v"]); plain.append(f["k"], f["v"]); plain.update(f["r"], f["a"])
+        n = c.n
+        kh, gid, fl = oc.cached_half(c.k).reshape(n, -1).astype(np.float64), c.gid.copy(), None
+        keep = c.update(f["r"], f["a"])
+        assert c.n == min((t + 1) * cfg.M, cfg.B) and len(np.unique(c.gid)) == c.n
+        assert np.isin(np.arange(cfg.M)[synth.frame_inputs(cfg, 0, 0)["a"] != 0], c.gid).all()
+        if n > cfg.B:
+            fl = np.zeros(n, bool); fl[np.isin(gid, c.gid[c.flag != 0])] = True
+            hist = (np.arange(n) < n - cfg.M) & ~fl; new = (np.arange(n) >= n - cfg.M) & ~fl
+            s = np.sqrt(oc.tree_sum_sq_f32(f["r"]).astype(np.float64))
+            r = np.zeros(n); r[hist], r[new] = oc.hybrid_rank(kh[hist], s[new[n - cfg.M:]], 0.5)
+            ev = ~fl
+            assert keep[fl].all() and keep.sum() == cfg.B
+            assert r[keep & ev].min() >= r[~keep].max() - 2e-5              # kept ones outrank evicted ones
+        differs |= not np.array_equal(np.sort(c.gid), np.sort(plain.gid))
+    assert differs
