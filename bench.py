@@ -52,7 +52,7 @@ def profiled_traffic(kernel, workload, layers):
     return None
 
 
-def cpu_baseline(cfg, warm_frames, timed_frames):
+def cpu_baseline(cfg, warm_frames, timed_frames, smooth=None, hybrid_beta=None):
     """The oracle as it stands: attention-free warm-up to reach the steady-state
     cache, then whole steps (fp64 attention + score + select + compact) timed."""
     from oracle import ovggt_oracle as oc            # cpu_baseline leg only
@@ -61,7 +61,7 @@ def cpu_baseline(cfg, warm_frames, timed_frames):
         cores = max((p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()), default=1)
     except Exception:
         cores = os.cpu_count() or 1
-    orc = oc.OracleCache(cfg.M, cfg.H, cfg.d, cfg.B)
+    orc = oc.OracleCache(cfg.M, cfg.H, cfg.d, cfg.B, smooth=smooth, hybrid_beta=hybrid_beta)
     for t in range(warm_frames):
         f = synth.frame_inputs(cfg, 0, t, want=("k", "v", "r", "a"))
         orc.append(f["k"], f["v"])
@@ -86,6 +86,10 @@ def main():
     ap.add_argument("--config", type=int, default=1, help="workload preset (1 = the headline layer)")
     ap.add_argument("--layers", type=int, default=None, help="override the preset's layer count")
     ap.add_argument("--budget", type=int, default=None)
+    ap.add_argument("--hybrid-beta", type=float, default=None,
+                    help="rank by hybrid scoring (Eq. 7) with this beta instead of the stored Eq. 5 scores")
+    ap.add_argument("--smooth-alpha", type=float, default=None,
+                    help="activation smoothing (Eq. 6) with this alpha and a 3x3 Gaussian (sigma 1) over the patch map")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-frames", type=int, default=3)
     ap.add_argument("--detail-steps", type=int, default=40, help="extra untimed steps with per-kernel events")
@@ -142,7 +146,11 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    cache = B.Cache(L, cfg.H, cfg.d, cfg.M, cfg.C, cfg.B, cfg.dtype)
+    smooth = None
+    if args.smooth_alpha:
+        ph, pw = synth.patch_grid(cfg)
+        smooth = (args.smooth_alpha, ph, pw, cfg.M - ph * pw, synth.gaussian_kernel3(1.0))
+    cache = B.Cache(L, cfg.H, cfg.d, cfg.M, cfg.C, cfg.B, cfg.dtype, smooth=smooth, hybrid_beta=args.hybrid_beta)
     out = cache.new_output()                             # fp32 outputs (fp32 accumulators stored unrounded)
     layer = B.OVGGT_ALL_LAYERS if L > 1 else 0
 
@@ -228,7 +236,10 @@ def main():
         "config": {"workload": f"{cfg.name}: {L} layer(s) x (M={cfg.M} tokens/frame, {cfg.H}x{cfg.d} heads, "
                                f"C={cfg.C}, budget B={cfg.B}), {T}-frame stream, {cfg.dtype}",
                    "tokens_per_frame": cfg.M, "budget": cfg.B, "layers": L, "frames": T,
-                   "resident_keys_steady": int(n_keys), "out_dtype": "f32"},
+                   "resident_keys_steady": int(n_keys), "out_dtype": "f32",
+                   "ranking": ("hybrid Eq. 7, beta=%g" % args.hybrid_beta) if args.hybrid_beta is not None
+                              else "stored Eq. 5 scores",
+                   "smoothing": ("Eq. 6, alpha=%g, 3x3 Gaussian sigma 1" % args.smooth_alpha) if smooth else "off"},
         "roofline": roofline,
         "kernels_us": kernels,
         "hbm_kernels": hbm,
@@ -253,7 +264,8 @@ def main():
                                "note": "event-bracketed whole steps, every 8th timed step, frames with a full cache"}
     cache.close()
     if not args.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline(cfg, warm_frames=max(cfg.B // cfg.M + 2, 2), timed_frames=args.cpu_frames)
+        res["cpu_baseline"] = cpu_baseline(cfg, warm_frames=max(cfg.B // cfg.M + 2, 2), timed_frames=args.cpu_frames,
+                                           smooth=smooth, hybrid_beta=args.hybrid_beta)
     print(json.dumps(res))
 
 

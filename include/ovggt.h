@@ -70,7 +70,8 @@ typedef struct {
   int32_t resid_dim;         /* C: width of the FFN-residual rows, 1..4096                 */
   int32_t budget;            /* B tokens per layer, protected tokens included; B >= M      */
   int32_t dtype;             /* OVGGT_F32 or OVGGT_BF16: Q/K/V/O/residual and cache storage */
-  int32_t score_mode;        /* 0 = every entry keeps the Eq. 5 score it entered with      */
+  int32_t score_mode;        /* 0 = every entry keeps the Eq. 5 score it entered with;
+                                1 = hybrid scoring (Eq. 7), see hybrid_beta below           */
   float   softmax_scale;     /* 0 => 1/sqrt(head_dim)                                      */
   int32_t out_dtype;         /* type of the attention output O: OVGGT_F32, or OVGGT_BF16
                                 (bf16 handles only).  bf16 handles accumulate O in fp32
@@ -88,6 +89,21 @@ typedef struct {
   float   smooth_alpha;
   int32_t patch_h, patch_w, n_special;
   float   smooth_kernel[9];
+  /* Hybrid scoring (Eq. 7), score_mode 1, bf16 handles with n_heads <= 64 only.  Whenever a
+   * selection has to evict (n > B after the append), every evictable entry is ranked by
+   *   r = (1 - beta) * minmax(d_i),  d_i = 1 - cos(k_i, kbar)   for the entries of earlier frames,
+   *   r = beta * minmax(s_i)                                     for the current frame's tokens
+   * (s_i = sqrt(ss_i), or Eq. 6's smoothed value when smoothing is on), and r replaces the
+   * entry's stored score (`ss` of export); protected entries keep theirs.  k_i is the cached
+   * (half precision) key of all heads concatenated, kbar the centroid of the evictable earlier
+   * entries, summed exactly in 64-bit fixed point (units of 2^-24) and rounded to fp32 via fp64;
+   * dot products and squared norms are fp32 balanced trees over the index h*d + e (zero-padded
+   * to a power of two); cos = dot / (sqrt(|k_i|^2) * sqrt(|kbar|^2)), 0 when that product is 0;
+   * minmax(x) = (x - min) / (max - min) over the evictable entries of the same source, 0 when
+   * max = min.  Every step is one correctly rounded fp32 operation.  Which tokens form the
+   * centroid, the concatenation over heads and the degenerate cases are not fixed by the paper.
+   * Frames that fit the budget are not ranked at all.  0 <= beta <= 1; ignored in score_mode 0. */
+  float   hybrid_beta;
 } ovggt_config;
 
 /* Sizes (bytes) of the three caller-allocated device buffers for `cfg`:

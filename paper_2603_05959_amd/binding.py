@@ -32,7 +32,8 @@ class ovggt_config(C.Structure):
                 ("tokens_per_frame", C.c_int32), ("resid_dim", C.c_int32), ("budget", C.c_int32),
                 ("dtype", C.c_int32), ("score_mode", C.c_int32), ("softmax_scale", C.c_float),
                 ("out_dtype", C.c_int32), ("smooth_alpha", C.c_float), ("patch_h", C.c_int32),
-                ("patch_w", C.c_int32), ("n_special", C.c_int32), ("smooth_kernel", C.c_float * 9)]
+                ("patch_w", C.c_int32), ("n_special", C.c_int32), ("smooth_kernel", C.c_float * 9),
+                ("hybrid_beta", C.c_float)]
 
 
 class OvggtError(RuntimeError):
@@ -101,8 +102,9 @@ def _ptr(t) -> int:
 
 
 def make_config(n_layers, n_heads, head_dim, tokens_per_frame, resid_dim, budget, dtype,
-                score_mode=0, softmax_scale=0.0, out_dtype="f32", smooth=None) -> ovggt_config:
-    """smooth: None, or (alpha, patch_h, patch_w, n_special, kernel) with kernel nine floats, row-major."""
+                score_mode=0, softmax_scale=0.0, out_dtype="f32", smooth=None, hybrid_beta=0.0) -> ovggt_config:
+    """smooth: None, or (alpha, patch_h, patch_w, n_special, kernel) with kernel nine floats, row-major.
+    hybrid_beta: Eq. 7's beta, read when score_mode is 1."""
     codes = {"f32": OVGGT_F32, "bf16": OVGGT_BF16}
     cfg = ovggt_config(n_layers, n_heads, head_dim, tokens_per_frame, resid_dim, budget,
                        codes.get(dtype, dtype), score_mode, softmax_scale, codes.get(out_dtype, out_dtype))
@@ -110,6 +112,7 @@ def make_config(n_layers, n_heads, head_dim, tokens_per_frame, resid_dim, budget
         alpha, ph, pw, ns, kern = smooth
         cfg.smooth_alpha, cfg.patch_h, cfg.patch_w, cfg.n_special = float(alpha), int(ph), int(pw), int(ns)
         cfg.smooth_kernel = (C.c_float * 9)(*[float(x) for x in np.asarray(kern, dtype=np.float32).reshape(9)])
+    cfg.hybrid_beta = float(hybrid_beta)
     return cfg
 
 
@@ -210,11 +213,12 @@ class Cache:
     Holds no logic of its own beyond marshalling."""
 
     def __init__(self, n_layers, n_heads, head_dim, tokens_per_frame, resid_dim, budget, dtype,
-                 softmax_scale=0.0, device="cuda:0", out_dtype="f32", smooth=None):
+                 softmax_scale=0.0, device="cuda:0", out_dtype="f32", smooth=None, hybrid_beta=None):
         import torch
         self.torch = torch
         self.cfg = make_config(n_layers, n_heads, head_dim, tokens_per_frame, resid_dim, budget, dtype,
-                               0, softmax_scale, out_dtype, smooth)
+                               0 if hybrid_beta is None else 1, softmax_scale, out_dtype, smooth,
+                               0.0 if hybrid_beta is None else hybrid_beta)
         self.dtype = dtype
         self.out_dtype = out_dtype
         self.L, self.H, self.d, self.M, self.Cdim, self.B = n_layers, n_heads, head_dim, tokens_per_frame, resid_dim, budget

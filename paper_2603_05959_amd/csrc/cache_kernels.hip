@@ -45,6 +45,16 @@ __global__ void __launch_bounds__(256)
 append_kernel(Geom g, char* kv, char* meta, int layer0, const char* k_new, const char* v_new,
               int n, uint32_t gid0) {
   const int layer = layer0 + blockIdx.y;
+  if (g.hybrid && blockIdx.x == 0) {
+    // Hybrid scoring: the frame's diversity pass wants the centroid in fp32.  The running sum (64-bit
+    // integers in units of 2^-24, final since the previous frame's update) is rounded integer -> fp64
+    // -> fp32, each to nearest even, and scaled by 2^-24 exactly.
+    char* mb = layer_meta(meta, g, layer);
+    const long long* csum = (const long long*)(mb + g.off_csum);
+    float* cvec = (float*)(mb + g.off_cvec);
+    for (int e = threadIdx.x; e < g.H * g.d; e += blockDim.x)
+      cvec[e] = (float)(double)csum[e] * 5.9604644775390625e-8f;
+  }
   const int row_bytes = g.d * g.esize;             // 128 (bf16) or 256 (f32)
   const int pieces = row_bytes / 16;
   const size_t per_layer_in = (size_t)g.M * g.H * row_bytes;

@@ -1,0 +1,323 @@
+// Diversity scores of the cached history (paper Eq. 7, first case): d_i = 1 - cos(k_i, kbar),
+// where k_i is a token's key over all heads and kbar the centroid of the evictable history.
+//
+// The centroid is kept as a running sum of the evictable resident keys.  Every half is an integer
+// multiple of 2^-24, so the sum is a 64-bit integer in those units: exact, independent of the
+// order in which workgroups and atomics add their parts, and therefore something that can be
+// maintained frame by frame (add the tokens that stay, subtract the entries that leave: O(M) rows)
+// instead of re-read from the whole cache (O(B) rows).
+//   centroid_update_kernel   the per-frame maintenance, after the selection
+//   centroid_rebuild_kernel  the same sum from nothing, after a cache import
+//   diversity_kernel  the HBM-bound pass over the layer's K cache, one wave per history slot: dot(k_i, c), |k_i|^2 and |c|^2 as fp32 balanced
+//                     trees over the concatenated index h*d + e (lane l owns E consecutive
+//                     elements, pairwise sums in registers, then six xor-butterfly steps), then
+//                     d_i = 1 - dot / (sqrt(|k_i|^2) * sqrt(|c|^2)), written to the layer's d_i array.
+// The selection kernel min-max normalises these and blends them with the new frame's scores.
+#include "ovggt_internal.h"
+#include "../../include/ovggt.h"
+#include <hip/hip_fp16.h>
+
+namespace ovggt {
+
+constexpr int kCenThreads = 256;
+constexpr int kCenUnroll = 8;                 // 16-byte loads a thread keeps in flight
+constexpr int kCenMaxAdds = 64;               // 64 * 2^24 < 2^31
+constexpr int kDivThreads = 256;
+constexpr int kDivWaves = kDivThreads / 64;
+constexpr int kDivRows = 8;                   // slots per wave and round (independent loads in flight together); 1 for very wide keys
+
+__device__ inline void unpack_halfs(const uint4& w, float f[8]) {
+  const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    const __half2 h = *(const __half2*)&ww[t];
+    f[2 * t] = __low2float(h);
+    f[2 * t + 1] = __high2float(h);
+  }
+}
+
+// ---- exact centroid sum -------------------------------------------------------------------------
+// A thread owns 8 consecutive elements of one head (a 16-byte piece of a slot's 128-byte row);
+// 8*H threads cover a key, kCenThreads / (8*H) keys are read side by side, and kCenUnroll loads per
+// thread are in flight before any is consumed.  `row(v, &slot)` names the cache slot of the
+// workgroup's v-th row and returns +1 (add), -1 (subtract) or 0 (skip); each workgroup ends with
+// one 64-bit atomic per key element it changed.
+template <typename RowFn>
+__device__ inline void accumulate_rows(const Geom& g, const char* K, unsigned long long* csum,
+                                       int v0, int v1, RowFn row) {
+  __shared__ long long part[kCenThreads][8];
+  const int pieces = g.H * 8;                         // 16-byte pieces per key
+  for (int p0 = 0; p0 < pieces; p0 += kCenThreads) {  // one trip unless the key is wider than 32 heads
+    const int lanes = min(pieces - p0, kCenThreads);  // threads that hold a piece in this trip
+    const int side = kCenThreads / lanes;             // keys read side by side
+    const int piece = p0 + (int)threadIdx.x % lanes, sl = (int)threadIdx.x / lanes;
+    const int h = piece >> 3, cg = piece & 7;
+    const char* Kp = K + (size_t)h * g.cap * 128 + cg * 16;
+    // value * 2^24 = hi * 2^16 + lo with |hi| < 2^24 and |lo| < 2^16; a thread adds at most
+    // kCenMaxAdds of them into the 32-bit sums before they are widened
+    int hi[8], lo[8];
+    long long acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { hi[j] = 0; lo[j] = 0; acc[j] = 0; }
+    int adds = 0;
+    if (sl < side) {
+      for (int base = v0 + sl; base < v1; base += side * kCenUnroll) {
+        uint4 w[kCenUnroll];
+        int sign[kCenUnroll];
+#pragma unroll
+        for (int u = 0; u < kCenUnroll; ++u) {
+          const int v = base + u * side;
+          int slot = 0;
+          sign[u] = v < v1 ? row(v, &slot) : 0;
+          w[u] = *(const uint4*)(Kp + (size_t)slot * 128);       // slot 0 when the row is skipped: in bounds
+        }
+#pragma unroll
+        for (int u = 0; u < kCenUnroll; ++u) {
+          if (sign[u] == 0) continue;
+          float f[8];
+          unpack_halfs(w[u], f);
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            const float a = f[j] * 256.0f;            // exact
+            const int ih = (int)a;                    // towards zero
+            const float rem = a - (float)ih;          // exact, |rem| < 1, a multiple of 2^-16
+            hi[j] += sign[u] * ih;
+            lo[j] += sign[u] * (int)(rem * 65536.0f);
+          }
+        }
+        adds += kCenUnroll;
+        if (adds + kCenUnroll > kCenMaxAdds) {
+#pragma unroll
+          for (int j = 0; j < 8; ++j) { acc[j] += (long long)hi[j] * 65536 + (long long)lo[j]; hi[j] = 0; lo[j] = 0; }
+          adds = 0;
+        }
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) part[threadIdx.x][j] = acc[j] + (long long)hi[j] * 65536 + (long long)lo[j];
+    __syncthreads();
+    // element e of the trip's pieces: sum over the keys read side by side, one atomic per element
+    for (int e = threadIdx.x; e < lanes * 8; e += kCenThreads) {
+      long long t = 0;
+      for (int r = 0; r < side; ++r) t += part[r * lanes + (e >> 3)][e & 7];
+      if (t != 0) atomicAdd(&csum[(size_t)p0 * 8 + e], (unsigned long long)t);
+    }
+    __syncthreads();
+  }
+}
+
+// Sum of all evictable entries among slots [0, n): builds the centroid sum from nothing (after an
+// import).  grid (chunks, 1); the sums must be zero on entry.
+__global__ void __launch_bounds__(kCenThreads)
+centroid_rebuild_kernel(Geom g, char* kv, char* meta, int layer, int n, int chunk) {
+  char* mb = layer_meta(meta, g, layer);
+  const uint8_t* flags = (const uint8_t*)(mb + g.off_flags);
+  const int v0 = blockIdx.x * chunk, v1 = min(v0 + chunk, n);
+  accumulate_rows(g, layer_k(kv, g, layer), (unsigned long long*)(mb + g.off_csum), v0, v1,
+                  [&](int v, int* slot) { *slot = v; return flags[v] ? 0 : 1; });
+}
+
+// After a frame's selection: the sum gains the frame's evictable tokens that stay and loses the
+// evicted entries of earlier frames, so that it again covers every evictable resident entry.
+// Rows [0, M) are the frame's slots n_old + v; rows [M, 2M) walk the hole list (slots below B whose
+// entry was evicted), of which the ones below n_old held earlier frames' entries.  grid (chunks, layers).
+__global__ void __launch_bounds__(kCenThreads)
+centroid_update_kernel(Geom g, char* kv, char* meta, int layer0, int n_total, int chunk) {
+  const int layer = layer0 + blockIdx.y;
+  char* mb = layer_meta(meta, g, layer);
+  const uint8_t* flags = (const uint8_t*)(mb + g.off_flags);
+  const uint32_t* evbits = (const uint32_t*)(mb + g.off_evbits);
+  const uint32_t* holes = (const uint32_t*)(mb + g.off_mvdst);
+  const int n_old = n_total - g.M;
+  const bool evicting = n_total > g.B;
+  const int n_holes = evicting ? (int)min(((const Ctrl*)(mb + g.off_ctrl))->n_moves, (uint32_t)g.M) : 0;
+  const int v0 = blockIdx.x * chunk, v1 = min(v0 + chunk, 2 * g.M);
+  accumulate_rows(g, layer_k(kv, g, layer), (unsigned long long*)(mb + g.off_csum), v0, v1,
+                  [&](int v, int* slot) {
+                    if (v < g.M) {
+                      const int s = n_old + v;
+                      if (flags[s]) return 0;
+                      if (evicting && ((evbits[s >> 5] >> (s & 31)) & 1u)) return 0;
+                      *slot = s;
+                      return 1;
+                    }
+                    const int j = v - g.M;
+                    if (j >= n_holes) return 0;
+                    const int s = (int)holes[j];
+                    if (s >= n_old) return 0;          // a token of this frame: never entered the sum
+                    *slot = s;
+                    return -1;
+                  });
+}
+
+constexpr int div_rows(int e) { return e >= 32 ? 1 : (e == 16 ? 4 : kDivRows); }   // keeps a round's keys in registers
+
+// ---- pass 2: d_i per history slot ----------------------------------------------------------------
+// Sum over the wave of one value per lane, as the balanced tree that pairs lanes differing in bit 0,
+// then bit 1, ... bit 5.  After each level all lanes of a group hold the group's sum, so the partner
+// may be any lane of the sibling group: quad permutes, the two row mirrors and the two lane-swap
+// instructions reach one without going through the LDS crossbar.
+__device__ inline float dpp_f(float v, int ctrl_is) {
+  // ctrl_is: 0 quad [1,0,3,2], 1 quad [2,3,0,1], 2 row half mirror, 3 row mirror
+  const int x = __float_as_int(v);
+  int y;
+  switch (ctrl_is) {
+    case 0: y = __builtin_amdgcn_update_dpp(0, x, 0xB1, 0xF, 0xF, false); break;
+    case 1: y = __builtin_amdgcn_update_dpp(0, x, 0x4E, 0xF, 0xF, false); break;
+    case 2: y = __builtin_amdgcn_update_dpp(0, x, 0x141, 0xF, 0xF, false); break;
+    default: y = __builtin_amdgcn_update_dpp(0, x, 0x140, 0xF, 0xF, false); break;
+  }
+  return __int_as_float(y);
+}
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+__device__ inline float wave_tree_sum(float v) {
+  v = v + dpp_f(v, 0);
+  v = v + dpp_f(v, 1);
+  v = v + dpp_f(v, 2);
+  v = v + dpp_f(v, 3);
+  const u32x2 a = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  v = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+  const u32x2 b = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+
+template <int E>
+__device__ inline float tree64(float p[E]) {
+#pragma unroll
+  for (int w = 1; w < E; w *= 2)
+#pragma unroll
+    for (int j = 0; j < E; j += 2 * w) p[j] = p[j] + p[j + w];
+  return wave_tree_sum(p[0]);
+}
+
+// the lane's E key elements of one slot: elements [E*lane, E*lane + E) of the concatenated key,
+// which lie inside one head row because E divides 64
+template <int E>
+__device__ inline void load_key(const char* K, const Geom& g, int slot, int lane, bool live, float k[E]) {
+  const int j0 = E * lane, h = j0 >> 6, e0 = j0 & 63;
+  const char* p = K + ((size_t)h * g.cap + slot) * 128 + e0 * 2;
+  if (!live) {
+#pragma unroll
+    for (int j = 0; j < E; ++j) k[j] = 0.f;
+    return;
+  }
+  if constexpr (E >= 8) {
+#pragma unroll
+    for (int j = 0; j < E; j += 8) unpack_halfs(*(const uint4*)(p + 2 * j), k + j);
+  } else if constexpr (E == 4) {
+    const uint2 w = *(const uint2*)p;
+    const __half2 a = *(const __half2*)&w.x, b = *(const __half2*)&w.y;
+    k[0] = __low2float(a); k[1] = __high2float(a); k[2] = __low2float(b); k[3] = __high2float(b);
+  } else if constexpr (E == 2) {
+    const uint32_t w = *(const uint32_t*)p;
+    const __half2 a = *(const __half2*)&w;
+    k[0] = __low2float(a); k[1] = __high2float(a);
+  } else {
+    k[0] = __half2float(*(const __half*)p);
+  }
+}
+
+template <int E, int R>
+__global__ void __launch_bounds__(kDivThreads)
+diversity_kernel(Geom g, char* kv, char* meta, int layer0, int n_hist) {
+#pragma clang fp contract(off)
+  const int layer = layer0 + blockIdx.y;
+  char* mb = layer_meta(meta, g, layer);
+  const uint8_t* flags = (const uint8_t*)(mb + g.off_flags);
+  const float* cvec = (const float*)(mb + g.off_cvec);
+  float* dval = (float*)(mb + g.off_dval);
+  const char* K = layer_k(kv, g, layer);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const bool live = E * lane < g.H * 64;             // lanes past the key's width hold the tree's zero padding
+  const int n_waves = blockDim.x >> 6;
+  const int stride = gridDim.x * n_waves * R;
+  int s0 = (blockIdx.x * n_waves + wave) * R;
+  if (s0 >= n_hist) return;
+
+  // the first round's keys are requested before the centroid is unpacked
+  float k[R][E];
+  uint8_t fl;                                         // lane r < R: the flag of the round's r-th slot
+#pragma unroll
+  for (int r = 0; r < R; ++r) load_key<E>(K, g, min(s0 + r, n_hist - 1), lane, live, k[r]);
+  fl = flags[min(s0 + min(lane, R - 1), n_hist - 1)];
+
+  float c[E], t[E];
+#pragma unroll
+  for (int j = 0; j < E; ++j) {
+    c[j] = live ? cvec[E * lane + j] : 0.f;      // the fp32 centroid the frame's append left
+    t[j] = c[j] * c[j];
+  }
+  const float root_nc = __builtin_sqrtf(tree64<E>(t));
+
+  for (;;) {
+    // every lane ends up with the sums of all R slots; lane r keeps those of slot r and finishes it,
+    // so the square roots and the division run once per round, not once per slot
+    float dot = 0.f, nk = 0.f;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      float p[E], q[E];
+#pragma unroll
+      for (int j = 0; j < E; ++j) { p[j] = k[r][j] * c[j]; q[j] = k[r][j] * k[r][j]; }
+      const float dr = tree64<E>(p), nr = tree64<E>(q);
+      if (lane == r) { dot = dr; nk = nr; }
+    }
+    const int slot = s0 + lane;
+    if (lane < R && slot < n_hist && fl == 0) {
+      const float den = __builtin_sqrtf(nk) * root_nc;
+      const float cosv = den == 0.f ? 0.f : dot / den;
+      dval[slot] = 1.0f - cosv;
+    }
+    s0 += stride;
+    if (s0 >= n_hist) break;
+#pragma unroll
+    for (int r = 0; r < R; ++r) load_key<E>(K, g, min(s0 + r, n_hist - 1), lane, live, k[r]);
+    fl = flags[min(s0 + min(lane, R - 1), n_hist - 1)];
+  }
+}
+
+hipError_t launch_diversity(const Geom& g, char* kv, char* meta, int layer0, int nl, int n_hist, hipStream_t s) {
+  if (n_hist <= 0) return hipSuccess;
+  int width = 64;
+  while (width < g.H * 64) width *= 2;
+  const int E = width / 64;
+  const int per_wg = kDivWaves * div_rows(E);
+  long gx = (n_hist + per_wg - 1) / per_wg;
+  const long cap_x = 2048 / nl > 0 ? 2048 / nl : 1;
+  if (gx > cap_x) gx = cap_x;
+  dim3 dgrid((unsigned)gx, (unsigned)nl);
+#define OVGGT_DIV_LAUNCH(EE) \
+  hipLaunchKernelGGL((diversity_kernel<EE, div_rows(EE)>), dgrid, dim3(kDivThreads), 0, s, g, kv, meta, layer0, n_hist)
+  switch (E) {
+    case 1: OVGGT_DIV_LAUNCH(1); break;
+    case 2: OVGGT_DIV_LAUNCH(2); break;
+    case 4: OVGGT_DIV_LAUNCH(4); break;
+    case 8: OVGGT_DIV_LAUNCH(8); break;
+    case 16: OVGGT_DIV_LAUNCH(16); break;
+    case 32: OVGGT_DIV_LAUNCH(32); break;
+    default: OVGGT_DIV_LAUNCH(64); break;
+  }
+#undef OVGGT_DIV_LAUNCH
+  return hipGetLastError();
+}
+
+hipError_t launch_centroid_update(const Geom& g, char* kv, char* meta, int layer0, int nl, int n_total, hipStream_t s) {
+  // rows per workgroup: few enough that one layer's update is a single round of loads on many CUs,
+  // more when many layers share the launch (each workgroup ends with an atomic per key element)
+  int chunk = (int)(((long)2 * g.M * nl + 1023) / 1024 + 15) / 16 * 16;
+  if (chunk < 16) chunk = 16;
+  if (chunk > 64) chunk = 64;
+  dim3 grid((unsigned)((2 * g.M + chunk - 1) / chunk), (unsigned)nl);
+  hipLaunchKernelGGL(centroid_update_kernel, grid, dim3(kCenThreads), 0, s, g, kv, meta, layer0, n_total, chunk);
+  return hipGetLastError();
+}
+
+hipError_t launch_centroid_rebuild(const Geom& g, char* kv, char* meta, int layer, int n, hipStream_t s) {
+  hipError_t e = launch_fill_zero(layer_meta(meta, g, layer) + g.off_csum, (size_t)8 * g.H * g.d, s);
+  if (e != hipSuccess || n <= 0) return e;
+  const int chunk = 64;
+  hipLaunchKernelGGL(centroid_rebuild_kernel, dim3((unsigned)((n + chunk - 1) / chunk)), dim3(kCenThreads), 0, s,
+                     g, kv, meta, layer, n, chunk);
+  return hipGetLastError();
+}
+
+}  // namespace ovggt

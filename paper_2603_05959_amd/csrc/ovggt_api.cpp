@@ -82,7 +82,11 @@ bool valid_config(const ovggt_config* c) {
   if (c->budget < c->tokens_per_frame) return false;
   if ((int64_t)c->budget + c->tokens_per_frame > 128 * 1024) return false;   // selection handles <= 2^17 slots
   if (c->dtype != OVGGT_F32 && c->dtype != OVGGT_BF16) return false;
-  if (c->score_mode != 0) return false;
+  if (c->score_mode != 0 && c->score_mode != 1) return false;
+  if (c->score_mode == 1) {
+    if (c->dtype != OVGGT_BF16 || c->n_heads > 64) return false;       // the key pass reads the half-precision cache
+    if (!(c->hybrid_beta >= 0.f && c->hybrid_beta <= 1.f)) return false;
+  }
   if (c->out_dtype != OVGGT_F32 && c->out_dtype != OVGGT_BF16) return false;
   if (c->dtype == OVGGT_F32 && c->out_dtype != OVGGT_F32) return false;
   if (!(c->softmax_scale >= 0.f) || !std::isfinite(c->softmax_scale)) return false;
@@ -109,6 +113,11 @@ void make_geom(const ovggt_config& c, Geom* g) {
   g->off_ctrl = off;  off += sizeof(Ctrl);
   g->off_mvdst = off; off += up256((size_t)4 * g->M);
   g->off_mvsrc = off; off += up256((size_t)4 * g->M);
+  g->off_csum = off;  off += up256((size_t)8 * g->H * g->d);
+  g->off_evbits = off; off += up256((size_t)g->cap / 8);
+  g->off_cvec = off;  off += up256((size_t)4 * g->H * g->d);
+  g->off_dval = off;  off += c.score_mode == 1 ? up256((size_t)4 * g->cap) : 0;
+  g->hybrid = c.score_mode == 1 ? 1 : 0;
   g->meta_layer_bytes = off;
 }
 
@@ -280,7 +289,13 @@ int ovggt_score_select(ovggt_cache* c, int layer, const void* resid, const uint8
   if (!uniform(c, l0, nl, 1)) return OVGGT_ERR_STATE;
   {
     ProfScope ps(c, OVGGT_PROF_SELECT, (hipStream_t)hip_stream, c->prof_level >= 2);
-    if (launch_score_select(c->g, c->smooth, c->meta, l0, nl, resid, anchor_flags, c->n[l0], (hipStream_t)hip_stream) != hipSuccess)
+    const HybridParams hy = {c->cfg.score_mode == 1 ? 1 : 0, c->cfg.hybrid_beta};
+    if (hy.on && c->n[l0] > c->g.B &&
+        launch_diversity(c->g, c->kv, c->meta, l0, nl, c->n[l0] - c->g.M, (hipStream_t)hip_stream) != hipSuccess)
+      return OVGGT_ERR_HIP;
+    if (launch_score_select(c->g, c->smooth, hy, c->meta, l0, nl, resid, anchor_flags, c->n[l0], (hipStream_t)hip_stream) != hipSuccess)
+      return OVGGT_ERR_HIP;
+    if (hy.on && launch_centroid_update(c->g, c->kv, c->meta, l0, nl, c->n[l0], (hipStream_t)hip_stream) != hipSuccess)
       return OVGGT_ERR_HIP;
   }
   for (int l = l0; l < l0 + nl; ++l) c->phase[l] = 2;
@@ -396,6 +411,10 @@ int ovggt_cache_import(ovggt_cache* c, int layer, int32_t n, int64_t frames, con
           return OVGGT_ERR_HIP;
       }
     }
+  }
+  if (c->cfg.score_mode == 1) {
+    if (launch_centroid_rebuild(g, c->kv, c->meta, layer, n, (hipStream_t)hip_stream) != hipSuccess) return OVGGT_ERR_HIP;
+    if (hipStreamSynchronize((hipStream_t)hip_stream) != hipSuccess) return OVGGT_ERR_HIP;
   }
   c->n[layer] = n;
   c->frames[layer] = frames;

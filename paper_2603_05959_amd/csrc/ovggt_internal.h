@@ -27,9 +27,14 @@ struct Geom {
   int L, H, d, M, C, B;
   int cap;                 // slots per layer: round_up(B + M, kSlotTile)
   int esize;               // 2 (bf16) or 4 (f32)
+  int hybrid;              // 1: hybrid scoring (Eq. 7), the handle maintains the centroid of its evictable keys
   size_t kv_layer_bytes;   // 2 * H * cap * d * esize
   size_t meta_layer_bytes;
   size_t off_ids, off_ss, off_flags, off_ctrl, off_mvdst, off_mvsrc;   // byte offsets in a layer's metadata
+  size_t off_csum;         // H*d 64-bit sums of the evictable resident keys, units of 2^-24 (hybrid scoring)
+  size_t off_evbits;       // evict bit per slot of the last selection, 32 slots per word (hybrid scoring)
+  size_t off_dval;         // d_i = 1 - cos(k_i, centroid) of the slots below n_old, one fp32 per slot (hybrid scoring)
+  size_t off_cvec;         // the sum as H*d fp32 values, refreshed by each frame's append (hybrid scoring)
 };
 
 __host__ __device__ inline char* layer_k(char* kv, const Geom& g, int layer) {
@@ -67,10 +72,26 @@ struct SmoothParams {
   float g[9];
 };
 
+// Eq. 7: how the selection ranks (on = 0: every entry by the score it entered with).
+struct HybridParams {
+  int on;
+  float beta;
+};
+
+// Eq. 7, history side (bf16 handles only: the cache holds K as half).  The handle keeps the exact sum of
+// its evictable resident keys per layer:
+//   launch_diversity        d_i = 1 - cos(k_i, centroid) written to the d_i array for the evictable slots below n_hist
+//   launch_centroid_update  after the frame's selection: add the frame's evictable tokens that stay, subtract
+//                           the evicted entries of earlier frames (reads the hole list and the evict bitmap)
+//   launch_centroid_rebuild zero the sum and add every evictable slot below n (after an import)
+hipError_t launch_diversity(const Geom& g, char* kv, char* meta, int layer0, int nl, int n_hist, hipStream_t s);
+hipError_t launch_centroid_update(const Geom& g, char* kv, char* meta, int layer0, int nl, int n_total, hipStream_t s);
+hipError_t launch_centroid_rebuild(const Geom& g, char* kv, char* meta, int layer, int n, hipStream_t s);
+
 // Eq. 5 + anchor flags for the M slots [n_total-M, n_total), Eq. 6's smoothing of
 // their scores when enabled, then (when n_total > B) Eq. 8's selection and the
 // move list.
-hipError_t launch_score_select(const Geom& g, const SmoothParams& sm, char* meta, int layer0, int nl, const void* resid,
+hipError_t launch_score_select(const Geom& g, const SmoothParams& sm, const HybridParams& hy, char* meta, int layer0, int nl, const void* resid,
                                const uint8_t* anchors, int n_total, hipStream_t s);
 
 // Apply the move list to K, V and the per-slot metadata.

@@ -238,7 +238,7 @@ __device__ inline void radix_pass(SelShared& sh, int n_iter, uint32_t rank, Digi
 template <int KPT, bool IDREG>
 __device__ inline void select_phase(SelShared& sh, const Geom& g, const float* ss, const uint32_t* ids,
                                     const uint8_t* flags, Ctrl* ctrl, uint32_t* mvdst, uint32_t* mvsrc,
-                                    int n_total) {
+                                    uint32_t* evbits, int n_total) {
   constexpr int NREG = KPT > 0 ? KPT : 1;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n_chunks = (n_total + kSelThreads - 1) / kSelThreads;
@@ -365,6 +365,7 @@ __device__ inline void select_phase(SelShared& sh, const Geom& g, const float* s
     if (j < PP && wi < n_words) {
       const int s0 = wi << 5;
       const uint32_t e = sh.evmap[wi];
+      if (evbits) evbits[wi] = e;
       const uint32_t below_b = s0 + 32 <= g.B ? 0xFFFFFFFFu : (s0 >= g.B ? 0u : ((1u << (g.B - s0)) - 1u));
       const uint32_t below_n = s0 + 32 <= n_total ? 0xFFFFFFFFu : ((1u << (n_total - s0)) - 1u);
       hw[j] = e & below_b;
@@ -416,9 +417,80 @@ __device__ inline void select_phase(SelShared& sh, const Geom& g, const float* s
   }
 }
 
+// ---- Eq. 7: rank values of the evictable slots ----------------------------------------------------
+// Each source is min-max normalised over its evictable slots (all zeros when max = min) and
+// weighted: (1 - beta) * d^ for history, beta * s^ for the new frame.  One fp32 operation at a
+// time, in this order; the CPU reference repeats it.
+//
+// Workgroup-wide minimum and maximum of value_of(i), i in [0, n), over the unflagged slots.
+template <typename ValueOf>
+__device__ inline void block_min_max(SelShared& sh, const uint8_t* flags, int n, ValueOf value_of,
+                                     float* lo_out, float* hi_out) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const float inf = __builtin_inff();
+  float lo = inf, hi = -inf;
+  for (int i = tid; i < n; i += kSelThreads) {
+    if (flags[i]) continue;
+    const float x = value_of(i);
+    lo = fminf(lo, x); hi = fmaxf(hi, x);
+  }
+#pragma unroll
+  for (int off = 1; off < 64; off *= 2) {
+    lo = fminf(lo, __shfl_xor(lo, off, 64));
+    hi = fmaxf(hi, __shfl_xor(hi, off, 64));
+  }
+  float* red = (float*)sh.cnt;                               // 2 values per wave
+  __syncthreads();
+  if (lane == 0) { red[wave * 2] = lo; red[wave * 2 + 1] = hi; }
+  __syncthreads();
+#pragma unroll
+  for (int w = 0; w < kSelWaves; ++w) { lo = fminf(lo, red[w * 2]); hi = fmaxf(hi, red[w * 2 + 1]); }
+  __syncthreads();                                           // sh.cnt is reused afterwards
+  *lo_out = lo; *hi_out = hi;
+}
+
+// History side, spread over every workgroup of the layer's launch.  `dval` holds d_i of the slots
+// below n_old (written by this frame's diversity pass, read-only here).  Every workgroup finds the
+// same minimum and maximum by reading all of them (64 KB at most, from L2: cheaper than funnelling
+// them through atomics), then writes the rank values of its own share of slots over their scores,
+// written through like the scores of phase 1.
+__device__ inline void hybrid_history_values(SelShared& sh, const HybridParams& hy, const float* dval, float* ss,
+                                             const uint8_t* flags, int n_old) {
+#pragma clang fp contract(off)
+  float lo, hi;
+  block_min_max(sh, flags, n_old, [&](int i) { return dval[i]; }, &lo, &hi);
+  const float weight = 1.0f - hy.beta, range = hi - lo;
+  const int per = (n_old + (int)gridDim.x - 1) / (int)gridDim.x;
+  const int i1 = min(((int)blockIdx.x + 1) * per, n_old);
+  for (int i = blockIdx.x * per + threadIdx.x; i < i1; i += kSelThreads) {
+    if (flags[i]) continue;
+    const float unit = hi == lo ? 0.f : (dval[i] - lo) / range;
+    __hip_atomic_store(&ss[i], weight * unit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
+
+// New frame's side, by the workgroup that runs the selection: the slots [n_old, n_total) hold ss, or
+// Eq. 6's smoothed s.
+__device__ inline void hybrid_new_values(SelShared& sh, const HybridParams& hy, bool smoothed, float* ss,
+                                         const uint8_t* flags, int n_old, int n_total) {
+#pragma clang fp contract(off)
+  float lo, hi;
+  float* sn = ss + n_old;
+  const uint8_t* fn = flags + n_old;
+  auto value_of = [&](int i) { return smoothed ? sn[i] : __builtin_sqrtf(sn[i]); };
+  block_min_max(sh, fn, n_total - n_old, value_of, &lo, &hi);
+  const float range = hi - lo;
+  for (int i = threadIdx.x; i < n_total - n_old; i += kSelThreads) {
+    if (fn[i]) continue;
+    const float unit = hi == lo ? 0.f : (value_of(i) - lo) / range;
+    sn[i] = hy.beta * unit;
+  }
+  __syncthreads();
+}
+
 template <bool BF16, int KPT, bool IDREG>
 __global__ void __launch_bounds__(kSelThreads)
-score_select_kernel(Geom g, SmoothParams sm, char* meta, int layer0, const char* resid, const uint8_t* anchors,
+score_select_kernel(Geom g, SmoothParams sm, HybridParams hy, char* meta, int layer0, const char* resid, const uint8_t* anchors,
                     int n_total, int e_per_lane) {
   __shared__ SelShared sh;
   const int layer = layer0 + blockIdx.y;
@@ -450,6 +522,8 @@ score_select_kernel(Geom g, SmoothParams sm, char* meta, int layer0, const char*
       default: if (many) score_rows<64, BF16, kRowsPerWave>(rbase, row_bytes, g.C, g.M, al, sn, fn); else score_rows<64, BF16, 1>(rbase, row_bytes, g.C, g.M, al, sn, fn); break;
     }
   }
+  if (hy.on && n_total > g.B)
+    hybrid_history_values(sh, hy, (const float*)(mb + g.off_dval), ss, flags, n_old);
   const bool smoothing = sm.alpha > 0.f;
   if (n_total <= g.B && !smoothing) {        // under budget and no smoothing: nothing needs the whole frame
     if (blockIdx.x == 0 && tid == 0) ctrl->n_moves = 0;
@@ -484,11 +558,14 @@ score_select_kernel(Geom g, SmoothParams sm, char* meta, int layer0, const char*
       return;
     }
   }
-  select_phase<KPT, IDREG>(sh, g, ss, ids, flags, ctrl, mvdst, mvsrc, n_total);
+  if (hy.on) hybrid_new_values(sh, hy, smoothing, ss, flags, n_old, n_total);
+  // hybrid scoring keeps the evict bitmap: the centroid's maintenance reads it
+  select_phase<KPT, IDREG>(sh, g, ss, ids, flags, ctrl, mvdst, mvsrc,
+                           hy.on ? (uint32_t*)(mb + g.off_evbits) : nullptr, n_total);
 }
 
 template <bool BF16>
-static void launch_variant(const Geom& g, const SmoothParams& sm, char* meta, int layer0, int nl, const void* resid,
+static void launch_variant(const Geom& g, const SmoothParams& sm, const HybridParams& hy, char* meta, int layer0, int nl, const void* resid,
                            const uint8_t* anchors, int n_total, int e, hipStream_t s) {
   // One workgroup fits a CU (the selection's register-resident keys set the footprint), so the
   // launch stays within one round of the chip: a single layer spreads its rows one per wave, a
@@ -507,7 +584,7 @@ static void launch_variant(const Geom& g, const SmoothParams& sm, char* meta, in
   dim3 grid((unsigned)gx, (unsigned)nl);
   const int n_chunks = (n_total + kSelThreads - 1) / kSelThreads;
 #define OVGGT_SEL_LAUNCH(KPT, IDREG)                                                                  \
-  hipLaunchKernelGGL((score_select_kernel<BF16, KPT, IDREG>), grid, dim3(kSelThreads), 0, s, g, sm, meta, \
+  hipLaunchKernelGGL((score_select_kernel<BF16, KPT, IDREG>), grid, dim3(kSelThreads), 0, s, g, sm, hy, meta, \
                      layer0, (const char*)resid, anchors, n_total, e)
   // the variant only matters when a selection will run (n_total > B)
   if (n_total <= g.B || n_chunks <= 8) OVGGT_SEL_LAUNCH(8, true);
@@ -517,13 +594,13 @@ static void launch_variant(const Geom& g, const SmoothParams& sm, char* meta, in
 #undef OVGGT_SEL_LAUNCH
 }
 
-hipError_t launch_score_select(const Geom& g, const SmoothParams& sm, char* meta, int layer0, int nl, const void* resid,
+hipError_t launch_score_select(const Geom& g, const SmoothParams& sm, const HybridParams& hy, char* meta, int layer0, int nl, const void* resid,
                                const uint8_t* anchors, int n_total, hipStream_t s) {
   int cp = 1;
   while (cp < g.C) cp *= 2;
   const int e = cp >= 64 ? cp / 64 : 1;
-  if (g.esize == 2) launch_variant<true>(g, sm, meta, layer0, nl, resid, anchors, n_total, e, s);
-  else launch_variant<false>(g, sm, meta, layer0, nl, resid, anchors, n_total, e, s);
+  if (g.esize == 2) launch_variant<true>(g, sm, hy, meta, layer0, nl, resid, anchors, n_total, e, s);
+  else launch_variant<false>(g, sm, hy, meta, layer0, nl, resid, anchors, n_total, e, s);
   return hipGetLastError();
 }
 

@@ -71,6 +71,14 @@ def preset(k: int, **overrides) -> StreamConfig:
 CFG4_BUDGETS = (4096, 8192, 32768, 65536)
 
 
+def patch_grid(cfg: "StreamConfig") -> tuple[int, int]:
+    """(rows, columns) of the frame's patch map: the most nearly square factorisation of
+    M - n_special (37 x 37 for 518 x 518 input at patch size 14, 37 x 28 for 518 x 392)."""
+    p = cfg.M - cfg.n_special
+    w = max(x for x in range(1, int(p ** 0.5) + 1) if p % x == 0)
+    return p // w, w
+
+
 def gaussian_kernel3(sigma: float = 1.0) -> np.ndarray:
     """A normalised 3x3 Gaussian as float32 [3, 3]: the smoothing kernel handed to both the library
     and the oracle as a workload parameter (the paper gives no size or width for its G)."""

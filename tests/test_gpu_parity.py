@@ -19,8 +19,8 @@ def _torch():
     return torch
 
 
-def make_cache(cfg, L=None, smooth=None):
-    return B.Cache(L or cfg.L, cfg.H, cfg.d, cfg.M, cfg.C, cfg.B, cfg.dtype, smooth=smooth)
+def make_cache(cfg, L=None, smooth=None, hybrid_beta=None):
+    return B.Cache(L or cfg.L, cfg.H, cfg.d, cfg.M, cfg.C, cfg.B, cfg.dtype, smooth=smooth, hybrid_beta=hybrid_beta)
 
 
 def dev(a, cfg):
@@ -52,11 +52,12 @@ def compare_cache(cache, orc, layer=0, kv=True):
         assert np.array_equal(e["v"], stored_v(orc.v, cache.dtype))
 
 
-def run_stream(cfg, layer=0, attn_frames=None, cache_every=1, resid_fn=None, q_rows=None, log=None, smooth=None):
+def run_stream(cfg, layer=0, attn_frames=None, cache_every=1, resid_fn=None, q_rows=None, log=None, smooth=None,
+               hybrid_beta=None):
     """Drive both sides over cfg.T frames of one layer; returns max attention error."""
     torch = _torch()
-    cache = make_cache(cfg, L=1, smooth=smooth)
-    orc = oc.OracleCache(cfg.M, cfg.H, cfg.d, cfg.B, smooth=smooth)
+    cache = make_cache(cfg, L=1, smooth=smooth, hybrid_beta=hybrid_beta)
+    orc = oc.OracleCache(cfg.M, cfg.H, cfg.d, cfg.B, smooth=smooth, hybrid_beta=hybrid_beta)
     out = cache.new_output()[0]
     worst = 0.0
     for t in range(cfg.T):
@@ -331,6 +332,80 @@ def test_activation_smoothing_batched_layers_and_bad_configs():
                 (0.5, 8, 10, 3, np.full((3, 3), np.nan, np.float32))]:
         with pytest.raises(B.OvggtError):
             make_cache(cfg, smooth=bad)
+
+
+@pytest.mark.parametrize("M,H,C,B_,beta,ns", [
+    (50, 2, 64, 170, 0.5, 2),          # two elements per lane, budget not a multiple of the frame
+    (33, 1, 64, 100, 0.3, 1),          # one head: one element per lane
+    (40, 3, 128, 200, 0.5, 2),         # 192-wide keys: the tree's zero padding is live
+    (70, 5, 64, 300, 0.7, 3),          # 320-wide keys padded to 512
+    (200, 16, 256, 900, 0.5, 5),       # the paper's 16 x 64 keys, several centroid chunks
+    (64, 16, 64, 128, 0.0, 0),         # beta = 0: new tokens all rank 0, no anchors at all
+    (64, 4, 64, 128, 1.0, 4),          # beta = 1: history all ranks 0
+])
+def test_hybrid_scoring_matches_oracle(M, H, C, B_, beta, ns):
+    cfg = synth.preset(1, M=M, H=H, C=C, B=B_, T=2 * (B_ // M) + 6, n_special=ns)
+    run_stream(cfg, hybrid_beta=beta, attn_frames={0, cfg.T - 1})
+
+
+def test_hybrid_scoring_with_smoothing_and_batched_layers():
+    torch = _torch()
+    ph, pw, ns = 6, 9, 2
+    cfg = synth.preset(1, M=ns + ph * pw, H=4, C=128, B=210, T=9, n_special=ns, L=3)
+    sm = (0.5, ph, pw, ns, synth.gaussian_kernel3(1.0))
+    cache = make_cache(cfg, smooth=sm, hybrid_beta=0.5)
+    orcs = [oc.OracleCache(cfg.M, cfg.H, cfg.d, cfg.B, smooth=sm, hybrid_beta=0.5) for _ in range(cfg.L)]
+    out = cache.new_output()
+    for t in range(cfg.T):
+        fs = [synth.frame_inputs(cfg, l, t) for l in range(cfg.L)]
+        q, k, v, r = (dev(np.stack([f[x] for f in fs]), cfg) for x in "qkvr")
+        a = torch.from_numpy(np.stack([f["a"] for f in fs])).cuda()
+        cache.step(q, k, v, r, a, out)                                         # layer = all
+        for l, (f, o) in enumerate(zip(fs, orcs)):
+            o.append(f["k"], f["v"]); o.update(f["r"], f["a"])
+            compare_cache(cache, o, layer=l, kv=(t == cfg.T - 1))
+    assert all(cache.status(l) == 0 for l in range(cfg.L))
+    cache.close()
+
+
+def test_hybrid_scoring_resumes_from_an_imported_cache():
+    """The running centroid sum is rebuilt on import: a stream continued from an exported
+    mid-stream state matches the oracle continued from the same state."""
+    torch = _torch()
+    cfg = synth.preset(1, M=60, H=3, C=64, B=200, T=12, n_special=2)
+    a = make_cache(cfg, L=1, hybrid_beta=0.4)
+    orc = oc.OracleCache(cfg.M, cfg.H, cfg.d, cfg.B, hybrid_beta=0.4)
+    out = a.new_output()[0]
+
+    def feed(cache, t):
+        f = synth.frame_inputs(cfg, 0, t)
+        cache.step(dev(f["q"], cfg), dev(f["k"], cfg), dev(f["v"], cfg), dev(f["r"], cfg),
+                   torch.from_numpy(f["a"]).cuda(), out, layer=0)
+        return f
+
+    for t in range(6):
+        f = feed(a, t)
+        orc.append(f["k"], f["v"]); orc.update(f["r"], f["a"])
+    compare_cache(a, orc)
+    e = a.export(0)
+    # the exported bf16 values are the state both sides continue from (a half below 2^-14 need not
+    # survive the trip through bf16, so the oracle takes the exported keys, not its own)
+    orc.k, orc.v = e["k"].copy(), e["v"].copy()
+    bits = lambda x: (np.ascontiguousarray(x).view(np.uint32) >> np.uint32(16)).astype(np.uint16)
+    b = make_cache(cfg, L=1, hybrid_beta=0.4)
+    b.import_(0, 6, e["ids"], bits(e["k"]), bits(e["v"]), e["ss"], e["flags"])
+    for t in range(6, cfg.T):
+        f = feed(b, t)
+        orc.append(f["k"], f["v"]); orc.update(f["r"], f["a"])
+        compare_cache(b, orc)
+    assert b.status(0) == 0
+    a.close(); b.close()
+
+
+def test_hybrid_scoring_full_width_stream():
+    # the benchmark layer's shape at a reduced budget: 1374 tokens of 16 x 64 keys per frame
+    cfg = synth.preset(1, B=4096, T=8)
+    run_stream(cfg, hybrid_beta=0.5, attn_frames={cfg.T - 1}, cache_every=2)
 
 
 def test_bf16_output_is_the_rounded_fp32_output():

@@ -38,7 +38,8 @@ def test_query_bytes_and_config_validation():
     kv24, meta24, _ = B.ovggt_cache_query_bytes(B.make_config(24, 16, 64, 1374, 1024, 16384, "bf16"))
     assert kv24 == 24 * kv and meta24 == 24 * meta
     bad = [dict(head_dim=128), dict(budget=100), dict(n_layers=0), dict(resid_dim=0), dict(resid_dim=5000),
-           dict(dtype=7), dict(score_mode=1), dict(softmax_scale=-1.0), dict(budget=131072), dict(out_dtype=3),
+           dict(dtype=7), dict(score_mode=2), dict(score_mode=1, dtype="f32"), dict(score_mode=1, hybrid_beta=1.5),
+           dict(score_mode=1, hybrid_beta=-0.5), dict(score_mode=1, n_heads=65), dict(softmax_scale=-1.0), dict(budget=131072), dict(out_dtype=3),
            dict(dtype="f32", out_dtype="bf16")]
     for kw in bad:
         args = dict(n_layers=1, n_heads=16, head_dim=64, tokens_per_frame=1374, resid_dim=1024, budget=16384,
@@ -47,6 +48,7 @@ def test_query_bytes_and_config_validation():
         with pytest.raises(B.OvggtError) as e:
             B.ovggt_cache_query_bytes(B.make_config(**args))
         assert e.value.code == B.OVGGT_ERR_ARG
+    B.ovggt_cache_query_bytes(B.make_config(1, 16, 64, 1374, 1024, 16384, "bf16", score_mode=1, hybrid_beta=0.5))
 
 
 def test_null_and_misaligned_arguments_rejected_before_any_launch():
