@@ -224,6 +224,22 @@ class OracleCache:
         self.t += 1
         return keep
 
+    # Sec. 3.3, historical anchors: protection granted or withdrawn after the tokens were cached
+    def set_protect(self, frame: int, mask: np.ndarray | None, on: bool) -> int:
+        """Flag (on) or release (off) the still-resident tokens of frame `frame` whose bit in
+        `mask` [M] is set (None: every token of the frame).  Evicted tokens cannot be brought
+        back, so a late registration covers what is left of the frame.  A released token returns
+        to the evictable set with the score it holds.  Returns how many flags changed."""
+        local = self.gid.astype(np.int64) - frame * self.M
+        hit = (local >= 0) & (local < self.M)
+        if mask is not None:
+            m = np.asarray(mask) != 0
+            hit &= m[np.clip(local, 0, self.M - 1)]
+        new = np.uint8(1 if on else 0)
+        changed = int((hit & (self.flag != new)).sum())
+        self.flag[hit] = new
+        return changed
+
     def step(self, q_t, k_t, v_t, resid_t, anchor_t, attend: bool = True):
         """One frame through steps 1-6; returns O_t (or None when attend=False:
         cache contents never depend on attention outputs)."""
@@ -231,6 +247,52 @@ class OracleCache:
         out = self.attend(q_t) if attend else None
         self.update(resid_t, anchor_t)
         return out
+
+
+# --------------------------------------------------------------------------- #
+# Sec. 3.3 -- which frames become historical anchors, and which tokens of them
+# --------------------------------------------------------------------------- #
+class DapPolicy:
+    """The registration rule of Dynamic Anchor Protection, given the model's outputs as inputs.
+
+    Frame 0 is the global initial anchor: the caller protects all of its tokens when they are
+    inserted, it is never demoted and does not count towards K_max; it is the reference of the
+    first coverage test.  At frame t > 0 with coverage ratio rho_t (fraction of the latest
+    anchor's points that project inside the current image), a new anchor is registered when
+    rho_t < tau and at least `min_gap` frames have passed since the last registration (frame 0
+    counts as one).  Of the anchor frame's N_p patch tokens the ceil(eta * N_p) with the highest
+    per-point confidence are protected (equal confidences: lower patch index first); aux tokens
+    are not.  At most K_max historical anchors are active; registering one more demotes the
+    oldest (first in, first out).  |P| <= M + K_max * ceil(eta * N_p) (Eq. 9).
+    Ties, the role of frame 0 in the spacing rule and the treatment of aux tokens are this
+    build's reading."""
+
+    def __init__(self, k_max: int, min_gap: int, tau: float, eta: float, n_special: int, n_patches: int):
+        assert k_max >= 1 and min_gap >= 1 and 0 < eta <= 1 and n_patches >= 1 and n_special >= 0
+        self.k_max, self.min_gap, self.tau, self.eta = k_max, min_gap, float(tau), float(eta)
+        self.n_special, self.n_patches = n_special, n_patches
+        self.last_reg = 0
+        self.active: list[int] = []                    # oldest first
+
+    @property
+    def per_anchor(self) -> int:
+        return int(np.ceil(self.eta * self.n_patches))
+
+    def step(self, t: int, rho: float, conf: np.ndarray):
+        """Returns (mask, demoted): mask is a uint8 [M] array of the tokens of frame t to
+        protect, or None when frame t does not become an anchor; demoted is the frame whose
+        protection is to be released, or None."""
+        if t <= 0 or not (rho < self.tau) or t - self.last_reg < self.min_gap:
+            return None, None
+        conf = np.asarray(conf, dtype=np.float32)
+        assert conf.shape == (self.n_patches,)
+        order = np.lexsort((np.arange(self.n_patches), -conf.astype(np.float64)))   # confidence desc, index asc
+        mask = np.zeros(self.n_special + self.n_patches, np.uint8)
+        mask[self.n_special + order[:self.per_anchor]] = 1
+        demoted = self.active.pop(0) if len(self.active) == self.k_max else None
+        self.active.append(t)
+        self.last_reg = t
+        return mask, demoted
 
 
 # --------------------------------------------------------------------------- #

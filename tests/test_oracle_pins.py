@@ -569,3 +569,73 @@ def test_hybrid_stream_invariants_and_threshold():
             assert r[keep & ev].min() >= r[~keep].max() - 2e-5              # kept ones outrank evicted ones
         differs |= not np.array_equal(np.sort(c.gid), np.sort(plain.gid))
     assert differs
+
+
+# ----------------------------------------------------------------- Dynamic Anchor Protection (Sec. 3.3)
+def test_dap_policy_hand_worked_schedule():
+    # K_max = 2, at least 3 frames between registrations, tau = 0.5; coverage by frame:
+    rho = [1.0, 0.4, 0.4, 0.3, 0.9, 0.2, 0.2, 0.2, 0.1, 0.1, 0.1, 0.1]
+    #      0    1    2    3    4    5    6    7    8    9    10   11
+    # frame 3: low coverage and 3 frames after frame 0 -> anchor 3.  Frame 5: only 2 frames later -> no.
+    # frame 6: 3 frames after 3 -> anchor 6.  Frame 9: anchor 9, K_max reached -> 3 is released.
+    pol = oc.DapPolicy(k_max=2, min_gap=3, tau=0.5, eta=0.25, n_special=1, n_patches=8)
+    conf = np.array([0.1, 0.9, 0.5, 0.9, 0.2, 0.7, 0.3, 0.0], np.float32)
+    log = []
+    for t, r in enumerate(rho):
+        mask, dem = pol.step(t, r, conf)
+        if mask is not None:
+            log.append((t, dem))
+            # ceil(0.25 * 8) = 2 patches: the two 0.9s (indices 1 and 3); the aux token is not protected
+            assert np.array_equal(np.flatnonzero(mask), [1 + 1, 1 + 3])
+    assert log == [(3, None), (6, None), (9, 3)]
+    assert pol.active == [6, 9]
+
+
+def test_dap_policy_ties_bound_and_fifo():
+    g = golden()
+    n_p = 37 * 28
+    pol = oc.DapPolicy(k_max=int(g["k_max"]), min_gap=100, tau=0.5, eta=g["eta"], n_special=5, n_patches=n_p)
+    assert pol.per_anchor == math.ceil(g["eta"] * n_p)
+    rng = np.random.default_rng(81)
+    conf = rng.integers(0, 6, n_p).astype(np.float32)            # heavy ties
+    protected = {0: 5 + n_p}                                       # frame 0: every token
+    order = []
+    for t in range(1, 1200):
+        mask, dem = pol.step(t, 0.0, conf)                         # coverage always low: only the spacing limits
+        if mask is not None:
+            order.append(t)
+            sel = np.flatnonzero(mask) - 5
+            assert len(sel) == pol.per_anchor and mask[:5].sum() == 0
+            # brute force: nobody outside the chosen set beats anybody inside (value, then lower index)
+            out = np.setdiff1d(np.arange(n_p), sel)
+            worst_in = min((conf[i], -i) for i in sel); best_out = max((conf[i], -i) for i in out)
+            assert worst_in > best_out
+            protected[t] = len(sel)
+        if dem is not None:
+            assert dem == min(k for k in protected if k != 0)      # first in, first out; frame 0 never leaves
+            del protected[dem]
+        assert sum(protected.values()) <= 5 + n_p + pol.k_max * pol.per_anchor     # Eq. 9
+    assert order == list(range(100, 1200, 100))
+    assert sum(protected.values()) == g["anchor_bound_518x392"]
+
+
+def test_set_protect_late_registration_and_release():
+    cfg = synth.preset(0, M=10, B=30, T=8, n_special=1)
+    c = oc.OracleCache(cfg.M, cfg.H, cfg.d, cfg.B)
+    for t in range(5):
+        f = synth.frame_inputs(cfg, 0, t)
+        c.append(f["k"], f["v"]); c.update(f["r"], f["a"])
+    frame = 3
+    resident = np.flatnonzero((c.gid // cfg.M == frame) & (c.flag == 0))
+    assert 0 < len(resident) < cfg.M                               # part of frame 3 is already gone
+    mask = np.zeros(cfg.M, np.uint8); mask[2:] = 1
+    want = {int(g) for g in c.gid[resident] if g % cfg.M >= 2}
+    assert c.set_protect(frame, mask, True) == len(want)
+    assert {int(g) for g in c.gid[(c.flag != 0) & (c.gid // cfg.M == frame)]} >= want
+    for t in range(5, 8):
+        f = synth.frame_inputs(cfg, 0, t)
+        c.append(f["k"], f["v"]); c.update(f["r"], f["a"])
+        assert want <= set(c.gid.tolist())                         # protected: they stay
+    n_rel = c.set_protect(frame, None, False)
+    assert n_rel >= len(want) and not (c.flag[c.gid // cfg.M == frame] != 0).any()
+    assert c.set_protect(frame, None, False) == 0                  # idempotent
