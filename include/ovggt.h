@@ -154,6 +154,19 @@ int ovggt_cache_compact(ovggt_cache* c, int layer, void* hip_stream);
 /* Frees the host handle (device buffers stay with the caller). */
 int ovggt_cache_destroy(ovggt_cache* c);
 
+/* Sec. 3.3, historical anchors: grant (on != 0) or withdraw (on == 0) protection of tokens
+ * that are already cached.  Affects the still-resident tokens of frame `frame` (token ids
+ * frame*M .. frame*M + M - 1) whose byte in `mask` (device, uint8[M]) is nonzero; mask NULL =
+ * every token of the frame.  Tokens of the frame that were evicted earlier stay evicted: a late
+ * registration covers what is left.  A released token returns to the evictable set with the
+ * score it holds.  `layer` may be OVGGT_ALL_LAYERS (one mask for all).  Enqueues on `hip_stream`;
+ * no host synchronisation.  With hybrid scoring the running centroid sum follows the change.
+ * ERR_STATE unless the layer expects a new frame (after ovggt_cache_compact, before the next
+ * ovggt_global_attn); ERR_ARG for a frame not yet seen.  |P| > B shows at the next selection
+ * (OVGGT_STATUS_BUDGET). */
+int ovggt_cache_set_protect(ovggt_cache* c, int layer, int64_t frame, const uint8_t* mask, int on,
+                            void* hip_stream);
+
 /* ---- helpers, not on the hot path ------------------------------------- */
 
 /* Resident entries of `layer` (host arithmetic, no synchronisation): after a
@@ -204,6 +217,33 @@ int ovggt_profile_read(ovggt_cache* c, double* ms_sum, int64_t* count, void* hip
  * call it between frames only): what a bracket reports beyond the bracketed
  * kernel's own execution.  Synchronises `hip_stream`. */
 int ovggt_profile_overhead(ovggt_cache* c, int reps, double* ms_mean, void* hip_stream);
+
+/* ---- Dynamic Anchor Protection: which frames become anchors (Sec. 3.3) ------------------
+ * Host-only bookkeeping; no device work, usable without a GPU.  The model's outputs are inputs:
+ * the coverage ratio rho_t (fraction of the latest anchor's points that project inside the
+ * current image) and the per-patch confidences of the point head.
+ * Frame 0 is the global initial anchor: the caller protects all of its tokens when it inserts
+ * them (anchor_flags of ovggt_score_select); it is never demoted, does not count towards k_max,
+ * and is the reference of the first coverage test and of the spacing rule.  At frame t > 0 a
+ * new anchor is registered when rho_t < tau and t - (last registration) >= min_gap.  Of its
+ * n_patches patch tokens the ceil(eta * n_patches) (in double precision) with the highest
+ * confidence are protected, equal confidences going to the lower patch index; the n_special
+ * aux tokens are not.  When k_max anchors are active, the oldest is demoted (FIFO).  The
+ * protected set then obeys |P| <= M + k_max * ceil(eta * n_patches) (Eq. 9). */
+typedef struct ovggt_dap ovggt_dap;
+/* ERR_ARG unless k_max >= 1, min_gap >= 1, 0 < eta <= 1, n_patches >= 1, n_special >= 0 and tau is a number. */
+int ovggt_dap_create(ovggt_dap** out, int32_t k_max, int32_t min_gap, double tau, double eta,
+                     int32_t n_special, int32_t n_patches);
+/* Decision for frame t (frames must be fed in increasing order; ERR_ARG otherwise).  conf: host,
+ * float[n_patches], finite; may be NULL when the frame cannot become an anchor anyway.
+ * *register_frame = t and mask_out (host, uint8[n_special + n_patches], written in full) when
+ * frame t becomes an anchor, else -1 and mask_out untouched.  *demote_frame = the frame to
+ * release (pass it to ovggt_cache_set_protect with on = 0 and mask NULL), else -1. */
+int ovggt_dap_step(ovggt_dap* d, int64_t t, double rho, const float* conf, int64_t* register_frame,
+                   uint8_t* mask_out, int64_t* demote_frame);
+/* Active historical anchors, oldest first: writes up to cap frame numbers, *n = how many are active. */
+int ovggt_dap_active(const ovggt_dap* d, int64_t* frames, int32_t cap, int32_t* n);
+int ovggt_dap_destroy(ovggt_dap* d);
 
 const char* ovggt_strerror(int code);
 

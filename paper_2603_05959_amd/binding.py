@@ -23,6 +23,7 @@ EXPORTS = (
     "ovggt_cache_compact", "ovggt_cache_destroy", "ovggt_cache_size", "ovggt_cache_frames",
     "ovggt_cache_status", "ovggt_cache_export", "ovggt_cache_import", "ovggt_cache_last_moves",
     "ovggt_profile_enable", "ovggt_profile_read", "ovggt_profile_overhead", "ovggt_strerror",
+    "ovggt_cache_set_protect", "ovggt_dap_create", "ovggt_dap_step", "ovggt_dap_active", "ovggt_dap_destroy",
 )
 PROF_CLASSES = ("append", "attn", "combine", "score_select", "compact")
 
@@ -72,6 +73,11 @@ def lib() -> C.CDLL:
     L.ovggt_profile_enable.argtypes = [vp, C.c_int, C.c_int]
     L.ovggt_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64), vp]
     L.ovggt_profile_overhead.argtypes = [vp, C.c_int, C.POINTER(C.c_double), vp]
+    L.ovggt_cache_set_protect.argtypes = [vp, C.c_int, i64, u8p, C.c_int, vp]
+    L.ovggt_dap_create.argtypes = [C.POINTER(vp), i32, i32, C.c_double, C.c_double, i32, i32]
+    L.ovggt_dap_step.argtypes = [vp, i64, C.c_double, vp, C.POINTER(i64), u8p, C.POINTER(i64)]
+    L.ovggt_dap_active.argtypes = [vp, C.POINTER(i64), i32, C.POINTER(i32)]
+    L.ovggt_dap_destroy.argtypes = [vp]
     L.ovggt_strerror.argtypes = [C.c_int]
     L.ovggt_strerror.restype = C.c_char_p
     for name in EXPORTS:
@@ -183,6 +189,35 @@ def ovggt_cache_last_moves(h, layer, dst, src, stream: int = 0) -> int:
     return n.value
 
 
+def ovggt_cache_set_protect(h, layer, frame: int, mask, on: bool, stream: int = 0) -> None:
+    _check(lib().ovggt_cache_set_protect(h, layer, frame, _ptr(mask), 1 if on else 0, stream),
+           "ovggt_cache_set_protect")
+
+
+def ovggt_dap_create(k_max: int, min_gap: int, tau: float, eta: float, n_special: int, n_patches: int):
+    h = C.c_void_p()
+    _check(lib().ovggt_dap_create(C.byref(h), k_max, min_gap, tau, eta, n_special, n_patches), "ovggt_dap_create")
+    return h
+
+
+def ovggt_dap_step(h, t: int, rho: float, conf, mask_out):
+    """Returns (register_frame, demote_frame), each -1 for none; mask_out is filled on registration."""
+    reg, dem = C.c_int64(), C.c_int64()
+    _check(lib().ovggt_dap_step(h, t, rho, _ptr(conf), C.byref(reg), _ptr(mask_out), C.byref(dem)), "ovggt_dap_step")
+    return reg.value, dem.value
+
+
+def ovggt_dap_active(h, cap: int = 64) -> list:
+    frames = (C.c_int64 * cap)()
+    n = C.c_int32()
+    _check(lib().ovggt_dap_active(h, frames, cap, C.byref(n)), "ovggt_dap_active")
+    return [frames[i] for i in range(min(n.value, cap))]
+
+
+def ovggt_dap_destroy(h) -> None:
+    _check(lib().ovggt_dap_destroy(h), "ovggt_dap_destroy")
+
+
 def ovggt_profile_enable(h, level: int, every: int = 1) -> None:
     _check(lib().ovggt_profile_enable(h, level, every), "ovggt_profile_enable")
 
@@ -281,6 +316,10 @@ class Cache:
         flags = np.ascontiguousarray(flags, np.uint8)
         k_bits = np.ascontiguousarray(k_bits); v_bits = np.ascontiguousarray(v_bits)
         ovggt_cache_import(self.h, layer, len(ids), frames, ids, k_bits, v_bits, ss, flags, self.stream)
+
+    def set_protect(self, frame, mask, on, layer=OVGGT_ALL_LAYERS):
+        """mask: device uint8 tensor [M] or None (every token of the frame)."""
+        ovggt_cache_set_protect(self.h, layer, frame, mask, on, self.stream)
 
     def last_moves(self, layer=0):
         dst = np.zeros(self.M, np.uint32); src = np.zeros(self.M, np.uint32)

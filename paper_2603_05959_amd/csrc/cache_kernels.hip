@@ -133,6 +133,28 @@ compact_kernel(Geom g, char* kv, char* meta, int layer0) {
   }
 }
 
+// --------------------------------------------------------------------------
+// Sec. 3.3: protection granted or withdrawn for resident tokens of one frame.  One thread per
+// slot: ids in [gid_lo, gid_lo + M) whose mask byte is set (no mask: all of them) take the flag.
+__global__ void __launch_bounds__(256)
+set_protect_kernel(Geom g, char* meta, int layer0, int n, uint32_t gid_lo, const uint8_t* mask, int on) {
+  char* mb = layer_meta(meta, g, layer0 + blockIdx.y);
+  const int slot = blockIdx.x * blockDim.x + threadIdx.x;
+  if (slot >= n) return;
+  const uint32_t local = ((const uint32_t*)(mb + g.off_ids))[slot] - gid_lo;     // wraps for ids below gid_lo
+  if (local >= (uint32_t)g.M) return;
+  if (mask && mask[local] == 0) return;
+  ((uint8_t*)(mb + g.off_flags))[slot] = on ? 1 : 0;
+}
+
+hipError_t launch_set_protect(const Geom& g, char* meta, int layer0, int nl, int n, uint32_t gid_lo,
+                              const uint8_t* mask, int on, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  dim3 grid((unsigned)((n + 255) / 256), (unsigned)nl);
+  hipLaunchKernelGGL(set_protect_kernel, grid, dim3(256), 0, s, g, meta, layer0, n, gid_lo, mask, on);
+  return hipGetLastError();
+}
+
 hipError_t launch_compact(const Geom& g, char* kv, char* meta, int layer0, int nl, hipStream_t s) {
   dim3 grid((unsigned)g.M, (unsigned)nl);      // at most M entries move per frame
   hipLaunchKernelGGL(compact_kernel, grid, dim3(256), 0, s, g, kv, meta, layer0);

@@ -275,6 +275,39 @@ diversity_kernel(Geom g, char* kv, char* meta, int layer0, int n_hist) {
   }
 }
 
+// A change of protection (Sec. 3.3) moves tokens between P and the evictable set: the sum loses the
+// keys of the newly protected tokens and regains those of the released ones.  Reads the flags as they
+// were before the change; the flags themselves are rewritten by the launch that follows.
+__global__ void __launch_bounds__(kCenThreads)
+centroid_protect_kernel(Geom g, char* kv, char* meta, int layer0, int n, uint32_t gid_lo, const uint8_t* mask,
+                        int on, int chunk) {
+  const int layer = layer0 + blockIdx.y;
+  char* mb = layer_meta(meta, g, layer);
+  const uint8_t* flags = (const uint8_t*)(mb + g.off_flags);
+  const uint32_t* ids = (const uint32_t*)(mb + g.off_ids);
+  const int v0 = blockIdx.x * chunk, v1 = min(v0 + chunk, n);
+  accumulate_rows(g, layer_k(kv, g, layer), (unsigned long long*)(mb + g.off_csum), v0, v1,
+                  [&](int v, int* slot) {
+                    const uint32_t local = ids[v] - gid_lo;
+                    if (local >= (uint32_t)g.M) return 0;
+                    if (mask && mask[local] == 0) return 0;
+                    const int was = flags[v] ? 1 : 0, now = on ? 1 : 0;
+                    if (was == now) return 0;
+                    *slot = v;
+                    return now ? -1 : 1;
+                  });
+}
+
+hipError_t launch_centroid_protect(const Geom& g, char* kv, char* meta, int layer0, int nl, int n, uint32_t gid_lo,
+                                   const uint8_t* mask, int on, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  const int chunk = 64;
+  dim3 grid((unsigned)((n + chunk - 1) / chunk), (unsigned)nl);
+  hipLaunchKernelGGL(centroid_protect_kernel, grid, dim3(kCenThreads), 0, s, g, kv, meta, layer0, n, gid_lo, mask, on,
+                     chunk);
+  return hipGetLastError();
+}
+
 hipError_t launch_diversity(const Geom& g, char* kv, char* meta, int layer0, int nl, int n_hist, hipStream_t s) {
   if (n_hist <= 0) return hipSuccess;
   int width = 64;

@@ -320,6 +320,22 @@ int ovggt_cache_compact(ovggt_cache* c, int layer, void* hip_stream) {
   return OVGGT_OK;
 }
 
+int ovggt_cache_set_protect(ovggt_cache* c, int layer, int64_t frame, const uint8_t* mask, int on,
+                            void* hip_stream) {
+  if (!c) return OVGGT_ERR_ARG;
+  int l0, nl;
+  if (!layer_range(c, layer, &l0, &nl)) return OVGGT_ERR_ARG;
+  if (!uniform(c, l0, nl, 0)) return OVGGT_ERR_STATE;
+  if (frame < 0 || frame >= c->frames[l0]) return OVGGT_ERR_ARG;
+  const Geom& g = c->g;
+  const uint32_t gid_lo = (uint32_t)(frame * (int64_t)g.M);          // fits: the frame has been appended
+  hipStream_t s = (hipStream_t)hip_stream;
+  if (g.hybrid && launch_centroid_protect(g, c->kv, c->meta, l0, nl, c->n[l0], gid_lo, mask, on, s) != hipSuccess)
+    return OVGGT_ERR_HIP;
+  if (launch_set_protect(g, c->meta, l0, nl, c->n[l0], gid_lo, mask, on, s) != hipSuccess) return OVGGT_ERR_HIP;
+  return OVGGT_OK;
+}
+
 int ovggt_cache_destroy(ovggt_cache* c) {
   if (!c) return OVGGT_ERR_ARG;
   prof_recycle(c);

@@ -94,6 +94,14 @@ hipError_t launch_centroid_rebuild(const Geom& g, char* kv, char* meta, int laye
 hipError_t launch_score_select(const Geom& g, const SmoothParams& sm, const HybridParams& hy, char* meta, int layer0, int nl, const void* resid,
                                const uint8_t* anchors, int n_total, hipStream_t s);
 
+// Sec. 3.3: set or clear the protection flag of the resident tokens with ids in [gid_lo, gid_lo + M) whose mask
+// byte is set (mask may be null: all).  launch_centroid_protect adjusts the hybrid-scoring sum for the same change
+// and must run first (it reads the flags as they were).
+hipError_t launch_centroid_protect(const Geom& g, char* kv, char* meta, int layer0, int nl, int n, uint32_t gid_lo,
+                                   const uint8_t* mask, int on, hipStream_t s);
+hipError_t launch_set_protect(const Geom& g, char* meta, int layer0, int nl, int n, uint32_t gid_lo,
+                              const uint8_t* mask, int on, hipStream_t s);
+
 // Apply the move list to K, V and the per-slot metadata.
 hipError_t launch_compact(const Geom& g, char* kv, char* meta, int layer0, int nl, hipStream_t s);
 

@@ -23,7 +23,7 @@ import numpy as np
 
 BASE_SEED = 260305959
 
-_TID_Q, _TID_K, _TID_V, _TID_R, _TID_NORM, _TID_DUP = 1, 2, 3, 4, 5, 6
+_TID_Q, _TID_K, _TID_V, _TID_R, _TID_NORM, _TID_DUP, _TID_DAP = 1, 2, 3, 4, 5, 6, 7
 
 
 @dataclass(frozen=True)
@@ -47,7 +47,7 @@ class StreamConfig:
 
 
 def preset(k: int, **overrides) -> StreamConfig:
-    """The five benchmark workloads (index = position in the workload list)."""
+    """The five benchmark workloads (index = position in the workload list), and 5: the camera head's cache."""
     if k == 0:
         c = StreamConfig("cfg0-tiny", 65, 2, 64, 128, 256, 10, 1, "f32", 1,
                          "rowsigma", "frame0+camera")
@@ -63,6 +63,11 @@ def preset(k: int, **overrides) -> StreamConfig:
     elif k == 4:
         c = StreamConfig("cfg4-518x392", 1041, 16, 64, 1024, 8192, 1000, 1, "bf16", 5,
                          "lognormal_unit", "cap10")
+    elif k == 5:
+        # the camera head's cache (Supp. C): one token per frame, budget = the frames the 24-layer
+        # aggregator budget of the 518x392 runs holds (24 * 8192 / 1041 = 188); head shape assumed
+        c = StreamConfig("cfg5-camera-head", 1, 16, 64, 1024, 188, 2000, 1, "bf16", 1,
+                         "lognormal_unit", "frame0")
     else:
         raise ValueError(f"no preset {k}")
     return c.with_(**overrides) if overrides else c
@@ -168,6 +173,9 @@ def anchor_bits(cfg: StreamConfig, t: int) -> np.ndarray:
         if t == 0:
             a[:] = 1
         a[:cfg.n_special] = 1
+    elif cfg.anchors == "frame0":
+        if t == 0:
+            a[:] = 1
     elif cfg.anchors == "cap10":
         cap = cfg.B // 10
         if t == 0:
@@ -198,6 +206,19 @@ def frame_inputs(cfg: StreamConfig, layer: int, t: int, want=("q", "k", "v", "r"
     if "a" in want:
         out["a"] = anchor_bits(cfg, t)
     return out
+
+
+def coverage_and_confidence(cfg: StreamConfig, t: int) -> tuple[float, np.ndarray]:
+    """Stand-ins for the two model outputs the anchor policy consumes at frame t: the coverage
+    ratio rho_t (uniform in [0, 1)) and the point head's per-patch confidence (log-normal, with
+    a share of exact repeats so that equal confidences occur), float32 [M - n_special]."""
+    rng = _rng(cfg, 0, t, _TID_DAP)
+    rho = float(rng.random())
+    n_p = cfg.M - cfg.n_special
+    conf = np.exp(rng.standard_normal(n_p)).astype(np.float32)
+    rep = rng.random(n_p) < 0.2
+    conf[rep] = np.float32(1.0)
+    return rho, conf
 
 
 def rising_resid(cfg: StreamConfig, layer: int, t: int) -> np.ndarray:

@@ -408,6 +408,115 @@ def test_hybrid_scoring_full_width_stream():
     run_stream(cfg, hybrid_beta=0.5, attn_frames={cfg.T - 1}, cache_every=2)
 
 
+def _dap_stream(cfg, policy_args, hybrid_beta=None, layers=1, camera=None):
+    """A stream whose anchors are registered and demoted by the library's host policy; the oracle
+    follows its own policy object, and both caches are compared after every frame.  `camera`: also
+    run a one-token-per-frame cache (the camera head's) whose tokens are protected and released in
+    step with the anchors."""
+    torch = _torch()
+    cache = make_cache(cfg, L=layers, hybrid_beta=hybrid_beta)
+    orcs = [oc.OracleCache(cfg.M, cfg.H, cfg.d, cfg.B, hybrid_beta=hybrid_beta) for _ in range(layers)]
+    dap = B.ovggt_dap_create(*policy_args)
+    pol = oc.DapPolicy(*policy_args)
+    out = cache.new_output()
+    mask_host = np.zeros(cfg.M, np.uint8)
+    if camera is not None:
+        ccfg = camera
+        cam = make_cache(ccfg, L=1, hybrid_beta=hybrid_beta)
+        cam_orc = oc.OracleCache(1, ccfg.H, ccfg.d, ccfg.B, hybrid_beta=hybrid_beta)
+        cam_out = cam.new_output()[0]
+    events = 0
+    for t in range(cfg.T):
+        fs = [synth.frame_inputs(cfg, l, t) for l in range(layers)]
+        a0 = np.zeros(cfg.M, np.uint8)
+        if t == 0:
+            a0[:] = 1                                            # the global initial anchor
+        q, k, v, r = (dev(np.stack([f[x] for f in fs]), cfg) for x in "qkvr")
+        a = torch.from_numpy(np.stack([a0] * layers)).cuda()
+        cache.step(q, k, v, r, a, out)
+        for f, o in zip(fs, orcs):
+            o.append(f["k"], f["v"]); o.update(f["r"], a0)
+        if camera is not None:
+            cf = synth.frame_inputs(ccfg, 0, t)
+            ca = np.array([1 if t == 0 else 0], np.uint8)
+            cam.step(dev(cf["q"], ccfg), dev(cf["k"], ccfg), dev(cf["v"], ccfg), dev(cf["r"], ccfg),
+                     torch.from_numpy(ca).cuda(), cam_out, layer=0)
+            cam_orc.append(cf["k"], cf["v"]); cam_orc.update(cf["r"], ca)
+        rho, conf = synth.coverage_and_confidence(cfg, t)
+        reg, dem = B.ovggt_dap_step(dap, t, rho, conf, mask_host)
+        m_ref, d_ref = pol.step(t, rho, conf)
+        assert (reg == t) == (m_ref is not None) and dem == (-1 if d_ref is None else d_ref)
+        if dem >= 0:
+            cache.set_protect(dem, None, False)
+            for o in orcs:
+                o.set_protect(d_ref, None, False)
+            if camera is not None:
+                cam.set_protect(dem, None, False, layer=0); cam_orc.set_protect(d_ref, None, False)
+        if reg >= 0:
+            events += 1
+            cache.set_protect(reg, torch.from_numpy(mask_host).cuda(), True)
+            for o in orcs:
+                o.set_protect(t, m_ref, True)
+            if camera is not None:
+                cam.set_protect(reg, None, True, layer=0); cam_orc.set_protect(t, None, True)
+        for l, o in enumerate(orcs):
+            compare_cache(cache, o, layer=l, kv=(t == cfg.T - 1))
+        if camera is not None:
+            compare_cache(cam, cam_orc, kv=(t == cfg.T - 1))
+    assert events >= 3 and len(pol.active) == policy_args[0]
+    assert all(cache.status(l) == 0 for l in range(layers))
+    # Eq. 9 on the device's own flags
+    per = int(np.ceil(policy_args[3] * policy_args[5]))
+    assert int(cache.export(0)["flags"].sum()) <= cfg.M + policy_args[0] * per
+    B.ovggt_dap_destroy(dap)
+    cache.close()
+    if camera is not None:
+        cam.close()
+
+
+def test_dynamic_anchors_stored_scores():
+    cfg = synth.preset(1, M=2 + 8 * 9, H=2, C=128, B=400, T=40, n_special=2)
+    _dap_stream(cfg, (2, 5, 0.7, 0.1, 2, 72))
+
+
+def test_dynamic_anchors_hybrid_scoring_batched_layers():
+    cfg = synth.preset(1, M=2 + 8 * 9, H=3, C=64, B=400, T=40, n_special=2)
+    _dap_stream(cfg, (2, 5, 0.7, 0.1, 2, 72), hybrid_beta=0.5, layers=2)
+
+
+def test_camera_head_cache_follows_the_anchors():
+    """Supp. C: the camera head's cache holds one token per frame under the same policy (no
+    smoothing); its token is protected and released together with the aggregator's anchor."""
+    cfg = synth.preset(1, M=2 + 6 * 6, H=2, C=64, B=200, T=60, n_special=2)
+    cam = synth.preset(1, M=1, H=16, C=256, B=16, T=60, n_special=1)
+    _dap_stream(cfg, (3, 4, 0.8, 0.2, 2, 36), camera=cam)
+    _dap_stream(cfg, (3, 4, 0.8, 0.2, 2, 36), hybrid_beta=0.5, camera=cam)
+
+
+def test_set_protect_argument_and_state_errors():
+    torch = _torch()
+    cfg = synth.preset(1, M=16, H=1, C=64, B=64, T=3, n_special=1)
+    cache = make_cache(cfg, L=2)
+    out = cache.new_output()
+    with pytest.raises(B.OvggtError) as e:
+        cache.set_protect(0, None, True)                         # no frame seen yet
+    assert e.value.code == B.OVGGT_ERR_ARG
+    fs = [synth.frame_inputs(cfg, l, 0) for l in range(2)]
+    q, k, v, r = (dev(np.stack([f[x] for f in fs]), cfg) for x in "qkvr")
+    cache.global_attn(q, k, v, out)
+    with pytest.raises(B.OvggtError) as e:
+        cache.set_protect(0, None, True)                         # mid-frame
+    assert e.value.code == B.OVGGT_ERR_STATE
+    cache.score_select(r, None); cache.compact()
+    cache.set_protect(0, None, True, layer=1)
+    assert cache.export(0)["flags"].sum() == 0 and cache.export(1)["flags"].sum() == cfg.M
+    with pytest.raises(B.OvggtError):
+        cache.set_protect(1, None, True)                         # frame 1 has not been appended
+    with pytest.raises(B.OvggtError):
+        cache.set_protect(0, None, True, layer=5)
+    cache.close()
+
+
 def test_bf16_output_is_the_rounded_fp32_output():
     """out_dtype = bf16 stores RNE(bf16) of exactly the value the fp32-output run stores."""
     cfg = synth.preset(1, M=200, H=3, C=64, B=500, T=5, n_special=3)

@@ -4,6 +4,7 @@ import ctypes as C
 import os
 import re
 
+import numpy as np
 import pytest
 
 from paper_2603_05959_amd import binding as B
@@ -73,3 +74,30 @@ def test_product_path_does_not_touch_the_oracle():
             if f.endswith((".py", ".hip", ".cpp", ".h")):
                 src = open(os.path.join(dirpath, f)).read()
                 assert not re.search(r"(import|from)\s+oracle|oracle[/.]\w", src), f
+
+
+def test_dap_policy_follows_the_oracle_schedule():
+    """The host-side registration rule (no device work) against the oracle's on random inputs."""
+    from oracle import ovggt_oracle as oc
+    rng = np.random.default_rng(5)
+    for k_max, gap, tau, eta, ns, npch in [(3, 100, 0.5, 0.05, 5, 1036), (1, 1, 0.9, 1.0, 0, 7), (2, 3, 0.3, 0.34, 1, 50)]:
+        h = B.ovggt_dap_create(k_max, gap, tau, eta, ns, npch)
+        pol = oc.DapPolicy(k_max, gap, tau, eta, ns, npch)
+        mask = np.zeros(ns + npch, np.uint8)
+        for t in range(12 * gap + 5):
+            rho = float(rng.random())
+            conf = rng.integers(0, 5, npch).astype(np.float32) if t % 2 else rng.random(npch).astype(np.float32)
+            reg, dem = B.ovggt_dap_step(h, t, rho, conf, mask)
+            m_ref, d_ref = pol.step(t, rho, conf)
+            assert (reg == t) == (m_ref is not None) and (reg in (t, -1))
+            assert dem == (-1 if d_ref is None else d_ref)
+            if m_ref is not None:
+                assert np.array_equal(mask, m_ref)
+            assert B.ovggt_dap_active(h) == pol.active
+        with pytest.raises(B.OvggtError):
+            B.ovggt_dap_step(h, 3, 0.0, conf, mask)                  # frames must advance
+        B.ovggt_dap_destroy(h)
+    for bad in [(0, 100, 0.5, 0.05, 5, 10), (3, 0, 0.5, 0.05, 5, 10), (3, 100, 0.5, 0.0, 5, 10), (3, 100, 0.5, 1.5, 5, 10),
+                (3, 100, float("nan"), 0.05, 5, 10), (3, 100, 0.5, 0.05, -1, 10), (3, 100, 0.5, 0.05, 5, 0)]:
+        with pytest.raises(B.OvggtError):
+            B.ovggt_dap_create(*bad)
