@@ -245,6 +245,17 @@ int ovggt_dap_step(ovggt_dap* d, int64_t t, double rho, const float* conf, int64
 int ovggt_dap_active(const ovggt_dap* d, int64_t* frames, int32_t cap, int32_t* n);
 int ovggt_dap_destroy(ovggt_dap* d);
 
+/* Host-only: how the bf16 attention launch of `layers_in_launch` layers (1 or cfg->n_layers) over
+ * n_total resident slots would be divided among n_wgs workgroups (the library uses one per compute
+ * unit).  Walks the plan as the kernel does and checks that every (head, query block, key tile) is
+ * covered exactly once and that no workgroup needs more partial records than it owns.
+ * out[0..6] = workgroups, rounds per workgroup, tile segments, 1 if chunks are cost-balanced, most
+ * pieces given to one workgroup, fewest and most tiles given to one workgroup; cost[0..1] = largest
+ * and mean estimated cost per workgroup in tiles (tiles + a fixed charge per piece).
+ * OVGGT_OK, ERR_ARG (bad config or sizes), ERR_STATE (inconsistent plan: a bug). */
+int ovggt_attn_plan_stats(const ovggt_config* cfg, int32_t layers_in_launch, int32_t n_total, int32_t n_wgs,
+                          int32_t* out, float* cost);
+
 const char* ovggt_strerror(int code);
 
 #ifdef __cplusplus

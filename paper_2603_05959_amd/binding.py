@@ -24,6 +24,7 @@ EXPORTS = (
     "ovggt_cache_status", "ovggt_cache_export", "ovggt_cache_import", "ovggt_cache_last_moves",
     "ovggt_profile_enable", "ovggt_profile_read", "ovggt_profile_overhead", "ovggt_strerror",
     "ovggt_cache_set_protect", "ovggt_dap_create", "ovggt_dap_step", "ovggt_dap_active", "ovggt_dap_destroy",
+    "ovggt_attn_plan_stats",
 )
 PROF_CLASSES = ("append", "attn", "combine", "score_select", "compact")
 
@@ -78,6 +79,7 @@ def lib() -> C.CDLL:
     L.ovggt_dap_step.argtypes = [vp, i64, C.c_double, vp, C.POINTER(i64), u8p, C.POINTER(i64)]
     L.ovggt_dap_active.argtypes = [vp, C.POINTER(i64), i32, C.POINTER(i32)]
     L.ovggt_dap_destroy.argtypes = [vp]
+    L.ovggt_attn_plan_stats.argtypes = [cfgp, i32, i32, i32, C.POINTER(i32), C.POINTER(C.c_float)]
     L.ovggt_strerror.argtypes = [C.c_int]
     L.ovggt_strerror.restype = C.c_char_p
     for name in EXPORTS:
@@ -216,6 +218,17 @@ def ovggt_dap_active(h, cap: int = 64) -> list:
 
 def ovggt_dap_destroy(h) -> None:
     _check(lib().ovggt_dap_destroy(h), "ovggt_dap_destroy")
+
+
+def ovggt_attn_plan_stats(cfg: ovggt_config, layers_in_launch: int, n_total: int, n_wgs: int) -> dict:
+    out = (C.c_int32 * 7)()
+    cost = (C.c_float * 2)()
+    _check(lib().ovggt_attn_plan_stats(C.byref(cfg), layers_in_launch, n_total, n_wgs, out, cost),
+           "ovggt_attn_plan_stats")
+    keys = ("n_wgs", "rounds", "segments", "balanced", "pieces_max", "tiles_min", "tiles_max")
+    d = dict(zip(keys, list(out)))
+    d["cost_max"], d["cost_mean"] = cost[0], cost[1]
+    return d
 
 
 def ovggt_profile_enable(h, level: int, every: int = 1) -> None:

@@ -50,6 +50,8 @@
 // XOR-swizzled with the row index so both the K operand reads and the V
 // transpose reads are bank-conflict free.
 #include "ovggt_internal.h"
+#include <algorithm>
+#include <vector>
 
 namespace ovggt {
 
@@ -100,6 +102,7 @@ size_t attn_ws_bytes(int layer_heads) {
   return (size_t)chunks * kSegRecs * 2 * kPartialFloats * sizeof(float);
 }
 
+constexpr int kMaxChunksPerPair = 64;
 struct AttnParams {
   const char* q;
   char* out;
@@ -115,6 +118,8 @@ struct AttnParams {
   int NS, L0;                 // tile segments per item and their length (the last one takes the rest)
   int PP;                     // unit slots per head pair: QB * T, or that rounded up to whole chunks
   int rounds;                 // chunks per workgroup (chunk index = round * workgroups + workgroup's index)
+  int cpp;                    // > 0: every head pair is cut into cpp chunks at the unit offsets in cstart
+  int cstart[kMaxChunksPerPair + 1];   // (chunks of unequal tile counts but equal estimated cost); 0: equal chunks of `chunk` units
   size_t trace_off;           // floats from ws to the end of the record area (timing builds)
   int total_units;            // ceil(LH / 2) * PP
   float c;                    // softmax scale * log2(e)
@@ -151,6 +156,21 @@ __host__ __device__ inline UnitPos decode_unit(long u, int T, int QB, int NS, in
   r.tile = seg0 + r2 - r.qb * len;
   r.combo = (r.hp * NS + r.s) * QB + r.qb;
   return r;
+}
+
+// First unit of chunk c (c may be one past the last chunk), and the chunk a unit belongs to.
+__host__ __device__ inline long chunk_first_unit(const AttnParams& p, int c) {
+  if (p.cpp == 0) return min((long)c * p.chunk, (long)p.total_units);
+  const int hp = c / p.cpp;
+  return (long)hp * p.PP + p.cstart[c - hp * p.cpp];
+}
+__host__ __device__ inline int chunk_of_unit(const AttnParams& p, long u) {
+  if (p.cpp == 0) return (int)(u / p.chunk);
+  const int hp = (int)(u / p.PP);
+  const int r = (int)(u - (long)hp * p.PP);
+  int lc = 0;
+  while (lc + 1 < p.cpp && p.cstart[lc + 1] <= r) ++lc;
+  return hp * p.cpp + lc;
 }
 
 // Half a tile pair, global -> LDS: the calling wave fills 32 rows (4 KiB) of a K or V tile with four
@@ -209,7 +229,13 @@ __device__ inline f16x8 join4(const uint32_t* p) {
 template <bool SHIFT>
 __device__ __forceinline__ float tile_weights(const f32x16& s0, const f32x16& s1, float d,
                                               uint32_t (&p0)[8], uint32_t (&p1)[8]) {
-  float ls[4] = {0.f, 0.f, 0.f, 0.f};
+  // The row sum is taken over the weights as the matrix unit will see them (rounded to half), with
+  // packed half adds: one instruction per two weights instead of two fp32 adds, on the pipe that
+  // co-executes with the other set's MFMAs (v_dot2c_f32_f16 would be exact but runs on the matrix
+  // pipe and serialises with them: measured).  Four independent packed accumulators of 8 terms
+  // each, joined in fp32: the rounding of a tile's sum stays near 2^-11 relative and is unbiased.
+  // An overflowing weight or partial sum becomes +inf and trips the caller's limit test.
+  f16x2 ls[4] = {{0, 0}, {0, 0}, {0, 0}, {0, 0}};
 #pragma unroll
   for (int sb = 0; sb < 2; ++sb) {
     float e[16];
@@ -224,15 +250,13 @@ __device__ __forceinline__ float tile_weights(const f32x16& s0, const f32x16& s1
       f16x2 pk;
       pk[0] = (_Float16)e[2 * j];
       pk[1] = (_Float16)e[2 * j + 1];
-      // plain fp32 adds: v_dot2c_f32_f16 runs on the matrix pipe and serialises with the other
-      // set's MFMAs (measured), v_add_f32 co-executes with them
-      ls[j & 3] += e[2 * j];
-      ls[(j + 2) & 3] += e[2 * j + 1];
+      ls[j & 3] += pk;
       (sb ? p1 : p0)[j] = __builtin_bit_cast(uint32_t, pk);
     }
     __builtin_amdgcn_sched_barrier(0);
   }
-  return (ls[0] + ls[1]) + (ls[2] + ls[3]);
+  return ((float)ls[0][0] + (float)ls[1][0]) + ((float)ls[2][0] + (float)ls[3][0]) +
+         (((float)ls[0][1] + (float)ls[1][1]) + ((float)ls[2][1] + (float)ls[3][1]));
 }
 
 // The reference of a query block as the B operand of the bias step of S^T (a 32x32x8 MFMA, whose
@@ -522,7 +546,7 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
 
   const int G = gridDim.x;
   const int cidx = (blockIdx.x & 7) * (G >> 3) + (blockIdx.x >> 3);
-  if (cidx * p.chunk >= p.total_units) return;           // whole workgroup: no barrier has been executed yet
+  if (chunk_first_unit(p, cidx) >= p.total_units) return;   // whole workgroup: no barrier has been executed yet
 #ifdef OVGGT_TRACE
   const unsigned long long tr_w0 = wall_clock64(), tr_c0 = clock64();
   unsigned long long tr_n = 0;
@@ -569,8 +593,8 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
   // pair (its K/V tiles then live in that XCD's L2 while all its query blocks pass over them).
   for (int rnd = 0; rnd < p.rounds; ++rnd) {
   const int chunk_idx = rnd * G + cidx;
-  int u = chunk_idx * p.chunk;
-  const int u_end = min(u + p.chunk, p.total_units);
+  int u = (int)chunk_first_unit(p, chunk_idx);
+  const int u_end = (int)chunk_first_unit(p, chunk_idx + 1);
   const int u_begin = u;
   int n_piece = 0;
   while (u < u_end) {
@@ -772,10 +796,6 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(AttnParams p) {
   const int lh = item / p.QB;
   const int set = lh & 1;
   const int hp = lh >> 1;
-  if (p.NS == 1) {
-    const long ua = (long)hp * p.PP + (long)qb_idx * p.T;
-    if (ua / p.chunk == (ua + p.T - 1) / p.chunk) return;   // one workgroup did the whole item
-  }
   const int row = rgrp * kCombineRows + (threadIdx.x >> 4), piece = threadIdx.x & 15;
   const int li = lh / p.H;
   const int h = lh - li * p.H;
@@ -787,28 +807,44 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(AttnParams p) {
   float4 acc = {0.f, 0.f, 0.f, 0.f};
   float l = 0.f, mt = -INFINITY;
   for (int sg0 = 0; sg0 < p.NS; sg0 += kSegGroup) {
-    // one thread lists the records that hold pieces of this item (integer divisions, done once)
+    // The first wave lists the records that hold pieces of this item (integer divisions, done once).
+    // With a table of chunk starts, lane l holds the start of the head pair's chunk l and one ballot
+    // finds the chunk of a unit: the last one that starts at or before it.
     __syncthreads();
-    if (threadIdx.x == 0) {
+    if (threadIdx.x < 64) {
+      const int lane = threadIdx.x;
+      const int cs_l = (p.cpp > 0 && lane < p.cpp) ? p.cstart[lane] : 0x7FFFFFFF;
+      auto chunk_of = [&](long u) -> int {
+        if (p.cpp == 0) return (int)(u / p.chunk);
+        const int hp2 = (int)(u / p.PP);
+        const int r = (int)(u - (long)hp2 * p.PP);
+        const unsigned long long m = __ballot(cs_l <= r);             // never empty: the first chunk starts at 0
+        return hp2 * p.cpp + 63 - __builtin_clzll(m);
+      };
       int n = 0;
       for (int sg = sg0; sg < min(sg0 + kSegGroup, p.NS); ++sg) {
         const int seg0 = sg * p.L0;
         const int len = (sg == p.NS - 1 ? p.T : seg0 + p.L0) - seg0;
         const long ua = (long)hp * p.PP + (long)p.QB * seg0 + (long)qb_idx * len, ub = ua + len - 1;
-        const int cf = (int)(ua / p.chunk), cl = (int)(ub / p.chunk);
+        const int cf = chunk_of(ua), cl = chunk_of(ub);
+        if (p.NS == 1 && cf == cl) { n = -1; break; }          // one workgroup did the whole item and wrote it
         const int combo = (hp * p.NS + sg) * p.QB + qb_idx;
         for (int c = cf; c <= cl && n < kSegGroup * kSegRecs; ++c) {
           // which of the chunk's records: plain order, 0 if the chunk starts with this item, else
           // 1; segmented order, the pieces of a chunk are numbered in unit order
+          const long cu = chunk_first_unit(p, c);
+          if (cu >= chunk_first_unit(p, c + 1)) continue;       // an empty chunk holds nothing
           int ord;
-          if (p.NS == 1) ord = (long)c * p.chunk < ua ? 1 : 0;
-          else ord = combo - decode_unit((long)c * p.chunk, p.T, p.QB, p.NS, p.L0, p.PP).combo;
-          rec_list[n++] = (uint32_t)((kSegRecs * c + ord) * 2 + set);
+          if (p.NS == 1) ord = cu < ua ? 1 : 0;
+          else ord = combo - decode_unit(cu, p.T, p.QB, p.NS, p.L0, p.PP).combo;
+          if (lane == 0) rec_list[n] = (uint32_t)((kSegRecs * c + ord) * 2 + set);
+          ++n;
         }
       }
-      n_list = n;
+      if (lane == 0) n_list = n;
     }
     __syncthreads();
+    if (n_list < 0) return;
     const int n = n_list;
     if (qrow < p.M)
     for (int i0 = 0; i0 < n; i0 += kMaxParts) {
@@ -850,16 +886,101 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(AttnParams p) {
   }
 }
 
-hipError_t launch_attn_bf16(const Geom& g, char* kv, int layer0, int nl, const void* q, void* out,
-                            int n_total, float scale, char* ws, size_t ws_bytes, int n_wgs, bool out_f32,
-                            hipStream_t s, hipEvent_t* ev) {
-  AttnParams p;
-  p.q = (const char*)q;
-  p.out = (char*)out;
-  p.kv0 = layer_k(kv, g, layer0);
-  p.kv_layer_bytes = g.kv_layer_bytes;
-  p.v_off = (size_t)g.H * g.cap * g.d * g.esize;
-  p.ws = (float*)ws;
+// Cost of starting and finishing a piece (Q fragments, the first tile's reference, the merge of the
+// slot halves and the partial record), in tiles: measured 13-14 thousand cycles against 3.8 thousand
+// per tile.
+constexpr float kPieceCostTiles = 3.7f;
+
+// Cut one head pair's QB * T units into `cpp` chunks of equal estimated cost (tiles + kPieceCostTiles
+// per piece) and fill p.NS, p.L0, p.PP, p.cpp, p.cstart.  Segments before the last are L0 tiles long
+// and give one whole run (one piece) to a chunk each, so neighbouring workgroups still walk the same
+// K/V tiles side by side; the runs of the last segment are dealt out greedily.  With equal tile
+// counts instead, the workgroups that hold two or three pieces finish 10-20 % after the others.
+// False (p untouched) when the shape does not fit the table or a chunk would need more than
+// kSegRecs records.
+static bool plan_balanced_chunks(AttnParams& p, int cpp) {
+  if (cpp < 1 || cpp > kMaxChunksPerPair) return false;
+  const int QB = p.QB, T = p.T;
+  const float ov = kPieceCostTiles;
+  int L0 = (int)(((float)QB * T + ov * (QB - 1)) / cpp + 0.5f);
+  if (L0 < 1) L0 = 1;
+  int NS = (T + L0 - 1) / L0;
+  while (NS > 1 && (NS - 1) * QB >= cpp) {                                // the last segment needs a chunk too
+    ++L0;
+    NS = (T + L0 - 1) / L0;
+  }
+  if (NS > 1 && (T - (NS - 1) * L0) + ov < (L0 + ov) * 0.5f) --NS;      // a short remainder joins the segment before it
+  if (NS <= 1) { NS = 1; L0 = T; }
+  const int lead = (NS - 1) * QB;                 // chunks that are one whole run each
+  const int n_rem = cpp - lead;
+  const int R = T - (NS - 1) * L0;                // run length of the last segment
+  int cs[kMaxChunksPerPair + 1];
+  for (int c = 0; c < lead; ++c) cs[c] = c * L0;
+  const int base = lead * L0, total_last = QB * R;
+  // Last segment: QB runs of R tiles over n_rem chunks.  A chunk is filled run by run up to a cost
+  // limit (a piece of x tiles costs ov + x; the rest of a run is split off when at least one more
+  // tile fits); the smallest limit that needs no more than n_rem chunks is found by bisection.
+  auto fill = [&](float limit, int* starts) -> int {
+    int pos = 0, used = 0;
+    while (pos < total_last) {
+      if (starts && used < n_rem) starts[used] = base + pos;
+      ++used;
+      float cost = 0.f;
+      while (pos < total_last) {
+        const int run_left = R - pos % R;
+        int x = (int)(limit - cost - ov);
+        if (x < 1) {
+          if (cost > 0.f) break;
+          x = 1;                                   // an empty chunk takes at least one tile
+        }
+        if (x > run_left) x = run_left;
+        pos += x;
+        cost += ov + x;
+      }
+    }
+    return used;
+  };
+  float lo = ((float)total_last + ov * QB) / n_rem, hi = (float)total_last + ov * QB + 1.f;
+  if (fill(lo, nullptr) <= n_rem) hi = lo;
+  for (int it = 0; it < 24 && hi - lo > 0.05f; ++it) {
+    const float mid = 0.5f * (lo + hi);
+    if (fill(mid, nullptr) <= n_rem) hi = mid; else lo = mid;
+  }
+  const int used = fill(hi, cs + lead);
+  if (used > n_rem) return false;
+  for (int c = used; c < n_rem; ++c) cs[lead + c] = QB * T;          // chunks left over stay empty
+  cs[cpp] = QB * T;
+  // every chunk within kSegRecs pieces?
+  for (int c = lead; c < cpp; ++c) {
+    const int a = cs[c] - base, b = cs[c + 1] - base;
+    if (b > a && (b - 1) / R - a / R + 1 > kSegRecs) return false;
+  }
+  // walk one head pair the way the kernel will (all pairs are cut alike): the pieces must tile
+  // QB * T units without crossing a segment end, within the records a chunk owns
+  long covered = 0;
+  for (int c = 0; c < cpp; ++c) {
+    if (cs[c] > cs[c + 1]) return false;
+    int u = cs[c], partial = 0;
+    while (u < cs[c + 1]) {
+      const UnitPos up = decode_unit(u, T, QB, NS, L0, QB * T);
+      const int t1 = min(up.seg_end, up.tile + (cs[c + 1] - u));
+      if (!up.valid || t1 <= up.tile) return false;
+      if (!(NS == 1 && up.tile == 0 && t1 == T)) ++partial;
+      covered += t1 - up.tile;
+      u += t1 - up.tile;
+    }
+    if (NS > 1 ? partial > kSegRecs : partial > 2) return false;
+  }
+  if (covered != (long)QB * T) return false;
+  p.NS = NS; p.L0 = L0; p.PP = QB * T; p.cpp = cpp;
+  for (int c = 0; c <= cpp; ++c) p.cstart[c] = cs[c];
+  return true;
+}
+
+// How a launch is cut into chunks: fills the planning fields of p (LH, QB, T, chunk, NS, L0, PP,
+// rounds, cpp, cstart, total_units) and the grid size.  Host only.
+static hipError_t plan_attn(AttnParams& p, const Geom& g, int nl, int n_total, size_t ws_bytes, int* n_wgs_io) {
+  int n_wgs = *n_wgs_io;
   p.H = g.H; p.M = g.M; p.cap = g.cap; p.n_total = n_total;
   p.LH = nl * g.H;
   p.QB = (g.M + kQueryTile - 1) / kQueryTile;
@@ -870,6 +991,7 @@ hipError_t launch_attn_bf16(const Geom& g, char* kv, int layer0, int nl, const v
   if (n_wgs > kMaxAttnWgs) n_wgs = kMaxAttnWgs;
   n_wgs &= ~7;
   if (n_wgs < 8) n_wgs = 8;
+  *n_wgs_io = n_wgs;
   p.chunk = (int)((total + n_wgs - 1) / n_wgs);
   // Tile segments of the chunk's length, so that neighbouring workgroups walk the same tiles of
   // neighbouring query blocks together; a short remainder joins the segment before it, which
@@ -885,25 +1007,103 @@ hipError_t launch_attn_bf16(const Geom& g, char* kv, int layer0, int nl, const v
   }
   p.total_units = ((p.LH + 1) / 2) * p.PP;
   p.rounds = 1;
+  p.cpp = 0;
+  const int pairs = (p.LH + 1) / 2;
+  // one launch round and the workgroups divide evenly among the head pairs: chunks of equal cost
+  if (n_wgs % pairs == 0 && plan_balanced_chunks(p, n_wgs / pairs)) {
+    p.chunk = 0;
+    p.total_units = pairs * p.PP;
+  }
   // Many head pairs: deal them out to the XCDs round by round, one head pair per XCD and round, cut
   // into as many chunks as the XCD has workgroups.  The plain split above would hand a workgroup a
   // run of whole items, and the query blocks of a head would re-read its K/V from memory one after
   // the other.
   {
-    const int pairs = (p.LH + 1) / 2, per_xcd = n_wgs / 8;
+    const int per_xcd = n_wgs / 8;
     const long chunks = (long)pairs * per_xcd;
     if (pairs > 8 && pairs % 8 == 0 && p.QB * p.T >= per_xcd &&
         (size_t)chunks * kSegRecs * 2 * kPartialFloats * sizeof(float) <= ws_bytes) {
-      p.chunk = (p.QB * p.T + per_xcd - 1) / per_xcd;
-      p.NS = (p.T + p.chunk - 1) / p.chunk;
-      p.L0 = p.chunk;
-      if (p.NS > 1 && p.T - (p.NS - 1) * p.L0 < (p.chunk + 1) / 2) --p.NS;
-      if (p.NS <= 1) { p.NS = 1; p.L0 = p.T; }
-      p.PP = per_xcd * p.chunk;
+      if (plan_balanced_chunks(p, per_xcd)) {
+        p.chunk = 0;
+      } else {
+        p.cpp = 0;
+        p.chunk = (p.QB * p.T + per_xcd - 1) / per_xcd;
+        p.NS = (p.T + p.chunk - 1) / p.chunk;
+        p.L0 = p.chunk;
+        if (p.NS > 1 && p.T - (p.NS - 1) * p.L0 < (p.chunk + 1) / 2) --p.NS;
+        if (p.NS <= 1) { p.NS = 1; p.L0 = p.T; }
+        p.PP = per_xcd * p.chunk;
+      }
       p.total_units = pairs * p.PP;
       p.rounds = pairs / 8;
     }
   }
+  return hipSuccess;
+}
+
+// Walks a plan the way the kernel does and reports what the workgroups would be given.  Returns
+// false when the plan is inconsistent: a tile of some (head pair, query block) covered twice or not
+// at all, a piece crossing a segment end, or a chunk with more partial pieces than records.
+bool attn_plan_stats(const Geom& g, int nl, int n_total, int n_wgs, size_t ws_bytes, AttnPlanStats* st) {
+  AttnParams p;
+  if (plan_attn(p, g, nl, n_total, ws_bytes, &n_wgs) != hipSuccess) return false;
+  const int pairs = (p.LH + 1) / 2;
+  const long n_chunks = (long)p.rounds * n_wgs;
+  std::vector<uint8_t> seen((size_t)pairs * p.QB * p.T, 0);
+  st->n_wgs = n_wgs; st->rounds = p.rounds; st->segments = p.NS; st->balanced = p.cpp > 0 ? 1 : 0;
+  st->pieces_max = 0; st->tiles_min = 0x7FFFFFFF; st->tiles_max = 0; st->cost_max = 0.f; st->cost_mean = 0.f;
+  for (int w = 0; w < n_wgs; ++w) {
+    int tiles = 0, pieces_wg = 0;
+    for (int rnd = 0; rnd < p.rounds; ++rnd) {
+      const int c = rnd * n_wgs + w;
+      long u = chunk_first_unit(p, c);
+      const long u_end = chunk_first_unit(p, c + 1);
+      if (u > u_end || u_end > p.total_units) return false;
+      int partial = 0;
+      while (u < u_end) {
+        const UnitPos up = decode_unit(u, p.T, p.QB, p.NS, p.L0, p.PP);
+        if (!up.valid) break;
+        const int t0 = up.tile, t1 = (int)std::min<long>(up.seg_end, t0 + (u_end - u));
+        if (t1 <= t0 || t1 > p.T || up.hp >= pairs || up.qb >= p.QB) return false;
+        const bool full = p.NS == 1 && t0 == 0 && t1 == p.T;
+        if (!full) ++partial;
+        for (int t = t0; t < t1; ++t) {
+          uint8_t& cell = seen[((size_t)up.hp * p.QB + up.qb) * p.T + t];
+          if (cell) return false;
+          cell = 1;
+        }
+        if (!full && chunk_of_unit(p, u) != c) return false;          // the merge pass must find this chunk again
+        tiles += t1 - t0; ++pieces_wg;
+        u += t1 - t0;
+      }
+      if (p.NS > 1 ? partial > kSegRecs : partial > 2) return false;
+      if ((size_t)(c + 1) * kSegRecs * 2 * kPartialFloats * sizeof(float) > ws_bytes && partial > 0) return false;
+    }
+    st->pieces_max = std::max(st->pieces_max, pieces_wg);
+    st->tiles_min = std::min(st->tiles_min, tiles);
+    st->tiles_max = std::max(st->tiles_max, tiles);
+    const float cost = tiles + kPieceCostTiles * pieces_wg;
+    st->cost_max = std::max(st->cost_max, cost);
+    st->cost_mean += cost / n_wgs;
+  }
+  (void)n_chunks;
+  for (uint8_t v : seen)
+    if (!v) return false;
+  return true;
+}
+
+hipError_t launch_attn_bf16(const Geom& g, char* kv, int layer0, int nl, const void* q, void* out,
+                            int n_total, float scale, char* ws, size_t ws_bytes, int n_wgs, bool out_f32,
+                            hipStream_t s, hipEvent_t* ev) {
+  AttnParams p;
+  p.q = (const char*)q;
+  p.out = (char*)out;
+  p.kv0 = layer_k(kv, g, layer0);
+  p.kv_layer_bytes = g.kv_layer_bytes;
+  p.v_off = (size_t)g.H * g.cap * g.d * g.esize;
+  p.ws = (float*)ws;
+  const hipError_t pe = plan_attn(p, g, nl, n_total, ws_bytes, &n_wgs);
+  if (pe != hipSuccess) return pe;
   p.trace_off = ws_bytes / sizeof(float);
   p.c = scale * 1.4426950408889634f;
   p.out_f32 = out_f32 ? 1 : 0;

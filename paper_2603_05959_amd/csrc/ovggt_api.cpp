@@ -501,6 +501,21 @@ int ovggt_profile_overhead(ovggt_cache* c, int reps, double* ms_mean, void* hip_
   return OVGGT_OK;
 }
 
+int ovggt_attn_plan_stats(const ovggt_config* cfg, int32_t layers_in_launch, int32_t n_total, int32_t n_wgs,
+                          int32_t* out, float* cost) {
+  if (!valid_config(cfg) || !out || !cost || cfg->dtype != OVGGT_BF16) return OVGGT_ERR_ARG;
+  if (layers_in_launch != 1 && layers_in_launch != cfg->n_layers) return OVGGT_ERR_ARG;
+  if (n_total < 1 || n_total > cfg->budget + cfg->tokens_per_frame || n_wgs < 1) return OVGGT_ERR_ARG;
+  Geom g;
+  make_geom(*cfg, &g);
+  AttnPlanStats st;
+  if (!attn_plan_stats(g, layers_in_launch, n_total, n_wgs, ws_bytes_for(*cfg), &st)) return OVGGT_ERR_STATE;
+  out[0] = st.n_wgs; out[1] = st.rounds; out[2] = st.segments; out[3] = st.balanced; out[4] = st.pieces_max;
+  out[5] = st.tiles_min; out[6] = st.tiles_max;
+  cost[0] = st.cost_max; cost[1] = st.cost_mean;
+  return OVGGT_OK;
+}
+
 const char* ovggt_strerror(int code) {
   switch (code) {
     case OVGGT_OK: return "ok";

@@ -64,6 +64,13 @@ hipError_t launch_attn_bf16(const Geom& g, char* kv, int layer0, int nl, const v
                             int n_total, float scale, char* ws, size_t ws_bytes, int n_wgs, bool out_f32,
                             hipStream_t s, hipEvent_t* ev = nullptr);
 size_t attn_ws_bytes(int layer_heads);
+// What the attention launch over nl layers and n_total resident slots hands to its workgroups (host-side walk of
+// the plan; false: the plan is inconsistent).  cost = tiles + a fixed charge per piece, in tiles.
+struct AttnPlanStats {
+  int n_wgs, rounds, segments, balanced, pieces_max, tiles_min, tiles_max;
+  float cost_max, cost_mean;
+};
+bool attn_plan_stats(const Geom& g, int nl, int n_total, int n_wgs, size_t ws_bytes, AttnPlanStats* st);
 
 // Eq. 6: activation smoothing of a frame's patch scores (alpha = 0: off).
 struct SmoothParams {

@@ -101,3 +101,24 @@ def test_dap_policy_follows_the_oracle_schedule():
                 (3, 100, float("nan"), 0.05, 5, 10), (3, 100, 0.5, 0.05, -1, 10), (3, 100, 0.5, 0.05, 5, 0)]:
         with pytest.raises(B.OvggtError):
             B.ovggt_dap_create(*bad)
+
+
+def test_attention_plans_cover_every_tile_once():
+    """Host-side walk of the attention launch plan over many shapes: every (head, query block, key
+    tile) exactly once, pieces within the records a workgroup owns; where chunks are balanced by
+    estimated cost, the busiest workgroup stays close to the mean."""
+    shapes = [(1374, 16, 16384, 1), (1374, 16, 16384, 24), (1374, 16, 32768, 1), (1041, 16, 4096, 1),
+              (1041, 16, 65536, 1), (200, 3, 700, 1), (1, 1, 64, 1), (37, 2, 74, 1), (130, 5, 1000, 1),
+              (128, 16, 256, 1), (300, 8, 5000, 4), (130, 16, 300, 3), (150, 2, 400, 3), (1, 16, 188, 1),
+              (500, 4, 3000, 2), (129, 1, 100000, 1), (2000, 32, 9000, 1), (64, 64, 640, 2)]
+    for M, H, Bud, L in shapes:
+        cfg = B.make_config(L, H, 64, M, 64, max(Bud, M), "bf16")
+        for n_total in sorted({M, min(2 * M, Bud + M), (Bud + M) // 2, Bud + M - 1, Bud + M}):
+            for n_wgs in (256, 64, 304):
+                st = B.ovggt_attn_plan_stats(cfg, L, n_total, n_wgs)        # raises if inconsistent
+                assert st["tiles_max"] >= st["tiles_min"] >= 0 and st["pieces_max"] >= 1
+                if st["balanced"] and st["tiles_min"] > 30:
+                    assert st["cost_max"] <= 1.12 * st["cost_mean"] + 1, (M, H, Bud, L, n_total, n_wgs, st)
+    st = B.ovggt_attn_plan_stats(B.make_config(1, 16, 64, 1374, 1024, 16384, "bf16"), 1, 17758, 256)
+    assert st["balanced"] == 1 and st["segments"] == 3 and st["pieces_max"] <= 2
+    print(st)
