@@ -91,6 +91,7 @@ constexpr float kWeightSumLimit = 32768.0f;            // a lane's weight sum be
 // s_waitcnt immediates (gfx9 encoding: vmcnt [3:0] and [15:14], expcnt [6:4], lgkmcnt [11:8])
 constexpr int kWaitVm0 = 0x0F70;                       // vmcnt(0), nothing else
 constexpr int kWaitVm4 = 0x0F74;                       // vmcnt(4)
+constexpr int kWaitLgkm0 = 0xC07F;                     // lgkmcnt(0), nothing else
 
 constexpr int kSegRecs = 3;                            // partial records per workgroup and wave set
 // Workspace: kSegRecs partial records per chunk and wave set.  A launch over few (layer, head)
@@ -353,30 +354,34 @@ __device__ __forceinline__ void qk_tile(const f16x8 (&kf)[4][2], const f16x8 (&q
 // as every weight since the last rescale used the same one, which the exact half value guarantees.
 // O holds the tiles before this one (their P V products were issued in the preceding matrix
 // phase), so rescaling it here is consistent.
-template <int PAR>
+template <int PAR, bool force>
 __device__ __forceinline__ void softmax_tile(f32x16 (&S)[2][2], uint32_t (&P)[2][2][8], f32x16 (&O)[2][2],
                                              float (&ref)[2], f16x4 (&qbias)[2], float (&lrun)[2], int g,
-                                             int sbase, int n_total, bool tail, bool force, const char* lds,
+                                             int sbase, int n_total, bool tail, const char* lds,
                                              const int (&koff)[4], const f16x8 (&qf)[2][4], f16x4 kones) {
   float lsum[2];
+  bool overflow = false;
+  if constexpr (!force) {
 #pragma unroll
-  for (int qb = 0; qb < 2; ++qb)
-    lsum[qb] = tile_weights<false>(S[0][qb], S[1][qb], 0.f, P[0][qb], P[1][qb]);
+    for (int qb = 0; qb < 2; ++qb)
+      lsum[qb] = tile_weights<false>(S[0][qb], S[1][qb], 0.f, P[0][qb], P[1][qb]);
 
-  // one overflow test for both query blocks; the compare is issued before the conversions to half
-  // are forced out, so the branch does not wait for the VALU pipeline to drain
-  const bool overflow =
-      __builtin_amdgcn_ballot_w64(!(lsum[0] <= kWeightSumLimit) || !(lsum[1] <= kWeightSumLimit)) != 0ull;
+    // one overflow test for both query blocks; the compare is issued before the conversions to half
+    // are forced out, so the branch does not wait for the VALU pipeline to drain
+    overflow =
+        __builtin_amdgcn_ballot_w64(!(lsum[0] <= kWeightSumLimit) || !(lsum[1] <= kWeightSumLimit)) != 0ull;
 #pragma unroll
-  for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < 2; ++a)
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
+      for (int b = 0; b < 2; ++b)
 #pragma unroll
-      for (int j = 0; j < 8; ++j) asm volatile("" : "+v"(P[a][b][j]));
+        for (int j = 0; j < 8; ++j) asm volatile("" : "+v"(P[a][b][j]));
+  }
   if (__builtin_expect(overflow || force, 0)) {
     // rare: the exponents are recomputed from the K tile (still resident in this phase) rather than
-    // kept alive through the fast path, which frees their registers for the weights
-    {
+    // kept alive through the fast path, which frees their registers for the weights.  The first tile
+    // of a segment comes here directly: its exponents (taken against the reference 0) are still in S.
+    if constexpr (!force) {
       f16x8 kf[4][2];
       k_frags<PAR>(lds, koff, kf);
       qk_tile(kf, qf, qbias, kones, S);
@@ -508,8 +513,8 @@ __device__ __forceinline__ void tile_step(TileCtx& x, int tt, const int (&koff)[
     if (more)
       load_rows_to_lds(x.vbase + (size_t)((OVGGT_ABLATE & 128) ? ((tt + 1) & 7) : (tt + 1)) * kTileBytes, x.lane_off,
                        x.lds_ld + (PAR ^ 1) * 2 * kTileBytes + kTileBytes);
-    softmax_tile<PAR>(z.S, z.P, z.O, z.ref, z.qbias, z.lrun, x.g, tt * kSlotTile + x.slot0, x.n_total,
-                      tt == x.T - 1 && (x.n_total & (kSlotTile - 1)) != 0, FIRST, x.lds, koff, z.qf, z.kones);
+    softmax_tile<PAR, FIRST>(z.S, z.P, z.O, z.ref, z.qbias, z.lrun, x.g, tt * kSlotTile + x.slot0, x.n_total,
+                             tt == x.T - 1 && (x.n_total & (kSlotTile - 1)) != 0, x.lds, koff, z.qf, z.kones);
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
@@ -770,7 +775,10 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
         }
       }
     }
-    __syncthreads();                                  // merge scratch is reused as tile buffers
+    // the merge scratch is reused as tile buffers: everybody's LDS reads must be done, while the
+    // stores of the result may still be on their way
+    __builtin_amdgcn_s_waitcnt(kWaitLgkm0);
+    phase_barrier();
     u += t1 - t0;
   }
   }
@@ -887,9 +895,9 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(AttnParams p) {
 }
 
 // Cost of starting and finishing a piece (Q fragments, the first tile's reference, the merge of the
-// slot halves and the partial record), in tiles: measured 13-14 thousand cycles against 3.8 thousand
-// per tile.
-constexpr float kPieceCostTiles = 3.7f;
+// slot halves, the partial record, the two wave sets falling out of step), in tiles: workgroups with
+// one and with two pieces fit time = 3.6 thousand cycles per tile + 25 thousand per piece.
+constexpr float kPieceCostTiles = 7.0f;
 
 // Cut one head pair's QB * T units into `cpp` chunks of equal estimated cost (tiles + kPieceCostTiles
 // per piece) and fill p.NS, p.L0, p.PP, p.cpp, p.cstart.  Segments before the last are L0 tiles long
