@@ -100,7 +100,11 @@ constexpr int kSegRecs = 3;                            // partial records per wo
 size_t attn_ws_bytes(int layer_heads) {
   const long pairs = (layer_heads + 1) / 2;
   const long chunks = pairs * (kMaxAttnWgs / 8) > kMaxAttnWgs ? pairs * (kMaxAttnWgs / 8) : kMaxAttnWgs;
-  return (size_t)chunks * kSegRecs * 2 * kPartialFloats * sizeof(float);
+  size_t bytes = (size_t)chunks * kSegRecs * 2 * kPartialFloats * sizeof(float);
+#ifdef OVGGT_TRACE
+  bytes += (size_t)kMaxAttnWgs * 8 * 64;                // timing builds: one 64-byte record per wave behind the partials
+#endif
+  return bytes;
 }
 
 constexpr int kMaxChunksPerPair = 64;
@@ -732,45 +736,70 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
             O[db][qb][i] = O[db][qb][i] * a0 + mO[((db * 2 + qb) * 16 + i) * 64 + lane] * a1;
       }
       if (full) {
+        // same rule as below: offsets first, then nothing but stores
+        size_t oo[2];
+        float inv[2];
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+          const int qrow = q0 + qhalf * 64 + qb * 32 + l32;
+          oo[qb] = ((size_t)qrow * p.H) * 64 + 4 * g;
+          inv[qb] = 1.0f / lfin[qb];
+        }
+        asm volatile("" : "+v"(oo[0]), "+v"(oo[1]), "+v"(inv[0]), "+v"(inv[1]));
+        const size_t obase = ((size_t)li * p.M * p.H + h) * 64;          // uniform
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
           const int qrow = q0 + qhalf * 64 + qb * 32 + l32;
           if (qrow < p.M) {
-            const float inv = 1.0f / lfin[qb];
-            const size_t oel = (((size_t)li * p.M + qrow) * p.H + h) * 64;
+            if (p.out_f32) {
+              float* op = (float*)p.out + obase + oo[qb];
 #pragma unroll
-            for (int db = 0; db < 2; ++db)
+              for (int db = 0; db < 2; ++db)
 #pragma unroll
-              for (int ig = 0; ig < 4; ++ig) {
-                const int dcol = db * 32 + ig * 8 + 4 * g;
-                if (p.out_f32) {
-                  float4 w = {O[db][qb][ig * 4] * inv, O[db][qb][ig * 4 + 1] * inv,
-                              O[db][qb][ig * 4 + 2] * inv, O[db][qb][ig * 4 + 3] * inv};
-                  *(float4*)(p.out + (oel + dcol) * 4) = w;
-                } else {
+                for (int ig = 0; ig < 4; ++ig) {
+                  float4 w = {O[db][qb][ig * 4] * inv[qb], O[db][qb][ig * 4 + 1] * inv[qb],
+                              O[db][qb][ig * 4 + 2] * inv[qb], O[db][qb][ig * 4 + 3] * inv[qb]};
+                  *(float4*)(op + db * 32 + ig * 8) = w;
+                }
+            } else {
+              __bf16* op = (__bf16*)p.out + obase + oo[qb];
+#pragma unroll
+              for (int db = 0; db < 2; ++db)
+#pragma unroll
+                for (int ig = 0; ig < 4; ++ig) {
                   bf16x4 w;
 #pragma unroll
-                  for (int j = 0; j < 4; ++j) w[j] = (__bf16)(O[db][qb][ig * 4 + j] * inv);
-                  *(bf16x4*)(p.out + (oel + dcol) * 2) = w;
+                  for (int j = 0; j < 4; ++j) w[j] = (__bf16)(O[db][qb][ig * 4 + j] * inv[qb]);
+                  *(bf16x4*)(op + db * 32 + ig * 8) = w;
                 }
-              }
+            }
           }
         }
       } else {
+        // Every address is formed before the first store: a register reloaded from scratch between
+        // two stores would have to wait for all stores before it (one counter covers loads and
+        // stores), about a thousand cycles each time.
         float* rec = p.ws + (size_t)((kSegRecs * chunk_idx + rec_ord) * 2 + set) * kPartialFloats;
+        uint32_t ro = (uint32_t)((qhalf * 64 + l32) * 64 + 4 * g);          // query block 0; block 1 is 32 rows on
+        uint32_t mo = (uint32_t)(kQueryTile * 64 + qhalf * 64 + l32);
+        asm volatile("" : "+v"(ro), "+v"(mo));
+        float* rp0 = rec + ro;
+        float* mp = rec + mo;
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
-          const int r = qhalf * 64 + qb * 32 + l32;
 #pragma unroll
           for (int db = 0; db < 2; ++db)
 #pragma unroll
             for (int ig = 0; ig < 4; ++ig) {
               float4 w = {O[db][qb][ig * 4], O[db][qb][ig * 4 + 1], O[db][qb][ig * 4 + 2], O[db][qb][ig * 4 + 3]};
-              *(float4*)(rec + r * 64 + db * 32 + ig * 8 + 4 * g) = w;
+              *(float4*)(rp0 + qb * 32 * 64 + db * 32 + ig * 8) = w;
             }
-          if (g == 0) {
-            rec[kQueryTile * 64 + r] = mfin[qb];
-            rec[kQueryTile * 64 + kQueryTile + r] = lfin[qb];
+        }
+        if (g == 0) {
+#pragma unroll
+          for (int qb = 0; qb < 2; ++qb) {
+            mp[qb * 32] = mfin[qb];
+            mp[kQueryTile + qb * 32] = lfin[qb];
           }
         }
       }
