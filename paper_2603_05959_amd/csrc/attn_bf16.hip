@@ -70,10 +70,6 @@ typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 // variants keyed on higher row bits: this one has the fewest bank conflicts).
 __device__ __forceinline__ int swz(int row) { return row & 7; }
 
-#ifndef OVGGT_ABLATE
-#define OVGGT_ABLATE 0          // timing experiments only: bit 0 no MFMA, bit 1 no LDS operand reads, bit 2 no tile loads, bit 3 no fma, bit 4 no row-sum adds, bit 5 no overflow branch, bit 7 prefetches hit the L2 (eight tiles reused)
-#endif
-
 // Wave priority in the two phases.  The vector phase is the longer one and its VALU stream loses
 // issue slots to the other set's MFMAs; giving it the higher priority shortens the younger set's
 // vector phase by a tenth (measured) at no cost to the matrix phase that runs beside it.
@@ -185,9 +181,6 @@ __host__ __device__ inline int chunk_of_unit(const AttnParams& p, long u) {
 // would make every later LDS read wait for all outstanding loads.  The kernel orders these loads
 // itself with explicit vmcnt waits in front of the barrier that publishes a tile.
 __device__ __forceinline__ void load_rows_to_lds(const char* gtile, uint32_t lane_off, uint32_t lds_addr) {
-#if OVGGT_ABLATE & 4
-  return;
-#endif
   asm volatile("s_mov_b32 m0, %0\n\t"
                "s_nop 0\n\t"
                "global_load_lds_dwordx4 %1, %2 offset:0\n\t"
@@ -289,20 +282,12 @@ __device__ __forceinline__ void pv_tile(const char* lds, const int (&voff)[2][2]
 #pragma unroll
       for (int db = 0; db < 2; ++db) {
         const int o = (sb * 32 + 16 * s2) * 128;
-#if OVGGT_ABLATE & 2
-        const f16x8 vf = db ? pb1 : pb0;
-#else
         const s16x4 va = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, ldsV + voff[db][0] + o));
         const s16x4 vb = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, ldsV + voff[db][1] + o));
         const __attribute__((ext_vector_type(8))) short v8 = __builtin_shufflevector(va, vb, 0, 1, 2, 3, 4, 5, 6, 7);
         const f16x8 vf = __builtin_bit_cast(f16x8, v8);
-#endif
-#if OVGGT_ABLATE & 1
-        asm volatile("" :: "v"(vf));
-#else
         O[db][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pb0, O[db][0], 0, 0, 0);
         O[db][1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pb1, O[db][1], 0, 0, 0);
-#endif
       }
     }
 }
@@ -476,7 +461,7 @@ __device__ __forceinline__ void tile_step(TileCtx& x, int tt, const int (&koff)[
   __builtin_amdgcn_s_setprio(OVGGT_PRIO_M);
   if (x.active) {
     if (more)
-      load_rows_to_lds(x.kbase + (size_t)((OVGGT_ABLATE & 128) ? ((tt + 1) & 7) : (tt + 1)) * kTileBytes, x.lane_off, x.lds_ld + (PAR ^ 1) * 2 * kTileBytes);
+      load_rows_to_lds(x.kbase + (size_t)(tt + 1) * kTileBytes, x.lane_off, x.lds_ld + (PAR ^ 1) * 2 * kTileBytes);
     f16x8 kf[4][2];
     if (!FIRST) pv_tile<PAR ^ 1>(x.lds, voff, z.P, z.O);
     k_frags<PAR>(x.lds, koff, kf);
@@ -515,7 +500,7 @@ __device__ __forceinline__ void tile_step(TileCtx& x, int tt, const int (&koff)[
   // ---- vector phase
   if (x.active) {
     if (more)
-      load_rows_to_lds(x.vbase + (size_t)((OVGGT_ABLATE & 128) ? ((tt + 1) & 7) : (tt + 1)) * kTileBytes, x.lane_off,
+      load_rows_to_lds(x.vbase + (size_t)(tt + 1) * kTileBytes, x.lane_off,
                        x.lds_ld + (PAR ^ 1) * 2 * kTileBytes + kTileBytes);
     softmax_tile<PAR, FIRST>(z.S, z.P, z.O, z.ref, z.qbias, z.lrun, x.g, tt * kSlotTile + x.slot0, x.n_total,
                              tt == x.T - 1 && (x.n_total & (kSlotTile - 1)) != 0, x.lds, koff, z.qf, z.kones);
