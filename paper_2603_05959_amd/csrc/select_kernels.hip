@@ -166,6 +166,35 @@ __device__ inline uint32_t score_word(float ss, bool* bad) {
   return b;
 }
 
+// From the 256 bin counts in sh.cnt: the digit whose bucket holds the rank-th smallest candidate
+// (sh.digit), the rank inside that bucket (sh.rank), the bucket's size (sh.bucket) and the number
+// of candidates (sh.n_evictable).  Ends with a barrier.
+__device__ inline void pick_digit(SelShared& sh, uint32_t rank) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (wave == 0) {
+    uint32_t c4[4];
+    uint32_t s = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) { c4[j] = sh.cnt[4 * lane + j]; s += c4[j]; }
+    uint32_t inc = s;
+#pragma unroll
+    for (int off = 1; off < 64; off *= 2) {
+      const uint32_t y = __shfl_up(inc, off, 64);
+      if (lane >= off) inc += y;
+    }
+    uint32_t before = inc - s;
+    if (lane == 63) sh.n_evictable = inc;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (before < rank && rank <= before + c4[j]) {
+        sh.digit = 4 * lane + j; sh.rank = rank - before; sh.bucket = c4[j];
+      }
+      before += c4[j];
+    }
+  }
+  __syncthreads();
+}
+
 // One radix pass over the candidates: histogram of an 8-bit digit, then the
 // digit whose bucket holds the rank-th smallest candidate.  Results in sh.digit
 // / sh.rank / sh.bucket (and sh.n_evictable = number of candidates).
@@ -214,28 +243,32 @@ __device__ inline void radix_pass(SelShared& sh, int n_iter, uint32_t rank, Digi
 #ifdef OVGGT_TRACE
   if (ts && tid == 0) ts[2] = (uint32_t)wall_clock64();
 #endif
-  if (wave == 0) {
-    uint32_t c4[4];
-    uint32_t s = 0;
+  pick_digit(sh, rank);
+}
+
+// Light pass for keys held in registers: `cand` has a bit per key of this thread that is still a
+// candidate (usually few after the first pass), digit_of(c) is only evaluated for those.  Counts go
+// to one 256-bin histogram per wave with LDS atomics (a wave's lanes can collide on a bin, which
+// costs at most 64 turns per instruction whatever the data; no clearing and column-summing of the
+// big per-lane histogram).
+template <int KPT, typename DigitOf>
+__device__ inline void radix_pass_light(SelShared& sh, uint64_t cand, uint32_t rank, DigitOf digit_of) {
+  const int tid = threadIdx.x, wave = tid >> 6;
+  uint32_t* flat = &sh.hist[0][0];                    // [wave][256], over the column histogram's storage
+  for (int i = tid; i < kSelWaves * 256; i += kSelThreads) flat[i] = 0u;
+  __syncthreads();
 #pragma unroll
-    for (int j = 0; j < 4; ++j) { c4[j] = sh.cnt[4 * lane + j]; s += c4[j]; }
-    uint32_t inc = s;
+  for (int c = 0; c < KPT; ++c)
+    if ((cand >> c) & 1ull) atomicAdd(&flat[wave * 256 + digit_of(c)], 1u);
+  __syncthreads();
+  if (tid < 256) {
+    uint32_t t = 0;
 #pragma unroll
-    for (int off = 1; off < 64; off *= 2) {
-      const uint32_t y = __shfl_up(inc, off, 64);
-      if (lane >= off) inc += y;
-    }
-    uint32_t before = inc - s;
-    if (lane == 63) sh.n_evictable = inc;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      if (before < rank && rank <= before + c4[j]) {
-        sh.digit = 4 * lane + j; sh.rank = rank - before; sh.bucket = c4[j];
-      }
-      before += c4[j];
-    }
+    for (int w = 0; w < kSelWaves; ++w) t += flat[w * 256 + tid];
+    sh.cnt[tid] = t;
   }
   __syncthreads();
+  pick_digit(sh, rank);
 }
 
 // Selection by one workgroup.  KPT > 0: the score words (and, if IDREG, the
@@ -295,9 +328,82 @@ __device__ inline void select_phase(SelShared& sh, const Geom& g, const float* s
   TSTAMP(1);
 
   // radix select of the n_evict-th smallest (score word, inverted id) pair
-  uint32_t pre_hi = 0, pre_lo = 0, rank = n_evict;
+  uint32_t rank = n_evict;
   int pass = 0;
   bool budget_error = false, done = false;
+  if constexpr (KPT > 0) {
+    // Keys in registers: two bit masks per thread follow the selection, `cand` (keys that still tie
+    // with the threshold on every digit seen so far) and `evm` (keys already known to go).  The
+    // first pass looks at every key (most share a handful of leading digits: per-lane histogram
+    // columns); after it only the candidates are touched, and in the end the masks are the answer.
+    uint64_t cand = 0, evm = 0;
+#pragma unroll
+    for (int c = 0; c < KPT; ++c)
+      if (kw[c] != kNotEvictable) cand |= 1ull << c;
+    auto narrow = [&](auto digit_of) {                 // after a pass: below the chosen digit goes, above stays
+      const uint32_t chosen = sh.digit;
+#pragma unroll
+      for (int c = 0; c < KPT; ++c)
+        if ((cand >> c) & 1ull) {
+          const uint32_t dg = (uint32_t)digit_of(c);
+          if (dg < chosen) evm |= 1ull << c;
+          if (dg != chosen) cand &= ~(1ull << c);
+        }
+    };
+    {
+      auto digit0 = [&](int c) -> int { return kw[c] == kNotEvictable ? -1 : (int)(kw[c] >> 24); };
+      radix_pass<KPT>(sh, n_iter, rank, digit0, &ctrl->pad[20]);
+      if (sh.n_evictable < n_evict) budget_error = true;          // |P| > B
+      else {
+        narrow([&](int c) -> int { return (int)(kw[c] >> 24); });
+        rank = sh.rank;
+        done = (rank == sh.bucket);                   // the whole bucket goes
+      }
+      __syncthreads();
+      pass = 1;
+      TSTAMP(2);
+    }
+#pragma nounroll
+    for (; pass < 4 && !done && !budget_error; ++pass) {
+      const int shift = 24 - 8 * pass;
+      auto dig = [&](int c) -> int { return (int)((kw[c] >> shift) & 255u); };
+      radix_pass_light<KPT>(sh, cand, rank, dig);
+      narrow(dig);
+      rank = sh.rank;
+      done = (rank == sh.bucket);
+      __syncthreads();
+      TSTAMP(2 + pass);
+    }
+    if (!done && !budget_error) {
+      // equal scores straddle the threshold: the ids decide (all candidates share the score word)
+#pragma nounroll
+      for (int p2 = 0; p2 < 4 && !done; ++p2) {
+        const int shift = 24 - 8 * p2;
+        auto dig = [&](int c) -> int { return (int)((idw(c) >> shift) & 255u); };
+        radix_pass_light<KPT>(sh, cand, rank, dig);
+        narrow(dig);
+        rank = sh.rank;
+        done = (rank == sh.bucket);
+        __syncthreads();
+      }
+    }
+    if (done) evm |= cand;
+    if (budget_error) evm = 0;
+    if (bad) sh.bad = 1;
+    TSTAMP(10);
+    // evict bit per slot, published in slot order: the ballot of one chunk over one wave covers 64
+    // consecutive slots
+#pragma unroll
+    for (int c = 0; c < KPT; ++c)
+      if (c < n_chunks) {
+        const uint64_t bl = __ballot((evm >> c) & 1ull);
+        if (lane == 0) {
+          sh.evmap[(c * kSelThreads >> 5) + 2 * wave] = (uint32_t)bl;
+          sh.evmap[(c * kSelThreads >> 5) + 2 * wave + 1] = (uint32_t)(bl >> 32);
+        }
+      }
+  } else {
+  uint32_t pre_hi = 0, pre_lo = 0;
 #pragma nounroll
   for (; pass < 4 && !done; ++pass) {
     const int shift = 24 - 8 * pass;
@@ -338,7 +444,7 @@ __device__ inline void select_phase(SelShared& sh, const Geom& g, const float* s
 
   // evict bit per slot, published in slot order: the ballot of one chunk over one wave covers 64
   // consecutive slots
-  auto publish = [&](int c) {
+  for (int c = 0; c < n_chunks; ++c) {
     bool ev = false;
     if (!budget_error) {
       const uint32_t w = word(c);
@@ -347,18 +453,12 @@ __device__ inline void select_phase(SelShared& sh, const Geom& g, const float* s
         else ev = w < pre_hi || (w == pre_hi && (idw(c) >> lo_shift) <= (pre_lo >> lo_shift));
       }
     }
-    const uint64_t b = __ballot(ev);
+    const uint64_t bl = __ballot(ev);
     if (lane == 0) {
-      sh.evmap[(c * kSelThreads >> 5) + 2 * wave] = (uint32_t)b;
-      sh.evmap[(c * kSelThreads >> 5) + 2 * wave + 1] = (uint32_t)(b >> 32);
+      sh.evmap[(c * kSelThreads >> 5) + 2 * wave] = (uint32_t)bl;
+      sh.evmap[(c * kSelThreads >> 5) + 2 * wave + 1] = (uint32_t)(bl >> 32);
     }
-  };
-  if constexpr (KPT > 0) {
-#pragma unroll
-    for (int c = 0; c < KPT; ++c)
-      if (c < n_chunks) publish(c);
-  } else {
-    for (int c = 0; c < n_chunks; ++c) publish(c);
+  }
   }
   __syncthreads();
   TSTAMP(11);
