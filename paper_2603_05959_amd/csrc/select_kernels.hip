@@ -17,6 +17,7 @@
 // and the id half is only consulted when equal scores straddle the threshold.
 // Then emit the move list in ascending slot order.
 #include "ovggt_internal.h"
+#include <type_traits>
 #include "../../include/ovggt.h"
 
 namespace ovggt {
@@ -247,19 +248,29 @@ __device__ inline void radix_pass(SelShared& sh, int n_iter, uint32_t rank, Digi
 }
 
 // Light pass for keys held in registers: `cand` has a bit per key of this thread that is still a
-// candidate (usually few after the first pass), digit_of(c) is only evaluated for those.  Counts go
-// to one 256-bin histogram per wave with LDS atomics (a wave's lanes can collide on a bin, which
-// costs at most 64 turns per instruction whatever the data; no clearing and column-summing of the
-// big per-lane histogram).
-template <int KPT, typename DigitOf>
-__device__ inline void radix_pass_light(SelShared& sh, uint64_t cand, uint32_t rank, DigitOf digit_of) {
+// candidate (usually few after the first pass).  Each candidate is first settled against the digit
+// the previous pass chose (prev_of(c) below it: evicted; not equal: no candidate any more), the
+// rest are counted by digit_of(c).  Counts go to one 256-bin histogram per wave with LDS atomics (a
+// wave's lanes can collide on a bin, which costs at most 64 turns per instruction whatever the
+// data; no clearing and column-summing of the big per-lane histogram).
+template <int KPT, typename Mask, typename PrevOf, typename DigitOf>
+__device__ inline void radix_pass_light(SelShared& sh, Mask& cand, Mask& evm, uint32_t prev_chosen, uint32_t rank,
+                                        PrevOf prev_of, DigitOf digit_of) {
   const int tid = threadIdx.x, wave = tid >> 6;
   uint32_t* flat = &sh.hist[0][0];                    // [wave][256], over the column histogram's storage
   for (int i = tid; i < kSelWaves * 256; i += kSelThreads) flat[i] = 0u;
   __syncthreads();
 #pragma unroll
   for (int c = 0; c < KPT; ++c)
-    if ((cand >> c) & 1ull) atomicAdd(&flat[wave * 256 + digit_of(c)], 1u);
+    if ((cand >> c) & (Mask)1) {
+      const uint32_t pv = (uint32_t)prev_of(c);
+      if (pv != prev_chosen) {
+        cand &= ~((Mask)1 << c);
+        if (pv < prev_chosen) evm |= (Mask)1 << c;
+      } else {
+        atomicAdd(&flat[wave * 256 + digit_of(c)], 1u);
+      }
+    }
   __syncthreads();
   if (tid < 256) {
     uint32_t t = 0;
@@ -336,26 +347,29 @@ __device__ inline void select_phase(SelShared& sh, const Geom& g, const float* s
     // with the threshold on every digit seen so far) and `evm` (keys already known to go).  The
     // first pass looks at every key (most share a handful of leading digits: per-lane histogram
     // columns); after it only the candidates are touched, and in the end the masks are the answer.
-    uint64_t cand = 0, evm = 0;
+    using Mask = typename std::conditional<(KPT <= 32), uint32_t, uint64_t>::type;
+    Mask cand = 0, evm = 0;
 #pragma unroll
     for (int c = 0; c < KPT; ++c)
-      if (kw[c] != kNotEvictable) cand |= 1ull << c;
-    auto narrow = [&](auto digit_of) {                 // after a pass: below the chosen digit goes, above stays
+      if (kw[c] != kNotEvictable) cand |= (Mask)1 << c;
+    // settles the candidates against the digit the last pass chose: below it goes, above it stays
+    auto narrow = [&](auto digit_of) {
       const uint32_t chosen = sh.digit;
 #pragma unroll
       for (int c = 0; c < KPT; ++c)
-        if ((cand >> c) & 1ull) {
+        if ((cand >> c) & (Mask)1) {
           const uint32_t dg = (uint32_t)digit_of(c);
-          if (dg < chosen) evm |= 1ull << c;
-          if (dg != chosen) cand &= ~(1ull << c);
+          if (dg < chosen) evm |= (Mask)1 << c;
+          if (dg != chosen) cand &= ~((Mask)1 << c);
         }
     };
+    uint32_t chosen = 0;                               // digit of the last pass (its candidates are settled by the next one)
     {
       auto digit0 = [&](int c) -> int { return kw[c] == kNotEvictable ? -1 : (int)(kw[c] >> 24); };
       radix_pass<KPT>(sh, n_iter, rank, digit0, &ctrl->pad[20]);
       if (sh.n_evictable < n_evict) budget_error = true;          // |P| > B
       else {
-        narrow([&](int c) -> int { return (int)(kw[c] >> 24); });
+        chosen = sh.digit;
         rank = sh.rank;
         done = (rank == sh.bucket);                   // the whole bucket goes
       }
@@ -363,14 +377,18 @@ __device__ inline void select_phase(SelShared& sh, const Geom& g, const float* s
       pass = 1;
       TSTAMP(2);
     }
+    int last_shift = 24;                               // where the last pass took its digit from
+    bool last_id = false;
 #pragma nounroll
     for (; pass < 4 && !done && !budget_error; ++pass) {
       const int shift = 24 - 8 * pass;
-      auto dig = [&](int c) -> int { return (int)((kw[c] >> shift) & 255u); };
-      radix_pass_light<KPT>(sh, cand, rank, dig);
-      narrow(dig);
+      radix_pass_light<KPT, Mask>(sh, cand, evm, chosen, rank,
+                                  [&](int c) -> int { return (int)((kw[c] >> (shift + 8)) & 255u); },
+                                  [&](int c) -> int { return (int)((kw[c] >> shift) & 255u); });
+      chosen = sh.digit;
       rank = sh.rank;
       done = (rank == sh.bucket);
+      last_shift = shift;
       __syncthreads();
       TSTAMP(2 + pass);
     }
@@ -379,13 +397,27 @@ __device__ inline void select_phase(SelShared& sh, const Geom& g, const float* s
 #pragma nounroll
       for (int p2 = 0; p2 < 4 && !done; ++p2) {
         const int shift = 24 - 8 * p2;
-        auto dig = [&](int c) -> int { return (int)((idw(c) >> shift) & 255u); };
-        radix_pass_light<KPT>(sh, cand, rank, dig);
-        narrow(dig);
+        if (p2 == 0)
+          radix_pass_light<KPT, Mask>(sh, cand, evm, chosen, rank,
+                                      [&](int c) -> int { return (int)(kw[c] & 255u); },
+                                      [&](int c) -> int { return (int)(idw(c) >> 24); });
+        else
+          radix_pass_light<KPT, Mask>(sh, cand, evm, chosen, rank,
+                                      [&](int c) -> int { return (int)((idw(c) >> (shift + 8)) & 255u); },
+                                      [&](int c) -> int { return (int)((idw(c) >> shift) & 255u); });
+        chosen = sh.digit;
         rank = sh.rank;
         done = (rank == sh.bucket);
+        last_shift = shift;
+        last_id = true;
         __syncthreads();
       }
+    }
+    // the last pass's candidates are still unsettled
+    if (!budget_error) {
+      if (last_id) narrow([&](int c) -> int { return (int)((idw(c) >> last_shift) & 255u); });
+      else narrow([&](int c) -> int { return (int)((kw[c] >> last_shift) & 255u); });
+      (void)chosen;
     }
     if (done) evm |= cand;
     if (budget_error) evm = 0;
