@@ -104,6 +104,8 @@ size_t attn_ws_bytes(int layer_heads) {
 }
 
 constexpr int kMaxChunksPerPair = 64;
+constexpr int kMaxTableItems = 16, kMaxTableRecs = 12;  // query blocks, and partial records of one, in the merge pass's table
+constexpr uint8_t kWholeItem = 255;
 struct AttnParams {
   const char* q;
   char* out;
@@ -121,6 +123,13 @@ struct AttnParams {
   int rounds;                 // chunks per workgroup (chunk index = round * workgroups + workgroup's index)
   int cpp;                    // > 0: every head pair is cut into cpp chunks at the unit offsets in cstart
   int cstart[kMaxChunksPerPair + 1];   // (chunks of unequal tile counts but equal estimated cost); 0: equal chunks of `chunk` units
+  // With cpp > 0 and few enough query blocks, the merge pass finds an item's partial records in a
+  // table instead of working them out (the same table for every head pair): query block qb has
+  // rec_count[qb] entries, each chunk-in-pair + 256 * record-in-chunk; kWholeItem: one workgroup
+  // did the whole item and wrote the output itself.  rec_table_on = 0: no table.
+  int rec_table_on;
+  uint8_t rec_count[kMaxTableItems];
+  uint16_t rec_table[kMaxTableItems][kMaxTableRecs];
   size_t trace_off;           // floats from ws to the end of the record area (timing builds)
   int total_units;            // ceil(LH / 2) * PP
   float c;                    // softmax scale * log2(e)
@@ -806,6 +815,37 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
 #endif
 }
 
+// One round of the merge: up to kMaxParts partial records of a row are fetched together (all loads
+// in flight at once) and folded into the running (acc, l, mt) of a thread's four output columns.
+constexpr int kMaxParts = 4;
+__device__ __forceinline__ void combine_round(const AttnParams& p, const uint32_t (&recs)[kMaxParts], int n, int row,
+                                              int piece, float4& acc, float& l, float& mt) {
+  float m[kMaxParts], lp[kMaxParts];
+  float4 o[kMaxParts];
+#pragma unroll
+  for (int j = 0; j < kMaxParts; ++j) {
+    const float* rec = p.ws + (size_t)recs[j] * kPartialFloats;       // entries beyond n repeat the last one
+    m[j] = rec[kQueryTile * 64 + row];
+    lp[j] = rec[kQueryTile * 64 + kQueryTile + row];
+    o[j] = *(const float4*)(rec + row * 64 + piece * 4);
+  }
+  float mn = mt;
+#pragma unroll
+  for (int j = 0; j < kMaxParts; ++j)
+    if (j < n) mn = fmaxf(mn, m[j]);
+  const float rs = __builtin_amdgcn_exp2f(mt - mn);      // 0 in the first round (mt = -inf)
+  acc.x *= rs; acc.y *= rs; acc.z *= rs; acc.w *= rs;
+  l *= rs;
+  mt = mn;
+#pragma unroll
+  for (int j = 0; j < kMaxParts; ++j)
+    if (j < n) {
+      const float w = __builtin_amdgcn_exp2f(m[j] - mt);
+      l += lp[j] * w;
+      acc.x += o[j].x * w; acc.y += o[j].y * w; acc.z += o[j].z * w; acc.w += o[j].w * w;
+    }
+}
+
 // Merge the partials of every item that was split across workgroups.  A workgroup takes 16 query
 // rows of one item; a thread owns four output columns of one row, so every load is one 16-byte
 // piece of a 256-byte row and the few loads a thread issues (one per partial) are all in flight
@@ -822,12 +862,25 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(AttnParams p) {
   const int li = lh / p.H;
   const int h = lh - li * p.H;
   const int qrow = qb_idx * kQueryTile + row;
-  constexpr int kMaxParts = 4;                         // partials fetched per round
   constexpr int kSegGroup = 64;                        // segments whose records are listed at a time
   __shared__ uint32_t rec_list[kSegGroup * kSegRecs];
   __shared__ int n_list;
   float4 acc = {0.f, 0.f, 0.f, 0.f};
   float l = 0.f, mt = -INFINITY;
+  if (p.rec_table_on) {
+    // table of the item's records: no list to build, every thread walks the same few entries
+    const int n = p.rec_count[qb_idx];
+    if (n == kWholeItem || qrow >= p.M) return;
+    for (int i0 = 0; i0 < n; i0 += kMaxParts) {
+      uint32_t recs[kMaxParts];
+#pragma unroll
+      for (int j = 0; j < kMaxParts; ++j) {
+        const uint32_t e = p.rec_table[qb_idx][min(i0 + j, n - 1)];
+        recs[j] = (uint32_t)((kSegRecs * (hp * p.cpp + (int)(e & 255u)) + (int)(e >> 8)) * 2 + set);
+      }
+      combine_round(p, recs, min(kMaxParts, n - i0), row, piece, acc, l, mt);
+    }
+  } else
   for (int sg0 = 0; sg0 < p.NS; sg0 += kSegGroup) {
     // The first wave lists the records that hold pieces of this item (integer divisions, done once).
     // With a table of chunk starts, lane l holds the start of the head pair's chunk l and one ballot
@@ -869,32 +922,12 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(AttnParams p) {
     if (n_list < 0) return;
     const int n = n_list;
     if (qrow < p.M)
-    for (int i0 = 0; i0 < n; i0 += kMaxParts) {
-      float m[kMaxParts], lp[kMaxParts];
-      float4 o[kMaxParts];
+      for (int i0 = 0; i0 < n; i0 += kMaxParts) {
+        uint32_t recs[kMaxParts];
 #pragma unroll
-      for (int j = 0; j < kMaxParts; ++j) {
-        const float* rec = p.ws + (size_t)rec_list[min(i0 + j, n - 1)] * kPartialFloats;
-        m[j] = rec[kQueryTile * 64 + row];
-        lp[j] = rec[kQueryTile * 64 + kQueryTile + row];
-        o[j] = *(const float4*)(rec + row * 64 + piece * 4);
+        for (int j = 0; j < kMaxParts; ++j) recs[j] = rec_list[min(i0 + j, n - 1)];
+        combine_round(p, recs, min(kMaxParts, n - i0), row, piece, acc, l, mt);
       }
-      float mn = mt;
-#pragma unroll
-      for (int j = 0; j < kMaxParts; ++j)
-        if (i0 + j < n) mn = fmaxf(mn, m[j]);
-      const float rs = __builtin_amdgcn_exp2f(mt - mn);  // 0 in the first round (mt = -inf)
-      acc.x *= rs; acc.y *= rs; acc.z *= rs; acc.w *= rs;
-      l *= rs;
-      mt = mn;
-#pragma unroll
-      for (int j = 0; j < kMaxParts; ++j)
-        if (i0 + j < n) {
-          const float w = __builtin_amdgcn_exp2f(m[j] - mt);
-          l += lp[j] * w;
-          acc.x += o[j].x * w; acc.y += o[j].y * w; acc.z += o[j].z * w; acc.w += o[j].w * w;
-        }
-    }
   }
   if (qrow >= p.M) return;
   const float inv = 1.0f / l;
@@ -996,6 +1029,29 @@ static bool plan_balanced_chunks(AttnParams& p, int cpp) {
   if (covered != (long)QB * T) return false;
   p.NS = NS; p.L0 = L0; p.PP = QB * T; p.cpp = cpp;
   for (int c = 0; c <= cpp; ++c) p.cstart[c] = cs[c];
+  // which records hold the pieces of query block qb: the same in every head pair
+  p.rec_table_on = 0;
+  if (QB <= kMaxTableItems) {
+    bool ok = true;
+    for (int qb = 0; qb < QB && ok; ++qb) {
+      int n = 0;
+      for (int sg = 0; sg < NS && ok; ++sg) {
+        const int seg0 = sg * L0, len = (sg == NS - 1 ? T : seg0 + L0) - seg0;
+        const int ua = QB * seg0 + qb * len, ub = ua + len - 1;
+        const int cf = chunk_of_unit(p, ua), cl = chunk_of_unit(p, ub);
+        if (NS == 1 && cf == cl) { n = kWholeItem; break; }
+        const int combo = sg * QB + qb;
+        for (int c = cf; c <= cl; ++c) {
+          if (cs[c] >= cs[c + 1]) continue;
+          const int ord = NS == 1 ? (cs[c] < ua ? 1 : 0) : combo - decode_unit(cs[c], T, QB, NS, L0, QB * T).combo;
+          if (n == kMaxTableRecs || ord < 0 || ord >= kSegRecs) { ok = false; break; }
+          p.rec_table[qb][n++] = (uint16_t)(c + 256 * ord);
+        }
+      }
+      p.rec_count[qb] = (uint8_t)n;
+    }
+    p.rec_table_on = ok ? 1 : 0;
+  }
   return true;
 }
 
@@ -1030,6 +1086,7 @@ static hipError_t plan_attn(AttnParams& p, const Geom& g, int nl, int n_total, s
   p.total_units = ((p.LH + 1) / 2) * p.PP;
   p.rounds = 1;
   p.cpp = 0;
+  p.rec_table_on = 0;
   const int pairs = (p.LH + 1) / 2;
   // one launch round and the workgroups divide evenly among the head pairs: chunks of equal cost
   if (n_wgs % pairs == 0 && plan_balanced_chunks(p, n_wgs / pairs)) {
@@ -1049,6 +1106,7 @@ static hipError_t plan_attn(AttnParams& p, const Geom& g, int nl, int n_total, s
         p.chunk = 0;
       } else {
         p.cpp = 0;
+        p.rec_table_on = 0;
         p.chunk = (p.QB * p.T + per_xcd - 1) / per_xcd;
         p.NS = (p.T + p.chunk - 1) / p.chunk;
         p.L0 = p.chunk;
@@ -1072,6 +1130,7 @@ bool attn_plan_stats(const Geom& g, int nl, int n_total, int n_wgs, size_t ws_by
   const int pairs = (p.LH + 1) / 2;
   const long n_chunks = (long)p.rounds * n_wgs;
   std::vector<uint8_t> seen((size_t)pairs * p.QB * p.T, 0);
+  std::vector<int> table_refs((size_t)pairs * p.QB, 0);                  // partial pieces seen per item
   st->n_wgs = n_wgs; st->rounds = p.rounds; st->segments = p.NS; st->balanced = p.cpp > 0 ? 1 : 0;
   st->pieces_max = 0; st->tiles_min = 0x7FFFFFFF; st->tiles_max = 0; st->cost_max = 0.f; st->cost_mean = 0.f;
   for (int w = 0; w < n_wgs; ++w) {
@@ -1081,7 +1140,8 @@ bool attn_plan_stats(const Geom& g, int nl, int n_total, int n_wgs, size_t ws_by
       long u = chunk_first_unit(p, c);
       const long u_end = chunk_first_unit(p, c + 1);
       if (u > u_end || u_end > p.total_units) return false;
-      int partial = 0;
+      int partial = 0, n_piece = 0;
+      const long u_begin = u;
       while (u < u_end) {
         const UnitPos up = decode_unit(u, p.T, p.QB, p.NS, p.L0, p.PP);
         if (!up.valid) break;
@@ -1095,6 +1155,17 @@ bool attn_plan_stats(const Geom& g, int nl, int n_total, int n_wgs, size_t ws_by
           cell = 1;
         }
         if (!full && chunk_of_unit(p, u) != c) return false;          // the merge pass must find this chunk again
+        const int rec_ord = p.NS == 1 ? (u == u_begin ? 0 : 1) : n_piece;
+        ++n_piece;
+        if (p.rec_table_on) {                                           // ... and the table must list this record once
+          const int cnt = p.rec_count[up.qb];
+          int hits = 0;
+          if (cnt != kWholeItem)
+            for (int k = 0; k < cnt; ++k)
+              if (p.rec_table[up.qb][k] == (uint16_t)((c - up.hp * p.cpp) + 256 * rec_ord)) ++hits;
+          if (hits != (full ? 0 : 1)) return false;
+          if (!full) ++table_refs[(size_t)up.hp * p.QB + up.qb];
+        }
         tiles += t1 - t0; ++pieces_wg;
         u += t1 - t0;
       }
@@ -1111,6 +1182,11 @@ bool attn_plan_stats(const Geom& g, int nl, int n_total, int n_wgs, size_t ws_by
   (void)n_chunks;
   for (uint8_t v : seen)
     if (!v) return false;
+  if (p.rec_table_on)                                                     // no entry that no piece wrote
+    for (size_t i = 0; i < table_refs.size(); ++i) {
+      const int cnt = p.rec_count[i % p.QB];
+      if (table_refs[i] != (cnt == kWholeItem ? 0 : cnt)) return false;
+    }
   return true;
 }
 
