@@ -247,26 +247,44 @@ __device__ inline void radix_pass(SelShared& sh, int n_iter, uint32_t rank, Digi
   pick_digit(sh, rank);
 }
 
+// One bit per register-resident key of a thread.  Indices are compile-time constants once the loops
+// over the keys are unrolled, so the words stay in registers.
+template <int N>
+struct KeyBits {
+  uint32_t w[(N + 31) / 32];
+  __device__ inline void clear() {
+#pragma unroll
+    for (int i = 0; i < (N + 31) / 32; ++i) w[i] = 0u;
+  }
+  __device__ inline bool test(int c) const { return (w[c >> 5] >> (c & 31)) & 1u; }
+  __device__ inline void set(int c) { w[c >> 5] |= 1u << (c & 31); }
+  __device__ inline void reset(int c) { w[c >> 5] &= ~(1u << (c & 31)); }
+  __device__ inline void merge(const KeyBits& o) {
+#pragma unroll
+    for (int i = 0; i < (N + 31) / 32; ++i) w[i] |= o.w[i];
+  }
+};
+
 // Light pass for keys held in registers: `cand` has a bit per key of this thread that is still a
 // candidate (usually few after the first pass).  Each candidate is first settled against the digit
 // the previous pass chose (prev_of(c) below it: evicted; not equal: no candidate any more), the
 // rest are counted by digit_of(c).  Counts go to one 256-bin histogram per wave with LDS atomics (a
 // wave's lanes can collide on a bin, which costs at most 64 turns per instruction whatever the
 // data; no clearing and column-summing of the big per-lane histogram).
-template <int KPT, typename Mask, typename PrevOf, typename DigitOf>
-__device__ inline void radix_pass_light(SelShared& sh, Mask& cand, Mask& evm, uint32_t prev_chosen, uint32_t rank,
-                                        PrevOf prev_of, DigitOf digit_of) {
+template <int KPT, typename PrevOf, typename DigitOf>
+__device__ inline void radix_pass_light(SelShared& sh, KeyBits<KPT>& cand, KeyBits<KPT>& evm, uint32_t prev_chosen,
+                                        uint32_t rank, PrevOf prev_of, DigitOf digit_of) {
   const int tid = threadIdx.x, wave = tid >> 6;
   uint32_t* flat = &sh.hist[0][0];                    // [wave][256], over the column histogram's storage
   for (int i = tid; i < kSelWaves * 256; i += kSelThreads) flat[i] = 0u;
   __syncthreads();
 #pragma unroll
   for (int c = 0; c < KPT; ++c)
-    if ((cand >> c) & (Mask)1) {
+    if (cand.test(c)) {
       const uint32_t pv = (uint32_t)prev_of(c);
       if (pv != prev_chosen) {
-        cand &= ~((Mask)1 << c);
-        if (pv < prev_chosen) evm |= (Mask)1 << c;
+        cand.reset(c);
+        if (pv < prev_chosen) evm.set(c);
       } else {
         atomicAdd(&flat[wave * 256 + digit_of(c)], 1u);
       }
@@ -308,23 +326,33 @@ __device__ inline void select_phase(SelShared& sh, const Geom& g, const float* s
     return 0xFFFFFFFFu - ids[i < n_total ? i : n_total - 1];
   };
   if constexpr (KPT > 0) {
-    // every load is unconditional (indices are clamped), so all of them are in flight together
-    uint8_t fl[KPT];
-    float sv[KPT];
+    // every load is unconditional (indices are clamped), so a batch of them is in flight together
+    constexpr int kBatch = KPT <= 20 ? KPT : 18;
 #pragma unroll
-    for (int c = 0; c < KPT; ++c) {
-      const int i = c * kSelThreads + tid;
-      const int ic = i < n_total ? i : n_total - 1;
-      fl[c] = flags[ic];
-      sv[c] = ss[ic];
-      if constexpr (IDREG) kid[c] = ids[ic];
-    }
+    for (int c0 = 0; c0 < KPT; c0 += kBatch) {
+      uint8_t fl[kBatch];
+      float sv[kBatch];
 #pragma unroll
-    for (int c = 0; c < KPT; ++c) {
-      const int i = c * kSelThreads + tid;
-      const uint32_t w = score_word(sv[c], &bad);
-      kw[c] = (i >= n_total || fl[c] != 0) ? kNotEvictable : w;
-      if constexpr (IDREG) kid[c] = 0xFFFFFFFFu - kid[c];
+      for (int j = 0; j < kBatch; ++j) {
+        const int c = c0 + j;
+        if (c < KPT) {
+          const int i = c * kSelThreads + tid;
+          const int ic = i < n_total ? i : n_total - 1;
+          fl[j] = flags[ic];
+          sv[j] = ss[ic];
+          if constexpr (IDREG) kid[c] = ids[ic];
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < kBatch; ++j) {
+        const int c = c0 + j;
+        if (c < KPT) {
+          const int i = c * kSelThreads + tid;
+          const uint32_t w = score_word(sv[j], &bad);
+          kw[c] = (i >= n_total || fl[j] != 0) ? kNotEvictable : w;
+          if constexpr (IDREG) kid[c] = 0xFFFFFFFFu - kid[c];
+        }
+      }
     }
   }
   auto word = [&](int c) -> uint32_t { if constexpr (KPT > 0) return kw[c]; else return load_word(c); };
@@ -347,20 +375,20 @@ __device__ inline void select_phase(SelShared& sh, const Geom& g, const float* s
     // with the threshold on every digit seen so far) and `evm` (keys already known to go).  The
     // first pass looks at every key (most share a handful of leading digits: per-lane histogram
     // columns); after it only the candidates are touched, and in the end the masks are the answer.
-    using Mask = typename std::conditional<(KPT <= 32), uint32_t, uint64_t>::type;
-    Mask cand = 0, evm = 0;
+    KeyBits<KPT> cand, evm;
+    cand.clear(); evm.clear();
 #pragma unroll
     for (int c = 0; c < KPT; ++c)
-      if (kw[c] != kNotEvictable) cand |= (Mask)1 << c;
+      if (kw[c] != kNotEvictable) cand.set(c);
     // settles the candidates against the digit the last pass chose: below it goes, above it stays
     auto narrow = [&](auto digit_of) {
       const uint32_t chosen = sh.digit;
 #pragma unroll
       for (int c = 0; c < KPT; ++c)
-        if ((cand >> c) & (Mask)1) {
+        if (cand.test(c)) {
           const uint32_t dg = (uint32_t)digit_of(c);
-          if (dg < chosen) evm |= (Mask)1 << c;
-          if (dg != chosen) cand &= ~((Mask)1 << c);
+          if (dg < chosen) evm.set(c);
+          if (dg != chosen) cand.reset(c);
         }
     };
     uint32_t chosen = 0;                               // digit of the last pass (its candidates are settled by the next one)
@@ -382,7 +410,7 @@ __device__ inline void select_phase(SelShared& sh, const Geom& g, const float* s
 #pragma nounroll
     for (; pass < 4 && !done && !budget_error; ++pass) {
       const int shift = 24 - 8 * pass;
-      radix_pass_light<KPT, Mask>(sh, cand, evm, chosen, rank,
+      radix_pass_light<KPT>(sh, cand, evm, chosen, rank,
                                   [&](int c) -> int { return (int)((kw[c] >> (shift + 8)) & 255u); },
                                   [&](int c) -> int { return (int)((kw[c] >> shift) & 255u); });
       chosen = sh.digit;
@@ -398,11 +426,11 @@ __device__ inline void select_phase(SelShared& sh, const Geom& g, const float* s
       for (int p2 = 0; p2 < 4 && !done; ++p2) {
         const int shift = 24 - 8 * p2;
         if (p2 == 0)
-          radix_pass_light<KPT, Mask>(sh, cand, evm, chosen, rank,
+          radix_pass_light<KPT>(sh, cand, evm, chosen, rank,
                                       [&](int c) -> int { return (int)(kw[c] & 255u); },
                                       [&](int c) -> int { return (int)(idw(c) >> 24); });
         else
-          radix_pass_light<KPT, Mask>(sh, cand, evm, chosen, rank,
+          radix_pass_light<KPT>(sh, cand, evm, chosen, rank,
                                       [&](int c) -> int { return (int)((idw(c) >> (shift + 8)) & 255u); },
                                       [&](int c) -> int { return (int)((idw(c) >> shift) & 255u); });
         chosen = sh.digit;
@@ -419,8 +447,8 @@ __device__ inline void select_phase(SelShared& sh, const Geom& g, const float* s
       else narrow([&](int c) -> int { return (int)((kw[c] >> last_shift) & 255u); });
       (void)chosen;
     }
-    if (done) evm |= cand;
-    if (budget_error) evm = 0;
+    if (done) evm.merge(cand);
+    if (budget_error) evm.clear();
     if (bad) sh.bad = 1;
     TSTAMP(10);
     // evict bit per slot, published in slot order: the ballot of one chunk over one wave covers 64
@@ -428,7 +456,7 @@ __device__ inline void select_phase(SelShared& sh, const Geom& g, const float* s
 #pragma unroll
     for (int c = 0; c < KPT; ++c)
       if (c < n_chunks) {
-        const uint64_t bl = __ballot((evm >> c) & 1ull);
+        const uint64_t bl = __ballot(evm.test(c));
         if (lane == 0) {
           sh.evmap[(c * kSelThreads >> 5) + 2 * wave] = (uint32_t)bl;
           sh.evmap[(c * kSelThreads >> 5) + 2 * wave + 1] = (uint32_t)(bl >> 32);
@@ -738,8 +766,8 @@ static void launch_variant(const Geom& g, const SmoothParams& sm, const HybridPa
   // the variant only matters when a selection will run (n_total > B)
   if (n_total <= g.B || n_chunks <= 8) OVGGT_SEL_LAUNCH(8, true);
   else if (n_chunks <= 20) OVGGT_SEL_LAUNCH(20, true);
-  else if (n_chunks <= 36) OVGGT_SEL_LAUNCH(36, true);
-  else OVGGT_SEL_LAUNCH(0, false);
+  else if (n_chunks <= 36) OVGGT_SEL_LAUNCH(36, false);      // ids stay in memory: fetched only for keys whose equal scores straddle the threshold
+  else OVGGT_SEL_LAUNCH(0, false);                           // (72 keys per thread in registers measured slower than streaming)
 #undef OVGGT_SEL_LAUNCH
 }
 
