@@ -747,15 +747,13 @@ static void launch_variant(const Geom& g, const SmoothParams& sm, const HybridPa
   // One workgroup fits a CU (the selection's register-resident keys set the footprint), so the
   // launch stays within one round of the chip: a single layer spreads its rows one per wave, a
   // batch of layers gives each workgroup several rounds of kRowsPerWave rows per wave.
-  static int n_cus = 0;
-  if (n_cus == 0) {
+  static const int n_cus = [] {                       // once per process (thread-safe initialisation)
     int dev = 0, v = 0;
     if (hipGetDevice(&dev) == hipSuccess &&
         hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
-      n_cus = v;
-    else
-      n_cus = 256;
-  }
+      return v;
+    return 256;
+  }();
   int gx = (g.M + kSelWaves - 1) / kSelWaves;
   if ((long)gx * nl > n_cus) gx = n_cus / nl > 0 ? n_cus / nl : 1;
   dim3 grid((unsigned)gx, (unsigned)nl);
