@@ -91,7 +91,7 @@ def main():
     ap.add_argument("--smooth-alpha", type=float, default=None,
                     help="activation smoothing (Eq. 6) with this alpha and a 3x3 Gaussian (sigma 1) over the patch map")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-frames", type=int, default=3)
+    ap.add_argument("--cpu-frames", type=int, default=12)
     ap.add_argument("--detail-steps", type=int, default=40, help="extra untimed steps with per-kernel events")
     ap.add_argument("--flatness", action="store_true",
                     help="also bracket every 8th timed step with events and report the slope of step latency over the stream")
