@@ -8,9 +8,8 @@
 // instead of re-read from the whole cache (O(B) rows).
 //   centroid_update_kernel   the per-frame maintenance, after the selection
 //   centroid_rebuild_kernel  the same sum from nothing, after a cache import
-//   diversity_kernel  the HBM-bound pass over the layer's K cache, one wave per history slot: dot(k_i, c), |k_i|^2 and |c|^2 as fp32 balanced
-//                     trees over the concatenated index h*d + e (lane l owns E consecutive
-//                     elements, pairwise sums in registers, then six xor-butterfly steps), then
+//   diversity_kernel  the HBM-bound pass over the layer's K cache: dot(k_i, c), |k_i|^2 and |c|^2 as
+//                     fp32 balanced trees over the concatenated index h*d + e, then
 //                     d_i = 1 - dot / (sqrt(|k_i|^2) * sqrt(|c|^2)), written to the layer's d_i array.
 // The selection kernel min-max normalises these and blends them with the new frame's scores.
 #include "ovggt_internal.h"
@@ -24,7 +23,6 @@ constexpr int kCenUnroll = 8;                 // 16-byte loads a thread keeps in
 constexpr int kCenMaxAdds = 64;               // 64 * 2^24 < 2^31
 constexpr int kDivThreads = 256;
 constexpr int kDivWaves = kDivThreads / 64;
-constexpr int kDivRows = 8;                   // slots per wave and round (independent loads in flight together); 1 for very wide keys
 
 __device__ inline void unpack_halfs(const uint4& w, float f[8]) {
   const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
@@ -150,128 +148,116 @@ centroid_update_kernel(Geom g, char* kv, char* meta, int layer0, int n_total, in
                   });
 }
 
-constexpr int div_rows(int e) { return e >= 32 ? 1 : (e == 16 ? 4 : kDivRows); }   // keeps a round's keys in registers
-
 // ---- pass 2: d_i per history slot ----------------------------------------------------------------
-// Sum over the wave of one value per lane, as the balanced tree that pairs lanes differing in bit 0,
-// then bit 1, ... bit 5.  After each level all lanes of a group hold the group's sum, so the partner
-// may be any lane of the sibling group: quad permutes, the two row mirrors and the two lane-swap
-// instructions reach one without going through the LDS crossbar.
+// A wave takes 8 consecutive slots.  For every head one load instruction fetches the 8 slots' rows,
+// 1 KiB of consecutive memory (the cache is head-major: a slot's key is H rows 2 MB apart, and
+// pieces shorter than this made the pass latency- rather than bandwidth-bound): lane l holds the
+// 16-byte piece l & 7 of slot l >> 3.  The balanced tree over the concatenated index h*64 + e
+// (zero-padded to a power of two) is evaluated as: a pairwise tree over the lane's 8 elements, three
+// butterfly steps over the 8 lanes of a slot (quad permutes and the half-row mirror: after each
+// step all lanes of a group hold the group's sum, so any lane of the sibling group is a valid
+// partner), and a tree over the heads folded in as they arrive (a binary counter of partial sums).
 __device__ inline float dpp_f(float v, int ctrl_is) {
-  // ctrl_is: 0 quad [1,0,3,2], 1 quad [2,3,0,1], 2 row half mirror, 3 row mirror
+  // ctrl_is: 0 quad [1,0,3,2], 1 quad [2,3,0,1], 2 row half mirror
   const int x = __float_as_int(v);
   int y;
   switch (ctrl_is) {
     case 0: y = __builtin_amdgcn_update_dpp(0, x, 0xB1, 0xF, 0xF, false); break;
     case 1: y = __builtin_amdgcn_update_dpp(0, x, 0x4E, 0xF, 0xF, false); break;
-    case 2: y = __builtin_amdgcn_update_dpp(0, x, 0x141, 0xF, 0xF, false); break;
-    default: y = __builtin_amdgcn_update_dpp(0, x, 0x140, 0xF, 0xF, false); break;
+    default: y = __builtin_amdgcn_update_dpp(0, x, 0x141, 0xF, 0xF, false); break;
   }
   return __int_as_float(y);
 }
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-__device__ inline float wave_tree_sum(float v) {
+__device__ inline float tree8_lanes8(const float (&p)[8]) {
+  float v = ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
   v = v + dpp_f(v, 0);
   v = v + dpp_f(v, 1);
   v = v + dpp_f(v, 2);
-  v = v + dpp_f(v, 3);
-  const u32x2 a = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
-  v = __uint_as_float(a[0]) + __uint_as_float(a[1]);
-  const u32x2 b = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
-  return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+  return v;
 }
+constexpr int ilog2(int x) { return x <= 1 ? 0 : 1 + ilog2(x / 2); }
 
-template <int E>
-__device__ inline float tree64(float p[E]) {
+// dot(k, c) and |k|^2 of the 8 slots of a wave; key_of(h, k8) delivers the lane's 8 elements of head h
+// (h < H).  cs: the centroid in LDS, H*64 floats.  Every lane of a slot's group returns the slot's sums.
+template <int HP, typename KeyOf>
+__device__ inline void slot_sums(const float* cs, int piece, int H, KeyOf key_of, float* dot, float* nk) {
+#pragma clang fp contract(off)
+  constexpr int LV = ilog2(HP);
+  float sd[LV + 1], sn[LV + 1];
+  float vd = 0.f, vn = 0.f;
 #pragma unroll
-  for (int w = 1; w < E; w *= 2)
+  for (int h = 0; h < HP; ++h) {
+    vd = 0.f; vn = 0.f;                                // heads beyond H are the tree's zero padding
+    if (h < H) {
+      float k8[8];
+      key_of(h, k8);
+      const float4 c0 = *(const float4*)(cs + h * 64 + piece * 8), c1 = *(const float4*)(cs + h * 64 + piece * 8 + 4);
+      const float cc[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
+      float p[8], q[8];
 #pragma unroll
-    for (int j = 0; j < E; j += 2 * w) p[j] = p[j] + p[j + w];
-  return wave_tree_sum(p[0]);
-}
-
-// the lane's E key elements of one slot: elements [E*lane, E*lane + E) of the concatenated key,
-// which lie inside one head row because E divides 64
-template <int E>
-__device__ inline void load_key(const char* K, const Geom& g, int slot, int lane, bool live, float k[E]) {
-  const int j0 = E * lane, h = j0 >> 6, e0 = j0 & 63;
-  const char* p = K + ((size_t)h * g.cap + slot) * 128 + e0 * 2;
-  if (!live) {
+      for (int i = 0; i < 8; ++i) { p[i] = k8[i] * cc[i]; q[i] = k8[i] * k8[i]; }
+      vd = tree8_lanes8(p);
+      vn = tree8_lanes8(q);
+    }
 #pragma unroll
-    for (int j = 0; j < E; ++j) k[j] = 0.f;
-    return;
+    for (int lvl = 0; lvl < LV; ++lvl) {
+      if ((h >> lvl) & 1) { vd = sd[lvl] + vd; vn = sn[lvl] + vn; }
+      else { sd[lvl] = vd; sn[lvl] = vn; break; }
+    }
   }
-  if constexpr (E >= 8) {
-#pragma unroll
-    for (int j = 0; j < E; j += 8) unpack_halfs(*(const uint4*)(p + 2 * j), k + j);
-  } else if constexpr (E == 4) {
-    const uint2 w = *(const uint2*)p;
-    const __half2 a = *(const __half2*)&w.x, b = *(const __half2*)&w.y;
-    k[0] = __low2float(a); k[1] = __high2float(a); k[2] = __low2float(b); k[3] = __high2float(b);
-  } else if constexpr (E == 2) {
-    const uint32_t w = *(const uint32_t*)p;
-    const __half2 a = *(const __half2*)&w;
-    k[0] = __low2float(a); k[1] = __high2float(a);
-  } else {
-    k[0] = __half2float(*(const __half*)p);
-  }
+  *dot = vd; *nk = vn;
 }
 
-template <int E, int R>
+constexpr int kDivHeadBatch = 16;              // head rows of a round requested together (64 registers)
+
+template <int HP>
 __global__ void __launch_bounds__(kDivThreads)
 diversity_kernel(Geom g, char* kv, char* meta, int layer0, int n_hist) {
 #pragma clang fp contract(off)
+  __shared__ float cs[HP * 64];
   const int layer = layer0 + blockIdx.y;
   char* mb = layer_meta(meta, g, layer);
   const uint8_t* flags = (const uint8_t*)(mb + g.off_flags);
-  const float* cvec = (const float*)(mb + g.off_cvec);
+  const float* cvec = (const float*)(mb + g.off_cvec);   // the fp32 centroid the frame's append left
   float* dval = (float*)(mb + g.off_dval);
   const char* K = layer_k(kv, g, layer);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const bool live = E * lane < g.H * 64;             // lanes past the key's width hold the tree's zero padding
-  const int n_waves = blockDim.x >> 6;
-  const int stride = gridDim.x * n_waves * R;
-  int s0 = (blockIdx.x * n_waves + wave) * R;
-  if (s0 >= n_hist) return;
+  const int sl = lane >> 3, piece = lane & 7;
+  const int H = g.H;
+  for (int i = threadIdx.x; i < H * 64; i += kDivThreads) cs[i] = cvec[i];
+  __syncthreads();
 
-  // the first round's keys are requested before the centroid is unpacked
-  float k[R][E];
-  uint8_t fl;                                         // lane r < R: the flag of the round's r-th slot
+  // |c|^2 by the same tree (the centroid plays the key)
+  float nc, unused;
+  slot_sums<HP>(cs, piece, H, [&](int h, float (&k8)[8]) {
 #pragma unroll
-  for (int r = 0; r < R; ++r) load_key<E>(K, g, min(s0 + r, n_hist - 1), lane, live, k[r]);
-  fl = flags[min(s0 + min(lane, R - 1), n_hist - 1)];
+    for (int i = 0; i < 8; ++i) k8[i] = cs[h * 64 + piece * 8 + i];
+  }, &nc, &unused);
+  const float root_nc = __builtin_sqrtf(nc);
 
-  float c[E], t[E];
+  const int stride = gridDim.x * kDivWaves * 8;
+  for (int s0 = (blockIdx.x * kDivWaves + wave) * 8; s0 < n_hist; s0 += stride) {
+    const int slot = s0 + sl;
+    const int sc = min(slot, n_hist - 1);
+    const uint8_t fl = flags[sc];
+    const char* row0 = K + (size_t)sc * 128 + piece * 16;
+    float dot, nk;
+    if constexpr (HP <= kDivHeadBatch) {
+      uint4 w[HP];
 #pragma unroll
-  for (int j = 0; j < E; ++j) {
-    c[j] = live ? cvec[E * lane + j] : 0.f;      // the fp32 centroid the frame's append left
-    t[j] = c[j] * c[j];
-  }
-  const float root_nc = __builtin_sqrtf(tree64<E>(t));
-
-  for (;;) {
-    // every lane ends up with the sums of all R slots; lane r keeps those of slot r and finishes it,
-    // so the square roots and the division run once per round, not once per slot
-    float dot = 0.f, nk = 0.f;
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-      float p[E], q[E];
-#pragma unroll
-      for (int j = 0; j < E; ++j) { p[j] = k[r][j] * c[j]; q[j] = k[r][j] * k[r][j]; }
-      const float dr = tree64<E>(p), nr = tree64<E>(q);
-      if (lane == r) { dot = dr; nk = nr; }
+      for (int h = 0; h < HP; ++h)
+        if (h < H) w[h] = *(const uint4*)(row0 + (size_t)h * g.cap * 128);
+      slot_sums<HP>(cs, piece, H, [&](int h, float (&k8)[8]) { unpack_halfs(w[h], k8); }, &dot, &nk);
+    } else {
+      slot_sums<HP>(cs, piece, H, [&](int h, float (&k8)[8]) {
+        unpack_halfs(*(const uint4*)(row0 + (size_t)h * g.cap * 128), k8);
+      }, &dot, &nk);
     }
-    const int slot = s0 + lane;
-    if (lane < R && slot < n_hist && fl == 0) {
+    if (piece == 0 && slot < n_hist && fl == 0) {
       const float den = __builtin_sqrtf(nk) * root_nc;
       const float cosv = den == 0.f ? 0.f : dot / den;
       dval[slot] = 1.0f - cosv;
     }
-    s0 += stride;
-    if (s0 >= n_hist) break;
-#pragma unroll
-    for (int r = 0; r < R; ++r) load_key<E>(K, g, min(s0 + r, n_hist - 1), lane, live, k[r]);
-    fl = flags[min(s0 + min(lane, R - 1), n_hist - 1)];
   }
 }
 
@@ -310,17 +296,16 @@ hipError_t launch_centroid_protect(const Geom& g, char* kv, char* meta, int laye
 
 hipError_t launch_diversity(const Geom& g, char* kv, char* meta, int layer0, int nl, int n_hist, hipStream_t s) {
   if (n_hist <= 0) return hipSuccess;
-  int width = 64;
-  while (width < g.H * 64) width *= 2;
-  const int E = width / 64;
-  const int per_wg = kDivWaves * div_rows(E);
+  int hp = 1;
+  while (hp < g.H) hp *= 2;
+  const int per_wg = kDivWaves * 8;
   long gx = (n_hist + per_wg - 1) / per_wg;
-  const long cap_x = 2048 / nl > 0 ? 2048 / nl : 1;
+  const long cap_x = 4096 / nl > 0 ? 4096 / nl : 1;
   if (gx > cap_x) gx = cap_x;
   dim3 dgrid((unsigned)gx, (unsigned)nl);
-#define OVGGT_DIV_LAUNCH(EE) \
-  hipLaunchKernelGGL((diversity_kernel<EE, div_rows(EE)>), dgrid, dim3(kDivThreads), 0, s, g, kv, meta, layer0, n_hist)
-  switch (E) {
+#define OVGGT_DIV_LAUNCH(HH) \
+  hipLaunchKernelGGL(diversity_kernel<HH>, dgrid, dim3(kDivThreads), 0, s, g, kv, meta, layer0, n_hist)
+  switch (hp) {
     case 1: OVGGT_DIV_LAUNCH(1); break;
     case 2: OVGGT_DIV_LAUNCH(2); break;
     case 4: OVGGT_DIV_LAUNCH(4); break;
