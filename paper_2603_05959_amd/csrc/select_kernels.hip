@@ -149,7 +149,9 @@ __device__ inline void smooth_new_scores(const SmoothParams& sm, int M, float* k
 
 // ---- phase 2 helpers ---------------------------------------------------------
 struct SelShared {
-  uint32_t hist[128][64];          // two 16-bit bins per word, one column per lane id
+  uint32_t hist[256][64];          // one column per lane id; rows 0..127 are cleared and read (streaming passes pack
+                                   // two 16-bit bins per word there), rows above only absorb the marker word
+  uint32_t wave_hist[kSelWaves][256];   // later passes over register-resident keys; zero between uses
   uint32_t cnt[256];
   uint32_t evmap[kMaxSelChunks * kSelThreads / 32];   // evict bit per slot, slot order
   uint32_t scan_tmp[2][kSelWaves];
@@ -196,10 +198,11 @@ __device__ inline void pick_digit(SelShared& sh, uint32_t rank) {
   __syncthreads();
 }
 
-// One radix pass over the candidates: histogram of an 8-bit digit, then the
-// digit whose bucket holds the rank-th smallest candidate.  Results in sh.digit
-// / sh.rank / sh.bucket (and sh.n_evictable = number of candidates).
-template <int KPT, typename DigitOf>
+// One radix pass of the streaming selection (keys re-read from memory): histogram of an 8-bit digit
+// of the candidates (digit_of(chunk) < 0: not a candidate), then the digit whose bucket holds the
+// rank-th smallest candidate.  Results in sh.digit / sh.rank / sh.bucket (and sh.n_evictable =
+// number of candidates).
+template <typename DigitOf>
 __device__ inline void radix_pass(SelShared& sh, int n_iter, uint32_t rank, DigitOf digit_of, uint32_t* ts = nullptr) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   for (int i = tid; i < 128 * 64; i += kSelThreads) (&sh.hist[0][0])[i] = 0u;
@@ -207,22 +210,14 @@ __device__ inline void radix_pass(SelShared& sh, int n_iter, uint32_t rank, Digi
 #ifdef OVGGT_TRACE
   if (ts && tid == 0) ts[0] = (uint32_t)wall_clock64();
 #endif
-  if constexpr (KPT > 0) {
+  // digits of 8 chunks are fetched together so their loads overlap
+  for (int c0 = 0; c0 < n_iter; c0 += 8) {
+    int dg[8];
 #pragma unroll
-    for (int c = 0; c < KPT; ++c) {
-      const int dg = digit_of(c);                     // < 0: not a candidate
-      if (dg >= 0) atomicAdd(&sh.hist[dg >> 1][lane], 1u << (16 * (dg & 1)));
-    }
-  } else {
-    // streaming: digits of 8 chunks are fetched together so their loads overlap
-    for (int c0 = 0; c0 < n_iter; c0 += 8) {
-      int dg[8];
+    for (int j = 0; j < 8; ++j) dg[j] = c0 + j < n_iter ? digit_of(c0 + j) : -1;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) dg[j] = c0 + j < n_iter ? digit_of(c0 + j) : -1;
-#pragma unroll
-      for (int j = 0; j < 8; ++j)
-        if (dg[j] >= 0) atomicAdd(&sh.hist[dg[j] >> 1][lane], 1u << (16 * (dg[j] & 1)));
-    }
+    for (int j = 0; j < 8; ++j)
+      if (dg[j] >= 0) atomicAdd(&sh.hist[dg[j] >> 1][lane], 1u << (16 * (dg[j] & 1)));
   }
   __syncthreads();
 #ifdef OVGGT_TRACE
@@ -239,6 +234,40 @@ __device__ inline void radix_pass(SelShared& sh, int n_iter, uint32_t rank, Digi
     s += __shfl_xor(s, 1, 64);
     s += __shfl_xor(s, 2, 64);
     if (quarter == 0) sh.cnt[bin] = s;
+  }
+  __syncthreads();
+#ifdef OVGGT_TRACE
+  if (ts && tid == 0) ts[2] = (uint32_t)wall_clock64();
+#endif
+  pick_digit(sh, rank);
+}
+
+// First pass over register-resident keys: every key of the thread is counted by its leading byte
+// into the per-lane-column histogram, which the workgroup cleared when the kernel started.  Real
+// score words are non-negative floats, so their leading byte is below 128; the word that marks a
+// protected or absent slot has 255 and lands in a row that nobody clears or reads -- no test per key.
+template <int KPT>
+__device__ inline void first_pass_registers(SelShared& sh, const uint32_t (&kw)[KPT > 0 ? KPT : 1], uint32_t rank, uint32_t* ts) {
+  const int tid = threadIdx.x, lane = tid & 63;
+  uint32_t* col = &sh.hist[0][0] + lane;
+#pragma unroll
+  for (int c = 0; c < KPT; ++c) {
+    atomicAdd(col + (kw[c] >> 24) * 64u, 1u);
+  }
+  __syncthreads();
+#ifdef OVGGT_TRACE
+  if (ts && tid == 0) ts[1] = (uint32_t)wall_clock64();
+#endif
+  {   // column sums: thread -> (bin, eighth of the 64 columns); a wave's 64 reads hit 64 distinct columns
+    const int bin = tid >> 3, part = tid & 7;
+    uint32_t s = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) s += sh.hist[bin][part * 8 + ((j + (lane >> 3)) & 7)];
+    s += __shfl_xor(s, 1, 64);
+    s += __shfl_xor(s, 2, 64);
+    s += __shfl_xor(s, 4, 64);
+    if (part == 0) sh.cnt[bin] = s;
+    if (tid < 128) sh.cnt[128 + tid] = 0u;
   }
   __syncthreads();
 #ifdef OVGGT_TRACE
@@ -275,9 +304,7 @@ template <int KPT, typename PrevOf, typename DigitOf>
 __device__ inline void radix_pass_light(SelShared& sh, KeyBits<KPT>& cand, KeyBits<KPT>& evm, uint32_t prev_chosen,
                                         uint32_t rank, PrevOf prev_of, DigitOf digit_of) {
   const int tid = threadIdx.x, wave = tid >> 6;
-  uint32_t* flat = &sh.hist[0][0];                    // [wave][256], over the column histogram's storage
-  for (int i = tid; i < kSelWaves * 256; i += kSelThreads) flat[i] = 0u;
-  __syncthreads();
+  uint32_t* mine = sh.wave_hist[wave];                // zero on entry: cleared at kernel start and after every use
 #pragma unroll
   for (int c = 0; c < KPT; ++c)
     if (cand.test(c)) {
@@ -286,14 +313,14 @@ __device__ inline void radix_pass_light(SelShared& sh, KeyBits<KPT>& cand, KeyBi
         cand.reset(c);
         if (pv < prev_chosen) evm.set(c);
       } else {
-        atomicAdd(&flat[wave * 256 + digit_of(c)], 1u);
+        atomicAdd(&mine[digit_of(c)], 1u);
       }
     }
   __syncthreads();
   if (tid < 256) {
     uint32_t t = 0;
 #pragma unroll
-    for (int w = 0; w < kSelWaves; ++w) t += flat[w * 256 + tid];
+    for (int w = 0; w < kSelWaves; ++w) { t += sh.wave_hist[w][tid]; sh.wave_hist[w][tid] = 0u; }
     sh.cnt[tid] = t;
   }
   __syncthreads();
@@ -393,16 +420,14 @@ __device__ inline void select_phase(SelShared& sh, const Geom& g, const float* s
     };
     uint32_t chosen = 0;                               // digit of the last pass (its candidates are settled by the next one)
     {
-      auto digit0 = [&](int c) -> int { return kw[c] == kNotEvictable ? -1 : (int)(kw[c] >> 24); };
-      radix_pass<KPT>(sh, n_iter, rank, digit0, &ctrl->pad[20]);
+      first_pass_registers<KPT>(sh, kw, rank, &ctrl->pad[20]);
       if (sh.n_evictable < n_evict) budget_error = true;          // |P| > B
       else {
         chosen = sh.digit;
         rank = sh.rank;
         done = (rank == sh.bucket);                   // the whole bucket goes
       }
-      __syncthreads();
-      pass = 1;
+      pass = 1;                                       // (the next pass runs two barriers before it writes these again)
       TSTAMP(2);
     }
     int last_shift = 24;                               // where the last pass took its digit from
@@ -417,7 +442,6 @@ __device__ inline void select_phase(SelShared& sh, const Geom& g, const float* s
       rank = sh.rank;
       done = (rank == sh.bucket);
       last_shift = shift;
-      __syncthreads();
       TSTAMP(2 + pass);
     }
     if (!done && !budget_error) {
@@ -438,7 +462,6 @@ __device__ inline void select_phase(SelShared& sh, const Geom& g, const float* s
         done = (rank == sh.bucket);
         last_shift = shift;
         last_id = true;
-        __syncthreads();
       }
     }
     // the last pass's candidates are still unsettled
@@ -467,7 +490,7 @@ __device__ inline void select_phase(SelShared& sh, const Geom& g, const float* s
 #pragma nounroll
   for (; pass < 4 && !done; ++pass) {
     const int shift = 24 - 8 * pass;
-    radix_pass<KPT>(sh, n_iter, rank, [&](int c) -> int {
+    radix_pass(sh, n_iter, rank, [&](int c) -> int {
       const uint32_t w = word(c);
       if (w == kNotEvictable) return -1;
       if (pass > 0 && (w >> (shift + 8)) != (pre_hi >> (shift + 8))) return -1;
@@ -486,7 +509,7 @@ __device__ inline void select_phase(SelShared& sh, const Geom& g, const float* s
 #pragma nounroll
     for (int p2 = 0; p2 < 4 && !done; ++p2) {
       const int shift = 24 - 8 * p2;
-      radix_pass<KPT>(sh, n_iter, rank, [&](int c) -> int {
+      radix_pass(sh, n_iter, rank, [&](int c) -> int {
         if (word(c) != pre_hi) return -1;
         const uint32_t w = idw(c);
         if (p2 > 0 && (w >> (shift + 8)) != (pre_lo >> (shift + 8))) return -1;
@@ -529,6 +552,7 @@ __device__ inline void select_phase(SelShared& sh, const Geom& g, const float* s
   const int PP = (n_words + kSelThreads - 1) / kSelThreads;      // <= 4
   uint32_t hw[4], mw[4];
   uint32_t nh = 0, nm = 0;
+  const bool wave_has_words = wave * 64 * PP < n_words;          // the other waves only keep the barriers company
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     hw[j] = mw[j] = 0u;
@@ -545,34 +569,38 @@ __device__ inline void select_phase(SelShared& sh, const Geom& g, const float* s
       nm += __popc(mw[j]);
     }
   }
-  bool consistent;
+  bool consistent = false;
   {
     uint32_t inc_h = nh, inc_m = nm;
+    if (wave_has_words) {
 #pragma unroll
-    for (int off = 1; off < 64; off *= 2) {
-      const uint32_t yh = __shfl_up(inc_h, off, 64), ym = __shfl_up(inc_m, off, 64);
-      if (lane >= off) { inc_h += yh; inc_m += ym; }
+      for (int off = 1; off < 64; off *= 2) {
+        const uint32_t yh = __shfl_up(inc_h, off, 64), ym = __shfl_up(inc_m, off, 64);
+        if (lane >= off) { inc_h += yh; inc_m += ym; }
+      }
     }
     if (lane == 63) { sh.scan_tmp[0][wave] = inc_h; sh.scan_tmp[1][wave] = inc_m; }
     __syncthreads();
-    uint32_t base_h = 0, base_m = 0, tot_h = 0, tot_m = 0;
+    if (wave_has_words) {
+      uint32_t base_h = 0, base_m = 0, tot_h = 0, tot_m = 0;
 #pragma unroll
-    for (int w = 0; w < kSelWaves; ++w) {
-      const uint32_t th = sh.scan_tmp[0][w], tm = sh.scan_tmp[1][w];
-      if (w < wave) { base_h += th; base_m += tm; }
-      tot_h += th; tot_m += tm;
-    }
-    consistent = !budget_error && tot_h == tot_m && tot_h <= (uint32_t)g.M;
-    if (tid == 0) sh.totals[0] = tot_h;
-    if (consistent) {
-      uint32_t hp = base_h + inc_h - nh, mp = base_m + inc_m - nm;
+      for (int w = 0; w < kSelWaves; ++w) {
+        const uint32_t th = sh.scan_tmp[0][w], tm = sh.scan_tmp[1][w];
+        if (w < wave) { base_h += th; base_m += tm; }
+        tot_h += th; tot_m += tm;
+      }
+      consistent = !budget_error && tot_h == tot_m && tot_h <= (uint32_t)g.M;
+      if (tid == 0) sh.totals[0] = tot_h;
+      if (consistent) {
+        uint32_t hp = base_h + inc_h - nh, mp = base_m + inc_m - nm;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const uint32_t s0 = (uint32_t)(tid * PP + j) << 5;
-        uint32_t b = hw[j];
-        while (b) { mvdst[hp++] = s0 + (uint32_t)__builtin_ctz(b); b &= b - 1; }
-        b = mw[j];
-        while (b) { mvsrc[mp++] = s0 + (uint32_t)__builtin_ctz(b); b &= b - 1; }
+        for (int j = 0; j < 4; ++j) {
+          const uint32_t s0 = (uint32_t)(tid * PP + j) << 5;
+          uint32_t b = hw[j];
+          while (b) { mvdst[hp++] = s0 + (uint32_t)__builtin_ctz(b); b &= b - 1; }
+          b = mw[j];
+          while (b) { mvsrc[mp++] = s0 + (uint32_t)__builtin_ctz(b); b &= b - 1; }
+        }
       }
     }
   }
@@ -679,6 +707,14 @@ score_select_kernel(Geom g, SmoothParams sm, HybridParams hy, char* meta, int la
 #ifdef OVGGT_TRACE
   if (blockIdx.x == 0 && tid == 0) ctrl->pad[15] = (uint32_t)wall_clock64();
 #endif
+  // Whichever workgroup ends up running the selection wants its histograms cleared: every
+  // workgroup does that now, in the shadow of phase 1's loads.
+  if (n_total > g.B) {
+    uint4* h4 = (uint4*)&sh.hist[0][0];
+    const uint4 z = {0u, 0u, 0u, 0u};
+    h4[tid] = z; h4[tid + kSelThreads] = z;                       // rows 0..127
+    ((uint4*)&sh.wave_hist[0][0])[tid] = z;
+  }
   // ---- phase 1: scores and flags of the M new slots
   {
     const size_t row_bytes = (size_t)g.C * g.esize;
