@@ -19,6 +19,9 @@
  *    Hot-path calls only enqueue work on it and never synchronise; inputs must
  *    stay valid until the stream has executed the call.  Calls on one handle
  *    must be issued on streams that order them (normally the same stream).
+ *  - A handle keeps host-side state and is not synchronised: use it from one
+ *    thread at a time.  Different handles are independent.  The device that is
+ *    current when a handle is created must be current for every call on it.
  *  - Every function returns OVGGT_OK (0) or a negative error code.  Arguments
  *    and call order are validated on the host before anything is launched; a
  *    failed call changes no state.  Conditions only the device can see set bits

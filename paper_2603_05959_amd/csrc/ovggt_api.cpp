@@ -264,6 +264,9 @@ int ovggt_global_attn(ovggt_cache* c, int layer, const void* q, const void* k_ne
     if (prof_attn) {
       for (auto& x : ev) x = prof_event(c);
       have = ev[0] && ev[1] && ev[2];
+      if (!have)                                       // out of events: this call goes untimed
+        for (hipEvent_t x : ev)
+          if (x) c->prof_free.push_back(x);
     }
     e = launch_attn_bf16(g, c->kv, l0, nl, q, out, n + g.M, c->scale, c->ws, ws_bytes_for(c->cfg), c->n_wgs,
                          c->cfg.out_dtype == OVGGT_F32, s, have ? ev : nullptr);
@@ -479,24 +482,27 @@ int ovggt_profile_overhead(ovggt_cache* c, int reps, double* ms_mean, void* hip_
   if (!c || !ms_mean || reps < 1 || reps > 1024) return OVGGT_ERR_ARG;
   hipStream_t s = (hipStream_t)hip_stream;
   std::vector<std::pair<hipEvent_t, hipEvent_t>> ev;
+  bool failed = false;
   for (int i = 0; i < reps; ++i) {
     hipEvent_t e0 = prof_event(c), e1 = prof_event(c);
-    if (!e0 || !e1) return OVGGT_ERR_HIP;
+    bool ok = e0 && e1;
     // the same bracket as around a timed kernel, around a launch that does next to nothing
-    if (hipEventRecord(e0, s) != hipSuccess || launch_fill_zero(c->ws, 256, s) != hipSuccess ||
-        hipEventRecord(e1, s) != hipSuccess)
-      return OVGGT_ERR_HIP;
-    ev.push_back({e0, e1});
+    ok = ok && hipEventRecord(e0, s) == hipSuccess && launch_fill_zero(c->ws, 256, s) == hipSuccess &&
+         hipEventRecord(e1, s) == hipSuccess;
+    if (e0) ev.push_back({e0, e1});                  // returned to the free list below, also after a failure
+    else if (e1) c->prof_free.push_back(e1);
+    if (!ok) { failed = true; break; }
   }
-  if (hipStreamSynchronize(s) != hipSuccess) return OVGGT_ERR_HIP;
+  if (hipStreamSynchronize(s) != hipSuccess) failed = true;
   double sum = 0.0;
   for (auto& pr : ev) {
     float ms = 0.f;
-    if (hipEventElapsedTime(&ms, pr.first, pr.second) != hipSuccess) return OVGGT_ERR_HIP;
+    if (!failed && hipEventElapsedTime(&ms, pr.first, pr.second) != hipSuccess) failed = true;
     sum += ms;
     c->prof_free.push_back(pr.first);
-    c->prof_free.push_back(pr.second);
+    if (pr.second) c->prof_free.push_back(pr.second);
   }
+  if (failed) return OVGGT_ERR_HIP;
   *ms_mean = sum / reps;
   return OVGGT_OK;
 }
