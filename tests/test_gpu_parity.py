@@ -103,7 +103,10 @@ def test_bf16_ragged_small():
     print("ragged worst attention err/RMS:", worst)
 
 
-@pytest.mark.parametrize("M,B,H,C", [(1, 64, 1, 64), (37, 74, 2, 1024), (130, 1000, 5, 4096), (128, 256, 16, 8)])
+# the last shape has 17 query blocks: more than the merge pass's table of records holds, so the pass
+# lists each item's records itself
+@pytest.mark.parametrize("M,B,H,C", [(1, 64, 1, 64), (37, 74, 2, 1024), (130, 1000, 5, 4096), (128, 256, 16, 8),
+                                     (2100, 2500, 2, 64)])
 def test_bf16_odd_shapes(M, B, H, C):
     cfg = synth.preset(1, M=M, H=H, C=C, B=B, T=max(6, 2 * B // M + 3) if M > 1 else 70, n_special=min(M - 1, 2))
     run_stream(cfg)
