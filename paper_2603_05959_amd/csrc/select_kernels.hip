@@ -24,7 +24,9 @@ namespace ovggt {
 
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / 64;
-constexpr int kRowsPerWave = 4;             // tokens scored per wave and round when many layers are batched
+// Tokens scored per wave and round when many layers are batched (one round covers 24 layers of 1374
+// rows with 10 workgroups each; measured 23 us with 4 rows in flight per wave, 19.5 us with 9).
+constexpr int kRowsPerWave = 9;
 constexpr int kMaxSelChunks = 128;          // n_total <= 128 * 1024 slots
 
 __device__ inline float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
