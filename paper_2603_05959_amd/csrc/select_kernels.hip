@@ -25,7 +25,8 @@ namespace ovggt {
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / 64;
 // Tokens scored per wave and round when many layers are batched (one round covers 24 layers of 1374
-// rows with 10 workgroups each; measured 23 us with 4 rows in flight per wave, 19.5 us with 9).
+// rows with 10 workgroups each; measured 23 us with 4 rows in flight per wave, 19.5 us with 9,
+// 17.8 us once the wave's scores leave in one store instruction).
 constexpr int kRowsPerWave = 9;
 constexpr int kMaxSelChunks = 128;          // n_total <= 128 * 1024 slots
 
@@ -104,16 +105,18 @@ __device__ inline void score_rows(const char* rbase, size_t row_bytes, int C, in
 #pragma unroll
     for (int r = 0; r < R; ++r)
       v[r] = row_sum_sq<E, BF16>(rbase + (size_t)min(tok0 + r, M - 1) * row_bytes, C, lane);
+    // Every lane holds every row's sum after the butterfly: lane r publishes row r, so the wave's
+    // R consecutive tokens leave in one store instruction for the scores and one for the flags.
+    // Device-coherent (write-through) stores: the selection may run on another XCD, and a
+    // device-scope release fence per workgroup (an L2 write-back each) would cost far more.
+    float mine = v[0];
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-      const int tok = tok0 + r;
-      if (lane == 0 && tok < M) {
-        // device-coherent (write-through) stores: the selection may run on another XCD, and a
-        // device-scope release fence per workgroup (an L2 write-back each) would cost far more
-        __hip_atomic_store(&ss_new[tok], v[r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(&flags_new[tok], (uint8_t)((anchors_layer && anchors_layer[tok]) ? 1 : 0),
-                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      }
+    for (int r = 1; r < R; ++r) mine = lane == r ? v[r] : mine;
+    const int tok = tok0 + lane;
+    if (lane < R && tok < M) {
+      __hip_atomic_store(&ss_new[tok], mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(&flags_new[tok], (uint8_t)((anchors_layer && anchors_layer[tok]) ? 1 : 0),
+                         __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
 }
