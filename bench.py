@@ -37,16 +37,17 @@ def gen_frames(cfg, frames, layers, pool):
     return dict(zip(jobs, pool.map(lambda lt: synth.frame_inputs(cfg, lt[0], lt[1]), jobs)))
 
 
-def profiled_traffic(kernel, workload, layers):
-    """HBM-side bytes per launch of `kernel` from the committed rocprofv3 --pmc summary of this
-    workload (FETCH_SIZE + WRITE_SIZE, calibrated there against a plain copy), or None."""
+def profiled_figure(what, kernel, workload, layers):
+    """A per-launch figure of `kernel` from the committed rocprofv3 summary of this workload, or
+    None: "traffic_bytes_per_launch" (FETCH_SIZE + WRITE_SIZE, calibrated there against a plain
+    copy) or "trace_avg_kernel_us" (steady-state duration in the kernel trace)."""
     path = os.path.join(ROOT, "profiles", "bench_%s_kernels_and_traffic.md" % workload)
-    tag = "traffic_bytes_per_launch %s %s layers=%d:" % (kernel, workload, layers)
+    tag = "%s %s %s layers=%d:" % (what, kernel, workload, layers)
     try:
         with open(path) as f:
             for line in f:
                 if line.startswith(tag):
-                    return int(line[len(tag):].split()[0])
+                    return float(line[len(tag):].split()[0])
     except OSError:
         pass
     return None
@@ -203,10 +204,17 @@ def main():
     bracket_ms = attn_ms / max(attn_cnt, 1)
     attn_avg_ms = max(bracket_ms - bracket_overhead_ms, 1e-6)
     achieved = flop / (attn_avg_ms * 1e-3) / 1e12 if attn_cnt else 0.0
+    # from the committed rocprofv3 summary of this workload (stored-score ranking, no smoothing): HBM
+    # bytes per launch, and the kernel's steady-state duration in the trace (the profiled run is a
+    # few per cent slower than a plain one)
+    wl = cfg.name.split("-")[0]
+    traffic = profiled_figure("traffic_bytes_per_launch", "attn_bf16_kernel", wl, L)
+    traffic = None if traffic is None else int(traffic)
+    trace_us = profiled_figure("trace_avg_kernel_us", "attn_bf16_kernel", wl, L)
     roofline = {"bound": "mfma", "kernel": "attn_bf16_kernel", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
-                "traffic": profiled_traffic("attn_bf16_kernel", cfg.name.split("-")[0], L),
-                "avg_kernel_ms": attn_avg_ms, "event_bracket_ms": bracket_ms,
+                "traffic": traffic, "avg_kernel_ms": attn_avg_ms,
+                "profiled_kernel_ms": None if trace_us is None else trace_us * 1e-3, "event_bracket_ms": bracket_ms,
                 "event_bracket_of_empty_launch_ms": bracket_overhead_ms, "launches_timed": int(attn_cnt),
                 "flop_per_launch": flop, "keys_per_launch": int(n_keys)}
 
