@@ -96,6 +96,9 @@ def main():
     ap.add_argument("--detail-steps", type=int, default=40, help="extra untimed steps with per-kernel events")
     ap.add_argument("--flatness", action="store_true",
                     help="also bracket every 8th timed step with events and report the slope of step latency over the stream")
+    ap.add_argument("--rising-scores", action="store_true",
+                    help="worst case for compaction: residual norms grow with t, so every new token survives and "
+                         "M cached entries move per frame (all frames of the run are generated: keep the run short)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (reference dispatch for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -124,12 +127,17 @@ def main():
 
     # ---- inputs: generated on the host, staged to HBM before anything is timed
     distinct = min(T, max(64, 2 * (cfg.B // cfg.M) + 8)) if L > 1 else T
+    if args.rising_scores:
+        distinct = T + args.detail_steps                 # a reused frame would rank below the cache and break the pattern
     t_gen = time.perf_counter()
     staged = []
     with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 8)) as pool:
         for t0_ in range(0, distinct, 8):
             batch = range(t0_, min(distinct, t0_ + 8))
             host = gen_frames(cfg, batch, L, pool)
+            if args.rising_scores:
+                for (l, t), f in host.items():
+                    f["r"] = synth.rising_resid(cfg, l, t)
             for t in batch:
                 fs = [host[(l, t)] for l in range(L)]
                 pack = lambda key: B.to_device(np.stack([f[key] for f in fs]), cfg.dtype, dev)
@@ -230,6 +238,12 @@ def main():
     if "append" in kernels:
         byts = L * 4 * cfg.M * cfg.H * cfg.d * esz
         hbm["append"] = {"algorithmic_bytes": byts, "GB/s": byts / (kernels["append"]["avg_us"] * 1e-6) / 1e9}
+    if args.rising_scores and "compact" in kernels:
+        moves = len(cache.last_moves(0)[0])
+        assert moves == cfg.M, f"rising scores: {moves} of {cfg.M} entries moved in the last frame"
+        byts = L * moves * (2 * cfg.H * cfg.d * esz + 9) * 2                 # K, V, id, score, flag: read and written
+        hbm["compact"] = {"algorithmic_bytes": byts, "GB/s": byts / (kernels["compact"]["avg_us"] * 1e-6) / 1e9,
+                          "entries_moved_per_layer": moves}
     for v in hbm.values():
         v["frac_of_8TBs"] = v["GB/s"] / HBM_PEAK_GBS
 
@@ -247,7 +261,8 @@ def main():
                    "resident_keys_steady": int(n_keys), "out_dtype": "f32",
                    "ranking": ("hybrid Eq. 7, beta=%g" % args.hybrid_beta) if args.hybrid_beta is not None
                               else "stored Eq. 5 scores",
-                   "smoothing": ("Eq. 6, alpha=%g, 3x3 Gaussian sigma 1" % args.smooth_alpha) if smooth else "off"},
+                   "smoothing": ("Eq. 6, alpha=%g, 3x3 Gaussian sigma 1" % args.smooth_alpha) if smooth else "off",
+                   "scores": "rising with t (worst case for compaction)" if args.rising_scores else "workload's own"},
         "roofline": roofline,
         "kernels_us": kernels,
         "hbm_kernels": hbm,
