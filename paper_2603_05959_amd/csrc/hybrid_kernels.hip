@@ -235,8 +235,8 @@ diversity_kernel(Geom g, char* kv, char* meta, int layer0, int n_hist) {
   }, &nc, &unused);
   const float root_nc = __builtin_sqrtf(nc);
 
-  // minimum and maximum of the d_i this workgroup writes: the selection normalises with them and
-  // reads one pair per workgroup instead of every d_i
+  // minimum and maximum of the d_i this wave writes: the selection normalises with them and reads
+  // one pair per wave of this pass instead of every d_i
   float d_lo = __builtin_inff(), d_hi = -__builtin_inff();
   const int stride = gridDim.x * kDivWaves * 8;
   for (int s0 = (blockIdx.x * kDivWaves + wave) * 8; s0 < n_hist; s0 += stride) {
@@ -264,20 +264,14 @@ diversity_kernel(Geom g, char* kv, char* meta, int layer0, int n_hist) {
       d_lo = fminf(d_lo, dv); d_hi = fmaxf(d_hi, dv);
     }
   }
+  // only the first lane of each slot's eight holds values: three butterfly steps across the slots,
+  // one pair per wave (no workgroup barrier: a workgroup lives for a few slot groups only)
 #pragma unroll
-  for (int off = 1; off < 64; off *= 2) {
+  for (int off = 8; off < 64; off *= 2) {
     d_lo = fminf(d_lo, __shfl_xor(d_lo, off, 64));
     d_hi = fmaxf(d_hi, __shfl_xor(d_hi, off, 64));
   }
-  __syncthreads();                                     // the centroid in cs is not needed any more
-  if (lane == 0) { cs[2 * wave] = d_lo; cs[2 * wave + 1] = d_hi; }
-  __syncthreads();
-  if (threadIdx.x == 0) {
-#pragma unroll
-    for (int w = 1; w < kDivWaves; ++w) { d_lo = fminf(d_lo, cs[2 * w]); d_hi = fmaxf(d_hi, cs[2 * w + 1]); }
-    float2* part = (float2*)(mb + g.off_dpart);
-    part[blockIdx.x] = make_float2(d_lo, d_hi);
-  }
+  if (lane == 0) ((float2*)(mb + g.off_dpart))[blockIdx.x * kDivWaves + wave] = make_float2(d_lo, d_hi);
 }
 
 // A change of protection (Sec. 3.3) moves tokens between P and the evictable set: the sum loses the
@@ -317,7 +311,7 @@ hipError_t launch_diversity(const Geom& g, char* kv, char* meta, int layer0, int
   if (n_hist <= 0) return hipSuccess;
   int hp = 1;
   while (hp < g.H) hp *= 2;
-  static_assert(kDivWaves * 8 == kDivSlotsPerWg, "a wave takes 8 slots at a time");
+  static_assert(kDivWaves * 8 == kDivSlotsPerWg && kDivWaves == kDivWavesPerWg, "a wave takes 8 slots at a time");
   dim3 dgrid((unsigned)diversity_grid_x(n_hist, nl), (unsigned)nl);
 #define OVGGT_DIV_LAUNCH(HH) \
   hipLaunchKernelGGL(diversity_kernel<HH>, dgrid, dim3(kDivThreads), 0, s, g, kv, meta, layer0, n_hist)

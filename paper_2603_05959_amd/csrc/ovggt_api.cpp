@@ -117,7 +117,7 @@ void make_geom(const ovggt_config& c, Geom* g) {
   g->off_evbits = off; off += up256((size_t)g->cap / 8);
   g->off_cvec = off;  off += up256((size_t)4 * g->H * g->d);
   g->off_dval = off;  off += c.score_mode == 1 ? up256((size_t)4 * g->cap) : 0;
-  g->off_dpart = off; off += c.score_mode == 1 ? up256((size_t)8 * diversity_grid_x(g->cap, 1)) : 0;
+  g->off_dpart = off; off += c.score_mode == 1 ? up256((size_t)8 * kDivWavesPerWg * diversity_grid_x(g->cap, 1)) : 0;
   g->hybrid = c.score_mode == 1 ? 1 : 0;
   g->meta_layer_bytes = off;
 }
@@ -294,7 +294,7 @@ int ovggt_score_select(ovggt_cache* c, int layer, const void* resid, const uint8
   {
     ProfScope ps(c, OVGGT_PROF_SELECT, (hipStream_t)hip_stream, c->prof_level >= 2);
     const HybridParams hy = {c->cfg.score_mode == 1 ? 1 : 0, c->cfg.hybrid_beta,
-                             diversity_grid_x(c->n[l0] - c->g.M, nl)};
+                             kDivWavesPerWg * diversity_grid_x(c->n[l0] - c->g.M, nl)};
     if (hy.on && c->n[l0] > c->g.B &&
         launch_diversity(c->g, c->kv, c->meta, l0, nl, c->n[l0] - c->g.M, (hipStream_t)hip_stream) != hipSuccess)
       return OVGGT_ERR_HIP;

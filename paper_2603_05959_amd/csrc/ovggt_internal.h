@@ -35,7 +35,7 @@ struct Geom {
   size_t off_evbits;       // evict bit per slot of the last selection, 32 slots per word (hybrid scoring)
   size_t off_dval;         // d_i = 1 - cos(k_i, centroid) of the slots below n_old, one fp32 per slot (hybrid scoring)
   size_t off_cvec;         // the sum as H*d fp32 values, refreshed by each frame's append (hybrid scoring)
-  size_t off_dpart;        // (min, max) of d_i over the evictable slots of each workgroup of the diversity pass (hybrid scoring)
+  size_t off_dpart;        // (min, max) of d_i over the evictable slots of each wave of the diversity pass (hybrid scoring)
 };
 
 __host__ __device__ inline char* layer_k(char* kv, const Geom& g, int layer) {
@@ -84,11 +84,12 @@ struct SmoothParams {
 struct HybridParams {
   int on;
   float beta;
-  int n_part;              // workgroups of the frame's diversity pass = (min, max) pairs it left per layer
+  int n_part;              // waves of the frame's diversity pass = (min, max) pairs it left per layer
 };
 
 // Slots per workgroup and workgroups per layer of the diversity pass (a wave takes 8 slots at a time).
 constexpr int kDivSlotsPerWg = 32;
+constexpr int kDivWavesPerWg = 4;
 inline int diversity_grid_x(int n_hist, int nl) {
   long gx = (n_hist + kDivSlotsPerWg - 1) / kDivSlotsPerWg;
   const long cap_x = 4096 / nl > 0 ? 4096 / nl : 1;

@@ -656,8 +656,8 @@ __device__ inline void block_min_max(SelShared& sh, const uint8_t* flags, int n,
 }
 
 // History side, spread over every workgroup of the layer's launch.  `dval` holds d_i of the slots
-// below n_old, `part` the (minimum, maximum) over the evictable slots of each workgroup of this
-// frame's diversity pass (both read-only here).  Every workgroup folds the few hundred pairs into
+// below n_old, `part` the (minimum, maximum) over the evictable slots of each wave of this
+// frame's diversity pass (both read-only here).  Every workgroup folds the few thousand pairs into
 // the same minimum and maximum (reading all d_i and flags instead, 80 KB per workgroup, made this
 // phase take 13.5 us instead of 4.8), then writes the rank values of its own share of slots over
 // their scores, written through like the scores of phase 1.
