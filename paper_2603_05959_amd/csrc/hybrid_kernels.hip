@@ -246,10 +246,11 @@ diversity_kernel(Geom g, char* kv, char* meta, int layer0, int n_hist) {
     const char* row0 = K + (size_t)sc * 128 + piece * 16;
     float dot, nk;
     if constexpr (HP <= kDivHeadBatch) {
+      // every load is issued (heads beyond H repeat the last one): no branch between the loads, so
+      // all of them are in flight before the first wait
       uint4 w[HP];
 #pragma unroll
-      for (int h = 0; h < HP; ++h)
-        if (h < H) w[h] = *(const uint4*)(row0 + (size_t)h * g.cap * 128);
+      for (int h = 0; h < HP; ++h) w[h] = *(const uint4*)(row0 + (size_t)min(h, H - 1) * g.cap * 128);
       slot_sums<HP>(cs, piece, H, [&](int h, float (&k8)[8]) { unpack_halfs(w[h], k8); }, &dot, &nk);
     } else {
       slot_sums<HP>(cs, piece, H, [&](int h, float (&k8)[8]) {

@@ -92,7 +92,7 @@ constexpr int kDivSlotsPerWg = 32;
 constexpr int kDivWavesPerWg = 4;
 inline int diversity_grid_x(int n_hist, int nl) {
   long gx = (n_hist + kDivSlotsPerWg - 1) / kDivSlotsPerWg;
-  const long cap_x = 4096 / nl > 0 ? 4096 / nl : 1;
+  const long cap_x = 8192 / nl > 0 ? 8192 / nl : 1;      // 24 layers: 155 us at 8192 workgroups, 159 at 4096, 160 at 12288
   return (int)(gx > cap_x ? cap_x : gx);
 }
 
