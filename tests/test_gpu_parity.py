@@ -53,7 +53,7 @@ def compare_cache(cache, orc, layer=0, kv=True):
 
 
 def run_stream(cfg, layer=0, attn_frames=None, cache_every=1, resid_fn=None, q_rows=None, log=None, smooth=None,
-               hybrid_beta=None):
+               hybrid_beta=None, qkv_fn=None):
     """Drive both sides over cfg.T frames of one layer; returns max attention error."""
     torch = _torch()
     cache = make_cache(cfg, L=1, smooth=smooth, hybrid_beta=hybrid_beta)
@@ -64,6 +64,8 @@ def run_stream(cfg, layer=0, attn_frames=None, cache_every=1, resid_fn=None, q_r
         f = synth.frame_inputs(cfg, layer, t)
         if resid_fn is not None:
             f["r"] = resid_fn(cfg, layer, t)
+        if qkv_fn is not None:
+            qkv_fn(cfg, t, f)
         q, k, v, r = (dev(f[x], cfg) for x in "qkvr")
         a = torch.from_numpy(f["a"]).to("cuda:0")
         cache.step(q, k, v, r, a, out, layer=0)
@@ -101,6 +103,42 @@ def test_bf16_ragged_small():
     cfg = synth.preset(1, M=200, H=3, C=200, B=700, T=9, n_special=3)
     worst = run_stream(cfg)
     print("ragged worst attention err/RMS:", worst)
+
+
+def _hard_values(kind):
+    """Q/K/V regimes that stress the attention kernel's running reference and half-precision
+    weights; every array is rounded to the run dtype like the generator's own."""
+    def fn(cfg, t, f):
+        j = (t * cfg.M + np.arange(cfg.M, dtype=np.float32))[:, None, None]      # global token index
+        ones = np.ones((cfg.M, cfg.H, cfg.d), np.float32)
+        if kind == "peaky":                     # logit std 16: nearly one-hot rows
+            f["q"] = f["q"] * 4.0; f["k"] = f["k"] * 4.0
+        elif kind == "rising":                  # the maximum grows by ~0.9 (log2) per slot: a rescale in every tile
+            f["k"] = ones * (j / 100.0); f["q"] = ones * 1.0
+        elif kind == "falling":                 # the first slot dominates, later weights underflow
+            f["k"] = ones * (-j / 100.0); f["q"] = ones * 1.0
+        elif kind == "constant":                # uniform weights over the whole cache
+            f["k"] = ones * 0.5
+        elif kind == "zero_q":
+            f["q"] = np.zeros_like(f["q"])
+        elif kind == "big_v":
+            f["v"] = f["v"] * 300.0
+        elif kind == "tiny_v":
+            f["v"] = f["v"] * 1e-3
+        elif kind == "outlier_key":             # one key per frame carries most of every row's mass
+            f["q"] = np.abs(f["q"]); f["k"][7] = 3.0
+        for x in "qkv":
+            f[x] = synth.quantise(np.ascontiguousarray(f[x], dtype=np.float32), cfg.dtype)
+    return fn
+
+
+@pytest.mark.parametrize("kind", ["peaky", "rising", "falling", "constant", "zero_q", "big_v", "tiny_v", "outlier_key"])
+def test_attention_hard_value_distributions(kind):
+    # 6 frames of 200 tokens under a budget that keeps everything: 1200 slots = 9 tiles + a tail,
+    # every frame's output compared
+    cfg = synth.preset(1, M=200, H=2, C=64, B=2000, T=6, n_special=2)
+    worst = run_stream(cfg, qkv_fn=_hard_values(kind))
+    print(f"{kind}: worst attention err/RMS {worst:.3e}")
 
 
 # the last shape has 17 query blocks: more than the merge pass's table of records holds, so the pass
