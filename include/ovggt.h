@@ -130,8 +130,11 @@ int ovggt_cache_init(ovggt_cache** out, const ovggt_config* cfg,
  * Q K^T and P V on the f16 MFMA with fp32 accumulation (K and V are cached as IEEE
  * half, the queries are multiplied by scale*log2(e) and rounded to half, softmax
  * weights are rounded to half) and an fp32 online softmax; f32 runs compute in
- * fp32.  ERR_STATE unless the layer expects a new
- * frame. */
+ * fp32.  Accuracy of bf16 runs: the rounded query makes a logit of magnitude x
+ * (after the scale, in units of ln 2) uncertain by about x * 2^-12, so the
+ * output error relative to the output's RMS is a few 1e-3 for logits of unit
+ * spread and approaches 2e-2 when their spread reaches 16.  ERR_STATE unless the
+ * layer expects a new frame. */
 int ovggt_global_attn(ovggt_cache* c, int layer, const void* q, const void* k_new, const void* v_new,
                       void* out, void* hip_stream);
 
