@@ -118,6 +118,7 @@ void make_geom(const ovggt_config& c, Geom* g) {
   g->off_cvec = off;  off += up256((size_t)4 * g->H * g->d);
   g->off_dval = off;  off += c.score_mode == 1 ? up256((size_t)4 * g->cap) : 0;
   g->off_dpart = off; off += c.score_mode == 1 ? up256((size_t)8 * kDivWavesPerWg * diversity_grid_x(g->cap, 1)) : 0;
+  g->off_hist = off;  off += up256((size_t)4 * kSelHistBins);
   g->hybrid = c.score_mode == 1 ? 1 : 0;
   g->meta_layer_bytes = off;
 }

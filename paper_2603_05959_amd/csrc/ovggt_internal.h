@@ -36,7 +36,11 @@ struct Geom {
   size_t off_dval;         // d_i = 1 - cos(k_i, centroid) of the slots below n_old, one fp32 per slot (hybrid scoring)
   size_t off_cvec;         // the sum as H*d fp32 values, refreshed by each frame's append (hybrid scoring)
   size_t off_dpart;        // (min, max) of d_i over the evictable slots of each wave of the diversity pass (hybrid scoring)
+  size_t off_hist;         // kSelHistBins counters: the selection's first-level histogram of the cached entries' score
+                           // words, filled by all workgroups of a launch and zeroed again by the one that selects
 };
+
+constexpr int kSelHistBins = 2048;  // the 11 bits below the sign of a score word
 
 __host__ __device__ inline char* layer_k(char* kv, const Geom& g, int layer) {
   return kv + (size_t)layer * g.kv_layer_bytes;

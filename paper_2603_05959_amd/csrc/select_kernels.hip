@@ -8,16 +8,21 @@
 // reproducible by a plain pairwise sum on any machine.  HBM-bound: each row is
 // read once with 16-byte loads.
 //
+// While its rows load, every workgroup also counts its share of the cached
+// entries by the 11 leading bits of their score words (LDS histogram, flushed
+// to per-layer counters in memory with one device-scope atomic per occupied bin).
+//
 // Phase 2 (the workgroup that arrives last for a layer, found with an arrival
 // counter; nobody waits): if more than B entries are resident, find the E =
 // n - B lowest-ranked evictable entries under the total order (ss ascending,
-// token id descending) by an 8-bit-digit radix select on the 64-bit key
-// (ss bits, ~id) held in registers, with a per-lane-column LDS histogram (no
-// bank or address conflicts); passes stop as soon as a whole bucket is evicted,
-// and the id half is only consulted when equal scores straddle the threshold.
+// token id descending) on the 64-bit key (ss bits, ~id): the counters give the
+// threshold's first-level bin, one pass over the score words marks what lies
+// below it and collects what lies in it, a second 11-bit level over those
+// candidates leaves a handful of keys that one wave orders (ids included).
+// Populations that defeat the two levels (thousands of keys in one bin, more
+// than 64 equal in 22 leading bits) take a streaming 8-bit radix selection.
 // Then emit the move list in ascending slot order.
 #include "ovggt_internal.h"
-#include <type_traits>
 #include "../../include/ovggt.h"
 
 namespace ovggt {
@@ -154,15 +159,23 @@ __device__ inline void smooth_new_scores(const SmoothParams& sm, int M, float* k
 
 // ---- phase 2 helpers ---------------------------------------------------------
 struct SelShared {
-  uint32_t hist[256][64];          // one column per lane id; rows 0..127 are cleared and read (streaming passes pack
-                                   // two 16-bit bins per word there), rows above only absorb the marker word
-  uint32_t wave_hist[kSelWaves][256];   // later passes over register-resident keys; zero between uses
+  uint32_t hist[256][64];          // histogram selection: the candidate lists (score words, then slots); streaming
+                                   // selection: one histogram column per lane id in rows 0..127 (two 16-bit bins a word)
+  uint32_t level[2][kSelHistBins]; // histogram selection: first-level counts (a workgroup's share of the cache, then
+                                   // the new frame's tokens) and second-level counts of the candidates
   uint32_t cnt[256];
   uint32_t evmap[kMaxSelChunks * kSelThreads / 32];   // evict bit per slot, slot order
+  uint32_t candmap[kMaxSelChunks * kSelThreads / 32]; // histogram selection: slots whose key lies in the threshold's bin
   uint32_t scan_tmp[2][kSelWaves];
-  uint32_t totals[2];
   uint32_t digit, rank, bucket, is_last, n_evictable, bad;
+  uint32_t n_cand, n_final;        // histogram selection: entries of the candidate list, of the final list
+  uint32_t final_list[64];         // candidate-list positions of the keys that the last wave step orders
 };
+
+// Histogram selection: sizes of its lists.
+constexpr int kCandCap = 8192;     // candidates (keys in the threshold's first-level bin) held in LDS
+constexpr int kFinalCap = 64;      // keys that still tie after the second level: ordered by one wave
+static_assert(sizeof(((SelShared*)nullptr)->hist) == 2 * kCandCap * sizeof(uint32_t), "candidate lists overlay hist");
 
 constexpr uint32_t kNotEvictable = 0xFFFFFFFFu;   // score word of protected / absent slots (no real score maps to it)
 
@@ -208,13 +221,10 @@ __device__ inline void pick_digit(SelShared& sh, uint32_t rank) {
 // rank-th smallest candidate.  Results in sh.digit / sh.rank / sh.bucket (and sh.n_evictable =
 // number of candidates).
 template <typename DigitOf>
-__device__ inline void radix_pass(SelShared& sh, int n_iter, uint32_t rank, DigitOf digit_of, uint32_t* ts = nullptr) {
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+__device__ inline void radix_pass(SelShared& sh, int n_iter, uint32_t rank, DigitOf digit_of) {
+  const int tid = threadIdx.x, lane = tid & 63;
   for (int i = tid; i < 128 * 64; i += kSelThreads) (&sh.hist[0][0])[i] = 0u;
   __syncthreads();
-#ifdef OVGGT_TRACE
-  if (ts && tid == 0) ts[0] = (uint32_t)wall_clock64();
-#endif
   // digits of 8 chunks are fetched together so their loads overlap
   for (int c0 = 0; c0 < n_iter; c0 += 8) {
     int dg[8];
@@ -225,9 +235,6 @@ __device__ inline void radix_pass(SelShared& sh, int n_iter, uint32_t rank, Digi
       if (dg[j] >= 0) atomicAdd(&sh.hist[dg[j] >> 1][lane], 1u << (16 * (dg[j] & 1)));
   }
   __syncthreads();
-#ifdef OVGGT_TRACE
-  if (ts && tid == 0) ts[1] = (uint32_t)wall_clock64();
-#endif
   {   // column sums: thread -> (bin, quarter of the 64 columns)
     const int bin = tid >> 2, quarter = tid & 3;
     uint32_t s = 0;
@@ -241,272 +248,148 @@ __device__ inline void radix_pass(SelShared& sh, int n_iter, uint32_t rank, Digi
     if (quarter == 0) sh.cnt[bin] = s;
   }
   __syncthreads();
-#ifdef OVGGT_TRACE
-  if (ts && tid == 0) ts[2] = (uint32_t)wall_clock64();
-#endif
   pick_digit(sh, rank);
 }
 
-// First pass over register-resident keys: every key of the thread is counted by its leading byte
-// into the per-lane-column histogram, which the workgroup cleared when the kernel started.  Real
-// score words are non-negative floats, so their leading byte is below 128; the word that marks a
-// protected or absent slot has 255 and lands in a row that nobody clears or reads -- no test per key.
-template <int KPT>
-__device__ inline void first_pass_registers(SelShared& sh, const uint32_t (&kw)[KPT > 0 ? KPT : 1], uint32_t rank, uint32_t* ts) {
-  const int tid = threadIdx.x, lane = tid & 63;
-  uint32_t* col = &sh.hist[0][0] + lane;
-#pragma unroll
-  for (int c = 0; c < KPT; ++c) {
-    atomicAdd(col + (kw[c] >> 24) * 64u, 1u);
-  }
-  __syncthreads();
+// timing builds leave 10 ns timestamps of the phases in the control block's padding
 #ifdef OVGGT_TRACE
-  if (ts && tid == 0) ts[1] = (uint32_t)wall_clock64();
+#define TSTAMP(k) do { if (tid == 0) ctrl->pad[k] = (uint32_t)wall_clock64(); } while (0)
+#else
+#define TSTAMP(k) do { } while (0)
 #endif
-  {   // column sums: thread -> (bin, eighth of the 64 columns); a wave's 64 reads hit 64 distinct columns
-    const int bin = tid >> 3, part = tid & 7;
-    uint32_t s = 0;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) s += sh.hist[bin][part * 8 + ((j + (lane >> 3)) & 7)];
-    s += __shfl_xor(s, 1, 64);
-    s += __shfl_xor(s, 2, 64);
-    s += __shfl_xor(s, 4, 64);
-    if (part == 0) sh.cnt[bin] = s;
-    if (tid < 128) sh.cnt[128 + tid] = 0u;
-  }
-  __syncthreads();
-#ifdef OVGGT_TRACE
-  if (ts && tid == 0) ts[2] = (uint32_t)wall_clock64();
-#endif
-  pick_digit(sh, rank);
-}
 
-// One bit per register-resident key of a thread.  Indices are compile-time constants once the loops
-// over the keys are unrolled, so the words stay in registers.
-template <int N>
-struct KeyBits {
-  uint32_t w[(N + 31) / 32];
-  __device__ inline void clear() {
+// The ordered move list from the evict bitmap in sh.evmap (complete, and a barrier behind it).
+// Holes (evicted slots below B) are sparse: a thread takes PP consecutive 32-slot words of the
+// bitmap below B, and one scan over the per-thread counts gives it the list position of its first
+// hole.  Movers (kept slots at or above B) are dense: one slot per thread and round, positions from
+// a ballot and the per-wave totals.
+__device__ inline void emit_moves(SelShared& sh, const Geom& g, Ctrl* ctrl, uint32_t* mvdst, uint32_t* mvsrc,
+                                  uint32_t* evbits, int n_total, bool budget_error, int pass) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  (void)pass;
+  const int n_words = (n_total + 31) >> 5;
+  if (evbits)
+    for (int wi = tid; wi < n_words; wi += kSelThreads) evbits[wi] = sh.evmap[wi];
+  const int hole_words = (g.B + 31) >> 5;
+  const int PP = (hole_words + kSelThreads - 1) / kSelThreads;   // <= 4
+  uint32_t hw[4];
+  uint32_t nh = 0;
+  const bool wave_has_words = wave * 64 * PP < hole_words;       // the other waves only keep the barriers company
 #pragma unroll
-    for (int i = 0; i < (N + 31) / 32; ++i) w[i] = 0u;
-  }
-  __device__ inline bool test(int c) const { return (w[c >> 5] >> (c & 31)) & 1u; }
-  __device__ inline void set(int c) { w[c >> 5] |= 1u << (c & 31); }
-  __device__ inline void reset(int c) { w[c >> 5] &= ~(1u << (c & 31)); }
-  __device__ inline void merge(const KeyBits& o) {
-#pragma unroll
-    for (int i = 0; i < (N + 31) / 32; ++i) w[i] |= o.w[i];
-  }
-};
-
-// Light pass for keys held in registers: `cand` has a bit per key of this thread that is still a
-// candidate (usually few after the first pass).  Each candidate is first settled against the digit
-// the previous pass chose (prev_of(c) below it: evicted; not equal: no candidate any more), the
-// rest are counted by digit_of(c).  Counts go to one 256-bin histogram per wave with LDS atomics (a
-// wave's lanes can collide on a bin, which costs at most 64 turns per instruction whatever the
-// data; no clearing and column-summing of the big per-lane histogram).
-template <int KPT, typename PrevOf, typename DigitOf>
-__device__ inline void radix_pass_light(SelShared& sh, KeyBits<KPT>& cand, KeyBits<KPT>& evm, uint32_t prev_chosen,
-                                        uint32_t rank, PrevOf prev_of, DigitOf digit_of) {
-  const int tid = threadIdx.x, wave = tid >> 6;
-  uint32_t* mine = sh.wave_hist[wave];                // zero on entry: cleared at kernel start and after every use
-#pragma unroll
-  for (int c = 0; c < KPT; ++c)
-    if (cand.test(c)) {
-      const uint32_t pv = (uint32_t)prev_of(c);
-      if (pv != prev_chosen) {
-        cand.reset(c);
-        if (pv < prev_chosen) evm.set(c);
-      } else {
-        atomicAdd(&mine[digit_of(c)], 1u);
-      }
+  for (int j = 0; j < 4; ++j) {
+    hw[j] = 0u;
+    const int wi = tid * PP + j;
+    if (j < PP && wi < hole_words) {
+      const int s0 = wi << 5;
+      const uint32_t below_b = s0 + 32 <= g.B ? 0xFFFFFFFFu : ((1u << (g.B - s0)) - 1u);
+      hw[j] = sh.evmap[wi] & below_b;
+      nh += __popc(hw[j]);
     }
-  __syncthreads();
-  if (tid < 256) {
-    uint32_t t = 0;
-#pragma unroll
-    for (int w = 0; w < kSelWaves; ++w) { t += sh.wave_hist[w][tid]; sh.wave_hist[w][tid] = 0u; }
-    sh.cnt[tid] = t;
   }
-  __syncthreads();
-  pick_digit(sh, rank);
+  uint32_t inc_h = nh;
+  if (wave_has_words) {
+#pragma unroll
+    for (int off = 1; off < 64; off *= 2) {
+      const uint32_t yh = __shfl_up(inc_h, off, 64);
+      if (lane >= off) inc_h += yh;
+    }
+  }
+  // first round of movers shares the barrier with the holes' scan
+  const uint64_t lanes_below = (1ull << lane) - 1ull;
+  uint32_t tot_m = 0;
+  const uint32_t m_cap = (uint32_t)g.M;
+  for (int s0 = g.B; s0 < n_total; s0 += kSelThreads) {
+    const int slot = s0 + tid;
+    const bool mover = !budget_error && slot < n_total && !((sh.evmap[slot >> 5] >> (slot & 31)) & 1u);
+    const uint64_t bl = __ballot(mover);
+    if (s0 != g.B) __syncthreads();                              // the previous round's totals have been read
+    if (lane == 0) sh.scan_tmp[1][wave] = (uint32_t)__popcll(bl);
+    if (s0 == g.B && lane == 63) sh.scan_tmp[0][wave] = inc_h;
+    __syncthreads();
+    uint32_t base_m = tot_m;
+#pragma unroll
+    for (int w = 0; w < kSelWaves; ++w) {
+      const uint32_t tm = sh.scan_tmp[1][w];
+      if (w < wave) base_m += tm;
+      tot_m += tm;
+    }
+    const uint32_t mp = base_m + (uint32_t)__popcll(bl & lanes_below);
+    if (mover && mp < m_cap) mvsrc[mp] = (uint32_t)slot;
+  }
+  uint32_t base_h = 0, tot_h = 0;
+#pragma unroll
+  for (int w = 0; w < kSelWaves; ++w) {
+    const uint32_t th = sh.scan_tmp[0][w];
+    if (w < wave) base_h += th;
+    tot_h += th;
+  }
+  const bool consistent = !budget_error && tot_h == tot_m && tot_h <= m_cap;
+  if (consistent && wave_has_words) {
+    uint32_t hp = base_h + inc_h - nh;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint32_t s0 = (uint32_t)(tid * PP + j) << 5;
+      uint32_t b = hw[j];
+      while (b) { mvdst[hp++] = s0 + (uint32_t)__builtin_ctz(b); b &= b - 1; }
+    }
+  }
+  if (tid == 0) {
+    ctrl->n_moves = consistent ? tot_h : 0u;
+    uint32_t st = 0;
+    if (budget_error || !consistent) st |= OVGGT_STATUS_BUDGET;
+    if (sh.bad) st |= OVGGT_STATUS_NONFINITE;
+    if (st) atomicOr(&ctrl->status, st);
+    TSTAMP(12);
+#ifdef OVGGT_TRACE
+    ctrl->pad[13] = (uint32_t)pass;
+#endif
+  }
 }
 
-// Selection by one workgroup.  KPT > 0: the score words (and, if IDREG, the
-// inverted ids) of up to KPT*1024 slots live in registers, so the radix passes
-// touch LDS only.  KPT == 0: every pass re-reads them from memory (any size).
-template <int KPT, bool IDREG>
-__device__ inline void select_phase(SelShared& sh, const Geom& g, const float* ss, const uint32_t* ids,
-                                    const uint8_t* flags, Ctrl* ctrl, uint32_t* mvdst, uint32_t* mvsrc,
-                                    uint32_t* evbits, int n_total) {
-  constexpr int NREG = KPT > 0 ? KPT : 1;
+// Streaming radix selection by one workgroup, for any population of keys: 8-bit digits of the
+// 64-bit key (score word, inverted id), every pass re-reads the score words (and, once equal
+// scores straddle the threshold, the ids) from memory; passes stop as soon as a whole bucket goes.
+// The histogram selection falls back to it when its lists overflow.
+__device__ inline void select_streaming(SelShared& sh, const Geom& g, const float* ss, const uint32_t* ids,
+                                        const uint8_t* flags, Ctrl* ctrl, uint32_t* mvdst, uint32_t* mvsrc,
+                                        uint32_t* evbits, int n_total) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n_chunks = (n_total + kSelThreads - 1) / kSelThreads;
-  const int n_iter = KPT > 0 ? KPT : n_chunks;
   const uint32_t n_evict = (uint32_t)(n_total - g.B);
   bool bad = false;
-  uint32_t kw[NREG], kid[(KPT > 0 && IDREG) ? KPT : 1];
-  auto load_word = [&](int c) -> uint32_t {          // branch-free so that loads of several chunks overlap
+  auto word = [&](int c) -> uint32_t {               // branch-free so that loads of several chunks overlap
     const int i = c * kSelThreads + tid;
     const int ic = i < n_total ? i : n_total - 1;
     const uint8_t f = flags[ic];
     const uint32_t w = score_word(ss[ic], &bad);
     return (i >= n_total || f != 0) ? kNotEvictable : w;
   };
-  auto load_id = [&](int c) -> uint32_t {
+  auto idw = [&](int c) -> uint32_t {
     const int i = c * kSelThreads + tid;
     return 0xFFFFFFFFu - ids[i < n_total ? i : n_total - 1];
   };
-  if constexpr (KPT > 0) {
-    // every load is unconditional (indices are clamped), so a batch of them is in flight together
-    constexpr int kBatch = KPT <= 20 ? KPT : 18;
-#pragma unroll
-    for (int c0 = 0; c0 < KPT; c0 += kBatch) {
-      uint8_t fl[kBatch];
-      float sv[kBatch];
-#pragma unroll
-      for (int j = 0; j < kBatch; ++j) {
-        const int c = c0 + j;
-        if (c < KPT) {
-          const int i = c * kSelThreads + tid;
-          const int ic = i < n_total ? i : n_total - 1;
-          fl[j] = flags[ic];
-          sv[j] = ss[ic];
-          if constexpr (IDREG) kid[c] = ids[ic];
-        }
-      }
-#pragma unroll
-      for (int j = 0; j < kBatch; ++j) {
-        const int c = c0 + j;
-        if (c < KPT) {
-          const int i = c * kSelThreads + tid;
-          const uint32_t w = score_word(sv[j], &bad);
-          kw[c] = (i >= n_total || fl[j] != 0) ? kNotEvictable : w;
-          if constexpr (IDREG) kid[c] = 0xFFFFFFFFu - kid[c];
-        }
-      }
-    }
-  }
-  auto word = [&](int c) -> uint32_t { if constexpr (KPT > 0) return kw[c]; else return load_word(c); };
-  auto idw = [&](int c) -> uint32_t { if constexpr (KPT > 0 && IDREG) return kid[c]; else return load_id(c); };
   if (tid == 0) sh.bad = 0;
-  // timing builds leave 10 ns timestamps of the phases in the control block's padding
-#ifdef OVGGT_TRACE
-#define TSTAMP(k) do { if (tid == 0) ctrl->pad[k] = (uint32_t)wall_clock64(); } while (0)
-#else
-#define TSTAMP(k) do { } while (0)
-#endif
   TSTAMP(1);
 
   // radix select of the n_evict-th smallest (score word, inverted id) pair
   uint32_t rank = n_evict;
   int pass = 0;
   bool budget_error = false, done = false;
-  if constexpr (KPT > 0) {
-    // Keys in registers: two bit masks per thread follow the selection, `cand` (keys that still tie
-    // with the threshold on every digit seen so far) and `evm` (keys already known to go).  The
-    // first pass looks at every key (most share a handful of leading digits: per-lane histogram
-    // columns); after it only the candidates are touched, and in the end the masks are the answer.
-    KeyBits<KPT> cand, evm;
-    cand.clear(); evm.clear();
-#pragma unroll
-    for (int c = 0; c < KPT; ++c)
-      if (kw[c] != kNotEvictable) cand.set(c);
-    // settles the candidates against the digit the last pass chose: below it goes, above it stays
-    auto narrow = [&](auto digit_of) {
-      const uint32_t chosen = sh.digit;
-#pragma unroll
-      for (int c = 0; c < KPT; ++c)
-        if (cand.test(c)) {
-          const uint32_t dg = (uint32_t)digit_of(c);
-          if (dg < chosen) evm.set(c);
-          if (dg != chosen) cand.reset(c);
-        }
-    };
-    uint32_t chosen = 0;                               // digit of the last pass (its candidates are settled by the next one)
-    {
-      first_pass_registers<KPT>(sh, kw, rank, &ctrl->pad[20]);
-      if (sh.n_evictable < n_evict) budget_error = true;          // |P| > B
-      else {
-        chosen = sh.digit;
-        rank = sh.rank;
-        done = (rank == sh.bucket);                   // the whole bucket goes
-      }
-      pass = 1;                                       // (the next pass runs two barriers before it writes these again)
-      TSTAMP(2);
-    }
-    int last_shift = 24;                               // where the last pass took its digit from
-    bool last_id = false;
-#pragma nounroll
-    for (; pass < 4 && !done && !budget_error; ++pass) {
-      const int shift = 24 - 8 * pass;
-      radix_pass_light<KPT>(sh, cand, evm, chosen, rank,
-                                  [&](int c) -> int { return (int)((kw[c] >> (shift + 8)) & 255u); },
-                                  [&](int c) -> int { return (int)((kw[c] >> shift) & 255u); });
-      chosen = sh.digit;
-      rank = sh.rank;
-      done = (rank == sh.bucket);
-      last_shift = shift;
-      TSTAMP(2 + pass);
-    }
-    if (!done && !budget_error) {
-      // equal scores straddle the threshold: the ids decide (all candidates share the score word)
-#pragma nounroll
-      for (int p2 = 0; p2 < 4 && !done; ++p2) {
-        const int shift = 24 - 8 * p2;
-        if (p2 == 0)
-          radix_pass_light<KPT>(sh, cand, evm, chosen, rank,
-                                      [&](int c) -> int { return (int)(kw[c] & 255u); },
-                                      [&](int c) -> int { return (int)(idw(c) >> 24); });
-        else
-          radix_pass_light<KPT>(sh, cand, evm, chosen, rank,
-                                      [&](int c) -> int { return (int)((idw(c) >> (shift + 8)) & 255u); },
-                                      [&](int c) -> int { return (int)((idw(c) >> shift) & 255u); });
-        chosen = sh.digit;
-        rank = sh.rank;
-        done = (rank == sh.bucket);
-        last_shift = shift;
-        last_id = true;
-      }
-    }
-    // the last pass's candidates are still unsettled
-    if (!budget_error) {
-      if (last_id) narrow([&](int c) -> int { return (int)((idw(c) >> last_shift) & 255u); });
-      else narrow([&](int c) -> int { return (int)((kw[c] >> last_shift) & 255u); });
-      (void)chosen;
-    }
-    if (done) evm.merge(cand);
-    if (budget_error) evm.clear();
-    if (bad) sh.bad = 1;
-    TSTAMP(10);
-    // evict bit per slot, published in slot order: the ballot of one chunk over one wave covers 64
-    // consecutive slots
-#pragma unroll
-    for (int c = 0; c < KPT; ++c)
-      if (c < n_chunks) {
-        const uint64_t bl = __ballot(evm.test(c));
-        if (lane == 0) {
-          sh.evmap[(c * kSelThreads >> 5) + 2 * wave] = (uint32_t)bl;
-          sh.evmap[(c * kSelThreads >> 5) + 2 * wave + 1] = (uint32_t)(bl >> 32);
-        }
-      }
-  } else {
   uint32_t pre_hi = 0, pre_lo = 0;
 #pragma nounroll
   for (; pass < 4 && !done; ++pass) {
     const int shift = 24 - 8 * pass;
-    radix_pass(sh, n_iter, rank, [&](int c) -> int {
+    radix_pass(sh, n_chunks, rank, [&](int c) -> int {
       const uint32_t w = word(c);
       if (w == kNotEvictable) return -1;
       if (pass > 0 && (w >> (shift + 8)) != (pre_hi >> (shift + 8))) return -1;
       return (int)((w >> shift) & 255u);
-    }, pass == 0 ? &ctrl->pad[20] : nullptr);
+    });
     if (pass == 0 && sh.n_evictable < n_evict) { budget_error = true; break; }   // |P| > B
     pre_hi |= sh.digit << shift;
     rank = sh.rank;
     done = (rank == sh.bucket);          // the whole bucket goes
     __syncthreads();
-    TSTAMP(2 + pass);
   }
   const int hi_shift = pass > 0 ? 24 - 8 * (pass - 1) : 24;
   int lo_shift = 32;                      // 32: ids did not have to be consulted
@@ -514,7 +397,7 @@ __device__ inline void select_phase(SelShared& sh, const Geom& g, const float* s
 #pragma nounroll
     for (int p2 = 0; p2 < 4 && !done; ++p2) {
       const int shift = 24 - 8 * p2;
-      radix_pass(sh, n_iter, rank, [&](int c) -> int {
+      radix_pass(sh, n_chunks, rank, [&](int c) -> int {
         if (word(c) != pre_hi) return -1;
         const uint32_t w = idw(c);
         if (p2 > 0 && (w >> (shift + 8)) != (pre_lo >> (shift + 8))) return -1;
@@ -528,7 +411,6 @@ __device__ inline void select_phase(SelShared& sh, const Geom& g, const float* s
     }
   }
   if (bad) sh.bad = 1;
-  TSTAMP(10);
 
   // evict bit per slot, published in slot order: the ballot of one chunk over one wave covers 64
   // consecutive slots
@@ -547,80 +429,263 @@ __device__ inline void select_phase(SelShared& sh, const Geom& g, const float* s
       sh.evmap[(c * kSelThreads >> 5) + 2 * wave + 1] = (uint32_t)(bl >> 32);
     }
   }
+  __syncthreads();
+  TSTAMP(11);
+  emit_moves(sh, g, ctrl, mvdst, mvsrc, evbits, n_total, budget_error, pass);
+}
+
+// ---- histogram selection -----------------------------------------------------------------------
+// The first radix level (the 11 bits below the sign of a score word, kSelHistBins bins) is counted
+// by every workgroup of the launch over its share of the cached entries, in an LDS histogram that
+// is flushed into the layer's counters in memory with one device-scope atomic per occupied bin; the
+// workgroup that selects adds the new frame's tokens, finds the threshold's bin, and then reads the
+// score words once: entries in lower bins go, entries in the bin become candidates (a bitmap, then
+// an LDS list) and are counted by their next 11 bits.  The second level usually leaves a handful of
+// keys, which one wave orders by (score word, inverted id).  Inputs that defeat this (more than
+// kCandCap keys in one first-level bin, more than kFinalCap keys equal in their leading 22 bits at
+// the threshold) take the streaming radix selection instead.  One CU executes this phase: 1024
+// threads cost 16 cycles per instruction slot, which is what bounds the pass over the score words.
+
+// Inclusive scan over the 2 * 1024 bin counts (thread t owns bins 2t and 2t+1): the bin that holds
+// the rank-th smallest key (sh.digit), the rank inside it (sh.rank), its size (sh.bucket) and the
+// total (sh.n_evictable).  rank > total leaves the first three unwritten.  Ends with a barrier.
+__device__ inline void pick_bin(SelShared& sh, uint32_t c0, uint32_t c1, uint32_t rank) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const uint32_t s = c0 + c1;
+  uint32_t inc = s;
+#pragma unroll
+  for (int off = 1; off < 64; off *= 2) {
+    const uint32_t y = __shfl_up(inc, off, 64);
+    if (lane >= off) inc += y;
+  }
+  if (lane == 63) sh.scan_tmp[0][wave] = inc;
+  __syncthreads();
+  uint32_t base = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < kSelWaves; ++w) {
+    const uint32_t t = sh.scan_tmp[0][w];
+    if (w < wave) base += t;
+    tot += t;
+  }
+  uint32_t before = base + inc - s;
+  if (before < rank && rank <= before + c0) { sh.digit = 2 * tid; sh.rank = rank - before; sh.bucket = c0; }
+  before += c0;
+  if (before < rank && rank <= before + c1) { sh.digit = 2 * tid + 1; sh.rank = rank - before; sh.bucket = c1; }
+  if (tid == 0) sh.n_evictable = tot;
+  __syncthreads();
+}
+
+// Every workgroup, before it announces its arrival, counts its share of the cached entries
+// [0, n_old) by first-level bin into `lh` (LDS, zero, a barrier behind the clearing).  Protected
+// entries do not take part.  The share's first two entries per thread are requested before the
+// frame's rows are scored (hist_share_load) and counted afterwards, so their latency hides there.
+struct HistShare { uint32_t w[2]; int next, end; };
+
+__device__ inline uint32_t evictable_word(float ssv, uint8_t flag) {
+  bool bad = false;                                     // bad scores are reported by the workgroup that selects
+  const uint32_t w = score_word(ssv, &bad);
+  return flag ? kNotEvictable : w;
+}
+
+__device__ inline HistShare hist_share_load(const float* ss, const uint8_t* flags, int n_old) {
+  HistShare h;
+  const int per = (n_old + (int)gridDim.x - 1) / (int)gridDim.x;
+  const int i0 = blockIdx.x * per + threadIdx.x;
+  h.end = min(((int)blockIdx.x + 1) * per, n_old);
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int i = i0 + j * kSelThreads;
+    const int ic = min(i, n_old - 1);                   // n_old >= 1 whenever a selection runs
+    const uint32_t w = evictable_word(ss[ic], flags[ic]);
+    h.w[j] = i < h.end ? w : kNotEvictable;
+  }
+  h.next = i0 + 2 * kSelThreads;
+  return h;
+}
+
+__device__ inline void hist_share_count(uint32_t* lh, const HistShare& h, const float* ss, const uint8_t* flags) {
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+    if (h.w[j] != kNotEvictable) atomicAdd(&lh[h.w[j] >> 20], 1u);
+  for (int i = h.next; i < h.end; i += kSelThreads) {
+    const uint32_t w = evictable_word(ss[i], flags[i]);
+    if (w != kNotEvictable) atomicAdd(&lh[w >> 20], 1u);
+  }
+}
+
+// Adds the occupied bins of `lh` to the layer's counters and leaves `lh` zero (a barrier in front).
+__device__ inline void hist_flush(uint32_t* lh, uint32_t* ghist) {
+  __syncthreads();
+#pragma unroll
+  for (int b = threadIdx.x; b < kSelHistBins; b += kSelThreads) {
+    const uint32_t v = lh[b];
+    if (v) {
+      __hip_atomic_fetch_add(&ghist[b], v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      lh[b] = 0u;
+    }
+  }
+}
+
+constexpr int kQuadBatch = 6;       // 16-byte score loads (4 slots each) a thread keeps in flight
+struct QuadBatch { float4 sv[kQuadBatch]; uint32_t fl[kQuadBatch]; };
+
+__device__ inline void select_hist(SelShared& sh, const Geom& g, const float* ss, const uint32_t* ids,
+                                   const uint8_t* flags, Ctrl* ctrl, uint32_t* mvdst, uint32_t* mvsrc,
+                                   uint32_t* evbits, uint32_t* ghist, int n_total) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n_old = n_total - g.M;
+  const uint32_t n_evict = (uint32_t)(n_total - g.B);
+  uint32_t* lh = sh.level[0];                           // first level, zero on entry
+  uint32_t* h2 = sh.level[1];                           // second level, zero on entry
+  uint32_t* cand_w = &sh.hist[0][0];                    // candidates: score word and slot
+  uint32_t* cand_slot = cand_w + kCandCap;
+  bool bad = false;
+  TSTAMP(1);
+  // first level: the other workgroups' counts of the cached entries, plus the frame's own tokens
+  const uint2 gh = *(const uint2*)(ghist + 2 * tid);
+  const int n_quads = (n_total + 3) >> 2;
+  auto load_batch = [&](QuadBatch& qb, int q0) {
+#pragma unroll
+    for (int j = 0; j < kQuadBatch; ++j) {
+      const int q = min(q0 + j * kSelThreads + tid, n_quads - 1);
+      qb.sv[j] = ((const float4*)ss)[q];
+      qb.fl[j] = ((const uint32_t*)flags)[q];
+    }
+  };
+  QuadBatch qb0;
+  if (tid == 0) { sh.bad = 0; sh.n_cand = 0; sh.n_final = 0; }
+  for (int wi = tid; wi < (n_total + 31) >> 5; wi += kSelThreads) sh.evmap[wi] = sh.candmap[wi] = 0u;   // a barrier follows below
+  for (int i0 = n_old + tid; i0 < n_total; i0 += 2 * kSelThreads) {    // two loads in flight per thread
+    uint32_t w[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int i = i0 + j * kSelThreads;
+      const int ic = min(i, n_total - 1);
+      const uint32_t x = evictable_word(ss[ic], flags[ic]);
+      w[j] = i < n_total ? x : kNotEvictable;
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+      if (w[j] != kNotEvictable) atomicAdd(&lh[w[j] >> 20], 1u);
+  }
+  load_batch(qb0, 0);                                   // in flight while the bin is picked
+  __syncthreads();
+  pick_bin(sh, gh.x + lh[2 * tid], gh.y + lh[2 * tid + 1], n_evict);
+  // the counters start the next frame at zero (written through; the values above are in registers)
+  __hip_atomic_store(&ghist[2 * tid], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __hip_atomic_store(&ghist[2 * tid + 1], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  const bool budget_error = sh.n_evictable < n_evict;   // |P| > B
+  const uint32_t bin1 = sh.digit, rank1 = sh.rank;
+  const bool all1 = rank1 == sh.bucket;                 // the whole bin goes
+  TSTAMP(2);
+  // One pass over the score words, four consecutive slots per thread and load, in batches of
+  // kQuadBatch loads per thread; the next batch is requested before the current one is used (the
+  // first one before the bin was picked).  Two bitmaps: "below the bin" (w < thr_lo: the entry
+  // goes) and "in the bin" (thr_lo <= w < thr_hi: a candidate).  Protected and absent slots carry
+  // the all-ones word, which is neither.
+  const uint32_t thr_lo = budget_error ? 0u : (all1 ? bin1 + 1u : bin1) << 20;
+  const uint32_t thr_hi = (budget_error || all1) ? thr_lo : thr_lo + (1u << 20);   // at most 2^31
+  auto use_batch = [&](const QuadBatch& qb, int q0) {
+#pragma unroll
+    for (int j = 0; j < kQuadBatch; ++j) {
+      const int q = q0 + j * kSelThreads + tid;
+      if (q < n_quads) {
+        const int base = q << 2, n_valid = n_total - base;
+        uint32_t w[4] = {__float_as_uint(qb.sv[j].x), __float_as_uint(qb.sv[j].y), __float_as_uint(qb.sv[j].z),
+                         __float_as_uint(qb.sv[j].w)};
+        const uint32_t w_max = max(max(w[0], w[1]), max(w[2], w[3]));
+        if (qb.fl[j] != 0u || n_valid < 4 || w_max > 0x7F800000u) {   // rare: protected, tail, NaN or negative
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const bool in_range = e < n_valid;
+            const bool odd = w[e] > 0x7F800000u;        // ranks lowest, reported
+            if (odd && in_range) bad = true;
+            if (odd) w[e] = 0u;
+            if (!in_range || ((qb.fl[j] >> (8 * e)) & 255u) != 0u) w[e] = kNotEvictable;
+          }
+        }
+        uint32_t nib_lo = 0, nib_hi = 0;
+#pragma unroll
+        for (int e = 3; e >= 0; --e) {
+          nib_lo = 2u * nib_lo + (w[e] < thr_lo ? 1u : 0u);
+          nib_hi = 2u * nib_hi + (w[e] < thr_hi ? 1u : 0u);
+        }
+        const uint32_t sft = base & 31;
+        if (nib_lo) atomicOr(&sh.evmap[base >> 5], nib_lo << sft);
+        if (nib_hi != nib_lo) atomicOr(&sh.candmap[base >> 5], (nib_hi ^ nib_lo) << sft);
+      }
+    }
+  };
+  constexpr int kStep = kQuadBatch * kSelThreads;
+  for (int q0 = 0; q0 < n_quads; q0 += 2 * kStep) {
+    QuadBatch qb1;
+    if (q0 + kStep < n_quads) load_batch(qb1, q0 + kStep);          // uniform
+    use_batch(qb0, q0);
+    if (q0 + 2 * kStep < n_quads) load_batch(qb0, q0 + 2 * kStep);
+    if (q0 + kStep < n_quads) use_batch(qb1, q0 + kStep);
+  }
+  if (bad) sh.bad = 1;
+  __syncthreads();
+  TSTAMP(5);
+  // the candidates (few) to a list, with their score words, and counted by their next 11 bits
+  for (int wi = tid; wi < (n_total + 31) >> 5; wi += kSelThreads) {
+    uint32_t bits = sh.candmap[wi];
+    while (bits) {
+      const uint32_t slot = ((uint32_t)wi << 5) + (uint32_t)__builtin_ctz(bits);
+      bits &= bits - 1;
+      const uint32_t b = __float_as_uint(ss[slot]);
+      const uint32_t w = b > 0x7F800000u ? 0u : b;
+      const uint32_t pos = atomicAdd(&sh.n_cand, 1u);
+      if (pos < (uint32_t)kCandCap) { cand_w[pos] = w; cand_slot[pos] = slot; }
+      atomicAdd(&h2[(w >> 9) & (kSelHistBins - 1)], 1u);
+    }
+  }
+  if (bad) sh.bad = 1;
+  __syncthreads();
+  TSTAMP(3);
+  const uint32_t n_cand = sh.n_cand;
+  bool fallback = n_cand > (uint32_t)kCandCap;
+  if (!fallback && n_cand > 0) {
+    // second level over the candidates (n_cand = the bin's size, rank1 of them go)
+    pick_bin(sh, h2[2 * tid], h2[2 * tid + 1], rank1);
+    const uint32_t bin2 = sh.digit, rank2 = sh.rank;
+    const bool all2 = rank2 == sh.bucket;
+    for (uint32_t e = tid; e < n_cand; e += kSelThreads) {
+      const uint32_t d2 = (cand_w[e] >> 9) & (kSelHistBins - 1), slot = cand_slot[e];
+      if (d2 < bin2 || (all2 && d2 == bin2)) atomicOr(&sh.evmap[slot >> 5], 1u << (slot & 31));
+      else if (d2 == bin2) {
+        const uint32_t pos = atomicAdd(&sh.n_final, 1u);
+        if (pos < (uint32_t)kFinalCap) sh.final_list[pos] = e;
+      }
+    }
+    __syncthreads();
+    TSTAMP(4);
+    const uint32_t n_final = sh.n_final;
+    fallback = n_final > (uint32_t)kFinalCap;
+    if (!fallback && n_final > 0 && wave == 0) {
+      // rank2 of these keys go: a key's position in the order is the number of smaller keys
+      uint32_t w = 0xFFFFFFFFu, inv = 0xFFFFFFFFu, slot = 0;
+      if ((uint32_t)lane < n_final) {
+        const uint32_t e = sh.final_list[lane];
+        w = cand_w[e]; slot = cand_slot[e];
+        inv = 0xFFFFFFFFu - ids[slot];
+      }
+      const uint64_t key = ((uint64_t)w << 32) | inv;
+      uint32_t below = 0;
+      for (uint32_t j = 0; j < n_final; ++j) {
+        const uint64_t kj = ((uint64_t)(uint32_t)__shfl((int)w, (int)j, 64) << 32) | (uint32_t)__shfl((int)inv, (int)j, 64);
+        below += kj < key ? 1u : 0u;
+      }
+      if ((uint32_t)lane < n_final && below < rank2) atomicOr(&sh.evmap[slot >> 5], 1u << (slot & 31));
+    }
+  }
+  if (fallback) {                                       // uniform: decided from shared counters behind a barrier
+    select_streaming(sh, g, ss, ids, flags, ctrl, mvdst, mvsrc, evbits, n_total);
+    return;
   }
   __syncthreads();
   TSTAMP(11);
-  // holes (evicted slot below B) and movers (kept slot at or above B), in slot order: a thread
-  // takes PP consecutive 32-slot words of the bitmap, one scan over the per-thread (holes, movers)
-  // counts gives it the list position of its first hole and first mover
-  const int n_words = (n_total + 31) >> 5;
-  const int PP = (n_words + kSelThreads - 1) / kSelThreads;      // <= 4
-  uint32_t hw[4], mw[4];
-  uint32_t nh = 0, nm = 0;
-  const bool wave_has_words = wave * 64 * PP < n_words;          // the other waves only keep the barriers company
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    hw[j] = mw[j] = 0u;
-    const int wi = tid * PP + j;
-    if (j < PP && wi < n_words) {
-      const int s0 = wi << 5;
-      const uint32_t e = sh.evmap[wi];
-      if (evbits) evbits[wi] = e;
-      const uint32_t below_b = s0 + 32 <= g.B ? 0xFFFFFFFFu : (s0 >= g.B ? 0u : ((1u << (g.B - s0)) - 1u));
-      const uint32_t below_n = s0 + 32 <= n_total ? 0xFFFFFFFFu : ((1u << (n_total - s0)) - 1u);
-      hw[j] = e & below_b;
-      mw[j] = ~e & ~below_b & below_n;
-      nh += __popc(hw[j]);
-      nm += __popc(mw[j]);
-    }
-  }
-  bool consistent = false;
-  {
-    uint32_t inc_h = nh, inc_m = nm;
-    if (wave_has_words) {
-#pragma unroll
-      for (int off = 1; off < 64; off *= 2) {
-        const uint32_t yh = __shfl_up(inc_h, off, 64), ym = __shfl_up(inc_m, off, 64);
-        if (lane >= off) { inc_h += yh; inc_m += ym; }
-      }
-    }
-    if (lane == 63) { sh.scan_tmp[0][wave] = inc_h; sh.scan_tmp[1][wave] = inc_m; }
-    __syncthreads();
-    if (wave_has_words) {
-      uint32_t base_h = 0, base_m = 0, tot_h = 0, tot_m = 0;
-#pragma unroll
-      for (int w = 0; w < kSelWaves; ++w) {
-        const uint32_t th = sh.scan_tmp[0][w], tm = sh.scan_tmp[1][w];
-        if (w < wave) { base_h += th; base_m += tm; }
-        tot_h += th; tot_m += tm;
-      }
-      consistent = !budget_error && tot_h == tot_m && tot_h <= (uint32_t)g.M;
-      if (tid == 0) sh.totals[0] = tot_h;
-      if (consistent) {
-        uint32_t hp = base_h + inc_h - nh, mp = base_m + inc_m - nm;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const uint32_t s0 = (uint32_t)(tid * PP + j) << 5;
-          uint32_t b = hw[j];
-          while (b) { mvdst[hp++] = s0 + (uint32_t)__builtin_ctz(b); b &= b - 1; }
-          b = mw[j];
-          while (b) { mvsrc[mp++] = s0 + (uint32_t)__builtin_ctz(b); b &= b - 1; }
-        }
-      }
-    }
-  }
-  __syncthreads();
-  if (tid == 0) {
-    ctrl->n_moves = consistent ? sh.totals[0] : 0u;
-    uint32_t st = 0;
-    if (budget_error || !consistent) st |= OVGGT_STATUS_BUDGET;
-    if (sh.bad) st |= OVGGT_STATUS_NONFINITE;
-    if (st) atomicOr(&ctrl->status, st);
-    TSTAMP(12);
-#ifdef OVGGT_TRACE
-    ctrl->pad[13] = (uint32_t)pass;
-#endif
-  }
+  emit_moves(sh, g, ctrl, mvdst, mvsrc, evbits, n_total, budget_error, 2);
 }
 
 // ---- Eq. 7: rank values of the evictable slots ----------------------------------------------------
@@ -660,9 +725,11 @@ __device__ inline void block_min_max(SelShared& sh, const uint8_t* flags, int n,
 // frame's diversity pass (both read-only here).  Every workgroup folds the few thousand pairs into
 // the same minimum and maximum (reading all d_i and flags instead, 80 KB per workgroup, made this
 // phase take 13.5 us instead of 4.8), then writes the rank values of its own share of slots over
-// their scores, written through like the scores of phase 1.
+// their scores, written through like the scores of phase 1, and counts them by first-level bin
+// into `lh`, which is zero and has a barrier behind its clearing.
 __device__ inline void hybrid_history_values(SelShared& sh, const HybridParams& hy, const float* dval,
-                                             const float2* part, float* ss, const uint8_t* flags, int n_old) {
+                                             const float2* part, float* ss, const uint8_t* flags, int n_old,
+                                             uint32_t* lh) {
 #pragma clang fp contract(off)
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   float lo = __builtin_inff(), hi = -__builtin_inff();
@@ -688,7 +755,10 @@ __device__ inline void hybrid_history_values(SelShared& sh, const HybridParams& 
   for (int i = blockIdx.x * per + threadIdx.x; i < i1; i += kSelThreads) {
     if (flags[i]) continue;
     const float unit = hi == lo ? 0.f : (dval[i] - lo) / range;
-    __hip_atomic_store(&ss[i], weight * unit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const float rv = weight * unit;
+    __hip_atomic_store(&ss[i], rv, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    bool bad = false;                                        // first-level count of this share
+    atomicAdd(&lh[score_word(rv, &bad) >> 20], 1u);
   }
 }
 
@@ -711,7 +781,7 @@ __device__ inline void hybrid_new_values(SelShared& sh, const HybridParams& hy, 
   __syncthreads();
 }
 
-template <bool BF16, int KPT, bool IDREG>
+template <bool BF16>
 __global__ void __launch_bounds__(kSelThreads)
 score_select_kernel(Geom g, SmoothParams sm, HybridParams hy, char* meta, int layer0, const char* resid, const uint8_t* anchors,
                     int n_total, int e_per_lane) {
@@ -729,13 +799,14 @@ score_select_kernel(Geom g, SmoothParams sm, HybridParams hy, char* meta, int la
 #ifdef OVGGT_TRACE
   if (blockIdx.x == 0 && tid == 0) ctrl->pad[15] = (uint32_t)wall_clock64();
 #endif
-  // Whichever workgroup ends up running the selection wants its histograms cleared: every
-  // workgroup does that now, in the shadow of phase 1's loads.
-  if (n_total > g.B) {
-    uint4* h4 = (uint4*)&sh.hist[0][0];
+  // The two histogram levels start at zero in every workgroup (each counts its share of the cache
+  // into the first, and whichever selects uses both); cleared in the shadow of phase 1's loads.
+  const bool selecting = n_total > g.B;
+  HistShare share = {};
+  if (selecting) {
     const uint4 z = {0u, 0u, 0u, 0u};
-    h4[tid] = z; h4[tid + kSelThreads] = z;                       // rows 0..127
-    ((uint4*)&sh.wave_hist[0][0])[tid] = z;
+    ((uint4*)&sh.level[0][0])[tid] = z;
+    if (!hy.on) share = hist_share_load(ss, flags, n_old);     // used after the rows are scored
   }
   // ---- phase 1: scores and flags of the M new slots
   {
@@ -755,8 +826,18 @@ score_select_kernel(Geom g, SmoothParams sm, HybridParams hy, char* meta, int la
       default: if (many) score_rows<64, BF16, kRowsPerWave>(rbase, row_bytes, g.C, g.M, al, sn, fn); else score_rows<64, BF16, 1>(rbase, row_bytes, g.C, g.M, al, sn, fn); break;
     }
   }
-  if (hy.on && n_total > g.B)
-    hybrid_history_values(sh, hy, (const float*)(mb + g.off_dval), (const float2*)(mb + g.off_dpart), ss, flags, n_old);
+  // first histogram level of this workgroup's share of the cached entries, added to the layer's counters
+  uint32_t* lh = sh.level[0];
+  uint32_t* ghist = (uint32_t*)(mb + g.off_hist);
+  if (selecting) {
+    if (hy.on)
+      hybrid_history_values(sh, hy, (const float*)(mb + g.off_dval), (const float2*)(mb + g.off_dpart), ss, flags, n_old, lh);
+    else {
+      __syncthreads();                         // the histogram was cleared when the kernel started
+      hist_share_count(lh, share, ss, flags);
+    }
+    hist_flush(lh, ghist);
+  }
   const bool smoothing = sm.alpha > 0.f;
   if (n_total <= g.B && !smoothing) {        // under budget and no smoothing: nothing needs the whole frame
     if (blockIdx.x == 0 && tid == 0) ctrl->n_moves = 0;
@@ -795,14 +876,14 @@ score_select_kernel(Geom g, SmoothParams sm, HybridParams hy, char* meta, int la
   }
   if (hy.on) hybrid_new_values(sh, hy, smoothing, ss, flags, n_old, n_total);
   // hybrid scoring keeps the evict bitmap: the centroid's maintenance reads it
-  select_phase<KPT, IDREG>(sh, g, ss, ids, flags, ctrl, mvdst, mvsrc,
-                           hy.on ? (uint32_t*)(mb + g.off_evbits) : nullptr, n_total);
+  uint32_t* evbits = hy.on ? (uint32_t*)(mb + g.off_evbits) : nullptr;
+  select_hist(sh, g, ss, ids, flags, ctrl, mvdst, mvsrc, evbits, ghist, n_total);
 }
 
 template <bool BF16>
 static void launch_variant(const Geom& g, const SmoothParams& sm, const HybridParams& hy, char* meta, int layer0, int nl, const void* resid,
                            const uint8_t* anchors, int n_total, int e, hipStream_t s) {
-  // One workgroup fits a CU (the selection's register-resident keys set the footprint), so the
+  // One workgroup fits a CU (1024 threads and the selection's LDS set the footprint), so the
   // launch stays within one round of the chip: a single layer spreads its rows one per wave, a
   // batch of layers gives each workgroup several rounds of kRowsPerWave rows per wave.
   static const int n_cus = [] {                       // once per process (thread-safe initialisation)
@@ -815,16 +896,8 @@ static void launch_variant(const Geom& g, const SmoothParams& sm, const HybridPa
   int gx = (g.M + kSelWaves - 1) / kSelWaves;
   if ((long)gx * nl > n_cus) gx = n_cus / nl > 0 ? n_cus / nl : 1;
   dim3 grid((unsigned)gx, (unsigned)nl);
-  const int n_chunks = (n_total + kSelThreads - 1) / kSelThreads;
-#define OVGGT_SEL_LAUNCH(KPT, IDREG)                                                                  \
-  hipLaunchKernelGGL((score_select_kernel<BF16, KPT, IDREG>), grid, dim3(kSelThreads), 0, s, g, sm, hy, meta, \
-                     layer0, (const char*)resid, anchors, n_total, e)
-  // the variant only matters when a selection will run (n_total > B)
-  if (n_total <= g.B || n_chunks <= 8) OVGGT_SEL_LAUNCH(8, true);
-  else if (n_chunks <= 20) OVGGT_SEL_LAUNCH(20, true);
-  else if (n_chunks <= 36) OVGGT_SEL_LAUNCH(36, false);      // ids stay in memory: fetched only for keys whose equal scores straddle the threshold
-  else OVGGT_SEL_LAUNCH(0, false);                           // (72 keys per thread in registers measured slower than streaming)
-#undef OVGGT_SEL_LAUNCH
+  hipLaunchKernelGGL((score_select_kernel<BF16>), grid, dim3(kSelThreads), 0, s, g, sm, hy, meta,
+                     layer0, (const char*)resid, anchors, n_total, e);
 }
 
 hipError_t launch_score_select(const Geom& g, const SmoothParams& sm, const HybridParams& hy, char* meta, int layer0, int nl, const void* resid,

@@ -392,6 +392,74 @@ def test_import_export_and_crafted_scores():
     cache.close()
 
 
+@pytest.mark.parametrize("regime,M,Bq", [(r, 256, 12000) for r in (
+    "spread", "few_ties", "many_ties", "one_bin", "all_equal", "whole_bin", "two_levels_equal", "protected_low")] + [
+    ("spread", 1041, 65536), ("many_ties", 1041, 65536), ("one_bin", 1041, 65536), ("protected_low", 1374, 32768)])
+def test_selection_threshold_regimes(regime, M, Bq):
+    """Hand-made score populations around the eviction threshold, one per branch of the
+    selection: a threshold among distinct keys, among a few or among hundreds of equal scores
+    (ids decide), every key within one leading-bits bin, all scores equal, a threshold on a bin
+    boundary, keys that agree in their 22 leading bits, and low scores that are protected; also
+    at the cache sizes of the largest workloads."""
+    H, d, C = 1, 64, 64
+    cfg = synth.preset(0, M=M, B=Bq, H=H, C=C, T=1, dtype="f32", n_special=1)
+    rng = np.random.default_rng(11)
+    n = Bq
+    frames_seen = (n + M - 1) // M + 3
+    ids = rng.permutation(frames_seen * M)[:n].astype(np.uint32)
+    flags = np.zeros(n, np.uint8)
+    spread = np.exp(rng.standard_normal(n)).astype(np.float32) + np.float32(4.0)      # all above 4
+    ss = spread.copy()
+    low = rng.permutation(n)                                                          # slots that get the low keys
+    ramp = lambda m: (1.0 + np.arange(m) / 4096.0).astype(np.float32)          # m distinct keys in [1, 1.5)
+    if regime == "few_ties":          # M - 20 distinct low keys, then 40 equal ones: 20 of them go
+        ss[low[:M - 20]] = ramp(M - 20)
+        ss[low[M - 20:M + 20]] = np.float32(2.5)
+    elif regime == "many_ties":       # 300 equal keys straddle the threshold
+        ss[low[:M - 156]] = ramp(M - 156)
+        ss[low[M - 156:M + 144]] = np.float32(2.5)
+    elif regime == "one_bin":         # every cached key shares sign, exponent and three mantissa bits
+        ss = (1.0 + rng.permutation(n) * 2.0 ** -20).astype(np.float32)
+    elif regime == "all_equal":
+        ss[:] = np.float32(3.0)
+    elif regime == "whole_bin":       # exactly M keys in [1.5, 1.625), the rest from 4.0 up
+        ss[low[:M]] = (1.5 + rng.random(M) * 0.12).astype(np.float32)
+    elif regime == "two_levels_equal":  # 90 keys that differ only below bit 9 of the score word
+        ss[low[:M - 56]] = ramp(M - 56)
+        ss[low[M - 56:M + 34]] = (np.float32(2.5).view(np.uint32) + rng.permutation(90).astype(np.uint32)).view(np.float32)
+    elif regime == "protected_low":   # 300 of the lowest keys are protected: they stay, others go
+        ss[low[:M + 444]] = ramp(M + 444)
+        flags[low[:300]] = 1
+    k = rng.standard_normal((n, H, d)).astype(np.float32); v = rng.standard_normal((n, H, d)).astype(np.float32)
+    cache = make_cache(cfg)
+    cache.import_(0, frames_seen, ids, k, v, ss, flags)
+    orc = oc.OracleCache(cfg.M, cfg.H, cfg.d, cfg.B)
+    orc.k, orc.v, orc.gid, orc.ss, orc.flag, orc.t = k.copy(), v.copy(), ids.copy(), ss.copy(), flags.copy(), frames_seen
+    torch = _torch()
+    f = synth.frame_inputs(cfg, 0, frames_seen)
+    r = np.zeros((M, C), np.float32)
+    r[:, 0] = np.float32(100.0)                               # new tokens: ss = 10 000, all stay ...
+    if regime == "all_equal":                                 # ... unless they tie with the cache: ss = 3 exactly
+        r[:, 0] = np.float32(1.0); r[:, 1] = np.float32(1.0); r[:, 2] = np.float32(1.0)
+    if regime == "spread":
+        r[:, 0] = np.exp(rng.standard_normal(M)).astype(np.float32) + np.float32(2.0)
+    f["r"] = r
+    a = np.zeros(M, np.uint8)
+    out = cache.new_output()[0]
+    cache.step(dev(f["q"], cfg), dev(f["k"], cfg), dev(f["v"], cfg), dev(r, cfg), torch.from_numpy(a).cuda(), out, layer=0)
+    ref = orc.step(f["q"], f["k"], f["v"], r, a)
+    assert rel_err(out.cpu().numpy().astype(np.float64), ref) < TOL["f32"]
+    compare_cache(cache, orc)
+    assert cache.status(0) == 0
+    # a second frame on top of the compacted cache (layout and scores carry over)
+    f2 = synth.frame_inputs(cfg, 0, frames_seen + 1)
+    r2 = r.copy(); r2[:, 0] = (r[:, 0] * np.float32(0.5)) if regime == "spread" else r[:, 0]
+    cache.step(dev(f2["q"], cfg), dev(f2["k"], cfg), dev(f2["v"], cfg), dev(r2, cfg), torch.from_numpy(a).cuda(), out, layer=0)
+    orc.step(f2["q"], f2["k"], f2["v"], r2, a)
+    compare_cache(cache, orc)
+    cache.close()
+
+
 @pytest.mark.parametrize("dtype,ph,pw,ns,H,C,B_,alpha", [
     ("bf16", 9, 13, 5, 2, 256, 500, 0.5),       # budget not a multiple of the frame, eviction from frame 4 on
     ("f32", 6, 7, 2, 2, 96, 130, 0.25),
