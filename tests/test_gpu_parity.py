@@ -204,6 +204,41 @@ def test_cfg3_full_budget_sampled():
     print("cfg3 worst sampled attention err/RMS:", worst)
 
 
+@pytest.mark.parametrize("preset,budget,evicting_frames", [(1, 16384, 300), (3, 32768, 500), (4, 65536, 250)])
+def test_full_size_streams_kept_ids_deep_into_eviction(preset, budget, evicting_frames):
+    """The two largest caches of the workload list at full size, well past the first eviction:
+    kept ids, slot layout, scores and flags bit-exact after every frame.  The cache policy of the
+    stored-score mode depends on residual rows and anchor bits only, so the oracle runs on a
+    one-element K/V (its attention is not used here) and the device side reuses one frame's
+    Q/K/V; the other full-size tests cover attention and the K/V moves."""
+    torch = _torch()
+    cfg = synth.preset(preset, B=budget)
+    T = budget // cfg.M + 1 + evicting_frames
+    cache = make_cache(cfg, L=1)
+    orc = oc.OracleCache(cfg.M, 1, 1, cfg.B)
+    out = cache.new_output()[0]
+    f0 = synth.frame_inputs(cfg, 0, 0, want=("q", "k", "v"))
+    q, k, v = (dev(f0[x], cfg) for x in "qkv")
+    zk = np.zeros((cfg.M, 1, 1), np.float32)
+    for t in range(T):
+        f = synth.frame_inputs(cfg, 0, t, want=("r", "a"))
+        cache.step(q, k, v, dev(f["r"], cfg), torch.from_numpy(f["a"]).to("cuda:0"), out, layer=0)
+        orc.append(zk, zk)
+        orc.update(f["r"], f["a"])
+        n = cache.size(0)
+        assert n == orc.n == min((t + 1) * cfg.M, cfg.B)
+        if t * cfg.M >= cfg.B - cfg.M or t % 8 == 0:           # every evicting frame, some of the warm-up
+            ids = np.zeros(n, np.uint32); ss = np.zeros(n, np.float32); flags = np.zeros(n, np.uint8)
+            B.ovggt_cache_export(cache.h, 0, ids, None, None, ss, flags, cache.stream)
+            assert np.array_equal(ids, orc.gid), f"frame {t}: kept ids / layout differ"
+            assert np.array_equal(ss.view(np.uint32), orc.ss.view(np.uint32)), f"frame {t}: scores differ"
+            assert np.array_equal(flags, orc.flag), f"frame {t}: flags differ"
+        if t % 10 == 0:
+            print(f"[full-size preset {preset}] frame {t} ok", flush=True)
+    assert cache.status(0) == 0
+    cache.close()
+
+
 def test_cfg2_full_size_24_layers_batched_sampled():
     """The 24-layer workload in the launch shape the benchmark times (all layers per call, 192 head
     pairs dealt out to the XCDs round by round).  Three distinct input streams are spread over the
