@@ -495,14 +495,15 @@ def test_selection_threshold_regimes(regime, M, Bq):
     cache.close()
 
 
-def _random_population_case(seed):
+def _random_population_case(seed, M=None, Bq=None):
     """One seeded cache population (frame size, budget, score distribution, ties, protected share
     all drawn at random), three frames of selection on top of it; True if ids, layout, scores and
     flags equal the oracle's after every frame."""
     torch = _torch()
     rng = np.random.default_rng(seed)
-    M = int(rng.choice([1, 3, 16, 17, 64, 100, 256, 700, 1041, 1374, 2100]))
-    Bq = max(M, int(rng.choice([M, M + 1, 2 * M + 5, 1000, 4096, 9000, 20000, 40000, 70000])))
+    M_ = int(rng.choice([1, 3, 16, 17, 64, 100, 256, 700, 1041, 1374, 2100]))
+    B_ = max(M_, int(rng.choice([M_, M_ + 1, 2 * M_ + 5, 1000, 4096, 9000, 20000, 40000, 70000])))
+    M, Bq = (M_, B_) if M is None else (M, Bq)
     H, d, C = 1, 64, 64
     n = Bq
     frames_seen = (n + M - 1) // M + 3
@@ -557,6 +558,15 @@ def _random_population_case(seed):
             np.array_equal(gs.view(np.uint32), orc.ss.view(np.uint32)) and np.array_equal(gf, orc.flag)
     cache.close()
     return ok
+
+
+def test_selection_at_the_largest_cache_the_library_accepts():
+    """B + M = 131 072 slots (the limit the configuration check enforces), every score distribution."""
+    bad = [seed for seed in range(12) if not _random_population_case(seed, M=2048, Bq=131072 - 2048)]
+    assert not bad, f"selection differs from the oracle for seeds {bad}"
+    cfg = B.make_config(1, 1, 64, 2048, 64, 131072 - 2047, "f32")          # one slot more: rejected
+    with pytest.raises(B.OvggtError):
+        B.ovggt_cache_query_bytes(cfg)
 
 
 def test_selection_random_populations():
