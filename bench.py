@@ -53,12 +53,16 @@ def profiled_figure(what, kernel, workload, layers):
     return None
 
 
-def cpu_baseline(cfg, warm_frames, timed_frames, smooth=None, hybrid_beta=None):
+def cpu_baseline(cfg, warm_frames, timed_frames, smooth=None, hybrid_beta=None, threads=None):
     """The oracle as it stands: attention-free warm-up to reach the steady-state
-    cache, then whole steps (fp64 attention + score + select + compact) timed."""
+    cache, then whole steps (fp64 attention + score + select + compact) timed.
+    threads: cap on the BLAS thread pool (None: whatever the box gives)."""
     from oracle import ovggt_oracle as oc            # cpu_baseline leg only
+    limit = None
     try:
         import threadpoolctl
+        if threads:
+            limit = threadpoolctl.threadpool_limits(limits=int(threads))
         cores = max((p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()), default=1)
     except Exception:
         cores = os.cpu_count() or 1
@@ -72,6 +76,8 @@ def cpu_baseline(cfg, warm_frames, timed_frames, smooth=None, hybrid_beta=None):
     for f in fs:
         orc.step(f["q"], f["k"], f["v"], f["r"], f["a"])
     dt = time.perf_counter() - t0
+    if limit is not None:
+        limit.restore_original_limits()
     return {"value": timed_frames / dt, "unit": "frames/s", "cores": int(cores), "kind": "oracle",
             "sample": f"{timed_frames} steady-state frames (t={warm_frames}..{warm_frames + timed_frames - 1}, "
                       f"{orc.n + cfg.M} resident keys) of the same workload, layer 0, after an attention-free "
@@ -93,6 +99,7 @@ def main():
                     help="activation smoothing (Eq. 6) with this alpha and a 3x3 Gaussian (sigma 1) over the patch map")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-frames", type=int, default=12)
+    ap.add_argument("--cpu-threads", type=int, default=None, help="cap the oracle's BLAS threads (default: all the box gives)")
     ap.add_argument("--detail-steps", type=int, default=40, help="extra untimed steps with per-kernel events")
     ap.add_argument("--flatness", action="store_true",
                     help="also bracket every 8th timed step with events and report the slope of step latency over the stream")
@@ -288,7 +295,7 @@ def main():
     cache.close()
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(cfg, warm_frames=max(cfg.B // cfg.M + 2, 2), timed_frames=args.cpu_frames,
-                                           smooth=smooth, hybrid_beta=args.hybrid_beta)
+                                           smooth=smooth, hybrid_beta=args.hybrid_beta, threads=args.cpu_threads)
     print(json.dumps(res))
 
 
