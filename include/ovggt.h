@@ -154,8 +154,19 @@ int ovggt_score_select(ovggt_cache* c, int layer, const void* resid, const uint8
  * r-th surviving slot at or above B (ascending), for K, V, ids, scores and
  * flags; the layer then holds min(n+M, B) entries.  Sources and destinations
  * are disjoint, so the rewrite is in place.  ERR_STATE unless ovggt_score_select
- * was the previous call for the layer. */
+ * was the previous call for the layer.
+ * The sources are exactly the slots the next frame's append overwrites, so the
+ * copy is enqueued with that append (one launch and one pass over those slots
+ * less per frame) on the stream of that ovggt_global_attn call; every other
+ * entry point that reads or changes the cache (export, import, set_protect,
+ * ovggt_cache_flush) applies it first, on its own stream.  Through this
+ * interface the cache always reads as compacted; only a caller that inspects
+ * the device buffers directly needs ovggt_cache_flush. */
 int ovggt_cache_compact(ovggt_cache* c, int layer, void* hip_stream);
+
+/* Enqueues any compaction of `layer` (or OVGGT_ALL_LAYERS) that has not been
+ * applied yet, as a launch of its own on `hip_stream`.  No-op otherwise. */
+int ovggt_cache_flush(ovggt_cache* c, int layer, void* hip_stream);
 
 /* Frees the host handle (device buffers stay with the caller). */
 int ovggt_cache_destroy(ovggt_cache* c);

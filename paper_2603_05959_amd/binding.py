@@ -24,7 +24,7 @@ EXPORTS = (
     "ovggt_cache_status", "ovggt_cache_export", "ovggt_cache_import", "ovggt_cache_last_moves",
     "ovggt_profile_enable", "ovggt_profile_read", "ovggt_profile_overhead", "ovggt_strerror",
     "ovggt_cache_set_protect", "ovggt_dap_create", "ovggt_dap_step", "ovggt_dap_active", "ovggt_dap_destroy",
-    "ovggt_attn_plan_stats",
+    "ovggt_attn_plan_stats", "ovggt_cache_flush",
 )
 PROF_CLASSES = ("append", "attn", "combine", "score_select", "compact")
 
@@ -64,6 +64,7 @@ def lib() -> C.CDLL:
     L.ovggt_global_attn.argtypes = [vp, C.c_int, vp, vp, vp, vp, vp]
     L.ovggt_score_select.argtypes = [vp, C.c_int, vp, u8p, vp]
     L.ovggt_cache_compact.argtypes = [vp, C.c_int, vp]
+    L.ovggt_cache_flush.argtypes = [vp, C.c_int, vp]
     L.ovggt_cache_destroy.argtypes = [vp]
     L.ovggt_cache_size.argtypes = [vp, C.c_int, C.POINTER(i32)]
     L.ovggt_cache_frames.argtypes = [vp, C.c_int, C.POINTER(i64)]
@@ -150,6 +151,10 @@ def ovggt_score_select(h, layer, resid, anchor_flags, stream: int = 0) -> None:
 
 def ovggt_cache_compact(h, layer, stream: int = 0) -> None:
     _check(lib().ovggt_cache_compact(h, layer, stream), "ovggt_cache_compact")
+
+
+def ovggt_cache_flush(h, layer, stream: int = 0) -> None:
+    _check(lib().ovggt_cache_flush(h, layer, stream), "ovggt_cache_flush")
 
 
 def ovggt_cache_destroy(h) -> None:
@@ -290,6 +295,9 @@ class Cache:
 
     def compact(self, layer=OVGGT_ALL_LAYERS):
         ovggt_cache_compact(self.h, layer, self.stream)
+
+    def flush(self, layer=OVGGT_ALL_LAYERS):
+        ovggt_cache_flush(self.h, layer, self.stream)
 
     def step(self, q, k_new, v_new, resid, anchor_flags, out, layer=OVGGT_ALL_LAYERS):
         self.global_attn(q, k_new, v_new, out, layer)

@@ -41,6 +41,12 @@ hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
 // --------------------------------------------------------------------------
 // Append.  Input rows are token-major [M][H][d]; the cache is head-major
 // [H][cap][d].  One thread per 16-byte piece of K and of V.
+// MOVES: the compaction that follows the previous frame's selection has not been applied yet
+// (n == B).  Its sources are exactly the slots this frame overwrites, so the thread that owns a
+// piece of slot B + m first carries the piece it finds there to the slot the selection assigned
+// (below B, disjoint from every slot written here), then stores the new one: no other thread
+// reads or writes either location.
+template <bool MOVES>
 __global__ void __launch_bounds__(256)
 append_kernel(Geom g, char* kv, char* meta, int layer0, const char* k_new, const char* v_new,
               int n, uint32_t gid0) {
@@ -69,6 +75,29 @@ append_kernel(Geom g, char* kv, char* meta, int layer0, const char* k_new, const
   uint4 kk = *(const uint4*)(k_new + src);
   uint4 vv = *(const uint4*)(v_new + src);
   char* mb = layer_meta(meta, g, layer);
+  if constexpr (MOVES) {
+    const uint32_t to = ((const uint32_t*)(mb + g.off_mvmap))[m];
+    if (to < (uint32_t)g.B) {                        // kNoMove, or anything out of range: nothing to carry
+      const size_t mv = ((size_t)h * g.cap + to) * row_bytes + piece * 16;
+      const uint4 ok = *(const uint4*)(layer_k(kv, g, layer) + dst);
+      const uint4 ov = *(const uint4*)(layer_v(kv, g, layer) + dst);
+      uint32_t id = 0; float sc = 0.f; uint8_t fl = 0;
+      const bool meta_thread = h == 0 && piece == 0;
+      if (meta_thread) {
+        id = ((const uint32_t*)(mb + g.off_ids))[n + m];
+        sc = ((const float*)(mb + g.off_ss))[n + m];
+        fl = ((const uint8_t*)(mb + g.off_flags))[n + m];
+      }
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the old contents are in registers before anything is stored
+      *(uint4*)(layer_k(kv, g, layer) + mv) = ok;
+      *(uint4*)(layer_v(kv, g, layer) + mv) = ov;
+      if (meta_thread) {
+        ((uint32_t*)(mb + g.off_ids))[to] = id;
+        ((float*)(mb + g.off_ss))[to] = sc;
+        ((uint8_t*)(mb + g.off_flags))[to] = fl;
+      }
+    }
+  }
   if (g.esize == 2) {
     bool clipped = false;
     kk.x = bf16pair_to_half(kk.x, &clipped); kk.y = bf16pair_to_half(kk.y, &clipped);
@@ -87,11 +116,17 @@ append_kernel(Geom g, char* kv, char* meta, int layer0, const char* k_new, const
 }
 
 hipError_t launch_append(const Geom& g, char* kv, char* meta, int layer0, int nl,
-                         const void* k_new, const void* v_new, int n, uint32_t gid0, hipStream_t s) {
+                         const void* k_new, const void* v_new, int n, uint32_t gid0, bool apply_moves, hipStream_t s) {
   const size_t total = (size_t)g.M * g.H * (g.d * g.esize / 16);
   dim3 grid((unsigned)((total + 255) / 256), (unsigned)nl);
-  hipLaunchKernelGGL(append_kernel, grid, dim3(256), 0, s, g, kv, meta, layer0,
-                     (const char*)k_new, (const char*)v_new, n, gid0);
+  if (apply_moves && n == g.B)
+    hipLaunchKernelGGL(append_kernel<true>, grid, dim3(256), 0, s, g, kv, meta, layer0,
+                       (const char*)k_new, (const char*)v_new, n, gid0);
+  else if (apply_moves)
+    return hipErrorInvalidValue;                     // a pending compaction implies a full cache
+  else
+    hipLaunchKernelGGL(append_kernel<false>, grid, dim3(256), 0, s, g, kv, meta, layer0,
+                       (const char*)k_new, (const char*)v_new, n, gid0);
   return hipGetLastError();
 }
 

@@ -25,6 +25,8 @@ struct ovggt_cache {
   std::vector<int32_t> n;          // resident (incl. pending) slots per layer
   std::vector<int64_t> frames;     // completed frames per layer
   std::vector<int8_t> phase;       // 0: expects global_attn, 1: score_select, 2: compact
+  std::vector<int8_t> pending;     // 1: the layer's last move list has not been applied yet (n == B); the next
+                                   // append applies it, anything else that touches the cache flushes it first
   // optional kernel timing (ovggt_profile_*): event pairs per kernel class
   int prof_level = 0, prof_every = 1;
   int64_t prof_calls = 0;
@@ -118,6 +120,7 @@ void make_geom(const ovggt_config& c, Geom* g) {
   g->off_cvec = off;  off += up256((size_t)4 * g->H * g->d);
   g->off_dval = off;  off += c.score_mode == 1 ? up256((size_t)4 * g->cap) : 0;
   g->off_dpart = off; off += c.score_mode == 1 ? up256((size_t)8 * kDivWavesPerWg * diversity_grid_x(g->cap, 1)) : 0;
+  g->off_mvmap = off; off += up256((size_t)4 * g->M);
   g->off_hist = off;  off += up256((size_t)4 * kSelHistBins);
   g->hybrid = c.score_mode == 1 ? 1 : 0;
   g->meta_layer_bytes = off;
@@ -181,6 +184,19 @@ struct ProfScope {
   }
 };
 
+// Applies the outstanding compactions of layers [l0, l0+nl) with the stand-alone kernel.
+int flush_pending(ovggt_cache* c, int l0, int nl, hipStream_t s) {
+  for (int l = l0; l < l0 + nl;) {
+    if (!c->pending[l]) { ++l; continue; }
+    int e = l;
+    while (e < l0 + nl && c->pending[e]) ++e;
+    ProfScope ps(c, OVGGT_PROF_COMPACT, s, c->prof_level >= 2);
+    if (launch_compact(c->g, c->kv, c->meta, l, e - l, s) != hipSuccess) return OVGGT_ERR_HIP;
+    for (; l < e; ++l) c->pending[l] = 0;
+  }
+  return OVGGT_OK;
+}
+
 inline Ctrl* ctrl_of(const ovggt_cache* c, int layer) {
   return (Ctrl*)(layer_meta(c->meta, c->g, layer) + c->g.off_ctrl);
 }
@@ -228,6 +244,7 @@ int ovggt_cache_init(ovggt_cache** out, const ovggt_config* cfg, void* kv_dev, v
   c->n.assign(c->g.L, 0);
   c->frames.assign(c->g.L, 0);
   c->phase.assign(c->g.L, 0);
+  c->pending.assign(c->g.L, 0);
   hipStream_t s = (hipStream_t)hip_stream;
   if (launch_fill_zero(c->kv, c->g.kv_layer_bytes * c->g.L, s) != hipSuccess ||
       launch_fill_zero(c->meta, c->g.meta_layer_bytes * c->g.L, s) != hipSuccess ||
@@ -254,11 +271,19 @@ int ovggt_global_attn(ovggt_cache* c, int layer, const void* q, const void* k_ne
   hipStream_t s = (hipStream_t)hip_stream;
   const bool prof_attn = c->prof_level >= 1 && (c->prof_calls++ % c->prof_every) == 0;
   const bool prof_all = c->prof_level >= 2;
+  // an outstanding compaction rides along with the append when every layer of the call has one
+  bool all_pending = true, any_pending = false;
+  for (int l = l0; l < l0 + nl; ++l) { all_pending = all_pending && c->pending[l]; any_pending = any_pending || c->pending[l]; }
+  if (any_pending && !all_pending) {
+    if (flush_pending(c, l0, nl, s) != OVGGT_OK) return OVGGT_ERR_HIP;
+    all_pending = false;
+  }
   {
     ProfScope ps(c, OVGGT_PROF_APPEND, s, prof_all);
-    if (launch_append(g, c->kv, c->meta, l0, nl, k_new, v_new, n, (uint32_t)gid0, s) != hipSuccess)
+    if (launch_append(g, c->kv, c->meta, l0, nl, k_new, v_new, n, (uint32_t)gid0, all_pending, s) != hipSuccess)
       return OVGGT_ERR_HIP;
   }
+  for (int l = l0; l < l0 + nl; ++l) c->pending[l] = 0;
   hipError_t e;
   if (g.esize == 2) {
     hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
@@ -314,16 +339,21 @@ int ovggt_cache_compact(ovggt_cache* c, int layer, void* hip_stream) {
   if (!layer_range(c, layer, &l0, &nl)) return OVGGT_ERR_ARG;
   if (!uniform(c, l0, nl, 2)) return OVGGT_ERR_STATE;
   const Geom& g = c->g;
-  if (c->n[l0] > g.B) {
-    ProfScope ps(c, OVGGT_PROF_COMPACT, (hipStream_t)hip_stream, c->prof_level >= 2);
-    if (launch_compact(g, c->kv, c->meta, l0, nl, (hipStream_t)hip_stream) != hipSuccess) return OVGGT_ERR_HIP;
-  }
+  // The move list is applied by the next frame's append (same pass over the same slots), or by the
+  // stand-alone kernel as soon as anything else reads or changes the cache.
   for (int l = l0; l < l0 + nl; ++l) {
-    if (c->n[l] > g.B) c->n[l] = g.B;
+    if (c->n[l] > g.B) { c->n[l] = g.B; c->pending[l] = 1; }
     c->frames[l] += 1;
     c->phase[l] = 0;
   }
   return OVGGT_OK;
+}
+
+int ovggt_cache_flush(ovggt_cache* c, int layer, void* hip_stream) {
+  if (!c) return OVGGT_ERR_ARG;
+  int l0, nl;
+  if (!layer_range(c, layer, &l0, &nl)) return OVGGT_ERR_ARG;
+  return flush_pending(c, l0, nl, (hipStream_t)hip_stream);
 }
 
 int ovggt_cache_set_protect(ovggt_cache* c, int layer, int64_t frame, const uint8_t* mask, int on,
@@ -336,6 +366,7 @@ int ovggt_cache_set_protect(ovggt_cache* c, int layer, int64_t frame, const uint
   const Geom& g = c->g;
   const uint32_t gid_lo = (uint32_t)(frame * (int64_t)g.M);          // fits: the frame has been appended
   hipStream_t s = (hipStream_t)hip_stream;
+  if (flush_pending(c, l0, nl, s) != OVGGT_OK) return OVGGT_ERR_HIP;
   if (g.hybrid && launch_centroid_protect(g, c->kv, c->meta, l0, nl, c->n[l0], gid_lo, mask, on, s) != hipSuccess)
     return OVGGT_ERR_HIP;
   if (launch_set_protect(g, c->meta, l0, nl, c->n[l0], gid_lo, mask, on, s) != hipSuccess) return OVGGT_ERR_HIP;
@@ -376,6 +407,7 @@ int ovggt_cache_status(ovggt_cache* c, int layer, int32_t* status, void* hip_str
 int ovggt_cache_export(ovggt_cache* c, int layer, uint32_t* ids, void* k, void* v, float* ss,
                        uint8_t* flags, void* hip_stream) {
   if (!c || layer < 0 || layer >= c->g.L) return OVGGT_ERR_ARG;
+  if (flush_pending(c, layer, 1, (hipStream_t)hip_stream) != OVGGT_OK) return OVGGT_ERR_HIP;
   if (hipStreamSynchronize((hipStream_t)hip_stream) != hipSuccess) return OVGGT_ERR_HIP;
   const Geom& g = c->g;
   const int n = c->n[layer];
@@ -413,6 +445,7 @@ int ovggt_cache_import(ovggt_cache* c, int layer, int32_t n, int64_t frames, con
   if ((frames + 1) * (int64_t)g.M > 0xFFFFFFFFLL) return OVGGT_ERR_ARG;
   if (c->phase[layer] != 0) return OVGGT_ERR_STATE;
   if (hipStreamSynchronize((hipStream_t)hip_stream) != hipSuccess) return OVGGT_ERR_HIP;
+  c->pending[layer] = 0;                               // the contents it would have rearranged are replaced
   char* mb = layer_meta(c->meta, g, layer);
   if (n > 0) {
     if (hipMemcpy(mb + g.off_ids, ids, (size_t)4 * n, hipMemcpyHostToDevice) != hipSuccess) return OVGGT_ERR_HIP;

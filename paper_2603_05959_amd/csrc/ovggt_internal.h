@@ -36,11 +36,13 @@ struct Geom {
   size_t off_dval;         // d_i = 1 - cos(k_i, centroid) of the slots below n_old, one fp32 per slot (hybrid scoring)
   size_t off_cvec;         // the sum as H*d fp32 values, refreshed by each frame's append (hybrid scoring)
   size_t off_dpart;        // (min, max) of d_i over the evictable slots of each wave of the diversity pass (hybrid scoring)
+  size_t off_mvmap;        // per slot B + j (j < M): the slot below B it moves to under the last selection, or kNoMove
   size_t off_hist;         // kSelHistBins counters: the selection's first-level histogram of the cached entries' score
                            // words, filled by all workgroups of a launch and zeroed again by the one that selects
 };
 
 constexpr int kSelHistBins = 2048;  // the 11 bits below the sign of a score word
+constexpr uint32_t kNoMove = 0xFFFFFFFFu;
 
 __host__ __device__ inline char* layer_k(char* kv, const Geom& g, int layer) {
   return kv + (size_t)layer * g.kv_layer_bytes;
@@ -56,9 +58,11 @@ __host__ __device__ inline char* layer_meta(char* meta, const Geom& g, int layer
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
 
 // Eq. 2: copy the frame's K/V rows into slots [n, n+M) of layers [layer0, layer0+nl)
-// and initialise their ids (gid0 + i), scores (0) and flags (0).
+// and initialise their ids (gid0 + i), scores (0) and flags (0).  apply_moves: the previous
+// frame's compaction is still outstanding (n == B then): every entry that the last selection
+// moves out of a slot the new frame overwrites is carried to its destination first.
 hipError_t launch_append(const Geom& g, char* kv, char* meta, int layer0, int nl,
-                         const void* k_new, const void* v_new, int n, uint32_t gid0, hipStream_t s);
+                         const void* k_new, const void* v_new, int n, uint32_t gid0, bool apply_moves, hipStream_t s);
 
 // Attention of M queries over n_total resident slots.
 hipError_t launch_attn_f32(const Geom& g, char* kv, int layer0, int nl, const void* q, void* out,

@@ -258,18 +258,21 @@ __device__ inline void radix_pass(SelShared& sh, int n_iter, uint32_t rank, Digi
 #define TSTAMP(k) do { } while (0)
 #endif
 
-// The ordered move list from the evict bitmap in sh.evmap (complete, and a barrier behind it).
+// The ordered move list from the evict bitmap in sh.evmap (complete, and a barrier behind it),
+// and the same moves keyed by source: mvmap[j] = destination of the entry in slot B + j, or
+// kNoMove (read by the append that applies an outstanding compaction).
 // Holes (evicted slots below B) are sparse: a thread takes PP consecutive 32-slot words of the
 // bitmap below B, and one scan over the per-thread counts gives it the list position of its first
 // hole.  Movers (kept slots at or above B) are dense: one slot per thread and round, positions from
-// a ballot and the per-wave totals.
+// a ballot and the per-wave totals; the r-th mover looks its destination up in the hole list.
 __device__ inline void emit_moves(SelShared& sh, const Geom& g, Ctrl* ctrl, uint32_t* mvdst, uint32_t* mvsrc,
-                                  uint32_t* evbits, int n_total, bool budget_error, int pass) {
+                                  uint32_t* mvmap, uint32_t* evbits, int n_total, bool budget_error, int pass) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   (void)pass;
   const int n_words = (n_total + 31) >> 5;
   if (evbits)
     for (int wi = tid; wi < n_words; wi += kSelThreads) evbits[wi] = sh.evmap[wi];
+  const uint32_t m_cap = (uint32_t)g.M;
   const int hole_words = (g.B + 31) >> 5;
   const int PP = (hole_words + kSelThreads - 1) / kSelThreads;   // <= 4
   uint32_t hw[4];
@@ -282,7 +285,7 @@ __device__ inline void emit_moves(SelShared& sh, const Geom& g, Ctrl* ctrl, uint
     if (j < PP && wi < hole_words) {
       const int s0 = wi << 5;
       const uint32_t below_b = s0 + 32 <= g.B ? 0xFFFFFFFFu : ((1u << (g.B - s0)) - 1u);
-      hw[j] = sh.evmap[wi] & below_b;
+      hw[j] = budget_error ? 0u : sh.evmap[wi] & below_b;
       nh += __popc(hw[j]);
     }
   }
@@ -294,17 +297,36 @@ __device__ inline void emit_moves(SelShared& sh, const Geom& g, Ctrl* ctrl, uint
       if (lane >= off) inc_h += yh;
     }
   }
-  // first round of movers shares the barrier with the holes' scan
+  if (lane == 63) sh.scan_tmp[0][wave] = inc_h;
+  __syncthreads();
+  uint32_t base_h = 0, tot_h = 0;
+#pragma unroll
+  for (int w = 0; w < kSelWaves; ++w) {
+    const uint32_t th = sh.scan_tmp[0][w];
+    if (w < wave) base_h += th;
+    tot_h += th;
+  }
+  if (wave_has_words) {                                          // the hole list (entries beyond M are never used)
+    uint32_t hp = base_h + inc_h - nh;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint32_t s0 = (uint32_t)(tid * PP + j) << 5;
+      uint32_t b = hw[j];
+      while (b) {
+        if (hp < m_cap) mvdst[hp] = s0 + (uint32_t)__builtin_ctz(b);
+        ++hp; b &= b - 1;
+      }
+    }
+  }
   const uint64_t lanes_below = (1ull << lane) - 1ull;
+  const uint32_t n_dst = min(tot_h, m_cap);
   uint32_t tot_m = 0;
-  const uint32_t m_cap = (uint32_t)g.M;
-  for (int s0 = g.B; s0 < n_total; s0 += kSelThreads) {
+  for (int s0 = g.B; s0 < g.B + g.M; s0 += kSelThreads) {
     const int slot = s0 + tid;
     const bool mover = !budget_error && slot < n_total && !((sh.evmap[slot >> 5] >> (slot & 31)) & 1u);
     const uint64_t bl = __ballot(mover);
-    if (s0 != g.B) __syncthreads();                              // the previous round's totals have been read
+    __syncthreads();                     // the hole list is visible; the previous round's totals have been read
     if (lane == 0) sh.scan_tmp[1][wave] = (uint32_t)__popcll(bl);
-    if (s0 == g.B && lane == 63) sh.scan_tmp[0][wave] = inc_h;
     __syncthreads();
     uint32_t base_m = tot_m;
 #pragma unroll
@@ -314,24 +336,15 @@ __device__ inline void emit_moves(SelShared& sh, const Geom& g, Ctrl* ctrl, uint
       tot_m += tm;
     }
     const uint32_t mp = base_m + (uint32_t)__popcll(bl & lanes_below);
+    uint32_t to = kNoMove;
+    if (mover && mp < n_dst) to = mvdst[mp];
     if (mover && mp < m_cap) mvsrc[mp] = (uint32_t)slot;
-  }
-  uint32_t base_h = 0, tot_h = 0;
-#pragma unroll
-  for (int w = 0; w < kSelWaves; ++w) {
-    const uint32_t th = sh.scan_tmp[0][w];
-    if (w < wave) base_h += th;
-    tot_h += th;
+    if (slot < g.B + g.M) mvmap[slot - g.B] = to;
   }
   const bool consistent = !budget_error && tot_h == tot_m && tot_h <= m_cap;
-  if (consistent && wave_has_words) {
-    uint32_t hp = base_h + inc_h - nh;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const uint32_t s0 = (uint32_t)(tid * PP + j) << 5;
-      uint32_t b = hw[j];
-      while (b) { mvdst[hp++] = s0 + (uint32_t)__builtin_ctz(b); b &= b - 1; }
-    }
+  if (!consistent) {                                             // uniform: nothing moves
+    __syncthreads();
+    for (int j = tid; j < g.M; j += kSelThreads) mvmap[j] = kNoMove;
   }
   if (tid == 0) {
     ctrl->n_moves = consistent ? tot_h : 0u;
@@ -352,7 +365,7 @@ __device__ inline void emit_moves(SelShared& sh, const Geom& g, Ctrl* ctrl, uint
 // The histogram selection falls back to it when its lists overflow.
 __device__ inline void select_streaming(SelShared& sh, const Geom& g, const float* ss, const uint32_t* ids,
                                         const uint8_t* flags, Ctrl* ctrl, uint32_t* mvdst, uint32_t* mvsrc,
-                                        uint32_t* evbits, int n_total) {
+                                        uint32_t* mvmap, uint32_t* evbits, int n_total) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n_chunks = (n_total + kSelThreads - 1) / kSelThreads;
   const uint32_t n_evict = (uint32_t)(n_total - g.B);
@@ -431,7 +444,7 @@ __device__ inline void select_streaming(SelShared& sh, const Geom& g, const floa
   }
   __syncthreads();
   TSTAMP(11);
-  emit_moves(sh, g, ctrl, mvdst, mvsrc, evbits, n_total, budget_error, pass);
+  emit_moves(sh, g, ctrl, mvdst, mvsrc, mvmap, evbits, n_total, budget_error, pass);
 }
 
 // ---- histogram selection -----------------------------------------------------------------------
@@ -531,7 +544,7 @@ struct QuadBatch { float4 sv[kQuadBatch]; uint32_t fl[kQuadBatch]; };
 
 __device__ inline void select_hist(SelShared& sh, const Geom& g, const float* ss, const uint32_t* ids,
                                    const uint8_t* flags, Ctrl* ctrl, uint32_t* mvdst, uint32_t* mvsrc,
-                                   uint32_t* evbits, uint32_t* ghist, int n_total) {
+                                   uint32_t* mvmap, uint32_t* evbits, uint32_t* ghist, int n_total) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n_old = n_total - g.M;
   const uint32_t n_evict = (uint32_t)(n_total - g.B);
@@ -680,12 +693,12 @@ __device__ inline void select_hist(SelShared& sh, const Geom& g, const float* ss
     }
   }
   if (fallback) {                                       // uniform: decided from shared counters behind a barrier
-    select_streaming(sh, g, ss, ids, flags, ctrl, mvdst, mvsrc, evbits, n_total);
+    select_streaming(sh, g, ss, ids, flags, ctrl, mvdst, mvsrc, mvmap, evbits, n_total);
     return;
   }
   __syncthreads();
   TSTAMP(11);
-  emit_moves(sh, g, ctrl, mvdst, mvsrc, evbits, n_total, budget_error, 2);
+  emit_moves(sh, g, ctrl, mvdst, mvsrc, mvmap, evbits, n_total, budget_error, 2);
 }
 
 // ---- Eq. 7: rank values of the evictable slots ----------------------------------------------------
@@ -877,7 +890,7 @@ score_select_kernel(Geom g, SmoothParams sm, HybridParams hy, char* meta, int la
   if (hy.on) hybrid_new_values(sh, hy, smoothing, ss, flags, n_old, n_total);
   // hybrid scoring keeps the evict bitmap: the centroid's maintenance reads it
   uint32_t* evbits = hy.on ? (uint32_t*)(mb + g.off_evbits) : nullptr;
-  select_hist(sh, g, ss, ids, flags, ctrl, mvdst, mvsrc, evbits, ghist, n_total);
+  select_hist(sh, g, ss, ids, flags, ctrl, mvdst, mvsrc, (uint32_t*)(mb + g.off_mvmap), evbits, ghist, n_total);
 }
 
 template <bool BF16>

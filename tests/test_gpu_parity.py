@@ -326,6 +326,62 @@ def test_batched_layers_match_per_layer_oracle(shape):
     cache.close()
 
 
+def test_compaction_carried_by_the_next_append_equals_the_stand_alone_kernel():
+    """The same stream through three handles: A is exported after every frame (the export applies
+    the outstanding compaction with the stand-alone kernel), B is never touched between frames (every
+    compaction rides along with the next frame's append), C is flushed explicitly on odd frames.
+    Outputs of every frame and the final caches must be identical, and equal to the oracle's."""
+    torch = _torch()
+    cfg = synth.preset(1, M=300, H=4, B=1500, T=16, n_special=5)
+    caches = [make_cache(cfg, L=1) for _ in range(3)]
+    orc = oc.OracleCache(cfg.M, cfg.H, cfg.d, cfg.B)
+    outs = [c.new_output()[0] for c in caches]
+    for t in range(cfg.T):
+        f = synth.frame_inputs(cfg, 0, t)
+        if t >= 6:
+            f["r"] = synth.rising_resid(cfg, 0, t)            # many movers per frame
+        q, k, v, r = (dev(f[x], cfg) for x in "qkvr")
+        a = torch.from_numpy(f["a"]).to("cuda:0")
+        for c, o in zip(caches, outs):
+            c.step(q, k, v, r, a, o, layer=0)
+        orc.step(f["q"], f["k"], f["v"], f["r"], f["a"])
+        assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2]), f"frame {t}: outputs differ"
+        compare_cache(caches[0], orc)
+        if t % 2 == 1:
+            caches[2].flush(0)
+    for c in caches:
+        compare_cache(c, orc)
+        assert c.status(0) == 0
+        c.close()
+
+
+def test_compaction_outstanding_in_some_layers_only():
+    """Three layers stepped together; between frames one layer is flushed, another one is given a
+    late anchor (which applies its compaction first), the third keeps its compaction outstanding:
+    the next batched call has to cope with the mix."""
+    torch = _torch()
+    cfg = synth.preset(1, M=200, H=2, C=256, B=900, T=12, n_special=3, L=3)
+    cache = make_cache(cfg)
+    orcs = [oc.OracleCache(cfg.M, cfg.H, cfg.d, cfg.B) for _ in range(cfg.L)]
+    out = cache.new_output()
+    for t in range(cfg.T):
+        fs = [synth.frame_inputs(cfg, l, t) for l in range(cfg.L)]
+        pack = lambda key: dev(np.stack([f[key] for f in fs]), cfg)
+        a = torch.from_numpy(np.stack([f["a"] for f in fs])).cuda()
+        cache.step(pack("q"), pack("k"), pack("v"), pack("r"), a, out)
+        for l in range(cfg.L):
+            orcs[l].step(fs[l]["q"], fs[l]["k"], fs[l]["v"], fs[l]["r"], fs[l]["a"])
+        if t >= 5:
+            cache.flush(0)
+            if t % 3 == 0:                                    # protect what is left of frame t-2 in layer 1
+                cache.set_protect(t - 2, None, True, layer=1)
+                orcs[1].set_protect(t - 2, None, True)
+    for l in range(cfg.L):
+        compare_cache(cache, orcs[l], layer=l)
+        assert cache.status(l) == 0
+    cache.close()
+
+
 def test_per_layer_calls_are_independent():
     cfg = synth.preset(2, M=64, H=1, C=64, B=128, T=5, L=2, n_special=1)
     torch = _torch()
