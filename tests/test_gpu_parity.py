@@ -554,7 +554,7 @@ def test_selection_threshold_regimes(regime, M, Bq):
 def _random_population_case(seed, M=None, Bq=None):
     """One seeded cache population (frame size, budget, score distribution, ties, protected share
     all drawn at random), three frames of selection on top of it; True if ids, layout, scores and
-    flags equal the oracle's after every frame."""
+    flags equal the oracle's after every frame (odd seeds) or after the last one (even seeds)."""
     torch = _torch()
     rng = np.random.default_rng(seed)
     M_ = int(rng.choice([1, 3, 16, 17, 64, 100, 256, 700, 1041, 1374, 2100]))
@@ -591,7 +591,7 @@ def _random_population_case(seed, M=None, Bq=None):
     z = torch.zeros((M, H, d), dtype=torch.float32, device="cuda:0")
     zk = np.zeros((M, H, d), np.float32)
     ok = True
-    for _ in range(3):
+    for step in range(3):
         mode = rng.integers(0, 4)
         r = np.zeros((M, C), np.float32)
         if mode == 0:
@@ -607,6 +607,8 @@ def _random_population_case(seed, M=None, Bq=None):
             a[:] = 0
         cache.step(z, z, z, B.to_device(r, "f32"), torch.from_numpy(a).cuda(), out, layer=0)
         orc.append(zk, zk); orc.update(r, a)
+        if seed % 2 == 0 and step < 2:
+            continue            # even seeds: no export between frames, so the appends carry the compactions
         nn = cache.size(0)
         gi = np.zeros(nn, np.uint32); gs = np.zeros(nn, np.float32); gf = np.zeros(nn, np.uint8)
         B.ovggt_cache_export(cache.h, 0, gi, None, None, gs, gf, cache.stream)
