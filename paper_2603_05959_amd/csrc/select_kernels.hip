@@ -653,7 +653,6 @@ __device__ inline void select_hist(SelShared& sh, const Geom& g, const float* ss
       atomicAdd(&h2[(w >> 9) & (kSelHistBins - 1)], 1u);
     }
   }
-  if (bad) sh.bad = 1;
   __syncthreads();
   TSTAMP(3);
   const uint32_t n_cand = sh.n_cand;
