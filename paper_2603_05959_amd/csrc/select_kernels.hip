@@ -158,6 +158,7 @@ __device__ inline void smooth_new_scores(const SmoothParams& sm, int M, float* k
 }
 
 // ---- phase 2 helpers ---------------------------------------------------------
+constexpr int kHoleListCap = 2048;   // hole-list entries mirrored in LDS (longer lists are read back from memory)
 struct SelShared {
   uint32_t hist[256][64];          // histogram selection: the candidate lists (score words, then slots); streaming
                                    // selection: one histogram column per lane id in rows 0..127 (two 16-bit bins a word)
@@ -170,6 +171,7 @@ struct SelShared {
   uint32_t digit, rank, bucket, is_last, n_evictable, bad;
   uint32_t n_cand, n_final;        // histogram selection: entries of the candidate list, of the final list
   uint32_t final_list[64];         // candidate-list positions of the keys that the last wave step orders
+  uint32_t hole_list[kHoleListCap]; // the first entries of the hole list, for the movers' look-up
 };
 
 // Histogram selection: sizes of its lists.
@@ -313,7 +315,9 @@ __device__ inline void emit_moves(SelShared& sh, const Geom& g, Ctrl* ctrl, uint
       const uint32_t s0 = (uint32_t)(tid * PP + j) << 5;
       uint32_t b = hw[j];
       while (b) {
-        if (hp < m_cap) mvdst[hp] = s0 + (uint32_t)__builtin_ctz(b);
+        const uint32_t hole = s0 + (uint32_t)__builtin_ctz(b);
+        if (hp < m_cap) mvdst[hp] = hole;
+        if (hp < (uint32_t)kHoleListCap) sh.hole_list[hp] = hole;
         ++hp; b &= b - 1;
       }
     }
@@ -337,7 +341,7 @@ __device__ inline void emit_moves(SelShared& sh, const Geom& g, Ctrl* ctrl, uint
     }
     const uint32_t mp = base_m + (uint32_t)__popcll(bl & lanes_below);
     uint32_t to = kNoMove;
-    if (mover && mp < n_dst) to = mvdst[mp];
+    if (mover && mp < n_dst) to = mp < (uint32_t)kHoleListCap ? sh.hole_list[mp] : mvdst[mp];
     if (mover && mp < m_cap) mvsrc[mp] = (uint32_t)slot;
     if (slot < g.B + g.M) mvmap[slot - g.B] = to;
   }
