@@ -109,6 +109,9 @@ def main():
     ap.add_argument("--standalone-compact", action="store_true",
                     help="apply every frame's compaction with the stand-alone kernel (ovggt_cache_flush after each step) "
                          "instead of letting the next frame's append carry it")
+    ap.add_argument("--mfma-loop", action="store_true",
+                    help="also measure what a loop of nothing but the attention kernel's MFMA sustains on this box "
+                         "(random and constant operands): the reachable denominator beside the published peak")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (reference dispatch for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -303,6 +306,12 @@ def main():
                                "mean_ms_last_quarter": float(ms[-q:].mean()),
                                "slope_us_per_1000_frames": float(slope * 1e6),
                                "note": "event-bracketed whole steps, every 8th timed step, frames with a full cache"}
+    if args.mfma_loop:
+        rnd = B.ovggt_profile_mfma_loop(cache.h, True, 20000, cache.stream)
+        cst = B.ovggt_profile_mfma_loop(cache.h, False, 20000, cache.stream)
+        res["mfma_loop"] = {"random_operands_TFLOPs": rnd, "constant_operands_TFLOPs": cst, "unit": "TFLOP/s",
+                            "instruction": "v_mfma_f32_32x32x16_f16", "waves_per_simd": 2,
+                            "attention_frac_of_random_operand_rate": res["roofline"]["achieved"] / rnd}
     cache.close()
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(cfg, warm_frames=max(cfg.B // cfg.M + 2, 2), timed_frames=args.cpu_frames,

@@ -235,6 +235,15 @@ int ovggt_profile_read(ovggt_cache* c, double* ms_sum, int64_t* count, void* hip
  * kernel's own execution.  Synchronises `hip_stream`. */
 int ovggt_profile_overhead(ovggt_cache* c, int reps, double* ms_mean, void* hip_stream);
 
+/* Measurement helper: the rate (TFLOP/s, host double) that the matrix cores sustain when every
+ * wave issues nothing but the attention kernel's MFMA (v_mfma_f32_32x32x16_f16) on register
+ * operands, two waves per SIMD on every CU, `iters` rounds of four per wave (20000 makes a
+ * launch of about a millisecond), twenty launches timed after one of warm-up.  random_operands
+ * != 0: unit-variance random operands, under which the chip lowers its clock; 0: constant
+ * operands.  Uses the first bytes of the handle's workspace as a sink that is never written;
+ * synchronises `hip_stream`.  Not for use between the hot-path calls of a frame. */
+int ovggt_profile_mfma_loop(ovggt_cache* c, int random_operands, int iters, double* tflops, void* hip_stream);
+
 /* ---- Dynamic Anchor Protection: which frames become anchors (Sec. 3.3) ------------------
  * Host-only bookkeeping; no device work, usable without a GPU.  The model's outputs are inputs:
  * the coverage ratio rho_t (fraction of the latest anchor's points that project inside the

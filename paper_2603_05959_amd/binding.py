@@ -24,7 +24,7 @@ EXPORTS = (
     "ovggt_cache_status", "ovggt_cache_export", "ovggt_cache_import", "ovggt_cache_last_moves",
     "ovggt_profile_enable", "ovggt_profile_read", "ovggt_profile_overhead", "ovggt_strerror",
     "ovggt_cache_set_protect", "ovggt_dap_create", "ovggt_dap_step", "ovggt_dap_active", "ovggt_dap_destroy",
-    "ovggt_attn_plan_stats", "ovggt_cache_flush",
+    "ovggt_attn_plan_stats", "ovggt_cache_flush", "ovggt_profile_mfma_loop",
 )
 PROF_CLASSES = ("append", "attn", "combine", "score_select", "compact")
 
@@ -75,6 +75,7 @@ def lib() -> C.CDLL:
     L.ovggt_profile_enable.argtypes = [vp, C.c_int, C.c_int]
     L.ovggt_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64), vp]
     L.ovggt_profile_overhead.argtypes = [vp, C.c_int, C.POINTER(C.c_double), vp]
+    L.ovggt_profile_mfma_loop.argtypes = [vp, C.c_int, C.c_int, C.POINTER(C.c_double), vp]
     L.ovggt_cache_set_protect.argtypes = [vp, C.c_int, i64, u8p, C.c_int, vp]
     L.ovggt_dap_create.argtypes = [C.POINTER(vp), i32, i32, C.c_double, C.c_double, i32, i32]
     L.ovggt_dap_step.argtypes = [vp, i64, C.c_double, vp, C.POINTER(i64), u8p, C.POINTER(i64)]
@@ -251,6 +252,14 @@ def ovggt_profile_overhead(h, reps: int = 64, stream: int = 0) -> float:
     ms = C.c_double()
     _check(lib().ovggt_profile_overhead(h, reps, C.byref(ms), stream), "ovggt_profile_overhead")
     return ms.value
+
+
+def ovggt_profile_mfma_loop(h, random_operands: bool, iters: int = 20000, stream: int = 0) -> float:
+    """TFLOP/s of a loop of nothing but the attention kernel's MFMA (see include/ovggt.h)."""
+    v = C.c_double()
+    _check(lib().ovggt_profile_mfma_loop(h, 1 if random_operands else 0, iters, C.byref(v), stream),
+           "ovggt_profile_mfma_loop")
+    return float(v.value)
 
 
 # ---- convenience owner of the device buffers ---------------------------------

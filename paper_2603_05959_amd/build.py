@@ -8,7 +8,7 @@ import sys
 PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libovggt.so")
-SOURCES = ["ovggt_api.cpp", "dap_policy.cpp", "cache_kernels.hip", "select_kernels.hip", "hybrid_kernels.hip", "attn_f32.hip", "attn_bf16.hip"]
+SOURCES = ["ovggt_api.cpp", "dap_policy.cpp", "cache_kernels.hip", "select_kernels.hip", "hybrid_kernels.hip", "attn_f32.hip", "attn_bf16.hip", "probe_kernels.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

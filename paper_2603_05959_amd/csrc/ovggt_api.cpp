@@ -543,6 +543,27 @@ int ovggt_profile_overhead(ovggt_cache* c, int reps, double* ms_mean, void* hip_
   return OVGGT_OK;
 }
 
+int ovggt_profile_mfma_loop(ovggt_cache* c, int random_operands, int iters, double* tflops, void* hip_stream) {
+  if (!c || !tflops || iters < 1 || iters > (1 << 20)) return OVGGT_ERR_ARG;
+  hipStream_t s = (hipStream_t)hip_stream;
+  const int wgs = 2 * c->n_wgs;                       // two waves per SIMD, as in the attention kernel
+  hipEvent_t e0 = prof_event(c), e1 = prof_event(c);
+  bool ok = e0 && e1;
+  const int reps = 20;
+  ok = ok && launch_mfma_loop((float*)c->ws, wgs, iters, random_operands, s) == hipSuccess;   // warm-up (clock settles)
+  ok = ok && hipEventRecord(e0, s) == hipSuccess;
+  for (int r = 0; ok && r < reps; ++r) ok = launch_mfma_loop((float*)c->ws, wgs, iters, random_operands, s) == hipSuccess;
+  ok = ok && hipEventRecord(e1, s) == hipSuccess && hipStreamSynchronize(s) == hipSuccess;
+  float ms = 0.f;
+  ok = ok && hipEventElapsedTime(&ms, e0, e1) == hipSuccess && ms > 0.f;
+  if (e0) c->prof_free.push_back(e0);
+  if (e1) c->prof_free.push_back(e1);
+  if (!ok) return OVGGT_ERR_HIP;
+  const double flop = (double)reps * wgs * 4.0 * 4.0 * iters * 2.0 * 32 * 32 * 16;
+  *tflops = flop / (ms * 1e-3) * 1e-12;
+  return OVGGT_OK;
+}
+
 int ovggt_attn_plan_stats(const ovggt_config* cfg, int32_t layers_in_launch, int32_t n_total, int32_t n_wgs,
                           int32_t* out, float* cost) {
   if (!valid_config(cfg) || !out || !cost || cfg->dtype != OVGGT_BF16) return OVGGT_ERR_ARG;

@@ -128,6 +128,10 @@ hipError_t launch_centroid_protect(const Geom& g, char* kv, char* meta, int laye
 hipError_t launch_set_protect(const Geom& g, char* meta, int layer0, int nl, int n, uint32_t gid_lo,
                               const uint8_t* mask, int on, hipStream_t s);
 
+// Measurement helper: `workgroups` workgroups of 4 waves, each wave 4 * iters back-to-back
+// v_mfma_f32_32x32x16_f16 on register operands (random != 0: unit-variance random, else ones).
+hipError_t launch_mfma_loop(float* sink, int workgroups, int iters, int random, hipStream_t s);
+
 // Apply the move list to K, V and the per-slot metadata.
 hipError_t launch_compact(const Geom& g, char* kv, char* meta, int layer0, int nl, hipStream_t s);
 

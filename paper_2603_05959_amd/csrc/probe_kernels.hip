@@ -1,0 +1,58 @@
+// Measurement helper, not part of the hot path: the rate the matrix cores sustain on this chip when
+// they do nothing but the attention kernel's MFMA (v_mfma_f32_32x32x16_f16, fp32 accumulation) --
+// the denominator that is reachable in practice, beside the published dense peak.  Operands live
+// in registers; with random operands the chip lowers its clock under the matrix load, with
+// constant ones it does not, so both are reported.
+#include "ovggt_internal.h"
+
+namespace ovggt {
+
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+__device__ inline uint32_t mix32(uint32_t x) {
+  x ^= x >> 16; x *= 0x7FEB352Du; x ^= x >> 15; x *= 0x846CA68Bu; x ^= x >> 16;
+  return x;
+}
+
+// One workgroup of 4 waves per launch slot; every wave issues 4 * iters independent-accumulator
+// MFMAs back to back.  random != 0: operands are sums of four uniform variates (unit variance,
+// bell-shaped), different in every lane and element; otherwise all ones.
+__global__ void __launch_bounds__(256) mfma_loop_kernel(float* sink, int iters, int random) {
+  f16x8 a[4], b[4];
+  uint32_t s = mix32(blockIdx.x * 256u + threadIdx.x + 1u);
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float va = 1.f, vb = 1.f;
+      if (random) {
+        float u = 0.f, w = 0.f;
+        for (int t = 0; t < 4; ++t) {
+          s = mix32(s); u += (float)(s >> 8) * (1.0f / 16777216.0f);
+          s = mix32(s); w += (float)(s >> 8) * (1.0f / 16777216.0f);
+        }
+        va = (u - 2.0f) * 1.7320508f; vb = (w - 2.0f) * 1.7320508f;     // variance 4/12 -> 1
+      }
+      a[i][e] = (_Float16)va; b[i][e] = (_Float16)vb;
+    }
+  f32x16 c0, c1, c2, c3;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) { c0[i] = 0.f; c1[i] = 0.f; c2[i] = 0.f; c3[i] = 0.f; }
+  for (int it = 0; it < iters; ++it) {
+    c0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[0], b[0], c0, 0, 0, 0);
+    c1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[1], b[1], c1, 0, 0, 0);
+    c2 = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[2], b[2], c2, 0, 0, 0);
+    c3 = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[3], b[3], c3, 0, 0, 0);
+  }
+  const float r = c0[0] + c1[1] + c2[2] + c3[3];
+  if (r == 12345.678f) sink[0] = r;                     // never true: keeps the loop alive
+}
+
+// FLOP of one launch: workgroups * 4 waves * 4 * iters MFMAs of 2*32*32*16 each.
+hipError_t launch_mfma_loop(float* sink, int workgroups, int iters, int random, hipStream_t s) {
+  hipLaunchKernelGGL(mfma_loop_kernel, dim3((unsigned)workgroups), dim3(256), 0, s, sink, iters, random);
+  return hipGetLastError();
+}
+
+}  // namespace ovggt
