@@ -870,3 +870,16 @@ def test_bf16_output_is_the_rounded_fp32_output():
         c16.step(*args, o16, layer=0)
         assert torch.equal(o32.to(torch.bfloat16), o16), t
     c32.close(); c16.close()
+
+
+def test_mfma_loop_probe_reports_a_plausible_rate():
+    """The measurement helper behind bench.py --mfma-loop: constant operands run near the chip's
+    dense f16 peak, random ones below it, neither above."""
+    cfg = synth.preset(1, M=200, H=2, C=64, B=400, T=1)
+    cache = make_cache(cfg, L=1)
+    cst = B.ovggt_profile_mfma_loop(cache.h, False, 2000, cache.stream)
+    rnd = B.ovggt_profile_mfma_loop(cache.h, True, 2000, cache.stream)
+    assert 500.0 < rnd <= cst * 1.05 and cst < 2600.0, (rnd, cst)
+    with pytest.raises(B.OvggtError):
+        B.ovggt_profile_mfma_loop(cache.h, True, 0, cache.stream)
+    cache.close()
