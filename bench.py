@@ -5,9 +5,16 @@ A step is one frame through the whole path for every layer of the workload:
 ovggt_global_attn (append + attention) -> ovggt_score_select -> ovggt_cache_compact,
 called through the C ABI with all inputs already resident in HBM.  The default
 workload is the VGGT-sized single global layer (1374 tokens/frame, 16x64 heads,
-budget 16384, bf16).  Prints ONE JSON line with the throughput in frames/s, the
-roofline of the dominant kernel (attention, MFMA-bound) measured with HIP
-events inside the timed region, and the CPU oracle timed on a bounded sample.
+budget 16384, bf16 in and out).  Prints ONE JSON line with the throughput in
+frames/s, the roofline of the dominant kernel (attention, MFMA-bound) measured
+with HIP events inside the timed region, the CPU oracle timed on a bounded
+sample, and (unless --no-extra-workloads) short runs of the other workloads.
+
+Every timed step runs on a full cache: before the --warmup steps the stream is
+fed until the budget is reached (ceil(B/M)+1 untimed frames, reported as
+config.prefill_frames), and a throw-away handle of the same shape is stepped for
+a fixed time (--settle-ms) so that the chip has reached the clock it sustains
+under this load; --warmup and --steps then mean what they say.
 """
 from __future__ import annotations
 
@@ -26,8 +33,9 @@ if ROOT not in sys.path:
 
 from paper_2603_05959_amd import synth  # noqa: E402
 
-MFMA_BF16_PEAK_TFLOPS = 2500.0       # MI355X dense bf16
+MFMA_F16_PEAK_TFLOPS = 2500.0        # MI355X dense f16 / bf16 (same figure)
 HBM_PEAK_GBS = 8000.0
+ARITHMETIC = "bf16 in/out, f16 MFMA (K, V and softmax weights as IEEE half), fp32 accumulate and softmax"
 
 
 def gen_frames(cfg, frames, layers, pool):
@@ -53,10 +61,10 @@ def profiled_figure(what, kernel, workload, layers):
     return None
 
 
-def cpu_baseline(cfg, warm_frames, timed_frames, smooth=None, hybrid_beta=None, threads=None):
-    """The oracle as it stands: attention-free warm-up to reach the steady-state
-    cache, then whole steps (fp64 attention + score + select + compact) timed.
-    threads: cap on the BLAS thread pool (None: whatever the box gives)."""
+def oracle_rate(cfg, warm_frames, timed_frames, smooth, hybrid_beta, threads):
+    """The oracle as it stands: attention-free warm-up to reach the steady-state cache, then whole
+    steps (fp64 attention + score + select + compact) timed.  threads: cap on the BLAS thread
+    pool (None: whatever the box gives).  Returns (frames/s, threads used, seconds, resident keys)."""
     from oracle import ovggt_oracle as oc            # cpu_baseline leg only
     limit = None
     try:
@@ -78,11 +86,274 @@ def cpu_baseline(cfg, warm_frames, timed_frames, smooth=None, hybrid_beta=None, 
     dt = time.perf_counter() - t0
     if limit is not None:
         limit.restore_original_limits()
-    return {"value": timed_frames / dt, "unit": "frames/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"{timed_frames} steady-state frames (t={warm_frames}..{warm_frames + timed_frames - 1}, "
-                      f"{orc.n + cfg.M} resident keys) of the same workload, layer 0, after an attention-free "
-                      f"{warm_frames}-frame warm-up; numpy/OpenBLAS fp64",
-            "seconds": dt}
+    return timed_frames / dt, int(cores), dt, orc.n + cfg.M
+
+
+def cpu_baseline(cfg, frames_all, frames_one, smooth=None, hybrid_beta=None, threads=None):
+    """All-core rate (the reported value) and the one-thread rate beside it, each on its own
+    bounded sample of steady-state frames of layer 0."""
+    warm = max(-(-cfg.B // cfg.M) + 1, 2)
+    v, cores, dt, keys = oracle_rate(cfg, warm, frames_all, smooth, hybrid_beta, threads)
+    res = {"value": v, "unit": "frames/s", "cores": cores, "kind": "oracle",
+           "sample": f"{frames_all} steady-state frames (t={warm}..{warm + frames_all - 1}, {keys} resident keys) "
+                     f"of the same workload, layer 0, after an attention-free {warm}-frame warm-up; numpy/OpenBLAS fp64",
+           "seconds": dt}
+    if frames_one > 0:
+        v1, c1, dt1, _ = oracle_rate(cfg, warm, frames_one, smooth, hybrid_beta, 1)
+        res["one_thread"] = {"value": v1, "unit": "frames/s", "cores": c1, "seconds": dt1,
+                             "sample": f"{frames_one} frames of the same sample with the BLAS pool capped at one thread"}
+    return res
+
+
+_STAGED = {}      # device-resident inputs of the most recent workload, reused when the next run wants the same
+
+
+def run_workload(cfg, W, K, *, hybrid_beta=None, smooth_alpha=None, rising=False, standalone_compact=False,
+                 detail_steps=40, flatness=False, settle_ms=300.0, distinct_cap=None, graph=False):
+    """Stage the inputs, fill the cache, settle the clock, then W warm-up and K timed steps.
+    Returns the measurements as a dict."""
+    import torch
+    from paper_2603_05959_amd import binding as B
+    L = cfg.L
+    dev = torch.device("cuda:0")
+    P = -(-cfg.B // cfg.M) + 1                            # frames until every step runs on a full cache
+    T = P + W + K
+    # distinct frames staged in HBM; frames beyond them reuse the staged ones (and carry no anchor bits)
+    distinct = T + detail_steps if rising else T          # rising scores: a reused frame would break the pattern
+    if distinct_cap and not rising:
+        distinct = min(distinct, max(distinct_cap, P + 8))
+    t_gen = time.perf_counter()
+    stage_key = (cfg, rising, distinct)
+    staged = _STAGED.get(stage_key, [])
+    with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 8)) as pool:
+        for t0_ in range(len(staged), distinct, 8):
+            batch = range(t0_, min(distinct, t0_ + 8))
+            host = gen_frames(cfg, batch, L, pool)
+            if rising:
+                for (l, t), f in host.items():
+                    f["r"] = synth.rising_resid(cfg, l, t)
+            for t in batch:
+                fs = [host[(l, t)] for l in range(L)]
+                pack = lambda key: B.to_device(np.stack([f[key] for f in fs]), cfg.dtype, dev)
+                staged.append((pack("q"), pack("k"), pack("v"), pack("r"),
+                               torch.from_numpy(np.stack([f["a"] for f in fs])).to(dev)))
+            del host
+    torch.cuda.synchronize()
+    gen_s = time.perf_counter() - t_gen
+    _STAGED.clear()                                      # keeps the last workload's inputs only
+    _STAGED[stage_key] = staged
+
+    smooth = None
+    if smooth_alpha:
+        ph, pw = synth.patch_grid(cfg)
+        smooth = (smooth_alpha, ph, pw, cfg.M - ph * pw, synth.gaussian_kernel3(1.0))
+    mk = lambda: B.Cache(L, cfg.H, cfg.d, cfg.M, cfg.C, cfg.B, cfg.dtype, smooth=smooth, hybrid_beta=hybrid_beta)
+    cache = mk()
+    out = cache.new_output()                             # fp32 outputs (fp32 accumulators stored unrounded)
+    layer = B.OVGGT_ALL_LAYERS if L > 1 else 0
+
+    def step(c, t):
+        q, k, v, r, a = staged[t % distinct]
+        c.step(q, k, v, r, a if t < distinct else None, out, layer)
+        if standalone_compact:
+            c.flush(layer)
+
+    # ---- untimed: fill the measured cache, then load the chip with a throw-away handle of the same shape
+    for t in range(P):
+        step(cache, t)
+    torch.cuda.synchronize()
+    settle_frames = 0
+    if settle_ms > 0:
+        spare = mk()
+        t_s = time.perf_counter()
+        while (time.perf_counter() - t_s) * 1e3 < settle_ms:
+            for _ in range(32):
+                step(spare, settle_frames)
+                settle_frames += 1
+            torch.cuda.synchronize()
+        spare.close()
+        del spare
+    for t in range(P, P + W):
+        step(cache, t)
+    torch.cuda.synchronize()
+    assert cache.size(0) == cfg.B, "the timed region must start on a full cache"
+
+    # ---- timed region: exactly K steps; the attention kernel of every `every`-th one is bracketed
+    every = 4 if K >= 40 else (2 if K >= 8 else 1)
+    B.ovggt_profile_enable(cache.h, 1, every)
+    flat_ev = []
+    t0 = time.perf_counter()
+    for t in range(P + W, T):
+        if flatness and (t - P - W) % 8 == 0:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            step(cache, t)
+            e1.record()
+            flat_ev.append((t, e0, e1))
+        else:
+            step(cache, t)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = B.ovggt_profile_read(cache.h, cache.stream)
+    # what an event bracket reports beyond the bracketed kernel's own execution (empty launch)
+    bracket_overhead_ms = B.ovggt_profile_overhead(cache.h, 64, cache.stream)
+    status = [cache.status(l) for l in range(L)]
+    assert not any(status), f"device status {status}"
+    assert cache.size(0) == cfg.B
+
+    # ---- per-kernel detail on further (untimed) steady-state steps
+    B.ovggt_profile_enable(cache.h, 2, 1)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(detail_steps)]
+    for i in range(detail_steps):
+        ev[i][0].record()
+        step(cache, T + i)
+        ev[i][1].record()
+    torch.cuda.synchronize()
+    detail = B.ovggt_profile_read(cache.h, cache.stream)
+    B.ovggt_profile_enable(cache.h, 0, 1)
+    lat = sorted(a.elapsed_time(b) for a, b in ev) if ev else [0.0]
+
+    # ---- roofline of the dominant kernel (attention): algorithmic FLOP = 4*M*N_t*H*d per layer,
+    # N_t = the keys resident in the bracketed launch (B + M in every timed step, by the assertion above)
+    timed_frames = [t for i, t in enumerate(range(P + W, T)) if i % every == 0]
+    keys = [min(t * cfg.M, cfg.B) + cfg.M for t in timed_frames]
+    attn_ms, attn_cnt = prof["attn"]
+    assert attn_cnt in (0, len(keys)), (attn_cnt, len(keys))
+    flop_sum = sum(4.0 * cfg.M * n * cfg.H * cfg.d * L for n in keys)
+    n_keys = cfg.B + cfg.M
+    bracket_ms = attn_ms / max(attn_cnt, 1)
+    attn_avg_ms = max(bracket_ms - bracket_overhead_ms, 1e-6)
+    achieved = flop_sum / max(attn_cnt, 1) / (attn_avg_ms * 1e-3) / 1e12 if attn_cnt else 0.0
+    # from the committed rocprofv3 summary of this workload (stored-score ranking, no smoothing): HBM
+    # bytes per launch, and the kernel's steady-state duration in the trace
+    wl = cfg.name.split("-")[0]
+    traffic = profiled_figure("traffic_bytes_per_launch", "attn_bf16_kernel", wl, L)
+    traffic = None if traffic is None else int(traffic)
+    trace_us = profiled_figure("trace_avg_kernel_us", "attn_bf16_kernel", wl, L)
+    roofline = {"bound": "mfma", "kernel": "attn_bf16_kernel", "achieved": achieved, "peak": MFMA_F16_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": achieved / MFMA_F16_PEAK_TFLOPS,
+                "traffic": traffic, "avg_kernel_ms": attn_avg_ms,
+                "profiled_kernel_ms": None if trace_us is None else trace_us * 1e-3, "event_bracket_ms": bracket_ms,
+                "event_bracket_of_empty_launch_ms": bracket_overhead_ms, "launches_timed": int(attn_cnt),
+                "flop_per_launch": flop_sum / max(len(keys), 1),
+                "keys_per_launch": sorted(set(keys)) if len(set(keys)) > 1 else int(keys[0]) if keys else n_keys}
+
+    kernels = {}
+    for name, (ms, cnt) in detail.items():
+        if cnt:
+            kernels[name] = {"avg_us": 1e3 * ms / cnt, "launches": int(cnt)}
+    esz = 2 if cfg.dtype == "bf16" else 4
+    hbm = {}
+    if "score_select" in kernels:
+        byts = L * (cfg.M * cfg.C * esz + 4 * cfg.M + 9 * n_keys)
+        hbm["score_select"] = {"algorithmic_bytes": byts, "GB/s": byts / (kernels["score_select"]["avg_us"] * 1e-6) / 1e9}
+    move_bytes = 0
+    moves = len(cache.last_moves(0)[0])
+    if rising:
+        assert moves == cfg.M, f"rising scores: {moves} of {cfg.M} entries moved in the last frame"
+        move_bytes = L * moves * (2 * cfg.H * cfg.d * esz + 9) * 2           # K, V, id, score, flag: read and written
+        if "compact" in kernels:
+            hbm["compact"] = {"algorithmic_bytes": move_bytes, "GB/s": move_bytes / (kernels["compact"]["avg_us"] * 1e-6) / 1e9,
+                              "entries_moved_per_layer": moves}
+    if "append" in kernels:
+        byts = L * 4 * cfg.M * cfg.H * cfg.d * esz
+        if move_bytes and not standalone_compact:                            # the append carries the moves as well
+            byts += move_bytes
+        hbm["append"] = {"algorithmic_bytes": byts, "GB/s": byts / (kernels["append"]["avg_us"] * 1e-6) / 1e9}
+        if move_bytes and not standalone_compact:
+            hbm["append"]["carries_moves_per_layer"] = moves
+    for v in hbm.values():
+        v["frac_of_8TBs"] = v["GB/s"] / HBM_PEAK_GBS
+
+    res = {
+        "value": K / elapsed, "ms_per_step": 1e3 * elapsed / K,
+        "config": {"workload": f"{cfg.name}: {L} layer(s) x (M={cfg.M} tokens/frame, {cfg.H}x{cfg.d} heads, "
+                               f"C={cfg.C}, budget B={cfg.B}), {cfg.dtype}; every timed step on a full cache "
+                               f"({n_keys} resident keys per layer)",
+                   "tokens_per_frame": cfg.M, "budget": cfg.B, "layers": L,
+                   "prefill_frames": P, "settle_ms": settle_ms, "settle_frames": settle_frames,
+                   "frames": T, "distinct_frames_staged": distinct,
+                   "resident_keys_steady": int(n_keys), "out_dtype": "f32", "arithmetic": ARITHMETIC,
+                   "kv_range": "K and V beyond +-65504 saturate (reported in the status word); bf16's wider range is not kept",
+                   "ranking": ("hybrid Eq. 7, beta=%g" % hybrid_beta) if hybrid_beta is not None
+                              else "stored Eq. 5 scores",
+                   "smoothing": ("Eq. 6, alpha=%g, 3x3 Gaussian sigma 1" % smooth_alpha) if smooth else "off",
+                   "scores": "rising with t (worst case for compaction)" if rising else "workload's own",
+                   "compaction": "stand-alone kernel after every frame" if standalone_compact
+                                 else "carried by the next frame's append"},
+        "roofline": roofline,
+        "kernels_us": kernels,
+        "hbm_kernels": hbm,
+        "step_latency_ms": {"p50": lat[len(lat) // 2], "p99": lat[min(len(lat) - 1, int(0.99 * len(lat)))],
+                            "note": "per-step events on untimed steady-state steps with per-kernel events enabled"},
+        "cache_bytes": {"kv": cache.bytes[0], "meta": cache.bytes[1], "workspace": cache.bytes[2]},
+        "input_staging_s": gen_s,
+    }
+    if flat_ev:
+        pts = [(t, a.elapsed_time(b)) for t, a, b in flat_ev]
+        if len(pts) >= 8:
+            tt = np.array([p[0] for p in pts], dtype=np.float64)
+            ms = np.array([p[1] for p in pts], dtype=np.float64)
+            slope, icpt = np.polyfit(tt, ms, 1)
+            q = len(pts) // 4
+            res["flatness"] = {"samples": len(pts), "first_frame": int(tt[0]), "last_frame": int(tt[-1]),
+                               "mean_ms": float(ms.mean()), "mean_ms_first_quarter": float(ms[:q].mean()),
+                               "mean_ms_last_quarter": float(ms[-q:].mean()),
+                               "slope_us_per_1000_frames": float(slope * 1e6),
+                               "note": "event-bracketed whole steps, every 8th timed step, all on a full cache"}
+    if graph:
+        res["graph_replay"] = graph_replay_rate(cache, staged, distinct, out, layer, T + detail_steps, K)
+    cache.close()
+    res["_smooth"] = smooth
+    return res
+
+
+def graph_replay_rate(cache, staged, distinct, out, layer, t_next, K):
+    """The same K steady-state steps replayed from one captured HIP graph of a whole step (inputs are
+    copied into fixed buffers before each replay, inside the timed loop, as a serving loop would)."""
+    import torch
+    from paper_2603_05959_amd import binding as B
+    fixed = [x.clone() for x in staged[0]]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            cache.step(fixed[0], fixed[1], fixed[2], fixed[3], None, out, layer)
+    torch.cuda.current_stream().wait_stream(side)
+    first = [True]                                        # the capture accounted for the first replay on the host side
+    def replay(t):
+        for dst, src in zip(fixed[:4], staged[t % distinct][:4]):
+            dst.copy_(src, non_blocking=True)
+        if not first[0]:
+            B.ovggt_cache_advance(cache.h, layer, 1)
+        first[0] = False
+        g.replay()
+    for i in range(8):
+        replay(t_next + i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        replay(t_next + 8 + i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    return {"value": K / dt, "unit": "frames/s", "ms_per_step": 1e3 * dt / K,
+            "note": "one captured graph of a whole step (append, attention, merge, score/select) replayed K times; "
+                    "the four input copies into the graph's fixed buffers are inside the timed loop"}
+
+
+def brief(r):
+    """The figures of a secondary workload that the main line carries."""
+    o = {"frames_per_s": r["value"], "ms_per_step": r["ms_per_step"], "workload": r["config"]["workload"],
+         "prefill_frames": r["config"]["prefill_frames"],
+         "attention": {"avg_kernel_ms": r["roofline"]["avg_kernel_ms"], "TFLOP/s": r["roofline"]["achieved"],
+                       "frac_of_2.5PFLOPs": r["roofline"]["frac"], "launches_timed": r["roofline"]["launches_timed"]},
+         "kernels_us": {k: v["avg_us"] for k, v in r["kernels_us"].items()},
+         "hbm_kernels": {k: {"GB/s": v["GB/s"], "frac_of_8TBs": v["frac_of_8TBs"], "algorithmic_bytes": v["algorithmic_bytes"]}
+                         for k, v in r["hbm_kernels"].items()}}
+    if "flatness" in r:
+        o["flatness"] = r["flatness"]
+    return o
 
 
 def main():
@@ -98,20 +369,25 @@ def main():
     ap.add_argument("--smooth-alpha", type=float, default=None,
                     help="activation smoothing (Eq. 6) with this alpha and a 3x3 Gaussian (sigma 1) over the patch map")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-frames", type=int, default=12)
+    ap.add_argument("--cpu-frames", type=int, default=8, help="frames of the all-core oracle sample")
+    ap.add_argument("--cpu-frames-one-thread", type=int, default=4, help="frames of the one-thread oracle sample (0: skip)")
     ap.add_argument("--cpu-threads", type=int, default=None, help="cap the oracle's BLAS threads (default: all the box gives)")
     ap.add_argument("--detail-steps", type=int, default=40, help="extra untimed steps with per-kernel events")
+    ap.add_argument("--settle-ms", type=float, default=300.0,
+                    help="untimed load on a throw-away handle of the same shape before the warm-up, so the clock has settled")
     ap.add_argument("--flatness", action="store_true",
                     help="also bracket every 8th timed step with events and report the slope of step latency over the stream")
+    ap.add_argument("--distinct-frames", type=int, default=None,
+                    help="stage at most this many distinct frames (at least the pre-fill + 8) and reuse them afterwards")
     ap.add_argument("--rising-scores", action="store_true",
                     help="worst case for compaction: residual norms grow with t, so every new token survives and "
                          "M cached entries move per frame (all frames of the run are generated: keep the run short)")
     ap.add_argument("--standalone-compact", action="store_true",
                     help="apply every frame's compaction with the stand-alone kernel (ovggt_cache_flush after each step) "
                          "instead of letting the next frame's append carry it")
-    ap.add_argument("--mfma-loop", action="store_true",
-                    help="also measure what a loop of nothing but the attention kernel's MFMA sustains on this box "
-                         "(random and constant operands): the reachable denominator beside the published peak")
+    ap.add_argument("--no-extra-workloads", action="store_true",
+                    help="only the selected workload: skip the short 24-layer, worst-case-compaction and long-stream "
+                         "runs and the MFMA-loop figure that the default line carries under `workloads`")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (reference dispatch for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -134,188 +410,70 @@ def main():
         over["B"] = args.budget
     cfg = synth.preset(args.config, **over)
     W, K = args.warmup, args.steps
-    T = W + K
-    L = cfg.L
-    dev = torch.device("cuda:0")
-
-    # ---- inputs: generated on the host, staged to HBM before anything is timed
-    distinct = min(T, max(64, 2 * (cfg.B // cfg.M) + 8)) if L > 1 else T
-    if args.rising_scores:
-        distinct = T + args.detail_steps                 # a reused frame would rank below the cache and break the pattern
-    t_gen = time.perf_counter()
-    staged = []
-    with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 8)) as pool:
-        for t0_ in range(0, distinct, 8):
-            batch = range(t0_, min(distinct, t0_ + 8))
-            host = gen_frames(cfg, batch, L, pool)
-            if args.rising_scores:
-                for (l, t), f in host.items():
-                    f["r"] = synth.rising_resid(cfg, l, t)
-            for t in batch:
-                fs = [host[(l, t)] for l in range(L)]
-                pack = lambda key: B.to_device(np.stack([f[key] for f in fs]), cfg.dtype, dev)
-                staged.append((pack("q"), pack("k"), pack("v"), pack("r"),
-                               torch.from_numpy(np.stack([f["a"] for f in fs])).to(dev)))
-            del host
-    torch.cuda.synchronize()
-    gen_s = time.perf_counter() - t_gen
 
     if args.calibrate_copy:                              # known traffic: reads 256 MiB, writes 256 MiB
-        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device=dev)
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda:0")
         dst = torch.empty_like(src)
         for _ in range(3):
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
 
-    smooth = None
-    if args.smooth_alpha:
-        ph, pw = synth.patch_grid(cfg)
-        smooth = (args.smooth_alpha, ph, pw, cfg.M - ph * pw, synth.gaussian_kernel3(1.0))
-    cache = B.Cache(L, cfg.H, cfg.d, cfg.M, cfg.C, cfg.B, cfg.dtype, smooth=smooth, hybrid_beta=args.hybrid_beta)
-    out = cache.new_output()                             # fp32 outputs (fp32 accumulators stored unrounded)
-    layer = B.OVGGT_ALL_LAYERS if L > 1 else 0
-
-    def step(t):
-        q, k, v, r, a = staged[t % distinct]
-        # frames reused past `distinct` keep their anchor bits only in frame 0's first use
-        cache.step(q, k, v, r, a if t < distinct else None, out, layer)
-        if args.standalone_compact:
-            cache.flush(layer)
-
-    for t in range(W):
-        step(t)
-    torch.cuda.synchronize()
-    B.ovggt_profile_enable(cache.h, 1, 4)                # attention kernel of every 4th step
-    flat_ev = []
-    t0 = time.perf_counter()
-    for t in range(W, T):
-        if args.flatness and (t - W) % 8 == 0:
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            step(t)
-            e1.record()
-            flat_ev.append((t, e0, e1))
-        else:
-            step(t)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    prof = B.ovggt_profile_read(cache.h, cache.stream)
-    # what an event bracket reports beyond the bracketed kernel's own execution (empty launch)
-    bracket_overhead_ms = B.ovggt_profile_overhead(cache.h, 64, cache.stream)
-    status = [cache.status(l) for l in range(L)]
-    assert not any(status), f"device status {status}"
-    n_res = cache.size(0)
-    assert n_res == min(T * cfg.M, cfg.B)
-
-    # ---- per-kernel detail on further (untimed) steady-state steps
-    B.ovggt_profile_enable(cache.h, 2, 1)
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.detail_steps)]
-    for i in range(args.detail_steps):
-        ev[i][0].record()
-        step(T + i)
-        ev[i][1].record()
-    torch.cuda.synchronize()
-    detail = B.ovggt_profile_read(cache.h, cache.stream)
-    B.ovggt_profile_enable(cache.h, 0, 1)
-    lat = sorted(a.elapsed_time(b) for a, b in ev) if ev else [0.0]
-
-    # ---- roofline of the dominant kernel (attention): algorithmic FLOP = 4*M*N*H*d per layer
-    n_keys = min(cfg.B, T * cfg.M) + cfg.M if T * cfg.M > cfg.B else T * cfg.M
-    attn_ms, attn_cnt = prof["attn"]
-    flop = 4.0 * cfg.M * n_keys * cfg.H * cfg.d * L
-    bracket_ms = attn_ms / max(attn_cnt, 1)
-    attn_avg_ms = max(bracket_ms - bracket_overhead_ms, 1e-6)
-    achieved = flop / (attn_avg_ms * 1e-3) / 1e12 if attn_cnt else 0.0
-    # from the committed rocprofv3 summary of this workload (stored-score ranking, no smoothing): HBM
-    # bytes per launch, and the kernel's steady-state duration in the trace (the profiled run is a
-    # few per cent slower than a plain one)
-    wl = cfg.name.split("-")[0]
-    traffic = profiled_figure("traffic_bytes_per_launch", "attn_bf16_kernel", wl, L)
-    traffic = None if traffic is None else int(traffic)
-    trace_us = profiled_figure("trace_avg_kernel_us", "attn_bf16_kernel", wl, L)
-    roofline = {"bound": "mfma", "kernel": "attn_bf16_kernel", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS,
-                "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
-                "traffic": traffic, "avg_kernel_ms": attn_avg_ms,
-                "profiled_kernel_ms": None if trace_us is None else trace_us * 1e-3, "event_bracket_ms": bracket_ms,
-                "event_bracket_of_empty_launch_ms": bracket_overhead_ms, "launches_timed": int(attn_cnt),
-                "flop_per_launch": flop, "keys_per_launch": int(n_keys)}
-
-    kernels = {}
-    for name, (ms, cnt) in detail.items():
-        if cnt:
-            kernels[name] = {"avg_us": 1e3 * ms / cnt, "launches": int(cnt)}
-    esz = 2 if cfg.dtype == "bf16" else 4
-    hbm = {}
-    if "score_select" in kernels:
-        byts = L * (cfg.M * cfg.C * esz + 4 * cfg.M + 9 * n_keys)
-        hbm["score_select"] = {"algorithmic_bytes": byts, "GB/s": byts / (kernels["score_select"]["avg_us"] * 1e-6) / 1e9}
-    move_bytes = 0
-    if args.rising_scores:
-        moves = len(cache.last_moves(0)[0])
-        assert moves == cfg.M, f"rising scores: {moves} of {cfg.M} entries moved in the last frame"
-        move_bytes = L * moves * (2 * cfg.H * cfg.d * esz + 9) * 2           # K, V, id, score, flag: read and written
-        if "compact" in kernels:
-            hbm["compact"] = {"algorithmic_bytes": move_bytes, "GB/s": move_bytes / (kernels["compact"]["avg_us"] * 1e-6) / 1e9,
-                              "entries_moved_per_layer": moves}
-    if "append" in kernels:
-        byts = L * 4 * cfg.M * cfg.H * cfg.d * esz
-        if move_bytes and not args.standalone_compact:                       # the append carries the moves as well
-            byts += move_bytes
-        hbm["append"] = {"algorithmic_bytes": byts, "GB/s": byts / (kernels["append"]["avg_us"] * 1e-6) / 1e9}
-    for v in hbm.values():
-        v["frac_of_8TBs"] = v["GB/s"] / HBM_PEAK_GBS
-
+    cap = args.distinct_frames
+    if cap is None and cfg.L > 1:
+        cap = 24                                         # many layers: host generation dominates otherwise
+    main_r = run_workload(cfg, W, K, hybrid_beta=args.hybrid_beta, smooth_alpha=args.smooth_alpha,
+                          rising=args.rising_scores, standalone_compact=args.standalone_compact,
+                          detail_steps=args.detail_steps, flatness=args.flatness, settle_ms=args.settle_ms,
+                          distinct_cap=cap, graph=True)
+    smooth = main_r.pop("_smooth")
     res = {
         "metric": "streamed frames/sec at fixed cache budget",
-        "value": K / elapsed,
+        "value": main_r["value"],
         "unit": "frames/s",
         "n_gpus": 1, "steps": K, "warmup": W,
-        "ms_per_step": 1e3 * elapsed / K,
+        "ms_per_step": main_r["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": cfg.dtype, "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: {L} layer(s) x (M={cfg.M} tokens/frame, {cfg.H}x{cfg.d} heads, "
-                               f"C={cfg.C}, budget B={cfg.B}), {T}-frame stream, {cfg.dtype}",
-                   "tokens_per_frame": cfg.M, "budget": cfg.B, "layers": L, "frames": T,
-                   "resident_keys_steady": int(n_keys), "out_dtype": "f32",
-                   "ranking": ("hybrid Eq. 7, beta=%g" % args.hybrid_beta) if args.hybrid_beta is not None
-                              else "stored Eq. 5 scores",
-                   "smoothing": ("Eq. 6, alpha=%g, 3x3 Gaussian sigma 1" % args.smooth_alpha) if smooth else "off",
-                   "scores": "rising with t (worst case for compaction)" if args.rising_scores else "workload's own",
-                   "compaction": "stand-alone kernel after every frame" if args.standalone_compact
-                                 else "carried by the next frame's append"},
-        "roofline": roofline,
-        "kernels_us": kernels,
-        "hbm_kernels": hbm,
-        "step_latency_ms": {"p50": lat[len(lat) // 2], "p99": lat[min(len(lat) - 1, int(0.99 * len(lat)))],
-                            "note": "per-step events on untimed steady-state steps with per-kernel events enabled"},
-        "cache_bytes": {"kv": cache.bytes[0], "meta": cache.bytes[1], "workspace": cache.bytes[2]},
-        "input_staging_s": gen_s,
+        "dtype": ARITHMETIC, "data": "synthetic",
     }
-    if flat_ev:
-        # steady state only: the resident key count is constant once the cache is full
-        full_from = cfg.B // cfg.M + 1
-        pts = [(t, a.elapsed_time(b)) for t, a, b in flat_ev if t >= full_from]
-        if len(pts) >= 8:
-            tt = np.array([p[0] for p in pts], dtype=np.float64)
-            ms = np.array([p[1] for p in pts], dtype=np.float64)
-            slope, icpt = np.polyfit(tt, ms, 1)
-            q = len(pts) // 4
-            res["flatness"] = {"samples": len(pts), "first_frame": int(tt[0]), "last_frame": int(tt[-1]),
-                               "mean_ms": float(ms.mean()), "mean_ms_first_quarter": float(ms[:q].mean()),
-                               "mean_ms_last_quarter": float(ms[-q:].mean()),
-                               "slope_us_per_1000_frames": float(slope * 1e6),
-                               "note": "event-bracketed whole steps, every 8th timed step, frames with a full cache"}
-    if args.mfma_loop:
-        rnd = B.ovggt_profile_mfma_loop(cache.h, True, 20000, cache.stream)
-        cst = B.ovggt_profile_mfma_loop(cache.h, False, 20000, cache.stream)
-        res["mfma_loop"] = {"random_operands_TFLOPs": rnd, "constant_operands_TFLOPs": cst, "unit": "TFLOP/s",
-                            "instruction": "v_mfma_f32_32x32x16_f16", "waves_per_simd": 2,
-                            "attention_frac_of_random_operand_rate": res["roofline"]["achieved"] / rnd}
-    cache.close()
+    for k in ("config", "roofline", "kernels_us", "hbm_kernels", "step_latency_ms", "cache_bytes", "input_staging_s",
+              "flatness", "graph_replay"):
+        if k in main_r and main_r[k] is not None:
+            res[k] = main_r[k]
+
+    if not args.no_extra_workloads:
+        from paper_2603_05959_amd import measure
+        wl = {}
+        # the 24-layer stack, all layers per call: attention fraction, append and score/select bandwidth
+        r = run_workload(synth.preset(2), 5, 30, detail_steps=20, settle_ms=args.settle_ms, distinct_cap=16)
+        r.pop("_smooth")
+        wl["cfg2-24-layers"] = brief(r)
+        # the same stack under the worst case for compaction: M entries move per layer and frame
+        r = run_workload(synth.preset(2), 2, 6, rising=True, detail_steps=6, settle_ms=0.0)
+        r.pop("_smooth")
+        wl["cfg2-24-layers-worst-case-compaction"] = brief(r)
+        r = run_workload(synth.preset(2), 2, 6, rising=True, standalone_compact=True, detail_steps=6, settle_ms=0.0)
+        r.pop("_smooth")
+        wl["cfg2-24-layers-worst-case-compaction-standalone-kernel"] = brief(r)
+        # the 2000-frame stream at B = 32768: flat step latency (staged frames are reused)
+        c3 = synth.preset(3)
+        P3 = -(-c3.B // c3.M) + 1
+        r = run_workload(c3, 8, c3.T - P3 - 8, detail_steps=20, flatness=True, settle_ms=args.settle_ms, distinct_cap=64)
+        r.pop("_smooth")
+        wl["cfg3-ultra-long"] = brief(r)
+        # what a loop of nothing but the attention kernel's MFMA sustains on this machine
+        sink = torch.zeros(64, dtype=torch.float32, device="cuda:0")
+        stream = torch.cuda.current_stream().cuda_stream
+        n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+        rnd = measure.ovggt_measure_mfma_loop(sink, 2 * n_cu, True, 20000, stream)
+        cst = measure.ovggt_measure_mfma_loop(sink, 2 * n_cu, False, 20000, stream)
+        wl["mfma_loop"] = {"random_operands_TFLOPs": rnd, "constant_operands_TFLOPs": cst, "unit": "TFLOP/s",
+                           "instruction": "v_mfma_f32_32x32x16_f16", "waves_per_simd": 2,
+                           "attention_frac_of_random_operand_rate": res["roofline"]["achieved"] / rnd}
+        res["workloads"] = wl
     if not args.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline(cfg, warm_frames=max(cfg.B // cfg.M + 2, 2), timed_frames=args.cpu_frames,
-                                           smooth=smooth, hybrid_beta=args.hybrid_beta, threads=args.cpu_threads)
+        res["cpu_baseline"] = cpu_baseline(cfg, args.cpu_frames, args.cpu_frames_one_thread, smooth=smooth,
+                                           hybrid_beta=args.hybrid_beta, threads=args.cpu_threads)
     print(json.dumps(res))
 
 

@@ -53,7 +53,7 @@ enum {
   OVGGT_OK = 0,
   OVGGT_ERR_ARG = -1,      /* NULL / misaligned pointer, bad layer, bad config value   */
   OVGGT_ERR_STATE = -2,    /* call out of order for that layer                          */
-  OVGGT_ERR_BUDGET = -3,   /* reserved: protected set larger than the budget (host-known) */
+  OVGGT_ERR_NOMEM = -3,    /* host memory for the handle could not be allocated         */
   OVGGT_ERR_HIP = -4       /* a HIP runtime call failed (launch, copy, query)            */
 };
 /* bits of the device status word */
@@ -118,7 +118,7 @@ int ovggt_cache_query_bytes(const ovggt_config* cfg, size_t* kv_bytes, size_t* m
 /* Create a handle over caller-allocated device buffers of at least the queried
  * sizes (256-byte aligned).  Enqueues zero-fill kernels for all three buffers on
  * `hip_stream`; the cache starts empty (Sec. 3.1: C_{-1} is empty).  *out is
- * host memory freed by ovggt_cache_destroy.  ERR_ARG / ERR_HIP. */
+ * host memory freed by ovggt_cache_destroy.  ERR_ARG / ERR_NOMEM / ERR_HIP. */
 int ovggt_cache_init(ovggt_cache** out, const ovggt_config* cfg,
                      void* kv_dev, void* meta_dev, void* ws_dev, void* hip_stream);
 
@@ -133,8 +133,12 @@ int ovggt_cache_init(ovggt_cache** out, const ovggt_config* cfg,
  * fp32.  Accuracy of bf16 runs: the rounded query makes a logit of magnitude x
  * (after the scale, in units of ln 2) uncertain by about x * 2^-12, so the
  * output error relative to the output's RMS is a few 1e-3 for logits of unit
- * spread and approaches 2e-2 when their spread reaches 16.  ERR_STATE unless the
- * layer expects a new frame. */
+ * spread and approaches 2e-2 when their spread reaches 16.  Range of bf16 runs: K
+ * and V elements beyond +-65504 saturate when cached (OVGGT_STATUS_VRANGE); a query
+ * element whose product with scale*log2(e) lies beyond +-65504 is clamped to that
+ * bound without a status bit (a finite result instead of NaN; such logits are far
+ * outside what the rounding above resolves).  ERR_STATE unless the layer expects a
+ * new frame. */
 int ovggt_global_attn(ovggt_cache* c, int layer, const void* q, const void* k_new, const void* v_new,
                       void* out, void* hip_stream);
 
@@ -150,19 +154,39 @@ int ovggt_global_attn(ovggt_cache* c, int layer, const void* q, const void* k_ne
 int ovggt_score_select(ovggt_cache* c, int layer, const void* resid, const uint8_t* anchor_flags,
                        void* hip_stream);
 
-/* Applies the move list: the r-th vacated slot below B (ascending) receives the
- * r-th surviving slot at or above B (ascending), for K, V, ids, scores and
- * flags; the layer then holds min(n+M, B) entries.  Sources and destinations
- * are disjoint, so the rewrite is in place.  ERR_STATE unless ovggt_score_select
- * was the previous call for the layer.
- * The sources are exactly the slots the next frame's append overwrites, so the
- * copy is enqueued with that append (one launch and one pass over those slots
- * less per frame) on the stream of that ovggt_global_attn call; every other
- * entry point that reads or changes the cache (export, import, set_protect,
- * ovggt_cache_flush) applies it first, on its own stream.  Through this
- * interface the cache always reads as compacted; only a caller that inspects
- * the device buffers directly needs ovggt_cache_flush. */
+/* Eq. 8's "evict the rest", applied to the layout: after the selection the layer holds
+ * min(n+M, B) entries.  Stream rule first: this call enqueues nothing on `hip_stream`.  It closes
+ * the frame on the host; the copy itself is enqueued by the next call that touches the layer's
+ * cache, on THAT call's stream -- normally the next ovggt_global_attn, whose append overwrites
+ * exactly the moved entries' old slots and carries them to their destinations in the same pass
+ * (one launch and one pass over those slots less per frame); export, import, set_protect and
+ * ovggt_cache_flush apply it first, on their own stream.  A caller that orders work by the
+ * stream passed here must therefore order the next call on the layer as well (the general rule:
+ * calls on one handle are issued on streams that order them), or call ovggt_cache_flush on the
+ * stream it wants the copy on.  Through this interface the cache always reads as compacted.
+ * Layout rule (the paper only says that the rest is evicted; this is the build's own choice,
+ * unpinned by the paper): the r-th vacated slot below B (ascending) receives the r-th surviving
+ * slot at or above B (ascending), for K, V, ids, scores and flags.  At most M entries move,
+ * sources and destinations are disjoint, so the rewrite is in place.  Slot order is then not
+ * chronological; attention does not depend on it.  ERR_STATE unless ovggt_score_select was the
+ * previous call for the layer. */
 int ovggt_cache_compact(ovggt_cache* c, int layer, void* hip_stream);
+
+/* Replaying a step from a HIP graph.  The three hot-path calls of a frame only launch kernels
+ * (no memset or copy nodes, no host synchronisation, no allocation) and no kernel argument depends
+ * on the frame number -- the frame's first token id t*M (Eq. 2's arrival order) is kept in device
+ * memory -- so once the cache is full a step may be captured into a graph (hipStreamBeginCapture
+ * on the stream passed to the calls; kernel timing off) and replayed for every later frame, with
+ * the frame's inputs copied into the captured buffers before each replay.  The capture requires
+ * the steady state: at least one evicting frame completed, nothing that flushes the compaction
+ * (export, set_protect, ...) since.  The captured calls update the host-side state as if they had
+ * run, so the capture accounts for the first replay; BEFORE every further replay call
+ * ovggt_cache_advance(c, layer, 1) (or once with the count before a run of replays): it checks
+ * that the handle is still in the state the graph was captured in and counts the frames.  If it
+ * fails, do not replay; issue the frame through the three calls instead.  Host arithmetic only.
+ * ERR_STATE unless the layer is in that steady state and expects a new frame; ERR_ARG if
+ * frames < 1 or the token ids would leave 32 bits. */
+int ovggt_cache_advance(ovggt_cache* c, int layer, int64_t frames);
 
 /* Enqueues any compaction of `layer` (or OVGGT_ALL_LAYERS) that has not been
  * applied yet, as a launch of its own on `hip_stream`.  No-op otherwise. */
@@ -234,15 +258,6 @@ int ovggt_profile_read(ovggt_cache* c, double* ms_sum, int64_t* count, void* hip
  * call it between frames only): what a bracket reports beyond the bracketed
  * kernel's own execution.  Synchronises `hip_stream`. */
 int ovggt_profile_overhead(ovggt_cache* c, int reps, double* ms_mean, void* hip_stream);
-
-/* Measurement helper: the rate (TFLOP/s, host double) that the matrix cores sustain when every
- * wave issues nothing but the attention kernel's MFMA (v_mfma_f32_32x32x16_f16) on register
- * operands, two waves per SIMD on every CU, `iters` rounds of four per wave (20000 makes a
- * launch of about a millisecond), twenty launches timed after one of warm-up.  random_operands
- * != 0: unit-variance random operands, under which the chip lowers its clock; 0: constant
- * operands.  Uses the first bytes of the handle's workspace as a sink that is never written;
- * synchronises `hip_stream`.  Not for use between the hot-path calls of a frame. */
-int ovggt_profile_mfma_loop(ovggt_cache* c, int random_operands, int iters, double* tflops, void* hip_stream);
 
 /* ---- Dynamic Anchor Protection: which frames become anchors (Sec. 3.3) ------------------
  * Host-only bookkeeping; no device work, usable without a GPU.  The model's outputs are inputs:

@@ -15,7 +15,7 @@ LIB_PATH = os.environ.get("OVGGT_LIB") or os.path.join(_PKG, "libovggt.so")   # 
 
 OVGGT_F32, OVGGT_BF16 = 0, 1
 OVGGT_ALL_LAYERS = -1
-OVGGT_OK, OVGGT_ERR_ARG, OVGGT_ERR_STATE, OVGGT_ERR_BUDGET, OVGGT_ERR_HIP = 0, -1, -2, -3, -4
+OVGGT_OK, OVGGT_ERR_ARG, OVGGT_ERR_STATE, OVGGT_ERR_NOMEM, OVGGT_ERR_HIP = 0, -1, -2, -3, -4
 OVGGT_STATUS_BUDGET, OVGGT_STATUS_NONFINITE, OVGGT_STATUS_VRANGE = 1, 2, 4
 
 EXPORTS = (
@@ -24,7 +24,7 @@ EXPORTS = (
     "ovggt_cache_status", "ovggt_cache_export", "ovggt_cache_import", "ovggt_cache_last_moves",
     "ovggt_profile_enable", "ovggt_profile_read", "ovggt_profile_overhead", "ovggt_strerror",
     "ovggt_cache_set_protect", "ovggt_dap_create", "ovggt_dap_step", "ovggt_dap_active", "ovggt_dap_destroy",
-    "ovggt_attn_plan_stats", "ovggt_cache_flush", "ovggt_profile_mfma_loop",
+    "ovggt_attn_plan_stats", "ovggt_cache_flush", "ovggt_cache_advance",
 )
 PROF_CLASSES = ("append", "attn", "combine", "score_select", "compact")
 
@@ -65,6 +65,7 @@ def lib() -> C.CDLL:
     L.ovggt_score_select.argtypes = [vp, C.c_int, vp, u8p, vp]
     L.ovggt_cache_compact.argtypes = [vp, C.c_int, vp]
     L.ovggt_cache_flush.argtypes = [vp, C.c_int, vp]
+    L.ovggt_cache_advance.argtypes = [vp, C.c_int, i64]
     L.ovggt_cache_destroy.argtypes = [vp]
     L.ovggt_cache_size.argtypes = [vp, C.c_int, C.POINTER(i32)]
     L.ovggt_cache_frames.argtypes = [vp, C.c_int, C.POINTER(i64)]
@@ -75,7 +76,6 @@ def lib() -> C.CDLL:
     L.ovggt_profile_enable.argtypes = [vp, C.c_int, C.c_int]
     L.ovggt_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64), vp]
     L.ovggt_profile_overhead.argtypes = [vp, C.c_int, C.POINTER(C.c_double), vp]
-    L.ovggt_profile_mfma_loop.argtypes = [vp, C.c_int, C.c_int, C.POINTER(C.c_double), vp]
     L.ovggt_cache_set_protect.argtypes = [vp, C.c_int, i64, u8p, C.c_int, vp]
     L.ovggt_dap_create.argtypes = [C.POINTER(vp), i32, i32, C.c_double, C.c_double, i32, i32]
     L.ovggt_dap_step.argtypes = [vp, i64, C.c_double, vp, C.POINTER(i64), u8p, C.POINTER(i64)]
@@ -156,6 +156,10 @@ def ovggt_cache_compact(h, layer, stream: int = 0) -> None:
 
 def ovggt_cache_flush(h, layer, stream: int = 0) -> None:
     _check(lib().ovggt_cache_flush(h, layer, stream), "ovggt_cache_flush")
+
+
+def ovggt_cache_advance(h, layer, frames: int = 1) -> None:
+    _check(lib().ovggt_cache_advance(h, layer, frames), "ovggt_cache_advance")
 
 
 def ovggt_cache_destroy(h) -> None:
@@ -254,14 +258,6 @@ def ovggt_profile_overhead(h, reps: int = 64, stream: int = 0) -> float:
     return ms.value
 
 
-def ovggt_profile_mfma_loop(h, random_operands: bool, iters: int = 20000, stream: int = 0) -> float:
-    """TFLOP/s of a loop of nothing but the attention kernel's MFMA (see include/ovggt.h)."""
-    v = C.c_double()
-    _check(lib().ovggt_profile_mfma_loop(h, 1 if random_operands else 0, iters, C.byref(v), stream),
-           "ovggt_profile_mfma_loop")
-    return float(v.value)
-
-
 # ---- convenience owner of the device buffers ---------------------------------
 @dataclass
 class _Bufs:
@@ -307,6 +303,9 @@ class Cache:
 
     def flush(self, layer=OVGGT_ALL_LAYERS):
         ovggt_cache_flush(self.h, layer, self.stream)
+
+    def advance(self, frames=1, layer=OVGGT_ALL_LAYERS):
+        ovggt_cache_advance(self.h, layer, frames)
 
     def step(self, q, k_new, v_new, resid, anchor_flags, out, layer=OVGGT_ALL_LAYERS):
         self.global_attn(q, k_new, v_new, out, layer)

@@ -73,10 +73,7 @@ __device__ __forceinline__ int swz(int row) { return row & 7; }
 // Wave priority in the two phases.  The vector phase is the longer one and its VALU stream loses
 // issue slots to the other set's MFMAs; giving it the higher priority shortens the younger set's
 // vector phase by a tenth (measured) at no cost to the matrix phase that runs beside it.
-#ifndef OVGGT_PRIO_M
-#define OVGGT_PRIO_M 0
-#define OVGGT_PRIO_V 3
-#endif
+constexpr int kPrioMatrix = 0, kPrioVector = 3;
 constexpr int kTileBytes = kSlotTile * 128;            // one K (or V) tile: 128 slots x 64 16-bit elements
 constexpr int kSetBytes = 4 * kTileBytes;              // LDS of one wave set: [parity][K | V]
 constexpr int kAttnThreads = 512;
@@ -334,13 +331,29 @@ __device__ __forceinline__ void qk_tile(const f16x8 (&kf)[4][2], const f16x8 (&q
   }
 }
 
+// Tail tile: accumulator i of slot block sb belongs to slot sbase + 32*sb + 8*(i/4) + i%4 (this lane's
+// contraction group is part of sbase).  Exponents of slots at or beyond n_total become -inf: exp2
+// gives them weight 0 and a maximum ignores them.  A lane (or a whole wave) left without any real
+// slot ends with the reference -65504 and a zero sum, which the merges treat as an empty part.
+__device__ __forceinline__ void mask_absent_slots(f32x16 (&S)[2][2], int sbase, int n_total) {
+  asm volatile("; tail tile: exponents of absent slots" ::: "memory");   // keeps the caller's test a real branch
+#pragma unroll
+  for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const bool absent = sbase + sb * 32 + (i >> 2) * 8 + (i & 3) >= n_total;
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb) S[sb][qb][i] = absent ? -INFINITY : S[sb][qb][i];
+    }
+}
+
 // Vector phase: online softmax of one 64-slot x 64-query tile of one wave.
 // S holds x = s*c - ref for the reference ref the query block had when the matrix phase ran; ref
 // is (a half-representable value near) the running maximum of s*c minus 7, so weights are stored
 // as 2^7 * p and sit in the middle of the half range.
-// tail: the tile extends past n_total (only the last tile can); weights of the absent slots are
-// cleared after the softmax (their rows hold zeros or stale but finite keys, so their exponents
-// are finite and merely move the reference).
+// tail: the tile extends past n_total (only the last tile can); the exponents of the absent slots
+// are set to -inf before anything looks at them, so they neither move the reference nor carry
+// weight (their rows hold zeros or stale but finite values, so 0 * V stays finite).
 //
 // Fast path: weights are formed against the current reference without looking for this tile's
 // maximum; p = exp2(x) is rounded to half and summed.  If the lane's sum stays below 2^15 no
@@ -359,6 +372,7 @@ __device__ __forceinline__ void softmax_tile(f32x16 (&S)[2][2], uint32_t (&P)[2]
                                              const int (&koff)[4], const f16x8 (&qf)[2][4], f16x4 kones) {
   float lsum[2];
   bool overflow = false;
+  if (__builtin_expect(tail, 0)) mask_absent_slots(S, sbase, n_total);
   if constexpr (!force) {
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb)
@@ -383,6 +397,7 @@ __device__ __forceinline__ void softmax_tile(f32x16 (&S)[2][2], uint32_t (&P)[2]
       f16x8 kf[4][2];
       k_frags<PAR>(lds, koff, kf);
       qk_tile(kf, qf, qbias, kones, S);
+      if (tail) mask_absent_slots(S, sbase, n_total);
     }
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
@@ -406,25 +421,6 @@ __device__ __forceinline__ void softmax_tile(f32x16 (&S)[2][2], uint32_t (&P)[2]
 #pragma unroll
         for (int i = 0; i < 16; ++i) O[db][qb][i] *= alpha;
       lsum[qb] = tile_weights<true>(S[0][qb], S[1][qb], d, P[0][qb], P[1][qb]);
-    }
-  }
-  if (__builtin_expect(tail, 0)) {
-    asm volatile("; tail tile: clear absent slots" ::: "memory");   // keeps this block a real branch (never if-converted)
-#pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-      float ls = 0.f;
-#pragma unroll
-      for (int sb = 0; sb < 2; ++sb)
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          const int slot = sbase + sb * 32 + (j >> 1) * 8 + (j & 1) * 2;      // slots of accumulators 2j, 2j+1
-          uint32_t w = P[sb][qb][j];
-          w &= (slot < n_total ? 0x0000FFFFu : 0u) | (slot + 1 < n_total ? 0xFFFF0000u : 0u);
-          P[sb][qb][j] = w;
-          const f16x2 h = __builtin_bit_cast(f16x2, w);
-          ls += (float)h[0] + (float)h[1];
-        }
-      lsum[qb] = ls;
     }
   }
   lrun[0] += lsum[0];
@@ -467,7 +463,7 @@ __device__ __forceinline__ void tile_step(TileCtx& x, int tt, const int (&koff)[
   __builtin_amdgcn_sched_barrier(0);
 #endif
   // ---- matrix phase
-  __builtin_amdgcn_s_setprio(OVGGT_PRIO_M);
+  __builtin_amdgcn_s_setprio(kPrioMatrix);
   if (x.active) {
     if (more)
       load_rows_to_lds(x.kbase + (size_t)(tt + 1) * kTileBytes, x.lane_off, x.lds_ld + (PAR ^ 1) * 2 * kTileBytes);
@@ -496,7 +492,7 @@ __device__ __forceinline__ void tile_step(TileCtx& x, int tt, const int (&koff)[
 #pragma unroll
       for (int b = 0; b < 2; ++b) asm volatile("" : "+v"(z.S[a][b]));      // issued before the barrier
   }
-  __builtin_amdgcn_s_setprio(OVGGT_PRIO_V);
+  __builtin_amdgcn_s_setprio(kPrioVector);
 #ifdef OVGGT_TRACE
   __builtin_amdgcn_sched_barrier(0);
   const unsigned long long tr1 = clock64();
@@ -642,8 +638,9 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           f16x2 hh;
-          hh[0] = (_Float16)(__uint_as_float(w[e] << 16) * p.c);
-          hh[1] = (_Float16)(__uint_as_float(w[e] & 0xFFFF0000u) * p.c);
+          // c * q beyond the half range is clamped to +-65504 (it would turn into +-inf and the row into NaN)
+          hh[0] = (_Float16)__builtin_amdgcn_fmed3f(__uint_as_float(w[e] << 16) * p.c, -65504.f, 65504.f);
+          hh[1] = (_Float16)__builtin_amdgcn_fmed3f(__uint_as_float(w[e] & 0xFFFF0000u) * p.c, -65504.f, 65504.f);
           r[e] = __builtin_bit_cast(uint32_t, hh);
         }
         z.qf[qb][ks] = __builtin_bit_cast(f16x8, r);

@@ -48,8 +48,7 @@ hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
 // reads or writes either location.
 template <bool MOVES>
 __global__ void __launch_bounds__(256)
-append_kernel(Geom g, char* kv, char* meta, int layer0, const char* k_new, const char* v_new,
-              int n, uint32_t gid0) {
+append_kernel(Geom g, char* kv, char* meta, int layer0, const char* k_new, const char* v_new, int n) {
   const int layer = layer0 + blockIdx.y;
   if (g.hybrid && blockIdx.x == 0) {
     // Hybrid scoring: the frame's diversity pass wants the centroid in fp32.  The running sum (64-bit
@@ -109,6 +108,9 @@ append_kernel(Geom g, char* kv, char* meta, int layer0, const char* k_new, const
   *(uint4*)(layer_k(kv, g, layer) + dst) = kk;
   *(uint4*)(layer_v(kv, g, layer) + dst) = vv;
   if (h == 0 && piece == 0) {
+    // ids t*M + i (Eq. 2's arrival order): the frame's first id lives in the control block, where the
+    // previous frame's selection left it, so the launch is the same for every frame (graph replay)
+    const uint32_t gid0 = ((const Ctrl*)(mb + g.off_ctrl))->gid_next;
     ((uint32_t*)(mb + g.off_ids))[n + m] = gid0 + (uint32_t)m;
     ((float*)(mb + g.off_ss))[n + m] = 0.f;
     ((uint8_t*)(mb + g.off_flags))[n + m] = 0;
@@ -116,17 +118,17 @@ append_kernel(Geom g, char* kv, char* meta, int layer0, const char* k_new, const
 }
 
 hipError_t launch_append(const Geom& g, char* kv, char* meta, int layer0, int nl,
-                         const void* k_new, const void* v_new, int n, uint32_t gid0, bool apply_moves, hipStream_t s) {
+                         const void* k_new, const void* v_new, int n, bool apply_moves, hipStream_t s) {
   const size_t total = (size_t)g.M * g.H * (g.d * g.esize / 16);
   dim3 grid((unsigned)((total + 255) / 256), (unsigned)nl);
   if (apply_moves && n == g.B)
     hipLaunchKernelGGL(append_kernel<true>, grid, dim3(256), 0, s, g, kv, meta, layer0,
-                       (const char*)k_new, (const char*)v_new, n, gid0);
+                       (const char*)k_new, (const char*)v_new, n);
   else if (apply_moves)
     return hipErrorInvalidValue;                     // a pending compaction implies a full cache
   else
     hipLaunchKernelGGL(append_kernel<false>, grid, dim3(256), 0, s, g, kv, meta, layer0,
-                       (const char*)k_new, (const char*)v_new, n, gid0);
+                       (const char*)k_new, (const char*)v_new, n);
   return hipGetLastError();
 }
 

@@ -1,11 +1,14 @@
-// Measurement helper, not part of the hot path: the rate the matrix cores sustain on this chip when
+// libovggt_measure: a measurement helper built as a library of its own, apart from the hot path's
+// (include/ovggt_measure.h).  It measures the rate the matrix cores sustain on this chip when
 // they do nothing but the attention kernel's MFMA (v_mfma_f32_32x32x16_f16, fp32 accumulation) --
 // the denominator that is reachable in practice, beside the published dense peak.  Operands live
 // in registers; with random operands the chip lowers its clock under the matrix load, with
 // constant ones it does not, so both are reported.
-#include "ovggt_internal.h"
+#include "../../../include/ovggt_measure.h"
+#include <hip/hip_runtime.h>
+#include <stdint.h>
 
-namespace ovggt {
+namespace {
 
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
@@ -49,10 +52,31 @@ __global__ void __launch_bounds__(256) mfma_loop_kernel(float* sink, int iters, 
   if (r == 12345.678f) sink[0] = r;                     // never true: keeps the loop alive
 }
 
-// FLOP of one launch: workgroups * 4 waves * 4 * iters MFMAs of 2*32*32*16 each.
-hipError_t launch_mfma_loop(float* sink, int workgroups, int iters, int random, hipStream_t s) {
-  hipLaunchKernelGGL(mfma_loop_kernel, dim3((unsigned)workgroups), dim3(256), 0, s, sink, iters, random);
-  return hipGetLastError();
-}
+}  // namespace
 
-}  // namespace ovggt
+extern "C" int ovggt_measure_mfma_loop(void* sink_dev, int32_t workgroups, int32_t random_operands, int32_t iters,
+                                       double* tflops, void* hip_stream) {
+  if (!sink_dev || !tflops || workgroups < 1 || workgroups > 65536 || iters < 1 || iters > (1 << 20)) return -1;
+  hipStream_t s = (hipStream_t)hip_stream;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  if (hipEventCreate(&e0) != hipSuccess) return -4;
+  if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return -4; }
+  const int reps = 20;
+  auto launch = [&]() {
+    hipLaunchKernelGGL(mfma_loop_kernel, dim3((unsigned)workgroups), dim3(256), 0, s, (float*)sink_dev, iters, random_operands);
+    return hipGetLastError() == hipSuccess;
+  };
+  bool ok = launch();                                   // warm-up: the clock settles under the load
+  ok = ok && hipEventRecord(e0, s) == hipSuccess;
+  for (int r = 0; ok && r < reps; ++r) ok = launch();
+  ok = ok && hipEventRecord(e1, s) == hipSuccess && hipStreamSynchronize(s) == hipSuccess;
+  float ms = 0.f;
+  ok = ok && hipEventElapsedTime(&ms, e0, e1) == hipSuccess && ms > 0.f;
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (!ok) return -4;
+  // FLOP of one launch: workgroups * 4 waves * 4 * iters MFMAs of 2*32*32*16 each
+  const double flop = (double)reps * workgroups * 4.0 * 4.0 * iters * 2.0 * 32 * 32 * 16;
+  *tflops = flop / (ms * 1e-3) * 1e-12;
+  return 0;
+}

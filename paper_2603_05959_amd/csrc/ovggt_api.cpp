@@ -224,7 +224,7 @@ int ovggt_cache_init(ovggt_cache** out, const ovggt_config* cfg, void* kv_dev, v
   if (hipGetDevice(&dev) != hipSuccess) return OVGGT_ERR_HIP;
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return OVGGT_ERR_HIP;
   ovggt_cache* c = new (std::nothrow) ovggt_cache();
-  if (!c) return OVGGT_ERR_ARG;
+  if (!c) return OVGGT_ERR_NOMEM;
   c->cfg = *cfg;
   make_geom(*cfg, &c->g);
   c->smooth.alpha = cfg->smooth_alpha;
@@ -235,10 +235,6 @@ int ovggt_cache_init(ovggt_cache** out, const ovggt_config* cfg, void* kv_dev, v
   int wgs = cus;
   wgs = (wgs + 7) & ~7;
   if (wgs < 8) wgs = 8;
-  if (const char* e = std::getenv("OVGGT_ATTN_WGS")) {          // tuning knob: attention workgroups per launch
-    const int v = std::atoi(e);
-    if (v >= 8) wgs = (v + 7) & ~7;
-  }
   if (wgs > kMaxAttnWgs) wgs = kMaxAttnWgs;
   c->n_wgs = wgs;
   c->n.assign(c->g.L, 0);
@@ -280,7 +276,7 @@ int ovggt_global_attn(ovggt_cache* c, int layer, const void* q, const void* k_ne
   }
   {
     ProfScope ps(c, OVGGT_PROF_APPEND, s, prof_all);
-    if (launch_append(g, c->kv, c->meta, l0, nl, k_new, v_new, n, (uint32_t)gid0, all_pending, s) != hipSuccess)
+    if (launch_append(g, c->kv, c->meta, l0, nl, k_new, v_new, n, all_pending, s) != hipSuccess)
       return OVGGT_ERR_HIP;
   }
   for (int l = l0; l < l0 + nl; ++l) c->pending[l] = 0;
@@ -346,6 +342,20 @@ int ovggt_cache_compact(ovggt_cache* c, int layer, void* hip_stream) {
     c->frames[l] += 1;
     c->phase[l] = 0;
   }
+  return OVGGT_OK;
+}
+
+int ovggt_cache_advance(ovggt_cache* c, int layer, int64_t frames) {
+  if (!c || frames < 1) return OVGGT_ERR_ARG;
+  int l0, nl;
+  if (!layer_range(c, layer, &l0, &nl)) return OVGGT_ERR_ARG;
+  const Geom& g = c->g;
+  // a replayed step is the steady-state step: full cache, the last selection's moves outstanding
+  for (int l = l0; l < l0 + nl; ++l)
+    if (c->phase[l] != 0 || c->n[l] != g.B || !c->pending[l]) return OVGGT_ERR_STATE;
+  for (int l = l0; l < l0 + nl; ++l)
+    if ((c->frames[l] + frames) * (int64_t)g.M > 0xFFFFFFFFLL) return OVGGT_ERR_ARG;   // token ids are 32-bit
+  for (int l = l0; l < l0 + nl; ++l) c->frames[l] += frames;
   return OVGGT_OK;
 }
 
@@ -471,6 +481,8 @@ int ovggt_cache_import(ovggt_cache* c, int layer, int32_t n, int64_t frames, con
     if (launch_centroid_rebuild(g, c->kv, c->meta, layer, n, (hipStream_t)hip_stream) != hipSuccess) return OVGGT_ERR_HIP;
     if (hipStreamSynchronize((hipStream_t)hip_stream) != hipSuccess) return OVGGT_ERR_HIP;
   }
+  const uint32_t gid_next = (uint32_t)(frames * (int64_t)g.M);
+  if (hipMemcpy(&ctrl_of(c, layer)->gid_next, &gid_next, 4, hipMemcpyHostToDevice) != hipSuccess) return OVGGT_ERR_HIP;
   c->n[layer] = n;
   c->frames[layer] = frames;
   return OVGGT_OK;
@@ -543,27 +555,6 @@ int ovggt_profile_overhead(ovggt_cache* c, int reps, double* ms_mean, void* hip_
   return OVGGT_OK;
 }
 
-int ovggt_profile_mfma_loop(ovggt_cache* c, int random_operands, int iters, double* tflops, void* hip_stream) {
-  if (!c || !tflops || iters < 1 || iters > (1 << 20)) return OVGGT_ERR_ARG;
-  hipStream_t s = (hipStream_t)hip_stream;
-  const int wgs = 2 * c->n_wgs;                       // two waves per SIMD, as in the attention kernel
-  hipEvent_t e0 = prof_event(c), e1 = prof_event(c);
-  bool ok = e0 && e1;
-  const int reps = 20;
-  ok = ok && launch_mfma_loop((float*)c->ws, wgs, iters, random_operands, s) == hipSuccess;   // warm-up (clock settles)
-  ok = ok && hipEventRecord(e0, s) == hipSuccess;
-  for (int r = 0; ok && r < reps; ++r) ok = launch_mfma_loop((float*)c->ws, wgs, iters, random_operands, s) == hipSuccess;
-  ok = ok && hipEventRecord(e1, s) == hipSuccess && hipStreamSynchronize(s) == hipSuccess;
-  float ms = 0.f;
-  ok = ok && hipEventElapsedTime(&ms, e0, e1) == hipSuccess && ms > 0.f;
-  if (e0) c->prof_free.push_back(e0);
-  if (e1) c->prof_free.push_back(e1);
-  if (!ok) return OVGGT_ERR_HIP;
-  const double flop = (double)reps * wgs * 4.0 * 4.0 * iters * 2.0 * 32 * 32 * 16;
-  *tflops = flop / (ms * 1e-3) * 1e-12;
-  return OVGGT_OK;
-}
-
 int ovggt_attn_plan_stats(const ovggt_config* cfg, int32_t layers_in_launch, int32_t n_total, int32_t n_wgs,
                           int32_t* out, float* cost) {
   if (!valid_config(cfg) || !out || !cost || cfg->dtype != OVGGT_BF16) return OVGGT_ERR_ARG;
@@ -584,7 +575,7 @@ const char* ovggt_strerror(int code) {
     case OVGGT_OK: return "ok";
     case OVGGT_ERR_ARG: return "invalid argument";
     case OVGGT_ERR_STATE: return "call out of order for this layer";
-    case OVGGT_ERR_BUDGET: return "protected set exceeds the budget";
+    case OVGGT_ERR_NOMEM: return "out of host memory";
     case OVGGT_ERR_HIP: return "HIP runtime error";
     default: return "unknown error";
   }

@@ -16,7 +16,9 @@ struct Ctrl {
   uint32_t status;     // OVGGT_STATUS_* bits
   uint32_t n_moves;    // length of the move list written by the last selection
   uint32_t arrive;     // arrival counter of the score kernel's workgroups
-  uint32_t pad[61];
+  uint32_t gid_next;   // token id of the next frame's first token (t * M): read by the append, advanced by M by
+                       // the frame's selection, so a step's launches carry no per-frame argument
+  uint32_t pad[60];
 };
 static_assert(sizeof(Ctrl) == 256, "Ctrl is one 256-byte block");
 
@@ -58,11 +60,11 @@ __host__ __device__ inline char* layer_meta(char* meta, const Geom& g, int layer
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
 
 // Eq. 2: copy the frame's K/V rows into slots [n, n+M) of layers [layer0, layer0+nl)
-// and initialise their ids (gid0 + i), scores (0) and flags (0).  apply_moves: the previous
+// and initialise their ids (the layer's gid_next + i), scores (0) and flags (0).  apply_moves: the previous
 // frame's compaction is still outstanding (n == B then): every entry that the last selection
 // moves out of a slot the new frame overwrites is carried to its destination first.
 hipError_t launch_append(const Geom& g, char* kv, char* meta, int layer0, int nl,
-                         const void* k_new, const void* v_new, int n, uint32_t gid0, bool apply_moves, hipStream_t s);
+                         const void* k_new, const void* v_new, int n, bool apply_moves, hipStream_t s);
 
 // Attention of M queries over n_total resident slots.
 hipError_t launch_attn_f32(const Geom& g, char* kv, int layer0, int nl, const void* q, void* out,
@@ -127,10 +129,6 @@ hipError_t launch_centroid_protect(const Geom& g, char* kv, char* meta, int laye
                                    const uint8_t* mask, int on, hipStream_t s);
 hipError_t launch_set_protect(const Geom& g, char* meta, int layer0, int nl, int n, uint32_t gid_lo,
                               const uint8_t* mask, int on, hipStream_t s);
-
-// Measurement helper: `workgroups` workgroups of 4 waves, each wave 4 * iters back-to-back
-// v_mfma_f32_32x32x16_f16 on register operands (random != 0: unit-variance random, else ones).
-hipError_t launch_mfma_loop(float* sink, int workgroups, int iters, int random, hipStream_t s);
 
 // Apply the move list to K, V and the per-slot metadata.
 hipError_t launch_compact(const Geom& g, char* kv, char* meta, int layer0, int nl, hipStream_t s);

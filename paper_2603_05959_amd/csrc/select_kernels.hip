@@ -856,7 +856,7 @@ score_select_kernel(Geom g, SmoothParams sm, HybridParams hy, char* meta, int la
   }
   const bool smoothing = sm.alpha > 0.f;
   if (n_total <= g.B && !smoothing) {        // under budget and no smoothing: nothing needs the whole frame
-    if (blockIdx.x == 0 && tid == 0) ctrl->n_moves = 0;
+    if (blockIdx.x == 0 && tid == 0) { ctrl->n_moves = 0; ctrl->gid_next += (uint32_t)g.M; }
     return;
   }
   // Publish this workgroup's scores and count its arrival.  The scores were written through to
@@ -881,6 +881,7 @@ score_select_kernel(Geom g, SmoothParams sm, HybridParams hy, char* meta, int la
   if (!sh.is_last) return;
 
   // ---- phase 2: this workgroup saw every other one arrive
+  if (tid == 0) ctrl->gid_next += (uint32_t)g.M;       // once per layer and frame: the next frame's first token id
   uint32_t* mvdst = (uint32_t*)(mb + g.off_mvdst);
   uint32_t* mvsrc = (uint32_t*)(mb + g.off_mvsrc);
   if (smoothing) {

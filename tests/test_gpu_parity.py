@@ -127,12 +127,16 @@ def _hard_values(kind):
             f["v"] = f["v"] * 1e-3
         elif kind == "outlier_key":             # one key per frame carries most of every row's mass
             f["q"] = np.abs(f["q"]); f["k"][7] = 3.0
+        elif kind == "all_low":                 # every logit near -40 nats: far below the zero rows behind the
+            f["q"] = ones * 1.0                 # cache's end, which must not pull the reference up (the softmax
+            f["k"] = ones * -5.0 + f["k"] * 0.25   # is shift-invariant); the resident count is no multiple of 128
         for x in "qkv":
             f[x] = synth.quantise(np.ascontiguousarray(f[x], dtype=np.float32), cfg.dtype)
     return fn
 
 
-@pytest.mark.parametrize("kind", ["peaky", "rising", "falling", "constant", "zero_q", "big_v", "tiny_v", "outlier_key"])
+@pytest.mark.parametrize("kind", ["peaky", "rising", "falling", "constant", "zero_q", "big_v", "tiny_v", "outlier_key",
+                                  "all_low"])
 def test_attention_hard_value_distributions(kind):
     # 6 frames of 200 tokens under a budget that keeps everything: 1200 slots = 9 tiles + a tail,
     # every frame's output compared
@@ -182,6 +186,157 @@ def test_cfg4_shape_budget_sweep_and_full_cache_equality():
     assert np.array_equal(e["ids"], np.arange(cfg.T * cfg.M))
     assert np.array_equal(e["k"], stored_v(np.concatenate(ks), "bf16"))
     assert np.array_equal(e["v"], stored_v(np.concatenate(vs), "bf16"))
+    cache.close()
+
+
+@pytest.mark.parametrize("budget", [32768, 65536])
+def test_cfg4_large_budgets_attention_full_size(budget):
+    """The two largest budgets of the 518x392 sweep at full size (up to 66 577 resident keys, 521
+    slot tiles): sampled query rows against the oracle while the cache still holds the whole stream
+    (budget >= total: the result must equal uncompressed causal streaming attention, Eq. 2 over the
+    concatenated frames, which the test builds itself from the frames it fed), on the frames around
+    the first eviction, and 50 frames into eviction; kept ids, scores and flags on the way."""
+    torch = _torch()
+    cfg = synth.preset(4, B=budget)
+    fill = budget // cfg.M                       # frames that fit entirely: 31 (32 271 tokens), 62 (64 542)
+    T = fill + 52
+    cache = make_cache(cfg, L=1)
+    orc = oc.OracleCache(cfg.M, cfg.H, cfg.d, cfg.B)
+    out = cache.new_output()[0]
+    rows = np.unique(np.concatenate([np.random.default_rng(4).choice(cfg.M, size=40, replace=False), [0, 127, 128, 1040]]))
+    under = {0, fill // 2, fill - 1}
+    check = under | {fill, fill + 1, fill + 50}
+    ks, vs = [], []
+    worst = 0.0
+    for t in range(T):
+        f = synth.frame_inputs(cfg, 0, t)
+        cache.step(dev(f["q"], cfg), dev(f["k"], cfg), dev(f["v"], cfg), dev(f["r"], cfg),
+                   torch.from_numpy(f["a"]).cuda(), out, layer=0)
+        orc.append(f["k"], f["v"])
+        if t < fill:
+            ks.append(f["k"]); vs.append(f["v"])
+        if t in check:
+            o_gpu = out.float().cpu().numpy().astype(np.float64)[rows]
+            if t in under:                       # nothing has been evicted: the whole stream so far
+                assert cache.size(0) == (t + 1) * cfg.M
+                o_ref = oc.attention(f["q"][rows], np.concatenate(ks), np.concatenate(vs))
+            else:
+                o_ref = oc.attention(f["q"][rows], orc.k, orc.v)
+            err = rel_err(o_gpu, o_ref)
+            worst = max(worst, err)
+            assert err < TOL["bf16"], f"B={budget} frame {t}: attention error {err:.3e}"
+        orc.update(f["r"], f["a"])
+        if t == fill - 1:
+            e = cache.export(0)
+            assert np.array_equal(e["ids"], np.arange(fill * cfg.M))
+            assert np.array_equal(e["k"], stored_v(np.concatenate(ks), "bf16"))
+            assert np.array_equal(e["v"], stored_v(np.concatenate(vs), "bf16"))
+            ks, vs = [], []
+        if t in check or t == T - 1:
+            compare_cache(cache, orc, kv=(t == T - 1))
+        if t % 10 == 0:
+            print(f"[cfg4 B={budget}] frame {t} ok", flush=True)
+    assert cache.status(0) == 0
+    print(f"cfg4 B={budget}: worst sampled attention err/RMS {worst:.3e}")
+    cache.close()
+
+
+def test_cfg2_24_layers_kept_ids_deep_into_eviction():
+    """The 24-layer workload, all layers per call, 100 frames past the first eviction: kept ids,
+    slot layout, scores and flags of six layers after every evicting frame.  Three residual
+    streams are spread over the layers (layer l gets stream l mod 3); the cache policy of the
+    stored-score mode depends on residual rows and anchor bits only, so three oracles on a
+    one-element K/V cover all layers and the device side reuses one frame's Q/K/V."""
+    torch = _torch()
+    cfg = synth.preset(2)
+    L, kinds = cfg.L, 3
+    T = cfg.B // cfg.M + 1 + 100
+    cache = make_cache(cfg)
+    orcs = [oc.OracleCache(cfg.M, 1, 1, cfg.B) for _ in range(kinds)]
+    out = cache.new_output()
+    layer_kind = (torch.arange(L) % kinds).cuda()
+    f0 = [synth.frame_inputs(cfg, k, 0, want=("q", "k", "v")) for k in range(kinds)]
+    q, k, v = (dev(np.stack([f[x] for f in f0]), cfg).index_select(0, layer_kind).contiguous() for x in "qkv")
+    zk = np.zeros((cfg.M, 1, 1), np.float32)
+    check_layers = (0, 1, 2, 9, 16, 23)
+    for t in range(T):
+        fs = [synth.frame_inputs(cfg, kk, t, want=("r", "a")) for kk in range(kinds)]
+        r = dev(np.stack([f["r"] for f in fs]), cfg).index_select(0, layer_kind).contiguous()
+        a = torch.from_numpy(np.stack([f["a"] for f in fs])).cuda().index_select(0, layer_kind).contiguous()
+        cache.step(q, k, v, r, a, out)
+        for kk in range(kinds):
+            orcs[kk].append(zk, zk)
+            orcs[kk].update(fs[kk]["r"], fs[kk]["a"])
+        if (t + 1) * cfg.M > cfg.B or t % 6 == 0:
+            for l in check_layers:
+                o = orcs[l % kinds]
+                n = cache.size(l)
+                assert n == o.n
+                ids = np.zeros(n, np.uint32); ss = np.zeros(n, np.float32); flags = np.zeros(n, np.uint8)
+                B.ovggt_cache_export(cache.h, l, ids, None, None, ss, flags, cache.stream)
+                assert np.array_equal(ids, o.gid), f"frame {t} layer {l}: kept ids / layout differ"
+                assert np.array_equal(ss.view(np.uint32), o.ss.view(np.uint32)), f"frame {t} layer {l}: scores differ"
+                assert np.array_equal(flags, o.flag), f"frame {t} layer {l}: flags differ"
+        if t % 10 == 0:
+            print(f"[cfg2 deep] frame {t} ok", flush=True)
+    assert all(cache.status(l) == 0 for l in range(L))
+    cache.close()
+
+
+def test_values_beyond_the_half_range_saturate_and_set_status():
+    """bf16 handles cache K and V as IEEE half: elements beyond +-65504 (bf16 reaches 3e38) are
+    saturated, the status word reports it, export returns the saturated image, and attention
+    runs on that image."""
+    torch = _torch()
+    cfg = synth.preset(1, M=130, H=2, C=64, B=600, T=3, n_special=2)
+    cache = make_cache(cfg, L=1)
+    out = cache.new_output()[0]
+    ks, vs = [], []
+    for t in range(cfg.T):
+        f = synth.frame_inputs(cfg, 0, t)
+        if t == 1:
+            f["k"][3, 0, 5] = 7.0e4; f["k"][4, 1, 0] = -1.0e30; f["k"][5, 1, 63] = 65536.0
+            f["v"][6, 0, 1] = 3.0e38; f["v"][7, 1, 2] = -65536.0; f["v"][8, 0, 0] = 65280.0   # the last one fits
+            f["k"] = synth.quantise(f["k"], "bf16"); f["v"] = synth.quantise(f["v"], "bf16")
+        cache.step(dev(f["q"], cfg), dev(f["k"], cfg), dev(f["v"], cfg), dev(f["r"], cfg),
+                   torch.from_numpy(f["a"]).cuda(), out, layer=0)
+        ks.append(f["k"]); vs.append(f["v"])
+        st = cache.status(0)                       # reads and clears
+        assert st == (B.OVGGT_STATUS_VRANGE if t == 1 else 0), (t, st)
+        kc, vc = oc.cached_half(np.concatenate(ks)), oc.cached_half(np.concatenate(vs))
+        ref = oc.attention(f["q"], kc, vc)
+        assert rel_err(out.float().cpu().numpy().astype(np.float64), ref) < TOL["bf16"], t
+    e = cache.export(0)
+    kc, vc = oc.cached_half(np.concatenate(ks)), oc.cached_half(np.concatenate(vs))
+    assert np.abs(kc).max() == 65504.0 and np.abs(vc).max() == 65504.0 and vc[130 + 8, 0, 0] == 65280.0
+    assert np.array_equal(e["k"], synth.quantise(kc, "bf16"))
+    assert np.array_equal(e["v"], synth.quantise(vc, "bf16"))
+    cache.close()
+
+
+def test_scaled_query_beyond_the_half_range_is_clamped():
+    """A query element whose product with scale*log2(e) leaves the half range is clamped to
+    +-65504, so the output stays finite and equals attention with the clamped query."""
+    torch = _torch()
+    cfg = synth.preset(1, M=130, H=2, C=64, B=600, T=2, n_special=2)
+    cache = make_cache(cfg, L=1)
+    out = cache.new_output()[0]
+    c = (1.0 / 8.0) * 1.4426950408889634
+    ks, vs = [], []
+    for t in range(cfg.T):
+        f = synth.frame_inputs(cfg, 0, t)
+        f["k"] = synth.quantise(f["k"] * 2.0 ** -10, "bf16")       # keeps the clamped logits apart by a few units
+        f["q"][5, 0, 3] = 1.0e6; f["q"][9, 1, 60] = -3.0e7
+        f["q"] = synth.quantise(f["q"], "bf16")
+        cache.step(dev(f["q"], cfg), dev(f["k"], cfg), dev(f["v"], cfg), dev(f["r"], cfg),
+                   torch.from_numpy(f["a"]).cuda(), out, layer=0)
+        ks.append(f["k"]); vs.append(f["v"])
+        o = out.float().cpu().numpy().astype(np.float64)
+        assert np.isfinite(o).all()
+        q_eff = np.clip(f["q"].astype(np.float64), -65504.0 / c, 65504.0 / c)
+        ref = oc.attention(q_eff, np.concatenate(ks), np.concatenate(vs))
+        assert rel_err(o, ref) < TOL["bf16"], t
+    assert cache.status(0) == 0
     cache.close()
 
 
@@ -872,14 +1027,79 @@ def test_bf16_output_is_the_rounded_fp32_output():
     c32.close(); c16.close()
 
 
-def test_mfma_loop_probe_reports_a_plausible_rate():
-    """The measurement helper behind bench.py --mfma-loop: constant operands run near the chip's
-    dense f16 peak, random ones below it, neither above."""
-    cfg = synth.preset(1, M=200, H=2, C=64, B=400, T=1)
+def test_captured_step_replayed_from_a_hip_graph_matches_the_oracle():
+    """One steady-state step (append with the carried moves, attention, merge, score/select) is
+    captured into a HIP graph and replayed for 20 further frames, the inputs copied into the captured
+    buffers before each replay: every replay's attention output against the oracle, and the cache
+    (kept ids, layout, scores, flags, K, V) bit-exact at the end.  No kernel argument depends on the
+    frame: the token ids come from device memory."""
+    torch = _torch()
+    cfg = synth.preset(1, M=300, H=4, C=256, B=1500, T=32, n_special=5)
     cache = make_cache(cfg, L=1)
-    cst = B.ovggt_profile_mfma_loop(cache.h, False, 2000, cache.stream)
-    rnd = B.ovggt_profile_mfma_loop(cache.h, True, 2000, cache.stream)
-    assert 500.0 < rnd <= cst * 1.05 and cst < 2600.0, (rnd, cst)
+    orc = oc.OracleCache(cfg.M, cfg.H, cfg.d, cfg.B)
+    out = cache.new_output()[0]
+    eager = 9                                             # 5 frames fill the cache, 4 more evict
+    f = synth.frame_inputs(cfg, 0, 0)
+    fixed = [dev(f[x], cfg) for x in "qkvr"] + [torch.from_numpy(f["a"]).cuda()]
+
+    def load(t):
+        f = synth.frame_inputs(cfg, 0, t)
+        for dst, x in zip(fixed[:4], "qkvr"):
+            dst.copy_(dev(f[x], cfg))
+        fixed[4].copy_(torch.from_numpy(f["a"]).cuda())
+        return f
+
+    def check(t, f):
+        ref = orc.step(f["q"], f["k"], f["v"], f["r"], f["a"])
+        torch.cuda.synchronize()
+        err = rel_err(out.float().cpu().numpy().astype(np.float64), ref)
+        assert err < TOL["bf16"], f"frame {t}: attention error {err:.3e}"
+
+    for t in range(eager):
+        f = load(t)
+        cache.step(*fixed, out, layer=0)
+        check(t, f)
     with pytest.raises(B.OvggtError):
-        B.ovggt_profile_mfma_loop(cache.h, True, 0, cache.stream)
+        B.ovggt_cache_advance(cache.h, 0, 0)
+    g = torch.cuda.CUDAGraph()
+    f = load(eager)                                       # the inputs of the first replay are in place before the capture
+    torch.cuda.synchronize()
+    with torch.cuda.graph(g):
+        cache.step(*fixed, out, layer=0)                  # enqueues nothing; counts as frame `eager` on the host
+    assert cache.frames(0) == eager + 1
+    for i in range(21):
+        t = eager + i
+        if i > 0:
+            f = load(t)
+            cache.advance(1, layer=0)
+        g.replay()
+        check(t, f)
+        assert cache.frames(0) == t + 1 and cache.size(0) == cfg.B
+        print(f"[graph] replay {i} (frame {t}) ok", flush=True)
+    compare_cache(cache, orc)                             # applies the outstanding compaction with the stand-alone kernel
+    with pytest.raises(B.OvggtError) as e:                # the handle left the captured state: a replay is refused
+        cache.advance(1, layer=0)
+    assert e.value.code == B.OVGGT_ERR_STATE
+    t = eager + 21                                        # eager steps continue from where the replays stopped
+    f = load(t)
+    cache.step(*fixed, out, layer=0)
+    check(t, f)
+    compare_cache(cache, orc)
+    assert cache.status(0) == 0
     cache.close()
+
+
+def test_mfma_loop_helper_runs_and_rejects_bad_arguments():
+    """The measurement helper behind bench.py's MFMA-loop figure (a library of its own): it runs, and
+    rejects bad arguments.  Rates are reported by the benchmark, not asserted here."""
+    from paper_2603_05959_amd import measure
+    torch = _torch()
+    sink = torch.zeros(64, dtype=torch.float32, device="cuda:0")
+    stream = torch.cuda.current_stream().cuda_stream
+    cst = measure.ovggt_measure_mfma_loop(sink, 512, False, 2000, stream)
+    rnd = measure.ovggt_measure_mfma_loop(sink, 512, True, 2000, stream)
+    assert np.isfinite([cst, rnd]).all() and cst > 0 and rnd > 0
+    assert float(sink.abs().sum()) == 0.0
+    for bad in ((None, 512, True, 100), (sink, 0, True, 100), (sink, 512, True, 0)):
+        with pytest.raises(RuntimeError):
+            measure.ovggt_measure_mfma_loop(*bad, stream)

@@ -13,7 +13,8 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def _built():
-    if not os.path.exists(B.LIB_PATH):
+    from paper_2603_05959_amd import measure
+    if not os.path.exists(B.LIB_PATH) or not os.path.exists(measure.LIB_PATH):
         from paper_2603_05959_amd import build
         build.build(verbose=False)
 
@@ -27,6 +28,15 @@ def test_header_symbols_are_exported():
     lib = B.lib()
     for name in declared:
         assert hasattr(lib, name), name
+    # the measurement helper is a library of its own with a header of its own
+    from paper_2603_05959_amd import measure
+    hdr = open(os.path.join(ROOT, "include", "ovggt_measure.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared_m = set(re.findall(r"\b(ovggt_[a-z_]+)\s*\(", hdr))
+    assert declared_m == set(measure.EXPORTS) and not (declared_m & declared)
+    for name in declared_m:
+        assert hasattr(measure.lib(), name), name
+        assert not hasattr(lib, name), name
 
 
 def test_query_bytes_and_config_validation():
@@ -64,6 +74,8 @@ def test_null_and_misaligned_arguments_rejected_before_any_launch():
     assert lib.ovggt_score_select(None, 0, None, None, None) == B.OVGGT_ERR_ARG
     assert lib.ovggt_cache_compact(None, 0, None) == B.OVGGT_ERR_ARG
     assert lib.ovggt_cache_destroy(None) == B.OVGGT_ERR_ARG
+    assert lib.ovggt_cache_advance(None, 0, 1) == B.OVGGT_ERR_ARG
+    assert "memory" in B.strerror(B.OVGGT_ERR_NOMEM)
     assert B.strerror(0) == "ok" and "order" in B.strerror(B.OVGGT_ERR_STATE)
 
 

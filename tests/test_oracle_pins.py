@@ -348,6 +348,67 @@ def test_budget_error_leaves_state():
     assert (c.n, c.t) == (n, t) and c.flag[4:].sum() == 0
 
 
+# ------------------------------------------------- half-precision cache image
+def _half_value(bits):
+    """Value of an IEEE binary16 bit pattern from the format's definition (1 sign, 5 exponent,
+    10 fraction bits, bias 15), not from a library cast."""
+    sign = -1.0 if bits & 0x8000 else 1.0
+    e, m = (bits >> 10) & 31, bits & 1023
+    if e == 31:
+        return sign * math.inf if m == 0 else math.nan
+    if e == 0:
+        return sign * m * 2.0 ** -24
+    return sign * (1024 + m) * 2.0 ** (e - 25)
+
+
+def test_cached_half_hand_values():
+    """`cached_half` against hand-written cases: saturation at the largest finite half, ties to
+    even on the normal and on the subnormal grid, exact multiples of 2^-24, NaN, signs."""
+    cases = [
+        (65504.0, 65504.0), (65520.0, 65504.0), (1.0e6, 65504.0), (-65520.0, -65504.0), (-3.0e38, -65504.0),
+        (math.inf, 65504.0), (-math.inf, -65504.0),
+        (65488.0, 65472.0),                       # tie between 65472 (even fraction) and 65504
+        (1.0 + 2.0 ** -11, 1.0),                  # tie, even neighbour below
+        (1.0 + 3 * 2.0 ** -11, 1.0 + 2.0 ** -9),  # tie, even neighbour above
+        (1.0 + 2.0 ** -11 + 2.0 ** -20, 1.0 + 2.0 ** -10),   # just above the tie
+        (2.0 ** -25, 0.0),                        # half the smallest subnormal: tie to even = 0
+        (3 * 2.0 ** -25, 2.0 ** -23),             # tie between 1 and 2 units of 2^-24
+        (2.0 ** -25 * 1.0001, 2.0 ** -24),
+        (5 * 2.0 ** -24, 5 * 2.0 ** -24), (1023 * 2.0 ** -24, 1023 * 2.0 ** -24),
+        (2.0 ** -14, 2.0 ** -14), (-0.3125, -0.3125), (0.0, 0.0), (1.0e-10, 0.0),
+    ]
+    x = np.array([c[0] for c in cases], np.float32)
+    want = np.array([c[1] for c in cases], np.float32)
+    got = oc.cached_half(x)
+    assert got.dtype == np.float32
+    assert np.array_equal(got, want), list(zip(x, got, want))
+    assert np.isnan(oc.cached_half(np.array([np.nan], np.float32))[0])
+    assert np.signbit(oc.cached_half(np.array([-0.0, -1e-10], np.float32))).all()
+
+
+def test_cached_half_is_the_nearest_representable_half_everywhere():
+    """Brute force over every finite half bit pattern: each result is a half value, no other half
+    is nearer to the input, and exact ties went to the even fraction."""
+    grid = np.array(sorted({_half_value(b) for b in range(0x10000) if ((b >> 10) & 31) != 31}), np.float64)
+    assert len(grid) == 2 * (31 * 1024) - 1 and grid[-1] == 65504.0
+    fraction_even = {_half_value(b): (b & 1) == 0 for b in range(0x10000) if ((b >> 10) & 31) != 31}
+    rng = np.random.default_rng(5)
+    mid = (grid[:-1] + grid[1:]) / 2                              # exact ties (representable in fp32)
+    x = np.concatenate([rng.normal(size=20000) * np.exp(rng.uniform(-20, 12, 20000)), mid,
+                        np.nextafter(mid.astype(np.float32), np.float32(np.inf)).astype(np.float64),
+                        grid, [7.0e4, -7.0e4, 1e30]]).astype(np.float32)
+    got = oc.cached_half(x).astype(np.float64)
+    xc = np.clip(x.astype(np.float64), -65504.0, 65504.0)
+    i = np.searchsorted(grid, got)
+    assert np.array_equal(grid[np.clip(i, 0, len(grid) - 1)], got), "a result that is no half value"
+    lo = grid[np.clip(np.searchsorted(grid, xc, side="right") - 1, 0, len(grid) - 1)]
+    hi = grid[np.clip(np.searchsorted(grid, xc, side="left"), 0, len(grid) - 1)]
+    best = np.minimum(np.abs(xc - lo), np.abs(xc - hi))
+    assert np.array_equal(np.abs(xc - got), best), "not the nearest half"
+    tie = (np.abs(xc - lo) == np.abs(xc - hi)) & (lo != hi)
+    assert tie.sum() >= len(mid) and all(fraction_even[g] for g in got[tie])
+
+
 # ----------------------------------------------------------- paper constants
 def test_paper_constants():
     g = golden()
