@@ -54,7 +54,8 @@ enum {
   OVGGT_ERR_ARG = -1,      /* NULL / misaligned pointer, bad layer, bad config value   */
   OVGGT_ERR_STATE = -2,    /* call out of order for that layer                          */
   OVGGT_ERR_NOMEM = -3,    /* host memory for the handle could not be allocated         */
-  OVGGT_ERR_HIP = -4       /* a HIP runtime call failed (launch, copy, query)            */
+  OVGGT_ERR_HIP = -4,      /* a HIP runtime call failed (launch, copy, query)            */
+  OVGGT_ERR_TOO_LARGE = -5 /* ovggt_global_attn_static_ws: the launch needs more than the fixed workspace */
 };
 /* bits of the device status word */
 enum {
@@ -141,6 +142,21 @@ int ovggt_cache_init(ovggt_cache** out, const ovggt_config* cfg,
  * new frame. */
 int ovggt_global_attn(ovggt_cache* c, int layer, const void* q, const void* k_new, const void* v_new,
                       void* out, void* hip_stream);
+
+/* ovggt_global_attn for callers that cannot allocate device memory at all (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc) and therefore have no workspace
+ * buffer to hand to ovggt_cache_init for the attention's partial results: the same call, same
+ * arguments, same kernels and same results, but the partial (O, m, l) records of the launch go to a
+ * device array that is part of the library (51 904 512 bytes, held by every GPU the library runs on
+ * until the process ends) instead of the handle's workspace.  Calls no allocating routine; nothing
+ * in the array has to be cleared between calls (every record the merge pass reads is written by the
+ * same launch).  Limit: a launch over more than 16 (layer, head) pairs (layers in the call times
+ * n_heads; such launches deal the heads out in several rounds and need more records than the
+ * array holds) returns OVGGT_ERR_TOO_LARGE and changes nothing; f32 handles use no workspace and
+ * behave as ovggt_global_attn.  Every call on a GPU shares that GPU's array: calls that may overlap
+ * on one GPU (different streams, different handles) race and must be ordered by the caller. */
+int ovggt_global_attn_static_ws(ovggt_cache* c, int layer, const void* q, const void* k_new, const void* v_new,
+                                void* out, void* hip_stream);
 
 /* Eq. 5 + Sec. 3.3 + Eq. 8.  Scores the M tokens appended by the preceding
  * ovggt_global_attn from their FFN-residual rows `resid` (device, [M, C]):

@@ -16,6 +16,7 @@ LIB_PATH = os.environ.get("OVGGT_LIB") or os.path.join(_PKG, "libovggt.so")   # 
 OVGGT_F32, OVGGT_BF16 = 0, 1
 OVGGT_ALL_LAYERS = -1
 OVGGT_OK, OVGGT_ERR_ARG, OVGGT_ERR_STATE, OVGGT_ERR_NOMEM, OVGGT_ERR_HIP = 0, -1, -2, -3, -4
+OVGGT_ERR_TOO_LARGE = -5
 OVGGT_STATUS_BUDGET, OVGGT_STATUS_NONFINITE, OVGGT_STATUS_VRANGE = 1, 2, 4
 
 EXPORTS = (
@@ -25,6 +26,7 @@ EXPORTS = (
     "ovggt_profile_enable", "ovggt_profile_read", "ovggt_profile_overhead", "ovggt_strerror",
     "ovggt_cache_set_protect", "ovggt_dap_create", "ovggt_dap_step", "ovggt_dap_active", "ovggt_dap_destroy",
     "ovggt_attn_plan_stats", "ovggt_cache_flush", "ovggt_cache_advance",
+    "ovggt_global_attn_static_ws",
 )
 PROF_CLASSES = ("append", "attn", "combine", "score_select", "compact")
 
@@ -62,6 +64,7 @@ def lib() -> C.CDLL:
     L.ovggt_cache_query_bytes.argtypes = [cfgp, szp, szp, szp]
     L.ovggt_cache_init.argtypes = [C.POINTER(vp), cfgp, vp, vp, vp, vp]
     L.ovggt_global_attn.argtypes = [vp, C.c_int, vp, vp, vp, vp, vp]
+    L.ovggt_global_attn_static_ws.argtypes = [vp, C.c_int, vp, vp, vp, vp, vp]
     L.ovggt_score_select.argtypes = [vp, C.c_int, vp, u8p, vp]
     L.ovggt_cache_compact.argtypes = [vp, C.c_int, vp]
     L.ovggt_cache_flush.argtypes = [vp, C.c_int, vp]
@@ -144,6 +147,11 @@ def ovggt_cache_init(cfg: ovggt_config, kv_dev, meta_dev, ws_dev, stream: int = 
 def ovggt_global_attn(h, layer, q, k_new, v_new, out, stream: int = 0) -> None:
     _check(lib().ovggt_global_attn(h, layer, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out), stream),
            "ovggt_global_attn")
+
+
+def ovggt_global_attn_static_ws(h, layer, q, k_new, v_new, out, stream: int = 0) -> None:
+    _check(lib().ovggt_global_attn_static_ws(h, layer, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out), stream),
+           "ovggt_global_attn_static_ws")
 
 
 def ovggt_score_select(h, layer, resid, anchor_flags, stream: int = 0) -> None:

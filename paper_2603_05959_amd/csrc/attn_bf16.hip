@@ -51,6 +51,7 @@
 // transpose reads are bank-conflict free.
 #include "ovggt_internal.h"
 #include <algorithm>
+#include <mutex>
 #include <vector>
 
 namespace ovggt {
@@ -98,6 +99,36 @@ size_t attn_ws_bytes(int layer_heads) {
   bytes += (size_t)kMaxAttnWgs * 8 * 64;                // timing builds: one 64-byte record per wave behind the partials
 #endif
   return bytes;
+}
+
+// ---- workspace for callers that cannot allocate ---------------------------------------------------
+// The partial records of a launch of up to kMaxAttnWgs chunks (one layer of any head count the
+// one-round plan covers), as a device array of the library itself: every GPU the library runs on
+// holds it until the process ends.  In host code the array's name is only a stand-in; its device
+// address is looked up once per device, with that device current, and kept.
+constexpr size_t kStaticWsBytes = (size_t)kMaxAttnWgs * kSegRecs * 2 * kPartialFloats * sizeof(float);   // 51 904 512 bytes
+static __device__ __align__(256) unsigned char scratch[kStaticWsBytes];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_static_ws_mutex;
+static char* g_static_ws_ptr[kMaxDevices];
+
+hipError_t attn_static_ws(char** ptr, size_t* bytes) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_static_ws_mutex);
+  if (!g_static_ws_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_static_ws_ptr[dev] = (char*)p;
+  }
+  *ptr = g_static_ws_ptr[dev];
+  *bytes = kStaticWsBytes;
+  return hipSuccess;
 }
 
 constexpr int kMaxChunksPerPair = 64;

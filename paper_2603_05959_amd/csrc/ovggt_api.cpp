@@ -252,14 +252,22 @@ int ovggt_cache_init(ovggt_cache** out, const ovggt_config* cfg, void* kv_dev, v
   return OVGGT_OK;
 }
 
-int ovggt_global_attn(ovggt_cache* c, int layer, const void* q, const void* k_new, const void* v_new,
-                      void* out, void* hip_stream) {
+// ovggt_global_attn, with the attention's partial records in the handle's workspace (static_ws =
+// false) or in the library's own device array.
+static int global_attn_impl(ovggt_cache* c, int layer, const void* q, const void* k_new, const void* v_new,
+                            void* out, void* hip_stream, bool static_ws) {
   if (!c) return OVGGT_ERR_ARG;
   int l0, nl;
   if (!layer_range(c, layer, &l0, &nl)) return OVGGT_ERR_ARG;
   if (!aligned16(q) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(out)) return OVGGT_ERR_ARG;
   if (!uniform(c, l0, nl, 0)) return OVGGT_ERR_STATE;
   const Geom& g = c->g;
+  char* ws = c->ws;
+  size_t ws_bytes = ws_bytes_for(c->cfg);
+  if (static_ws && g.esize == 2) {
+    if (attn_static_ws(&ws, &ws_bytes) != hipSuccess) return OVGGT_ERR_HIP;
+    if (attn_ws_bytes(nl * g.H) > ws_bytes) return OVGGT_ERR_TOO_LARGE;   // before anything is launched
+  }
   const int n = c->n[l0];
   const int64_t gid0 = c->frames[l0] * (int64_t)g.M;
   if (gid0 + g.M > 0xFFFFFFFFLL) return OVGGT_ERR_ARG;          // token ids are 32-bit
@@ -291,7 +299,7 @@ int ovggt_global_attn(ovggt_cache* c, int layer, const void* q, const void* k_ne
         for (hipEvent_t x : ev)
           if (x) c->prof_free.push_back(x);
     }
-    e = launch_attn_bf16(g, c->kv, l0, nl, q, out, n + g.M, c->scale, c->ws, ws_bytes_for(c->cfg), c->n_wgs,
+    e = launch_attn_bf16(g, c->kv, l0, nl, q, out, n + g.M, c->scale, ws, ws_bytes, c->n_wgs,
                          c->cfg.out_dtype == OVGGT_F32, s, have ? ev : nullptr);
     if (have) {
       c->prof_pending[OVGGT_PROF_ATTN].push_back({ev[0], ev[1]});
@@ -304,6 +312,16 @@ int ovggt_global_attn(ovggt_cache* c, int layer, const void* q, const void* k_ne
   if (e != hipSuccess) return OVGGT_ERR_HIP;
   for (int l = l0; l < l0 + nl; ++l) { c->n[l] = n + g.M; c->phase[l] = 1; }
   return OVGGT_OK;
+}
+
+int ovggt_global_attn(ovggt_cache* c, int layer, const void* q, const void* k_new, const void* v_new,
+                      void* out, void* hip_stream) {
+  return global_attn_impl(c, layer, q, k_new, v_new, out, hip_stream, false);
+}
+
+int ovggt_global_attn_static_ws(ovggt_cache* c, int layer, const void* q, const void* k_new, const void* v_new,
+                                void* out, void* hip_stream) {
+  return global_attn_impl(c, layer, q, k_new, v_new, out, hip_stream, true);
 }
 
 int ovggt_score_select(ovggt_cache* c, int layer, const void* resid, const uint8_t* anchor_flags,
@@ -577,6 +595,7 @@ const char* ovggt_strerror(int code) {
     case OVGGT_ERR_STATE: return "call out of order for this layer";
     case OVGGT_ERR_NOMEM: return "out of host memory";
     case OVGGT_ERR_HIP: return "HIP runtime error";
+    case OVGGT_ERR_TOO_LARGE: return "launch too large for the library's static workspace";
     default: return "unknown error";
   }
 }

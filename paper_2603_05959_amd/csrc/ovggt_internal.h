@@ -75,6 +75,10 @@ hipError_t launch_attn_bf16(const Geom& g, char* kv, int layer0, int nl, const v
                             int n_total, float scale, char* ws, size_t ws_bytes, int n_wgs, bool out_f32,
                             hipStream_t s, hipEvent_t* ev = nullptr);
 size_t attn_ws_bytes(int layer_heads);
+// The library's own workspace for the attention's partial records (a device array of fixed size, one
+// copy per GPU): its device address on the current device and its size.  Looks the address up on the
+// first call per device; allocates nothing.
+hipError_t attn_static_ws(char** ptr, size_t* bytes);
 // What the attention launch over nl layers and n_total resident slots hands to its workgroups (host-side walk of
 // the plan; false: the plan is inconsistent).  cost = tiles + a fixed charge per piece, in tiles.
 struct AttnPlanStats {
