@@ -151,9 +151,10 @@ int ovggt_global_attn(ovggt_cache* c, int layer, const void* q, const void* k_ne
  * until the process ends) instead of the handle's workspace.  Calls no allocating routine; nothing
  * in the array has to be cleared between calls (every record the merge pass reads is written by the
  * same launch).  Limit: a launch over more than 16 (layer, head) pairs (layers in the call times
- * n_heads; such launches deal the heads out in several rounds and need more records than the
- * array holds) returns OVGGT_ERR_TOO_LARGE and changes nothing; f32 handles use no workspace and
- * behave as ovggt_global_attn.  Every call on a GPU shares that GPU's array: calls that may overlap
+ * n_heads) whose heads cannot be handed out as whole (head pair, query block) items -- the head
+ * pairs do not divide among the chip's 8 XCDs, or there are fewer items than workgroups -- needs
+ * more records than the array holds, returns OVGGT_ERR_TOO_LARGE and changes nothing; f32 handles
+ * use no workspace and behave as ovggt_global_attn.  Every call on a GPU shares that GPU's array: calls that may overlap
  * on one GPU (different streams, different handles) race and must be ordered by the caller. */
 int ovggt_global_attn_static_ws(ovggt_cache* c, int layer, const void* q, const void* k_new, const void* v_new,
                                 void* out, void* hip_stream);

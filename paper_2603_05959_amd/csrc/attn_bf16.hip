@@ -79,6 +79,12 @@ constexpr int kTileBytes = kSlotTile * 128;            // one K (or V) tile: 128
 constexpr int kSetBytes = 4 * kTileBytes;              // LDS of one wave set: [parity][K | V]
 constexpr int kAttnThreads = 512;
 constexpr int kPartialFloats = kQueryTile * 64 + 2 * kQueryTile;
+// Float offset, inside a partial record's O part, of the 256-float block that holds the values
+// O[db][qb][4*ig .. 4*ig+3] of all 64 lanes of the waves of query half `qhalf` (lane * 4 + j inside
+// the block): element (row = 64*qhalf + 32*qb + lane % 32, column = 32*db + 8*ig + 4*(lane / 32) + j).
+__host__ __device__ constexpr int partial_block_offset(int qhalf, int db, int qb, int ig) {
+  return (((qhalf * 2 + db) * 2 + qb) * 4 + ig) * 256;
+}
 constexpr float kWeightBias = 7.0f;                    // weights are stored as 2^7 * p (half max 65504)
 constexpr float kWeightSumLimit = 32768.0f;            // a lane's weight sum below 2^15 proves no weight overflowed
 
@@ -89,11 +95,20 @@ constexpr int kWaitLgkm0 = 0xC07F;                     // lgkmcnt(0), nothing el
 
 constexpr int kSegRecs = 3;                            // partial records per workgroup and wave set
 // Workspace: kSegRecs partial records per chunk and wave set.  A launch over few (layer, head)
-// pairs has one chunk per workgroup; a launch whose head pairs are dealt out to the XCDs round by
-// round has kMaxAttnWgs / 8 chunks per head pair.
-size_t attn_ws_bytes(int layer_heads) {
+// pairs has one chunk per workgroup, and so has one that hands out whole items (only its last round
+// leaves records); a launch whose head pairs are dealt out to the XCDs round by round has
+// kMaxAttnWgs / 8 chunks per head pair.
+// Launches over many head pairs hand whole items (head pair x query block) to the workgroups when
+// the head pairs divide among the 8 XCDs and every workgroup gets at least one whole item.
+bool attn_whole_items(int layer_heads, int query_blocks, int n_wgs) {
+  const int pairs = (layer_heads + 1) / 2;
+  return pairs > 8 && pairs % 8 == 0 && (long)(pairs / 8) * query_blocks >= n_wgs / 8;
+}
+
+size_t attn_ws_bytes(int layer_heads, int query_blocks) {
   const long pairs = (layer_heads + 1) / 2;
-  const long chunks = pairs * (kMaxAttnWgs / 8) > kMaxAttnWgs ? pairs * (kMaxAttnWgs / 8) : kMaxAttnWgs;
+  long chunks = pairs * (kMaxAttnWgs / 8) > kMaxAttnWgs ? pairs * (kMaxAttnWgs / 8) : kMaxAttnWgs;
+  if (attn_whole_items(layer_heads, query_blocks, kMaxAttnWgs)) chunks = kMaxAttnWgs;   // holds for fewer workgroups too
   size_t bytes = (size_t)chunks * kSegRecs * 2 * kPartialFloats * sizeof(float);
 #ifdef OVGGT_TRACE
   bytes += (size_t)kMaxAttnWgs * 8 * 64;                // timing builds: one 64-byte record per wave behind the partials
@@ -158,6 +173,11 @@ struct AttnParams {
   int rec_table_on;
   uint8_t rec_count[kMaxTableItems];
   uint16_t rec_table[kMaxTableItems][kMaxTableRecs];
+  // Whole items (launches over many head pairs): an XCD's workgroups (per_xcd of them) own ppx
+  // consecutive head pairs = ppx * QB items; in each of the first rf rounds a workgroup takes one
+  // whole item (all T tiles, no partial record, no merge), and the items left over are cut evenly
+  // into per_xcd chunks of lo_chunk units for one last round.  item_mode = 0: off.
+  int item_mode, per_xcd, ppx, rf, lo_chunk;
   size_t trace_off;           // floats from ws to the end of the record area (timing builds)
   int total_units;            // ceil(LH / 2) * PP
   float c;                    // softmax scale * log2(e)
@@ -209,6 +229,32 @@ __host__ __device__ inline int chunk_of_unit(const AttnParams& p, long u) {
   int lc = 0;
   while (lc + 1 < p.cpp && p.cstart[lc + 1] <= r) ++lc;
   return hp * p.cpp + lc;
+}
+
+// Units [u0, u1) that workgroup `cidx` (XCD-major index: cidx / per_xcd is its XCD) works on in
+// round `rnd` of a launch of G workgroups, and the chunk number its partial records are filed under.
+struct ChunkRange { long u0, u1; int rec_chunk; };
+__host__ __device__ inline ChunkRange chunk_range(const AttnParams& p, int rnd, int cidx, int G) {
+  ChunkRange r;
+  if (!p.item_mode) {
+    const int c = rnd * G + cidx;
+    r.u0 = chunk_first_unit(p, c);
+    r.u1 = chunk_first_unit(p, c + 1);
+    r.rec_chunk = c;
+    return r;
+  }
+  const int x = cidx / p.per_xcd, j = cidx - x * p.per_xcd;
+  const long base = (long)x * p.ppx * p.PP;              // the XCD's first unit (PP = QB * T units per head pair)
+  r.rec_chunk = cidx;
+  if (rnd < p.rf) {
+    r.u0 = base + ((long)rnd * p.per_xcd + j) * p.T;
+    r.u1 = r.u0 + p.T;
+  } else {
+    const long lo0 = base + (long)p.rf * p.per_xcd * p.T, lo1 = base + (long)p.ppx * p.PP;
+    r.u0 = min(lo0 + (long)j * p.lo_chunk, lo1);
+    r.u1 = min(r.u0 + p.lo_chunk, lo1);
+  }
+  return r;
 }
 
 // Half a tile pair, global -> LDS: the calling wave fills 32 rows (4 KiB) of a K or V tile with four
@@ -576,7 +622,7 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
 
   const int G = gridDim.x;
   const int cidx = (blockIdx.x & 7) * (G >> 3) + (blockIdx.x >> 3);
-  if (chunk_first_unit(p, cidx) >= p.total_units) return;   // whole workgroup: no barrier has been executed yet
+  if (!p.item_mode && chunk_first_unit(p, cidx) >= p.total_units) return;   // whole workgroup: no barrier has been executed yet
 #ifdef OVGGT_TRACE
   const unsigned long long tr_w0 = wall_clock64(), tr_c0 = clock64();
   unsigned long long tr_n = 0;
@@ -622,9 +668,10 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
   // Head pairs are dealt out round by round: in every round an XCD's workgroups share one head
   // pair (its K/V tiles then live in that XCD's L2 while all its query blocks pass over them).
   for (int rnd = 0; rnd < p.rounds; ++rnd) {
-  const int chunk_idx = rnd * G + cidx;
-  int u = (int)chunk_first_unit(p, chunk_idx);
-  const int u_end = (int)chunk_first_unit(p, chunk_idx + 1);
+  const ChunkRange cr = chunk_range(p, rnd, cidx, G);
+  const int chunk_idx = cr.rec_chunk;
+  int u = (int)cr.u0;
+  const int u_end = (int)cr.u1;
   const int u_begin = u;
   int n_piece = 0;
   while (u < u_end) {
@@ -801,8 +848,12 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
         // Every address is formed before the first store: a register reloaded from scratch between
         // two stores would have to wait for all stores before it (one counter covers loads and
         // stores), about a thousand cycles each time.
+        // The O part of a record is laid out the way the accumulators sit in registers -- block
+        // (query half, db, qb, ig), then lane, then the lane's four values -- so every store
+        // instruction writes 1 KiB of consecutive memory (partial_block_offset; the merge pass
+        // reads it back the same way and transposes on its way out).
         float* rec = p.ws + (size_t)((kSegRecs * chunk_idx + rec_ord) * 2 + set) * kPartialFloats;
-        uint32_t ro = (uint32_t)((qhalf * 64 + l32) * 64 + 4 * g);          // query block 0; block 1 is 32 rows on
+        uint32_t ro = (uint32_t)(partial_block_offset(qhalf, 0, 0, 0) + lane * 4);
         uint32_t mo = (uint32_t)(kQueryTile * 64 + qhalf * 64 + l32);
         asm volatile("" : "+v"(ro), "+v"(mo));
         float* rp0 = rec + ro;
@@ -814,7 +865,7 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
 #pragma unroll
             for (int ig = 0; ig < 4; ++ig) {
               float4 w = {O[db][qb][ig * 4], O[db][qb][ig * 4 + 1], O[db][qb][ig * 4 + 2], O[db][qb][ig * 4 + 3]};
-              *(float4*)(rp0 + qb * 32 * 64 + db * 32 + ig * 8) = w;
+              *(float4*)(rp0 + partial_block_offset(0, db, qb, ig)) = w;
             }
         }
         if (g == 0) {
@@ -844,25 +895,27 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
 }
 
 // One round of the merge: up to kMaxParts partial records of a row are fetched together (all loads
-// in flight at once) and folded into the running (acc, l, mt) of a thread's four output columns.
+// in flight at once) and folded into the running (acc, l, mt) of the thread's two float4 pieces.
 constexpr int kMaxParts = 4;
 __device__ __forceinline__ void combine_round(const AttnParams& p, const uint32_t (&recs)[kMaxParts], int n, int row,
-                                              int piece, float4& acc, float& l, float& mt) {
+                                              int off0, int off1, float4& acc0, float4& acc1, float& l, float& mt) {
   float m[kMaxParts], lp[kMaxParts];
-  float4 o[kMaxParts];
+  float4 o0[kMaxParts], o1[kMaxParts];
 #pragma unroll
   for (int j = 0; j < kMaxParts; ++j) {
     const float* rec = p.ws + (size_t)recs[j] * kPartialFloats;       // entries beyond n repeat the last one
     m[j] = rec[kQueryTile * 64 + row];
     lp[j] = rec[kQueryTile * 64 + kQueryTile + row];
-    o[j] = *(const float4*)(rec + row * 64 + piece * 4);
+    o0[j] = *(const float4*)(rec + off0);
+    o1[j] = *(const float4*)(rec + off1);
   }
   float mn = mt;
 #pragma unroll
   for (int j = 0; j < kMaxParts; ++j)
     if (j < n) mn = fmaxf(mn, m[j]);
   const float rs = __builtin_amdgcn_exp2f(mt - mn);      // 0 in the first round (mt = -inf)
-  acc.x *= rs; acc.y *= rs; acc.z *= rs; acc.w *= rs;
+  acc0.x *= rs; acc0.y *= rs; acc0.z *= rs; acc0.w *= rs;
+  acc1.x *= rs; acc1.y *= rs; acc1.z *= rs; acc1.w *= rs;
   l *= rs;
   mt = mn;
 #pragma unroll
@@ -870,35 +923,45 @@ __device__ __forceinline__ void combine_round(const AttnParams& p, const uint32_
     if (j < n) {
       const float w = __builtin_amdgcn_exp2f(m[j] - mt);
       l += lp[j] * w;
-      acc.x += o[j].x * w; acc.y += o[j].y * w; acc.z += o[j].z * w; acc.w += o[j].w * w;
+      acc0.x += o0[j].x * w; acc0.y += o0[j].y * w; acc0.z += o0[j].z * w; acc0.w += o0[j].w * w;
+      acc1.x += o1[j].x * w; acc1.y += o1[j].y * w; acc1.z += o1[j].z * w; acc1.w += o1[j].w * w;
     }
 }
 
-// Merge the partials of every item that was split across workgroups.  A workgroup takes 16 query
-// rows of one item; a thread owns four output columns of one row, so every load is one 16-byte
-// piece of a 256-byte row and the few loads a thread issues (one per partial) are all in flight
-// together.
-constexpr int kCombineRows = 16;
+// Merge the partials of every item that was split across workgroups.  A workgroup takes the 32 query
+// rows of one (query half, qb) group of one item: 8 blocks of 256 floats in every record, two per
+// wave, read the way they were written (lane * 4 + j: 1 KiB of consecutive memory per wave and
+// load); the merged rows are transposed through LDS so that the output leaves in whole 256-byte rows.
+constexpr int kCombineRows = 32;
+constexpr int kCombinePitch = 68;                      // floats per LDS row (64 + 4: the transposing stores spread over the banks)
 __global__ void __launch_bounds__(256) attn_combine_kernel(AttnParams p) {
   const int item = blockIdx.x / (kQueryTile / kCombineRows);     // (layer-head, query block)
-  const int rgrp = blockIdx.x % (kQueryTile / kCombineRows);
+  const int rgrp = blockIdx.x % (kQueryTile / kCombineRows);     // 2 * query half + qb
   const int qb_idx = item % p.QB;
   const int lh = item / p.QB;
   const int set = lh & 1;
   const int hp = lh >> 1;
-  const int row = rgrp * kCombineRows + (threadIdx.x >> 4), piece = threadIdx.x & 15;
+  const int lane = threadIdx.x & 63, blk = threadIdx.x >> 6;
+  const int l32 = lane & 31, g = lane >> 5;
+  const int row = rgrp * kCombineRows + l32;                     // this thread's row within the query block
   const int li = lh / p.H;
   const int h = lh - li * p.H;
-  const int qrow = qb_idx * kQueryTile + row;
+  const int qrow0 = qb_idx * kQueryTile + rgrp * kCombineRows;   // the workgroup's first query
+  if (qrow0 >= p.M) return;                                      // whole workgroup, before any barrier
+  // this thread's two pieces: blocks 2*blk and 2*blk+1 of the group (block = 4*db + ig)
+  const int b0 = 2 * blk, b1 = 2 * blk + 1;
+  const int off0 = partial_block_offset(rgrp >> 1, b0 >> 2, rgrp & 1, b0 & 3) + lane * 4;
+  const int off1 = partial_block_offset(rgrp >> 1, b1 >> 2, rgrp & 1, b1 & 3) + lane * 4;
   constexpr int kSegGroup = 64;                        // segments whose records are listed at a time
   __shared__ uint32_t rec_list[kSegGroup * kSegRecs];
   __shared__ int n_list;
-  float4 acc = {0.f, 0.f, 0.f, 0.f};
+  __shared__ __attribute__((aligned(16))) float tile[kCombineRows * kCombinePitch];
+  float4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
   float l = 0.f, mt = -INFINITY;
   if (p.rec_table_on) {
     // table of the item's records: no list to build, every thread walks the same few entries
     const int n = p.rec_count[qb_idx];
-    if (n == kWholeItem || qrow >= p.M) return;
+    if (n == kWholeItem) return;
     for (int i0 = 0; i0 < n; i0 += kMaxParts) {
       uint32_t recs[kMaxParts];
 #pragma unroll
@@ -906,7 +969,26 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(AttnParams p) {
         const uint32_t e = p.rec_table[qb_idx][min(i0 + j, n - 1)];
         recs[j] = (uint32_t)((kSegRecs * (hp * p.cpp + (int)(e & 255u)) + (int)(e >> 8)) * 2 + set);
       }
-      combine_round(p, recs, min(kMaxParts, n - i0), row, piece, acc, l, mt);
+      combine_round(p, recs, min(kMaxParts, n - i0), row, off0, off1, acc0, acc1, l, mt);
+    }
+  } else if (p.item_mode) {
+    // whole-item launches: only the items of an XCD's last round were cut, each over a few of the
+    // XCD's chunks (plain order: a chunk's first piece is record 0, a later one record 1)
+    const int x = hp / p.ppx;
+    const int i = (hp - x * p.ppx) * p.QB + qb_idx;
+    if (i < p.rf * p.per_xcd) return;
+    const long ua = (long)(i - p.rf * p.per_xcd) * p.T, ub = ua + p.T - 1;
+    const int cf = (int)(ua / p.lo_chunk), cl = (int)(ub / p.lo_chunk);
+    if (cf == cl) return;                                  // one workgroup did the whole item and wrote it
+    for (int c0 = cf; c0 <= cl; c0 += kMaxParts) {
+      uint32_t recs[kMaxParts];
+#pragma unroll
+      for (int j = 0; j < kMaxParts; ++j) {
+        const int c = min(c0 + j, cl);
+        const int ord = (long)c * p.lo_chunk < ua ? 1 : 0;
+        recs[j] = (uint32_t)((kSegRecs * (x * p.per_xcd + c) + ord) * 2 + set);
+      }
+      combine_round(p, recs, min(kMaxParts, cl - c0 + 1), row, off0, off1, acc0, acc1, l, mt);
     }
   } else
   for (int sg0 = 0; sg0 < p.NS; sg0 += kSegGroup) {
@@ -915,7 +997,6 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(AttnParams p) {
     // finds the chunk of a unit: the last one that starts at or before it.
     __syncthreads();
     if (threadIdx.x < 64) {
-      const int lane = threadIdx.x;
       const int cs_l = (p.cpp > 0 && lane < p.cpp) ? p.cstart[lane] : 0x7FFFFFFF;
       auto chunk_of = [&](long u) -> int {
         if (p.cpp == 0) return (int)(u / p.chunk);
@@ -949,23 +1030,36 @@ __global__ void __launch_bounds__(256) attn_combine_kernel(AttnParams p) {
     __syncthreads();
     if (n_list < 0) return;
     const int n = n_list;
-    if (qrow < p.M)
-      for (int i0 = 0; i0 < n; i0 += kMaxParts) {
-        uint32_t recs[kMaxParts];
+    for (int i0 = 0; i0 < n; i0 += kMaxParts) {
+      uint32_t recs[kMaxParts];
 #pragma unroll
-        for (int j = 0; j < kMaxParts; ++j) recs[j] = rec_list[min(i0 + j, n - 1)];
-        combine_round(p, recs, min(kMaxParts, n - i0), row, piece, acc, l, mt);
-      }
+      for (int j = 0; j < kMaxParts; ++j) recs[j] = rec_list[min(i0 + j, n - 1)];
+      combine_round(p, recs, min(kMaxParts, n - i0), row, off0, off1, acc0, acc1, l, mt);
+    }
   }
-  if (qrow >= p.M) return;
+  // normalise, transpose through LDS, store whole rows
   const float inv = 1.0f / l;
-  const size_t oel = (((size_t)li * p.M + qrow) * p.H + h) * 64 + piece * 4;
-  if (p.out_f32) {
-    float4 w = {acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv};
-    *(float4*)(p.out + oel * 4) = w;
-  } else {
-    bf16x4 w = {(__bf16)(acc.x * inv), (__bf16)(acc.y * inv), (__bf16)(acc.z * inv), (__bf16)(acc.w * inv)};
-    *(bf16x4*)(p.out + oel * 2) = w;
+  {
+    float* t0 = tile + l32 * kCombinePitch + 4 * g;
+    const float4 w0 = {acc0.x * inv, acc0.y * inv, acc0.z * inv, acc0.w * inv};
+    const float4 w1 = {acc1.x * inv, acc1.y * inv, acc1.z * inv, acc1.w * inv};
+    *(float4*)(t0 + (b0 >> 2) * 32 + (b0 & 3) * 8) = w0;
+    *(float4*)(t0 + (b1 >> 2) * 32 + (b1 & 3) * 8) = w1;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    const int r = (threadIdx.x >> 4) + 16 * k, piece = threadIdx.x & 15;
+    const int qrow = qrow0 + r;
+    if (qrow >= p.M) continue;
+    const float4 w = *(const float4*)(tile + r * kCombinePitch + piece * 4);
+    const size_t oel = (((size_t)li * p.M + qrow) * p.H + h) * 64 + piece * 4;
+    if (p.out_f32) {
+      *(float4*)(p.out + oel * 4) = w;
+    } else {
+      bf16x4 wb = {(__bf16)w.x, (__bf16)w.y, (__bf16)w.z, (__bf16)w.w};
+      *(bf16x4*)(p.out + oel * 2) = wb;
+    }
   }
 }
 
@@ -1125,7 +1219,24 @@ static hipError_t plan_attn(AttnParams& p, const Geom& g, int nl, int n_total, s
   // into as many chunks as the XCD has workgroups.  The plain split above would hand a workgroup a
   // run of whole items, and the query blocks of a head would re-read its K/V from memory one after
   // the other.
-  {
+  p.item_mode = 0; p.per_xcd = n_wgs / 8; p.ppx = 0; p.rf = 0; p.lo_chunk = 1;
+  if (attn_whole_items(p.LH, p.QB, n_wgs)) {
+    // Many head pairs: every workgroup takes whole items, round after round (no partial records, no
+    // merge, 7 tiles' worth of piece overhead per 139-tile item instead of per 48-tile chunk), an
+    // XCD's workgroups staying on a few consecutive head pairs whose K/V tiles they walk side by
+    // side; only the items left over after the last full round are cut.
+    const int per_xcd = n_wgs / 8;
+    p.item_mode = 1;
+    p.ppx = pairs / 8;
+    const int ipx = p.ppx * p.QB;
+    p.rf = ipx / per_xcd;
+    const int lo = ipx - p.rf * per_xcd;
+    p.lo_chunk = lo > 0 ? (int)(((long)lo * p.T + per_xcd - 1) / per_xcd) : 1;
+    p.rounds = p.rf + (lo > 0 ? 1 : 0);
+    p.cpp = 0; p.rec_table_on = 0; p.chunk = 0;
+    p.NS = 1; p.L0 = p.T; p.PP = p.QB * p.T;
+    p.total_units = pairs * p.PP;
+  } else {
     const int per_xcd = n_wgs / 8;
     const long chunks = (long)pairs * per_xcd;
     if (pairs > 8 && pairs % 8 == 0 && p.QB * p.T >= per_xcd &&
@@ -1164,9 +1275,10 @@ bool attn_plan_stats(const Geom& g, int nl, int n_total, int n_wgs, size_t ws_by
   for (int w = 0; w < n_wgs; ++w) {
     int tiles = 0, pieces_wg = 0;
     for (int rnd = 0; rnd < p.rounds; ++rnd) {
-      const int c = rnd * n_wgs + w;
-      long u = chunk_first_unit(p, c);
-      const long u_end = chunk_first_unit(p, c + 1);
+      const ChunkRange cr = chunk_range(p, rnd, w, n_wgs);
+      const int c = cr.rec_chunk;
+      long u = cr.u0;
+      const long u_end = cr.u1;
       if (u > u_end || u_end > p.total_units) return false;
       int partial = 0, n_piece = 0;
       const long u_begin = u;
@@ -1182,7 +1294,17 @@ bool attn_plan_stats(const Geom& g, int nl, int n_total, int n_wgs, size_t ws_by
           if (cell) return false;
           cell = 1;
         }
-        if (!full && chunk_of_unit(p, u) != c) return false;          // the merge pass must find this chunk again
+        if (!full && !p.item_mode && chunk_of_unit(p, u) != c) return false;   // the merge pass must find this chunk again
+        if (p.item_mode) {                                              // ... here by the same arithmetic as the merge pass
+          const int x = up.hp / p.ppx, i = (up.hp - x * p.ppx) * p.QB + up.qb;
+          const bool whole_round = i < p.rf * p.per_xcd;
+          if (whole_round != (rnd < p.rf) || (whole_round && !full)) return false;
+          if (!whole_round) {
+            const long off = (long)(i - p.rf * p.per_xcd) * p.T + t0;
+            if (x * p.per_xcd + (int)(off / p.lo_chunk) != c || (full != ((off - t0) / p.lo_chunk == (off - t0 + p.T - 1) / p.lo_chunk)))
+              return false;
+          }
+        }
         const int rec_ord = p.NS == 1 ? (u == u_begin ? 0 : 1) : n_piece;
         ++n_piece;
         if (p.rec_table_on) {                                           // ... and the table must list this record once

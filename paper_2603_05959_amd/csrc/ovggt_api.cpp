@@ -126,8 +126,13 @@ void make_geom(const ovggt_config& c, Geom* g) {
   g->meta_layer_bytes = off;
 }
 
+int query_blocks(const ovggt_config& c) { return (c.tokens_per_frame + kQueryTile - 1) / kQueryTile; }
+
+// the larger of what a single-layer launch and an all-layers launch need
 size_t ws_bytes_for(const ovggt_config& c) {
-  return c.dtype == OVGGT_BF16 ? up256(attn_ws_bytes(c.n_layers * c.n_heads)) : 256;
+  if (c.dtype != OVGGT_BF16) return 256;
+  const size_t one = attn_ws_bytes(c.n_heads, query_blocks(c)), all = attn_ws_bytes(c.n_layers * c.n_heads, query_blocks(c));
+  return up256(one > all ? one : all);
 }
 
 bool aligned16(const void* p) { return p && ((uintptr_t)p & 15) == 0; }
@@ -266,7 +271,7 @@ static int global_attn_impl(ovggt_cache* c, int layer, const void* q, const void
   size_t ws_bytes = ws_bytes_for(c->cfg);
   if (static_ws && g.esize == 2) {
     if (attn_static_ws(&ws, &ws_bytes) != hipSuccess) return OVGGT_ERR_HIP;
-    if (attn_ws_bytes(nl * g.H) > ws_bytes) return OVGGT_ERR_TOO_LARGE;   // before anything is launched
+    if (attn_ws_bytes(nl * g.H, query_blocks(c->cfg)) > ws_bytes) return OVGGT_ERR_TOO_LARGE;   // before anything is launched
   }
   const int n = c->n[l0];
   const int64_t gid0 = c->frames[l0] * (int64_t)g.M;

@@ -74,7 +74,8 @@ hipError_t launch_attn_f32(const Geom& g, char* kv, int layer0, int nl, const vo
 hipError_t launch_attn_bf16(const Geom& g, char* kv, int layer0, int nl, const void* q, void* out,
                             int n_total, float scale, char* ws, size_t ws_bytes, int n_wgs, bool out_f32,
                             hipStream_t s, hipEvent_t* ev = nullptr);
-size_t attn_ws_bytes(int layer_heads);
+size_t attn_ws_bytes(int layer_heads, int query_blocks);
+bool attn_whole_items(int layer_heads, int query_blocks, int n_wgs);
 // The library's own workspace for the attention's partial records (a device array of fixed size, one
 // copy per GPU): its device address on the current device and its size.  Looks the address up on the
 // first call per device; allocates nothing.

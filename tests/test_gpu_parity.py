@@ -461,6 +461,8 @@ def test_worst_case_compaction_rising_scores():
     dict(M=150, H=2, C=256, B=400, T=7, L=3),          # 3 head pairs: one chunk per workgroup
     dict(M=300, H=8, C=64, B=5000, T=5, L=4),          # 16 head pairs: two rounds per XCD, tile segments
     dict(M=130, H=16, C=64, B=300, T=4, L=3),          # 24 head pairs: three rounds, short caches
+    dict(M=600, H=16, C=64, B=1000, T=4, L=8),         # 64 head pairs x 5 query blocks: whole items per workgroup for a
+                                                       # round, the 8 left over per XCD cut into 4-tile chunks (5 pieces each)
 ])
 def test_batched_layers_match_per_layer_oracle(shape):
     cfg = synth.preset(2, n_special=5, **shape)

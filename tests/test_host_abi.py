@@ -122,7 +122,8 @@ def test_attention_plans_cover_every_tile_once():
     shapes = [(1374, 16, 16384, 1), (1374, 16, 16384, 24), (1374, 16, 32768, 1), (1041, 16, 4096, 1),
               (1041, 16, 65536, 1), (200, 3, 700, 1), (1, 1, 64, 1), (37, 2, 74, 1), (130, 5, 1000, 1),
               (128, 16, 256, 1), (300, 8, 5000, 4), (130, 16, 300, 3), (150, 2, 400, 3), (1, 16, 188, 1),
-              (500, 4, 3000, 2), (129, 1, 100000, 1), (2000, 32, 9000, 1), (64, 64, 640, 2)]
+              (500, 4, 3000, 2), (129, 1, 100000, 1), (2000, 32, 9000, 1), (64, 64, 640, 2), (600, 16, 1000, 8),
+              (1041, 16, 8192, 24), (4096, 16, 4096, 1), (520, 2, 9000, 16)]
     for M, H, Bud, L in shapes:
         cfg = B.make_config(L, H, 64, M, 64, max(Bud, M), "bf16")
         for n_total in sorted({M, min(2 * M, Bud + M), (Bud + M) // 2, Bud + M - 1, Bud + M}):
@@ -133,4 +134,9 @@ def test_attention_plans_cover_every_tile_once():
                     assert st["cost_max"] <= 1.12 * st["cost_mean"] + 1, (M, H, Bud, L, n_total, n_wgs, st)
     st = B.ovggt_attn_plan_stats(B.make_config(1, 16, 64, 1374, 1024, 16384, "bf16"), 1, 17758, 256)
     assert st["balanced"] == 1 and st["segments"] == 3 and st["pieces_max"] <= 2
+    # 24 layers: 264 items per XCD over 32 workgroups = 8 rounds of whole items and one round of cut ones
+    cfg24 = B.make_config(24, 16, 64, 1374, 1024, 16384, "bf16")
+    st = B.ovggt_attn_plan_stats(cfg24, 24, 17758, 256)
+    assert st["rounds"] == 9 and st["segments"] == 1 and st["tiles_max"] - st["tiles_min"] <= 8
+    assert B.ovggt_cache_query_bytes(cfg24)[2] == B.ovggt_cache_query_bytes(B.make_config(1, 16, 64, 1374, 1024, 16384, "bf16"))[2]
     print(st)
