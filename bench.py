@@ -337,9 +337,17 @@ def graph_replay_rate(cache, staged, distinct, out, layer, t_next, K):
         replay(t_next + 8 + i)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    for i in range(K):                                    # the same inputs again and again: the replay alone
+        B.ovggt_cache_advance(cache.h, layer, 1)
+        g.replay()
+    torch.cuda.synchronize()
+    dt2 = time.perf_counter() - t0
     return {"value": K / dt, "unit": "frames/s", "ms_per_step": 1e3 * dt / K,
+            "replay_only": {"value": K / dt2, "unit": "frames/s", "ms_per_step": 1e3 * dt2 / K},
             "note": "one captured graph of a whole step (append, attention, merge, score/select) replayed K times; "
-                    "the four input copies into the graph's fixed buffers are inside the timed loop"}
+                    "value: with the four input copies into the graph's fixed buffers inside the timed loop; "
+                    "replay_only: without them (the last frame's inputs over and over)"}
 
 
 def brief(r):

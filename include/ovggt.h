@@ -270,10 +270,11 @@ enum { OVGGT_PROF_APPEND = 0, OVGGT_PROF_ATTN = 1, OVGGT_PROF_COMBINE = 2, OVGGT
        OVGGT_PROF_COMPACT = 4, OVGGT_PROF_CLASSES = 5 };
 int ovggt_profile_enable(ovggt_cache* c, int level, int every);
 int ovggt_profile_read(ovggt_cache* c, double* ms_sum, int64_t* count, void* hip_stream);
-/* Mean elapsed milliseconds of the same event bracket around `reps` launches of a
- * 256-byte fill (it rewrites the first 256 bytes of the workspace with zeros, so
- * call it between frames only): what a bracket reports beyond the bracketed
- * kernel's own execution.  Synchronises `hip_stream`. */
+/* What an event bracket reports beyond the bracketed kernel's own execution: the mean elapsed
+ * milliseconds of the same bracket around `reps` launches of a kernel that runs for a known time
+ * (one wave that watches the device's constant-rate wall clock for 0.1 ms, about as long as the
+ * kernels the brackets are used on), minus that time.  Touches no buffer of the handle.
+ * Synchronises `hip_stream`. */
 int ovggt_profile_overhead(ovggt_cache* c, int reps, double* ms_mean, void* hip_stream);
 
 /* ---- Dynamic Anchor Protection: which frames become anchors (Sec. 3.3) ------------------

@@ -314,9 +314,11 @@ __device__ __forceinline__ float tile_weights(const f32x16& s0, const f32x16& s1
   // packed half adds: one instruction per two weights instead of two fp32 adds, on the pipe that
   // co-executes with the other set's MFMAs (v_dot2c_f32_f16 would be exact but runs on the matrix
   // pipe and serialises with them: measured).  Four independent packed accumulators of 8 terms
-  // each, joined in fp32: the rounding of a tile's sum stays near 2^-11 relative and is unbiased.
-  // An overflowing weight or partial sum becomes +inf and trips the caller's limit test.
-  f16x2 ls[4] = {{0, 0}, {0, 0}, {0, 0}, {0, 0}};
+  // each (the first four pairs start them, no zero to add to), joined pairwise in half and widened
+  // once: 32 terms, five levels of half rounding, near 2^-11 relative and unbiased.  An
+  // overflowing weight or partial sum becomes +inf and trips the caller's limit test (sums
+  // beyond 2^15 take the slow path anyway).
+  f16x2 ls[4];
 #pragma unroll
   for (int sb = 0; sb < 2; ++sb) {
     float e[16];
@@ -331,13 +333,14 @@ __device__ __forceinline__ float tile_weights(const f32x16& s0, const f32x16& s1
       f16x2 pk;
       pk[0] = (_Float16)e[2 * j];
       pk[1] = (_Float16)e[2 * j + 1];
-      ls[j & 3] += pk;
+      if (sb == 0 && j < 4) ls[j] = pk; else ls[j & 3] += pk;
       (sb ? p1 : p0)[j] = __builtin_bit_cast(uint32_t, pk);
     }
     __builtin_amdgcn_sched_barrier(0);
   }
-  return ((float)ls[0][0] + (float)ls[1][0]) + ((float)ls[2][0] + (float)ls[3][0]) +
-         (((float)ls[0][1] + (float)ls[1][1]) + ((float)ls[2][1] + (float)ls[3][1]));
+  const f16x2 t = (ls[0] + ls[1]) + (ls[2] + ls[3]);
+  return (float)t[0] + (float)t[1];
+
 }
 
 // The reference of a query block as the B operand of the bias step of S^T (a 32x32x8 MFMA, whose

@@ -39,6 +39,22 @@ hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
 }
 
 // --------------------------------------------------------------------------
+// Timing aid: one wave that returns after `ticks` ticks of the constant-rate wall clock (or after
+// a fixed number of polls, whichever comes first, so the kernel ends under all circumstances).
+__global__ void __launch_bounds__(64) spin_kernel(unsigned long long ticks) {
+  const unsigned long long t0 = wall_clock64();
+  for (int i = 0; i < (1 << 22); ++i) {
+    if (wall_clock64() - t0 >= ticks) break;
+    __builtin_amdgcn_s_sleep(8);
+  }
+}
+
+hipError_t launch_spin(unsigned long long ticks, hipStream_t s) {
+  hipLaunchKernelGGL(spin_kernel, dim3(1), dim3(64), 0, s, ticks);
+  return hipGetLastError();
+}
+
+// --------------------------------------------------------------------------
 // Append.  Input rows are token-major [M][H][d]; the cache is head-major
 // [H][cap][d].  One thread per 16-byte piece of K and of V.
 // MOVES: the compaction that follows the previous frame's selection has not been applied yet

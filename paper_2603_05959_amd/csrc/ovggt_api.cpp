@@ -552,13 +552,19 @@ int ovggt_profile_read(ovggt_cache* c, double* ms_sum, int64_t* count, void* hip
 int ovggt_profile_overhead(ovggt_cache* c, int reps, double* ms_mean, void* hip_stream) {
   if (!c || !ms_mean || reps < 1 || reps > 1024) return OVGGT_ERR_ARG;
   hipStream_t s = (hipStream_t)hip_stream;
+  int dev = 0, khz = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess || khz <= 0)
+    return OVGGT_ERR_HIP;
+  const double spin_ms = 0.1;                          // as long as the kernels the brackets are used on
+  const unsigned long long ticks = (unsigned long long)(spin_ms * khz + 0.5);
   std::vector<std::pair<hipEvent_t, hipEvent_t>> ev;
   bool failed = false;
   for (int i = 0; i < reps; ++i) {
     hipEvent_t e0 = prof_event(c), e1 = prof_event(c);
     bool ok = e0 && e1;
-    // the same bracket as around a timed kernel, around a launch that does next to nothing
-    ok = ok && hipEventRecord(e0, s) == hipSuccess && launch_fill_zero(c->ws, 256, s) == hipSuccess &&
+    // the same bracket as around a timed kernel, around a kernel whose own duration is known
+    ok = ok && hipEventRecord(e0, s) == hipSuccess && launch_spin(ticks, s) == hipSuccess &&
          hipEventRecord(e1, s) == hipSuccess;
     if (e0) ev.push_back({e0, e1});                  // returned to the free list below, also after a failure
     else if (e1) c->prof_free.push_back(e1);
@@ -574,7 +580,7 @@ int ovggt_profile_overhead(ovggt_cache* c, int reps, double* ms_mean, void* hip_
     if (pr.second) c->prof_free.push_back(pr.second);
   }
   if (failed) return OVGGT_ERR_HIP;
-  *ms_mean = sum / reps;
+  *ms_mean = sum / reps - spin_ms;
   return OVGGT_OK;
 }
 

@@ -58,6 +58,8 @@ __host__ __device__ inline char* layer_meta(char* meta, const Geom& g, int layer
 
 // ---- launchers (each only enqueues on `s`) ---------------------------------
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
+// One wave that runs for `ticks` ticks of the device's constant-rate wall clock (timing aid).
+hipError_t launch_spin(unsigned long long ticks, hipStream_t s);
 
 // Eq. 2: copy the frame's K/V rows into slots [n, n+M) of layers [layer0, layer0+nl)
 // and initialise their ids (the layer's gid_next + i), scores (0) and flags (0).  apply_moves: the previous
