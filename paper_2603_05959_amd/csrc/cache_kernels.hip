@@ -91,11 +91,13 @@ append_kernel(Geom g, char* kv, char* meta, int layer0, const char* k_new, const
   uint4 vv = *(const uint4*)(v_new + src);
   char* mb = layer_meta(meta, g, layer);
   if constexpr (MOVES) {
+    // the entry that sits in the slot is fetched together with its destination, not after it: one
+    // round trip to memory less on the path of every moved piece
+    const uint4 ok = *(const uint4*)(layer_k(kv, g, layer) + dst);
+    const uint4 ov = *(const uint4*)(layer_v(kv, g, layer) + dst);
     const uint32_t to = ((const uint32_t*)(mb + g.off_mvmap))[m];
     if (to < (uint32_t)g.B) {                        // kNoMove, or anything out of range: nothing to carry
       const size_t mv = ((size_t)h * g.cap + to) * row_bytes + piece * 16;
-      const uint4 ok = *(const uint4*)(layer_k(kv, g, layer) + dst);
-      const uint4 ov = *(const uint4*)(layer_v(kv, g, layer) + dst);
       uint32_t id = 0; float sc = 0.f; uint8_t fl = 0;
       const bool meta_thread = h == 0 && piece == 0;
       if (meta_thread) {
