@@ -665,8 +665,10 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
     x.lds_ld = (uint32_t)(uintptr_t)LDS_PTR(char, lds) + (uint32_t)(set * kSetBytes + wv * 4096);
   }
 
-  // set B runs one barrier behind set A: its matrix phases coincide with A's vector phases
-  if (set == 1) phase_barrier();
+  // Set B runs one barrier behind set A, so that its matrix phases coincide with A's vector phases:
+  // it executes one barrier more than A before its first tile (below, once its first piece's loads
+  // are on their way) and A makes up for it at the end.  `started` is uniform over the workgroup.
+  bool started = false;
 
   // Head pairs are dealt out round by round: in every round an XCD's workgroups share one head
   // pair (its K/V tiles then live in that XCD's L2 while all its query blocks pass over them).
@@ -745,6 +747,10 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
       }
     }
 
+    // set B's extra barrier comes behind its first requests, not in front of them: both sets' cold
+    // loads of the first tiles and queries are in flight together instead of one after the other
+    if (!started && set == 1) phase_barrier();
+    started = true;
     // the builtin wait also tells the compiler that the loads it tracks itself (Q) are complete, so
     // it adds no vmcnt waits of its own inside the tile loop
     __builtin_amdgcn_s_waitcnt(kWaitVm0);
@@ -887,7 +893,7 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
     u += t1 - t0;
   }
   }
-  if (set == 0) phase_barrier();                       // set A: the barrier set B executed up front
+  if (started && set == 0) phase_barrier();            // set A: the barrier set B executed before its first tile
 #ifdef OVGGT_TRACE
   if (lane == 0) {
     unsigned long long* tr = (unsigned long long*)(p.ws + p.trace_off) - (size_t)(cidx * 8 + wave + 1) * 8;
