@@ -615,7 +615,29 @@ __device__ __forceinline__ void tile_step(TileCtx& x, int tt, const int (&koff)[
 #endif
 }
 
+// Touches every 64-byte line of the kernel's argument block (the explicit arguments and the
+// launch dimensions behind them) with one scalar load each, all in flight together, and waits for
+// them once.  The plan in AttnParams is read piecemeal and in dependent steps (grid size, chunk
+// table, unit decoding, tile addresses); left cold, each step is a round trip to memory of its own
+// at the start of every workgroup (measured: 4.5 thousand cycles before the first tile is
+// requested).  The wait is part of the same statement: the compiler does not know that these are
+// loads, so nothing of them may still be in flight when it reuses the register.
+__device__ __forceinline__ void warm_kernel_arguments() {
+  static_assert(sizeof(AttnParams) + 64 <= 14 * 64, "one load per 64-byte line of the argument block");
+  const char __attribute__((address_space(4)))* ka =
+      (const char __attribute__((address_space(4)))*)__builtin_amdgcn_kernarg_segment_ptr();
+  uint32_t sink;
+  asm volatile("s_load_dword %0, %1, 0x0\n\ts_load_dword %0, %1, 0x40\n\ts_load_dword %0, %1, 0x80\n\t"
+               "s_load_dword %0, %1, 0xc0\n\ts_load_dword %0, %1, 0x100\n\ts_load_dword %0, %1, 0x140\n\t"
+               "s_load_dword %0, %1, 0x180\n\ts_load_dword %0, %1, 0x1c0\n\ts_load_dword %0, %1, 0x200\n\t"
+               "s_load_dword %0, %1, 0x240\n\ts_load_dword %0, %1, 0x280\n\ts_load_dword %0, %1, 0x2c0\n\t"
+               "s_load_dword %0, %1, 0x300\n\ts_load_dword %0, %1, 0x340\n\t"
+               "s_waitcnt lgkmcnt(0)"
+               : "=&s"(sink) : "s"(ka) : "memory");
+}
+
 __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p) {
+  warm_kernel_arguments();
   __shared__ __attribute__((aligned(1024))) char lds[2 * kSetBytes];      // [set][parity][K | V]
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
