@@ -110,9 +110,7 @@ size_t attn_ws_bytes(int layer_heads, int query_blocks) {
   long chunks = pairs * (kMaxAttnWgs / 8) > kMaxAttnWgs ? pairs * (kMaxAttnWgs / 8) : kMaxAttnWgs;
   if (attn_whole_items(layer_heads, query_blocks, kMaxAttnWgs)) chunks = kMaxAttnWgs;   // holds for fewer workgroups too
   size_t bytes = (size_t)chunks * kSegRecs * 2 * kPartialFloats * sizeof(float);
-#ifdef OVGGT_TRACE
-  bytes += (size_t)kMaxAttnWgs * 8 * 64;                // timing builds: one 64-byte record per wave behind the partials
-#endif
+  OVGGT_TRACE_ONLY(bytes += (size_t)kMaxAttnWgs * 8 * 64;)   // timing builds: one 64-byte record per wave behind the partials
   return bytes;
 }
 
@@ -517,9 +515,7 @@ struct TileCtx {
   int t1, T, n_total, slot0;  // slot0: first slot of this lane's accumulator rows within a tile
   int g;                      // which 8-index group of the contraction this lane holds
   bool active;
-#ifdef OVGGT_TRACE
-  unsigned long long tr_m, tr_x, tr_v, tr_y, tr_w;   // cycles in matrix phase, at its barrier, in vector phase, at its barrier
-#endif
+  OVGGT_TRACE_ONLY(unsigned long long tr_m, tr_x, tr_v, tr_y, tr_w;)   // cycles in matrix phase, at its barrier, in vector phase, at its barrier
 };
 
 // Per-wave attention state of one segment.
@@ -538,10 +534,10 @@ template <int PAR, bool FIRST>
 __device__ __forceinline__ void tile_step(TileCtx& x, int tt, const int (&koff)[4],
                                           const int (&voff)[2][2], SegState& z) {
   const bool more = tt + 1 < x.t1;
-#ifdef OVGGT_TRACE
-  const unsigned long long tr0 = clock64();
-  __builtin_amdgcn_sched_barrier(0);
-#endif
+  OVGGT_TRACE_ONLY(
+    const unsigned long long tr0 = clock64();
+    __builtin_amdgcn_sched_barrier(0);
+  )
   // ---- matrix phase
   __builtin_amdgcn_s_setprio(kPrioMatrix);
   if (x.active) {
@@ -573,15 +569,15 @@ __device__ __forceinline__ void tile_step(TileCtx& x, int tt, const int (&koff)[
       for (int b = 0; b < 2; ++b) asm volatile("" : "+v"(z.S[a][b]));      // issued before the barrier
   }
   __builtin_amdgcn_s_setprio(kPrioVector);
-#ifdef OVGGT_TRACE
-  __builtin_amdgcn_sched_barrier(0);
-  const unsigned long long tr1 = clock64();
-#endif
+  OVGGT_TRACE_ONLY(
+    __builtin_amdgcn_sched_barrier(0);
+    const unsigned long long tr1 = clock64();
+  )
   phase_barrier();
-#ifdef OVGGT_TRACE
-  const unsigned long long tr2 = clock64();
-  __builtin_amdgcn_sched_barrier(0);
-#endif
+  OVGGT_TRACE_ONLY(
+    const unsigned long long tr2 = clock64();
+    __builtin_amdgcn_sched_barrier(0);
+  )
   // ---- vector phase
   if (x.active) {
     if (more)
@@ -596,23 +592,23 @@ __device__ __forceinline__ void tile_step(TileCtx& x, int tt, const int (&koff)[
 #pragma unroll
         for (int j = 0; j < 8; ++j) asm volatile("" : "+v"(z.P[a][b][j]));   // computed before the barrier
   }
-#ifdef OVGGT_TRACE
-  __builtin_amdgcn_sched_barrier(0);
-  const unsigned long long tr2b = clock64();
-  __builtin_amdgcn_sched_barrier(0);
-#endif
+  OVGGT_TRACE_ONLY(
+    __builtin_amdgcn_sched_barrier(0);
+    const unsigned long long tr2b = clock64();
+    __builtin_amdgcn_sched_barrier(0);
+  )
   // K of tile tt+1 (and everything older) has landed; only V of tile tt+1 may still be in flight
   if (more) __builtin_amdgcn_s_waitcnt(kWaitVm4);
   else __builtin_amdgcn_s_waitcnt(kWaitVm0);
-#ifdef OVGGT_TRACE
-  __builtin_amdgcn_sched_barrier(0);
-  const unsigned long long tr3 = clock64();
-#endif
+  OVGGT_TRACE_ONLY(
+    __builtin_amdgcn_sched_barrier(0);
+    const unsigned long long tr3 = clock64();
+  )
   phase_barrier();
-#ifdef OVGGT_TRACE
-  const unsigned long long tr4 = clock64();
-  x.tr_m += tr1 - tr0; x.tr_x += tr2 - tr1; x.tr_v += tr2b - tr2; x.tr_y += tr4 - tr3; x.tr_w += tr3 - tr2b;
-#endif
+  OVGGT_TRACE_ONLY(
+    const unsigned long long tr4 = clock64();
+    x.tr_m += tr1 - tr0; x.tr_x += tr2 - tr1; x.tr_v += tr2b - tr2; x.tr_y += tr4 - tr3; x.tr_w += tr3 - tr2b;
+  )
 }
 
 // Touches every 64-byte line of the kernel's argument block (the explicit arguments and the
@@ -648,10 +644,10 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
   const int G = gridDim.x;
   const int cidx = (blockIdx.x & 7) * (G >> 3) + (blockIdx.x >> 3);
   if (!p.item_mode && chunk_first_unit(p, cidx) >= p.total_units) return;   // whole workgroup: no barrier has been executed yet
-#ifdef OVGGT_TRACE
-  const unsigned long long tr_w0 = wall_clock64(), tr_c0 = clock64();
-  unsigned long long tr_n = 0;
-#endif
+  OVGGT_TRACE_ONLY(
+    const unsigned long long tr_w0 = wall_clock64(), tr_c0 = clock64();
+    unsigned long long tr_n = 0;
+  )
 
   // per-lane LDS offsets (the set's region included)
   char* const lset = lds + set * kSetBytes;
@@ -673,9 +669,7 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
   }
 
   TileCtx x;
-#ifdef OVGGT_TRACE
-  x.tr_m = x.tr_x = x.tr_v = x.tr_y = x.tr_w = 0;
-#endif
+  OVGGT_TRACE_ONLY(x.tr_m = x.tr_x = x.tr_v = x.tr_y = x.tr_w = 0;)
   x.lds = lds;
   x.T = p.T;
   x.n_total = p.n_total;
@@ -787,9 +781,7 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
     }
     const bool odd = tt >= t1;                           // an odd number of tiles: the last one had parity 0
     if (!odd) tile_step<1, false>(x, tt, koff, voff, z);
-#ifdef OVGGT_TRACE
-    tr_n += t1 - t0;
-#endif
+    OVGGT_TRACE_ONLY(tr_n += t1 - t0;)
 
     // P V of the last tile
     if (active) {
@@ -916,13 +908,13 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
   }
   }
   if (started && set == 0) phase_barrier();            // set A: the barrier set B executed before its first tile
-#ifdef OVGGT_TRACE
-  if (lane == 0) {
-    unsigned long long* tr = (unsigned long long*)(p.ws + p.trace_off) - (size_t)(cidx * 8 + wave + 1) * 8;
-    tr[0] = x.tr_w; tr[1] = wall_clock64() - tr_w0; tr[2] = clock64() - tr_c0; tr[5] = tr_n;
-    tr[3] = x.tr_m; tr[4] = x.tr_x; tr[6] = x.tr_v; tr[7] = x.tr_y;
-  }
-#endif
+  OVGGT_TRACE_ONLY(
+    if (lane == 0) {
+      unsigned long long* tr = (unsigned long long*)(p.ws + p.trace_off) - (size_t)(cidx * 8 + wave + 1) * 8;
+      tr[0] = x.tr_w; tr[1] = wall_clock64() - tr_w0; tr[2] = clock64() - tr_c0; tr[5] = tr_n;
+      tr[3] = x.tr_m; tr[4] = x.tr_x; tr[6] = x.tr_v; tr[7] = x.tr_y;
+    }
+  )
 }
 
 // One round of the merge: up to kMaxParts partial records of a row are fetched together (all loads

@@ -5,6 +5,14 @@
 #include <stdint.h>
 #include <stddef.h>
 
+// Timing builds (-DOVGGT_TRACE) keep cycle stamps of the kernels' phases; in product builds the
+// statements inside OVGGT_TRACE_ONLY(...) do not exist.
+#ifdef OVGGT_TRACE
+#define OVGGT_TRACE_ONLY(...) __VA_ARGS__
+#else
+#define OVGGT_TRACE_ONLY(...)
+#endif
+
 namespace ovggt {
 
 constexpr int kSlotTile = 128;      // attention consumes the cache in 128-slot tiles

@@ -357,9 +357,7 @@ __device__ inline void emit_moves(SelShared& sh, const Geom& g, Ctrl* ctrl, uint
     if (sh.bad) st |= OVGGT_STATUS_NONFINITE;
     if (st) atomicOr(&ctrl->status, st);
     TSTAMP(12);
-#ifdef OVGGT_TRACE
-    ctrl->pad[13] = (uint32_t)pass;
-#endif
+    OVGGT_TRACE_ONLY(ctrl->pad[13] = (uint32_t)pass;)
   }
 }
 
@@ -812,9 +810,7 @@ score_select_kernel(Geom g, SmoothParams sm, HybridParams hy, char* meta, int la
   const int tid = threadIdx.x;
   const int n_old = n_total - g.M;
 
-#ifdef OVGGT_TRACE
-  if (blockIdx.x == 0 && tid == 0) ctrl->pad[15] = (uint32_t)wall_clock64();
-#endif
+  OVGGT_TRACE_ONLY(if (blockIdx.x == 0 && tid == 0) ctrl->pad[15] = (uint32_t)wall_clock64();)
   // The two histogram levels start at zero in every workgroup (each counts its share of the cache
   // into the first, and whichever selects uses both); cleared in the shadow of phase 1's loads.
   const bool selecting = n_total > g.B;
@@ -871,9 +867,7 @@ score_select_kernel(Geom g, SmoothParams sm, HybridParams hy, char* meta, int la
     if (last) {
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
       __hip_atomic_store(&ctrl->arrive, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#ifdef OVGGT_TRACE
-      ctrl->pad[0] = (uint32_t)wall_clock64();
-#endif
+      OVGGT_TRACE_ONLY(ctrl->pad[0] = (uint32_t)wall_clock64();)
     }
     sh.is_last = last ? 1u : 0u;
   }
