@@ -240,8 +240,9 @@ def run_workload(cfg, W, K, *, hybrid_beta=None, smooth_alpha=None, rising=False
 
     kernels = {}
     for name, (ms, cnt) in detail.items():
-        if cnt:
-            kernels[name] = {"avg_us": 1e3 * ms / cnt, "launches": int(cnt)}
+        if cnt:                                          # the same bracket correction as for the attention kernel above
+            raw = 1e3 * ms / cnt
+            kernels[name] = {"avg_us": max(raw - 1e3 * bracket_overhead_ms, 0.1), "event_bracket_us": raw, "launches": int(cnt)}
     esz = 2 if cfg.dtype == "bf16" else 4
     hbm = {}
     if "score_select" in kernels:
