@@ -308,9 +308,12 @@ int ovggt_dap_destroy(ovggt_dap* d);
  * n_total resident slots would be divided among n_wgs workgroups (the library uses one per compute
  * unit).  Walks the plan as the kernel does and checks that every (head, query block, key tile) is
  * covered exactly once and that no workgroup needs more partial records than it owns.
- * out[0..6] = workgroups, rounds per workgroup, tile segments, 1 if chunks are cost-balanced, most
- * pieces given to one workgroup, fewest and most tiles given to one workgroup; cost[0..1] = largest
- * and mean estimated cost per workgroup in tiles (tiles + a fixed charge per piece).
+ * out[0..7] = workgroups, rounds per workgroup, tile segments, 1 if chunks are cost-balanced, most
+ * pieces given to one workgroup, fewest and most tiles given to one workgroup, work items in which
+ * both halves of a workgroup take two query blocks of one head (they fetch that head's K/V tiles
+ * once for both; the walk also checks that items and halves cover every query block of every head
+ * exactly once); cost[0..1] = largest and mean estimated cost per workgroup in tiles (tiles + a
+ * fixed charge per piece).
  * OVGGT_OK, ERR_ARG (bad config or sizes), ERR_STATE (inconsistent plan: a bug). */
 int ovggt_attn_plan_stats(const ovggt_config* cfg, int32_t layers_in_launch, int32_t n_total, int32_t n_wgs,
                           int32_t* out, float* cost);

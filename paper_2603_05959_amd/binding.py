@@ -239,11 +239,11 @@ def ovggt_dap_destroy(h) -> None:
 
 
 def ovggt_attn_plan_stats(cfg: ovggt_config, layers_in_launch: int, n_total: int, n_wgs: int) -> dict:
-    out = (C.c_int32 * 7)()
+    out = (C.c_int32 * 8)()
     cost = (C.c_float * 2)()
     _check(lib().ovggt_attn_plan_stats(C.byref(cfg), layers_in_launch, n_total, n_wgs, out, cost),
            "ovggt_attn_plan_stats")
-    keys = ("n_wgs", "rounds", "segments", "balanced", "pieces_max", "tiles_min", "tiles_max")
+    keys = ("n_wgs", "rounds", "segments", "balanced", "pieces_max", "tiles_min", "tiles_max", "shared_items")
     d = dict(zip(keys, list(out)))
     d["cost_max"], d["cost_mean"] = cost[0], cost[1]
     return d

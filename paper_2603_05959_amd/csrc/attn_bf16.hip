@@ -31,22 +31,28 @@
 // is in its matrix phase the other is in its vector phase and both pipes stay
 // busy.  Every wave executes the same sequence of barriers.
 //
-// Work split.  The two sets work on two different (layer, head) pairs of the same
-// 128-query block, each with its own K/V tile buffers, so they share control flow
-// (same tile range) but no data.  A pair item is (layer-head pair, query block);
-// its work is T = ceil(n/128) slot tiles.  The flat list of pair item x tile
-// units is cut into equal chunks, one per workgroup (one workgroup per CU,
-// persistent, stream-K style).  A set that covers its item completely writes the
-// output; otherwise it writes an unnormalised partial (O, m, l) that
-// attn_combine_kernel merges.  Chunks are handed to workgroups so that each XCD's
-// L2 sees as few heads as possible.
+// Work split.  A work item is one of the QB items of a (layer, head) pair; its work is
+// T = ceil(n/128) slot tiles for both wave sets, which share control flow (same tile range).
+// Where a head has two query blocks left, an item is two neighbouring 128-query blocks of ONE
+// head, one per set, and both sets read the same K/V tiles from set A's LDS buffers: set A
+// requests the K tiles, set B the V tiles, so a tile travels from L2 into LDS once for 256 queries
+// (work_of_item).  The odd last block of the pair's two heads makes up the last item, one head
+// per set, each with its own tile buffers (also the only form when the launch has an odd number
+// of heads).  The flat list of item x tile units is cut into chunks, one per workgroup (one
+// workgroup per CU, persistent, stream-K style).  A set that covers its block completely writes
+// the output; otherwise it writes an unnormalised partial (O, m, l) that attn_combine_kernel
+// merges.  Chunks are handed to workgroups so that each XCD's L2 sees as few heads as possible.
 //
 // Inside a set, wave = (query half, slot half) of the 128x128 tile; the two slot
 // halves are merged through LDS at the end of an item.  K and V tiles stream
 // global->LDS with 16-byte direct-to-LDS loads, double buffered: K of tile t+1 is
 // requested at the start of the matrix phase of tile t, V of tile t+1 at the
 // start of its vector phase, and both are awaited (vmcnt) just before the barrier
-// that precedes their first use.  LDS rows are 128 bytes; 16-byte pieces are
+// that precedes their first use.  With shared tiles the same two requests come from
+// set A (K, matrix phase) and set B (V, vector phase: the same moment, B being a phase
+// behind), B awaits its V rows one phase earlier (A multiplies by them first), and a
+// wave that has to redo a tile's exponents re-reads K from memory, because set A's next
+// request may already be filling the buffer set B's tile came from.  LDS rows are 128 bytes; 16-byte pieces are
 // XOR-swizzled with the row index so both the K operand reads and the V
 // transpose reads are bank-conflict free.
 #include "ovggt_internal.h"
@@ -77,6 +83,8 @@ __device__ __forceinline__ int swz(int row) { return row & 7; }
 constexpr int kPrioMatrix = 0, kPrioVector = 3;
 constexpr int kTileBytes = kSlotTile * 128;            // one K (or V) tile: 128 slots x 64 16-bit elements
 constexpr int kSetBytes = 4 * kTileBytes;              // LDS of one wave set: [parity][K | V]
+constexpr int kMergeBytes = 2 * 64 * 64 * 4 + 2 * 4 * 64 * 4;   // a set's slot-half merge area: O of two query halves, then (ref, l)
+static_assert((kSetBytes & (kSetBytes - 1)) == 0 && kMergeBytes <= kSetBytes, "region arithmetic of the tile loop");
 constexpr int kAttnThreads = 512;
 constexpr int kPartialFloats = kQueryTile * 64 + 2 * kQueryTile;
 // Float offset, inside a partial record's O part, of the 256-float block that holds the values
@@ -176,6 +184,9 @@ struct AttnParams {
   // whole item (all T tiles, no partial record, no merge), and the items left over are cut evenly
   // into per_xcd chunks of lo_chunk units for one last round.  item_mode = 0: off.
   int item_mode, per_xcd, ppx, rf, lo_chunk;
+  // share = 1: the two wave sets of a workgroup take two query blocks of ONE head wherever a head
+  // has two left, and read the same K/V tiles (see item_of_block); 0: always two heads, one block.
+  int share;
   size_t trace_off;           // floats from ws to the end of the record area (timing builds)
   int total_units;            // ceil(LH / 2) * PP
   float c;                    // softmax scale * log2(e)
@@ -197,6 +208,34 @@ struct UnitPos {
   int seg_end;                // end of the segment (exclusive)
   int combo;                  // running index of (hp, s, qb)
 };
+// What the two wave sets of a workgroup do with item j (0 .. QB-1) of head pair hp.  The plan only
+// knows items; which query blocks they stand for is decided here.  Without sharing, item j is query
+// block j of both heads, one head per wave set.  With sharing, a head's blocks are taken two at a
+// time by one workgroup -- items 0 .. QB/2-1 are block pairs of the first head, the next QB/2 those
+// of the second, both wave sets on the same head and the same K/V tiles, which are then fetched
+// into LDS once for 256 queries instead of once for 128 -- and an odd last block of the two heads
+// makes up the last item, one head per wave set as before.  The item count per head pair is QB
+// either way.
+struct SetWork {
+  int lh, qb;                 // (layer, head) index and query block of this wave set
+  bool shared;                // both sets read one head's tiles
+};
+__host__ __device__ inline SetWork work_of_item(int hp, int j, int set, int QB, int share) {
+  const int nsh = QB >> 1;
+  if (share && j < 2 * nsh) {
+    const int second = j >= nsh ? 1 : 0;
+    return {2 * hp + second, 2 * (j - second * nsh) + set, true};
+  }
+  return {2 * hp + set, j, false};
+}
+// The inverse: the item (within its head pair) and the wave set that handle query block qb of lh.
+struct ItemOfBlock { int j, set; };
+__host__ __device__ inline ItemOfBlock item_of_block(int lh, int qb, int QB, int share) {
+  const int nsh = QB >> 1;
+  if (share && qb < 2 * nsh) return {(lh & 1) * nsh + (qb >> 1), qb & 1};
+  return {qb, lh & 1};
+}
+
 __host__ __device__ inline UnitPos decode_unit(long u, int T, int QB, int NS, int L0, int PP) {
   UnitPos r;
   r.hp = (int)(u / PP);
@@ -271,6 +310,27 @@ __device__ __forceinline__ void load_rows_to_lds(const char* gtile, uint32_t lan
                : : "s"(lds_addr), "v"(lane_off), "s"(gtile) : "memory", "m0");
 }
 
+// One of the four loads of load_rows_to_lds (rows 8*I .. 8*I+7 of the wave's 32).  The vector phase
+// issues its four V loads one in front of each batch of sixteen exp2 instead of together at its
+// start (a direct-to-LDS load keeps its wave from issuing anything else for about 44 cycles;
+// measured: 1-2 % of the kernel on one layer, nothing on 24).
+template <int I>
+__device__ __forceinline__ void load_row_group_to_lds(const char* gtile, uint32_t lane_off, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\t"
+               "s_nop 0\n\t"
+               "global_load_lds_dwordx4 %1, %2 offset:%3"
+               : : "s"(lds_addr), "v"(lane_off), "s"(gtile), "n"(I * 1024) : "memory", "m0");
+}
+// The V loads of the next tile as a hook the softmax calls in front of its four batches (I = 0..3);
+// NoLoads does nothing (a piece's last tile, the redone weights of the slow path).
+struct NoLoads {
+  template <int I> __device__ __forceinline__ void at() const {}
+};
+struct TileLoads {
+  bool on; const char* gtile; uint32_t lane_off, lds_addr;
+  template <int I> __device__ __forceinline__ void at() const { if (on) load_row_group_to_lds<I>(gtile, lane_off, lds_addr); }
+};
+
 // Workgroup barrier that neither memory accesses nor ALU work may be moved across.
 __device__ __forceinline__ void phase_barrier() {
   __builtin_amdgcn_sched_barrier(0);
@@ -305,9 +365,9 @@ __device__ inline f16x8 join4(const uint32_t* p) {
 // them: an instruction that consumes the result of the one issued just before it stalls about four
 // cycles (measured for exp -> add), and left to itself the scheduler emits exactly such dependent
 // pairs to save registers.
-template <bool SHIFT>
+template <bool SHIFT, int QB, class Loads>
 __device__ __forceinline__ float tile_weights(const f32x16& s0, const f32x16& s1, float d,
-                                              uint32_t (&p0)[8], uint32_t (&p1)[8]) {
+                                              uint32_t (&p0)[8], uint32_t (&p1)[8], const Loads& loads) {
   // The row sum is taken over the weights as the matrix unit will see them (rounded to half), with
   // packed half adds: one instruction per two weights instead of two fp32 adds, on the pipe that
   // co-executes with the other set's MFMAs (v_dot2c_f32_f16 would be exact but runs on the matrix
@@ -320,6 +380,7 @@ __device__ __forceinline__ float tile_weights(const f32x16& s0, const f32x16& s1
 #pragma unroll
   for (int sb = 0; sb < 2; ++sb) {
     float e[16];
+    if (sb == 0) loads.template at<2 * QB>(); else loads.template at<2 * QB + 1>();
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       const float x = sb ? s1[i] : s0[i];
@@ -409,12 +470,26 @@ __device__ __forceinline__ void qk_tile(const f16x8 (&kf)[4][2], const f16x8 (&q
   }
 }
 
-// Tail tile: accumulator i of slot block sb belongs to slot sbase + 32*sb + 8*(i/4) + i%4 (this lane's
-// contraction group is part of sbase).  Exponents of slots at or beyond n_total become -inf: exp2
+// The lane number, read where it is needed.  For the rarely taken paths of the tile loop (the tail
+// tile, the redone exponents of a shared piece): a value derived from the lane number at the start
+// of the kernel would have to be kept, or spilled, across every loop; the statement is volatile so
+// that it is not moved out of the path either.
+__device__ __forceinline__ int lane_number_here() {
+  int ln;
+  asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(ln));
+  return ln;
+}
+
+// Tail tile: accumulator i of slot block sb belongs to slot sbase + 4*(lane/32) + 32*sb + 8*(i/4) + i%4
+// (sbase: the first slot of the wave's 64, uniform).  Exponents of slots at or beyond n_total become -inf: exp2
 // gives them weight 0 and a maximum ignores them.  A lane (or a whole wave) left without any real
 // slot ends with the reference -65504 and a zero sum, which the merges treat as an empty part.
 __device__ __forceinline__ void mask_absent_slots(f32x16 (&S)[2][2], int sbase, int n_total) {
-  asm volatile("; tail tile: exponents of absent slots" ::: "memory");   // keeps the caller's test a real branch
+  // The lane's share of the slot index is read here: it keeps the caller's test a real branch and
+  // the 32 comparisons below inside it (the tail tile is the last one, so from values known at the
+  // start of the kernel the compiler works them out once and carries 64 scalar registers of masks
+  // through every loop).
+  sbase += 4 * (lane_number_here() >> 5);
 #pragma unroll
   for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
@@ -443,18 +518,18 @@ __device__ __forceinline__ void mask_absent_slots(f32x16 (&S)[2][2], int sbase, 
 // as every weight since the last rescale used the same one, which the exact half value guarantees.
 // O holds the tiles before this one (their P V products were issued in the preceding matrix
 // phase), so rescaling it here is consistent.
-template <int PAR, bool force>
+template <int PAR, bool force, class Loads>
 __device__ __forceinline__ void softmax_tile(f32x16 (&S)[2][2], uint32_t (&P)[2][2][8], f32x16 (&O)[2][2],
                                              float (&ref)[2], f16x4 (&qbias)[2], float (&lrun)[2], int g,
                                              int sbase, int n_total, bool tail, const char* lds,
-                                             const int (&koff)[4], const f16x8 (&qf)[2][4], f16x4 kones) {
+                                             const int (&koff)[4], const f16x8 (&qf)[2][4], f16x4 kones,
+                                             const char* ktile_mem, int kfrag_row0, const Loads& loads) {
   float lsum[2];
   bool overflow = false;
   if (__builtin_expect(tail, 0)) mask_absent_slots(S, sbase, n_total);
   if constexpr (!force) {
-#pragma unroll
-    for (int qb = 0; qb < 2; ++qb)
-      lsum[qb] = tile_weights<false>(S[0][qb], S[1][qb], 0.f, P[0][qb], P[1][qb]);
+    lsum[0] = tile_weights<false, 0>(S[0][0], S[1][0], 0.f, P[0][0], P[1][0], loads);
+    lsum[1] = tile_weights<false, 1>(S[0][1], S[1][1], 0.f, P[0][1], P[1][1], loads);
 
     // one overflow test for both query blocks; the compare is issued before the conversions to half
     // are forced out, so the branch does not wait for the VALU pipeline to drain
@@ -472,8 +547,23 @@ __device__ __forceinline__ void softmax_tile(f32x16 (&S)[2][2], uint32_t (&P)[2]
     // kept alive through the fast path, which frees their registers for the weights.  The first tile
     // of a segment comes here directly: its exponents (taken against the reference 0) are still in S.
     if constexpr (!force) {
+      // (a piece whose tiles are shared by both wave sets reads them from memory instead: set B
+      // comes here while set A's request for the tile after next is already filling this buffer)
       f16x8 kf[4][2];
-      k_frags<PAR>(lds, koff, kf);
+      if (ktile_mem) {
+        // uniform base; this lane's offset is worked out here from the lane number (row kfrag_row0 +
+        // lane % 32, 16-byte piece lane / 32 of each 32-byte step): kept from the start of the
+        // kernel it would be one more value to spill around the tile loop
+        const int ln = lane_number_here();
+        const uint32_t kfrag_off = (uint32_t)((kfrag_row0 + (ln & 31)) * 128 + (ln >> 5) * 16);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+          kf[ks][0] = *(const f16x8*)(ktile_mem + (kfrag_off + ks * 32));
+          kf[ks][1] = *(const f16x8*)(ktile_mem + (kfrag_off + ks * 32 + 32 * 128));
+        }
+      } else {
+        k_frags<PAR>(lds, koff, kf);
+      }
       qk_tile(kf, qf, qbias, kones, S);
       if (tail) mask_absent_slots(S, sbase, n_total);
     }
@@ -498,7 +588,10 @@ __device__ __forceinline__ void softmax_tile(f32x16 (&S)[2][2], uint32_t (&P)[2]
       for (int db = 0; db < 2; ++db)
 #pragma unroll
         for (int i = 0; i < 16; ++i) O[db][qb][i] *= alpha;
-      lsum[qb] = tile_weights<true>(S[0][qb], S[1][qb], d, P[0][qb], P[1][qb]);
+      // (the forced first tile comes here without the fast path: its loads are issued here)
+      if (force && qb == 0) lsum[qb] = tile_weights<true, 0>(S[0][qb], S[1][qb], d, P[0][qb], P[1][qb], loads);
+      else if (force) lsum[qb] = tile_weights<true, 1>(S[0][qb], S[1][qb], d, P[0][qb], P[1][qb], loads);
+      else lsum[qb] = tile_weights<true, 0>(S[0][qb], S[1][qb], d, P[0][qb], P[1][qb], NoLoads());
     }
   }
   lrun[0] += lsum[0];
@@ -512,9 +605,17 @@ struct TileCtx {
   const char* vbase;
   uint32_t lane_off;          // this lane's byte offset inside a tile for the direct-to-LDS loads
   uint32_t lds_ld;            // LDS byte address of this wave's 32 rows in K buffer 0 of its set
-  int t1, T, n_total, slot0;  // slot0: first slot of this lane's accumulator rows within a tile
+  int t1, T, n_total, slot0;  // slot0: first slot of this wave's accumulator rows within a tile
   int g;                      // which 8-index group of the contraction this lane holds
   bool active;
+  // which of a tile's loads this wave set issues, and where it awaits them.  Two heads: each set
+  // loads its own K (matrix phase) and V (vector phase) and awaits K at the end of the vector phase.
+  // One head, shared tiles: set A loads K for both (awaited at the end of its vector phase), set B
+  // loads V for both at the start of its vector phase -- when set A, a phase ahead, has finished
+  // with the V tile two back -- and awaits it at the end of its next matrix phase, one phase before
+  // set A multiplies by it.
+  bool shared, ldk, ldv;
+  int kfrag_row0;             // first of this wave's 64 rows inside a K tile (slow path of shared pieces)
   OVGGT_TRACE_ONLY(unsigned long long tr_m, tr_x, tr_v, tr_y, tr_w;)   // cycles in matrix phase, at its barrier, in vector phase, at its barrier
 };
 
@@ -541,7 +642,7 @@ __device__ __forceinline__ void tile_step(TileCtx& x, int tt, const int (&koff)[
   // ---- matrix phase
   __builtin_amdgcn_s_setprio(kPrioMatrix);
   if (x.active) {
-    if (more)
+    if (more && x.ldk)
       load_rows_to_lds(x.kbase + (size_t)(tt + 1) * kTileBytes, x.lane_off, x.lds_ld + (PAR ^ 1) * 2 * kTileBytes);
     f16x8 kf[4][2];
     if (!FIRST) pv_tile<PAR ^ 1>(x.lds, voff, z.P, z.O);
@@ -569,6 +670,8 @@ __device__ __forceinline__ void tile_step(TileCtx& x, int tt, const int (&koff)[
       for (int b = 0; b < 2; ++b) asm volatile("" : "+v"(z.S[a][b]));      // issued before the barrier
   }
   __builtin_amdgcn_s_setprio(kPrioVector);
+  // shared tiles: the V rows this set requested a phase ago are multiplied by the other set next
+  if (x.shared && x.ldv) __builtin_amdgcn_s_waitcnt(kWaitVm0);
   OVGGT_TRACE_ONLY(
     __builtin_amdgcn_sched_barrier(0);
     const unsigned long long tr1 = clock64();
@@ -580,11 +683,11 @@ __device__ __forceinline__ void tile_step(TileCtx& x, int tt, const int (&koff)[
   )
   // ---- vector phase
   if (x.active) {
-    if (more)
-      load_rows_to_lds(x.vbase + (size_t)(tt + 1) * kTileBytes, x.lane_off,
-                       x.lds_ld + (PAR ^ 1) * 2 * kTileBytes + kTileBytes);
+    const TileLoads vl{more && x.ldv, x.vbase + (size_t)(tt + 1) * kTileBytes, x.lane_off,
+                       x.lds_ld + (PAR ^ 1) * 2 * kTileBytes + kTileBytes};
     softmax_tile<PAR, FIRST>(z.S, z.P, z.O, z.ref, z.qbias, z.lrun, x.g, tt * kSlotTile + x.slot0, x.n_total,
-                             tt == x.T - 1 && (x.n_total & (kSlotTile - 1)) != 0, x.lds, koff, z.qf, z.kones);
+                             tt == x.T - 1 && (x.n_total & (kSlotTile - 1)) != 0, x.lds, koff, z.qf, z.kones,
+                             x.shared ? x.kbase + (size_t)tt * kTileBytes : nullptr, x.kfrag_row0, vl);
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
@@ -598,8 +701,9 @@ __device__ __forceinline__ void tile_step(TileCtx& x, int tt, const int (&koff)[
     __builtin_amdgcn_sched_barrier(0);
   )
   // K of tile tt+1 (and everything older) has landed; only V of tile tt+1 may still be in flight
-  if (more) __builtin_amdgcn_s_waitcnt(kWaitVm4);
-  else __builtin_amdgcn_s_waitcnt(kWaitVm0);
+  // (a set that requests one kind only has four loads in flight at most: it awaits them all)
+  if (more && x.ldk && x.ldv) __builtin_amdgcn_s_waitcnt(kWaitVm4);
+  else if (x.ldk) __builtin_amdgcn_s_waitcnt(kWaitVm0);
   OVGGT_TRACE_ONLY(
     __builtin_amdgcn_sched_barrier(0);
     const unsigned long long tr3 = clock64();
@@ -634,12 +738,14 @@ __device__ __forceinline__ void warm_kernel_arguments() {
 
 __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p) {
   warm_kernel_arguments();
-  __shared__ __attribute__((aligned(1024))) char lds[2 * kSetBytes];      // [set][parity][K | V]
-  const int tid = threadIdx.x, lane = tid & 63;
+  // [set][parity][K | V]; behind them room for the second slot-half merge area of a piece whose tiles
+  // both sets share (such a piece keeps its tiles in set A's region and merges in set B's and behind)
+  __shared__ __attribute__((aligned(1024))) char lds[kSetBytes + 2 * kMergeBytes];
+  const int tid = threadIdx.x, lane0 = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int set = wave >> 2, wv = wave & 3;
   const int qhalf = wv & 1, khalf = wv >> 1;
-  const int l32 = lane & 31, g = lane >> 5;
+  const int lane = lane0, l32 = lane0 & 31, g = lane0 >> 5;   // for the set-up below; every piece forms its own
 
   const int G = gridDim.x;
   const int cidx = (blockIdx.x & 7) * (G >> 3) + (blockIdx.x >> 3);
@@ -649,8 +755,9 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
     unsigned long long tr_n = 0;
   )
 
-  // per-lane LDS offsets (the set's region included)
-  char* const lset = lds + set * kSetBytes;
+  // per-lane LDS offsets (the set's region included; set B's move to set A's region and back when
+  // a piece with shared tiles begins or ends: kSetBytes is a power of two, the move is one XOR)
+  int region = set * kSetBytes;                        // where this set's tiles are at the moment
   int koff[4];
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks)
@@ -674,11 +781,11 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
   x.T = p.T;
   x.n_total = p.n_total;
   x.g = g;
-  x.slot0 = khalf * 64 + 4 * g;
+  x.slot0 = khalf * 64;
   {
     const int ld_row = lane >> 3;
     x.lane_off = (uint32_t)((wv * 32 + ld_row) * 128 + (((lane & 7) ^ swz(ld_row)) << 4));
-    x.lds_ld = (uint32_t)(uintptr_t)LDS_PTR(char, lds) + (uint32_t)(set * kSetBytes + wv * 4096);
+    x.kfrag_row0 = khalf * 64;
   }
 
   // Set B runs one barrier behind set A, so that its matrix phases coincide with A's vector phases:
@@ -705,9 +812,36 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
     const int rec_ord = p.NS == 1 ? (u == u_begin ? 0 : 1) : n_piece;
     ++n_piece;
     const bool full = (p.NS == 1 && t0 == 0 && t1 == p.T);
-    const int qb_idx = up.qb;
-    const int lh = 2 * up.hp + set;                      // this set's (layer, head)
+    // What a piece needs of the lane number (query rows, operand constants, record offsets) is worked
+    // out again from an opaque copy at its start and at its end: carried from the start of the kernel,
+    // or across the tile loop, these values are what the register allocator spills to memory.
+    int lane_p = lane0;
+    asm volatile("" : "+v"(lane_p));
+    const int l32 = lane_p & 31, g = lane_p >> 5;
+    const SetWork sw = work_of_item(up.hp, up.qb, set, p.QB, p.share);
+    const int qb_idx = sw.qb;
+    const int lh = sw.lh;                                // this set's (layer, head)
     const bool active = lh < p.LH;
+    x.shared = sw.shared;
+    x.ldk = !sw.shared || set == 0;
+    x.ldv = !sw.shared || set == 1;
+    {
+      const int want = sw.shared ? 0 : set * kSetBytes;
+      if (want != region) {                              // uniform over the wave set
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) koff[ks] ^= kSetBytes;
+#pragma unroll
+        for (int db = 0; db < 2; ++db)
+#pragma unroll
+          for (int hh = 0; hh < 2; ++hh) voff[db][hh] ^= kSetBytes;
+        region = want;
+      }
+      x.lds_ld = (uint32_t)(uintptr_t)LDS_PTR(char, lds) + (uint32_t)(region + wv * 4096);
+    }
+    // slot-half merge area: the set's own tile region once its tiles are done with; pieces with
+    // shared tiles (all in set A's region, still read by set B while A merges) use set B's region
+    // and the space behind it
+    char* const lset = lds + (sw.shared ? kSetBytes + set * kMergeBytes : set * kSetBytes);
     const int li = active ? lh / p.H : 0;
     const int h = active ? lh - li * p.H : 0;
     x.active = active;
@@ -718,8 +852,8 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
 
     // prologue: first tile of the segment into the parity-0 buffers
     if (active) {
-      load_rows_to_lds(x.kbase + (size_t)t0 * kTileBytes, x.lane_off, x.lds_ld);
-      load_rows_to_lds(x.vbase + (size_t)t0 * kTileBytes, x.lane_off, x.lds_ld + kTileBytes);
+      if (x.ldk) load_rows_to_lds(x.kbase + (size_t)t0 * kTileBytes, x.lane_off, x.lds_ld);
+      if (x.ldv) load_rows_to_lds(x.vbase + (size_t)t0 * kTileBytes, x.lane_off, x.lds_ld + kTileBytes);
     }
 
     // Q'^T fragments: lane holds query (q0 + qhalf*64 + qb*32 + l32), d = ks*16 + 8g .. +8, as
@@ -783,6 +917,10 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
     if (!odd) tile_step<1, false>(x, tt, koff, voff, z);
     OVGGT_TRACE_ONLY(tr_n += t1 - t0;)
 
+    // (end of the piece: the lane-derived values again, from a second opaque copy)
+    int lane_e = lane0;
+    asm volatile("" : "+v"(lane_e));
+    const int l32e = lane_e & 31, ge = lane_e >> 5;
     // P V of the last tile
     if (active) {
       if (odd) pv_tile<0>(lds, voff, z.P, z.O);
@@ -804,11 +942,11 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
-          for (int i = 0; i < 16; ++i) mO[((db * 2 + qb) * 16 + i) * 64 + lane] = O[db][qb][i];
+          for (int i = 0; i < 16; ++i) mO[((db * 2 + qb) * 16 + i) * 64 + lane_e] = O[db][qb][i];
 #pragma unroll
       for (int qb = 0; qb < 2; ++qb) {
-        mML[qb * 64 + lane] = z.ref[qb];
-        mML[(2 + qb) * 64 + lane] = ltot[qb];
+        mML[qb * 64 + lane_e] = z.ref[qb];
+        mML[(2 + qb) * 64 + lane_e] = ltot[qb];
       }
     }
     __syncthreads();
@@ -816,16 +954,16 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
       float mfin[2], lfin[2];
 #pragma unroll
       for (int qb = 0; qb < 2; ++qb) {
-        const float m0 = z.ref[qb], m1 = mML[qb * 64 + lane];
+        const float m0 = z.ref[qb], m1 = mML[qb * 64 + lane_e];
         const float mt = fmaxf(m0, m1);
         const float a0 = __builtin_amdgcn_exp2f(m0 - mt), a1 = __builtin_amdgcn_exp2f(m1 - mt);
         mfin[qb] = mt;
-        lfin[qb] = ltot[qb] * a0 + mML[(2 + qb) * 64 + lane] * a1;
+        lfin[qb] = ltot[qb] * a0 + mML[(2 + qb) * 64 + lane_e] * a1;
 #pragma unroll
         for (int db = 0; db < 2; ++db)
 #pragma unroll
           for (int i = 0; i < 16; ++i)
-            O[db][qb][i] = O[db][qb][i] * a0 + mO[((db * 2 + qb) * 16 + i) * 64 + lane] * a1;
+            O[db][qb][i] = O[db][qb][i] * a0 + mO[((db * 2 + qb) * 16 + i) * 64 + lane_e] * a1;
       }
       if (full) {
         // same rule as below: offsets first, then nothing but stores
@@ -833,15 +971,15 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
         float inv[2];
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
-          const int qrow = q0 + qhalf * 64 + qb * 32 + l32;
-          oo[qb] = ((size_t)qrow * p.H) * 64 + 4 * g;
+          const int qrow = q0 + qhalf * 64 + qb * 32 + l32e;
+          oo[qb] = ((size_t)qrow * p.H) * 64 + 4 * ge;
           inv[qb] = 1.0f / lfin[qb];
         }
         asm volatile("" : "+v"(oo[0]), "+v"(oo[1]), "+v"(inv[0]), "+v"(inv[1]));
         const size_t obase = ((size_t)li * p.M * p.H + h) * 64;          // uniform
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
-          const int qrow = q0 + qhalf * 64 + qb * 32 + l32;
+          const int qrow = q0 + qhalf * 64 + qb * 32 + l32e;
           if (qrow < p.M) {
             if (p.out_f32) {
               float* op = (float*)p.out + obase + oo[qb];
@@ -876,8 +1014,8 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
         // instruction writes 1 KiB of consecutive memory (partial_block_offset; the merge pass
         // reads it back the same way and transposes on its way out).
         float* rec = p.ws + (size_t)((kSegRecs * chunk_idx + rec_ord) * 2 + set) * kPartialFloats;
-        uint32_t ro = (uint32_t)(partial_block_offset(qhalf, 0, 0, 0) + lane * 4);
-        uint32_t mo = (uint32_t)(kQueryTile * 64 + qhalf * 64 + l32);
+        uint32_t ro = (uint32_t)(partial_block_offset(qhalf, 0, 0, 0) + lane_e * 4);
+        uint32_t mo = (uint32_t)(kQueryTile * 64 + qhalf * 64 + l32e);
         asm volatile("" : "+v"(ro), "+v"(mo));
         float* rp0 = rec + ro;
         float* mp = rec + mo;
@@ -891,7 +1029,7 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
               *(float4*)(rp0 + partial_block_offset(0, db, qb, ig)) = w;
             }
         }
-        if (g == 0) {
+        if (ge == 0) {
 #pragma unroll
           for (int qb = 0; qb < 2; ++qb) {
             mp[qb * 32] = mfin[qb];
@@ -909,7 +1047,7 @@ __global__ void __launch_bounds__(kAttnThreads, 1) attn_bf16_kernel(AttnParams p
   }
   if (started && set == 0) phase_barrier();            // set A: the barrier set B executed before its first tile
   OVGGT_TRACE_ONLY(
-    if (lane == 0) {
+    if (lane0 == 0) {
       unsigned long long* tr = (unsigned long long*)(p.ws + p.trace_off) - (size_t)(cidx * 8 + wave + 1) * 8;
       tr[0] = x.tr_w; tr[1] = wall_clock64() - tr_w0; tr[2] = clock64() - tr_c0; tr[5] = tr_n;
       tr[3] = x.tr_m; tr[4] = x.tr_x; tr[6] = x.tr_v; tr[7] = x.tr_y;
@@ -960,16 +1098,18 @@ constexpr int kCombinePitch = 68;                      // floats per LDS row (64
 __global__ void __launch_bounds__(256) attn_combine_kernel(AttnParams p) {
   const int item = blockIdx.x / (kQueryTile / kCombineRows);     // (layer-head, query block)
   const int rgrp = blockIdx.x % (kQueryTile / kCombineRows);     // 2 * query half + qb
-  const int qb_idx = item % p.QB;
+  const int qb_out = item % p.QB;                                // the query block whose rows are written
   const int lh = item / p.QB;
-  const int set = lh & 1;
+  const ItemOfBlock ib = item_of_block(lh, qb_out, p.QB, p.share);
+  const int qb_idx = ib.j;                                       // the plan's item within the head pair
+  const int set = ib.set;
   const int hp = lh >> 1;
   const int lane = threadIdx.x & 63, blk = threadIdx.x >> 6;
   const int l32 = lane & 31, g = lane >> 5;
   const int row = rgrp * kCombineRows + l32;                     // this thread's row within the query block
   const int li = lh / p.H;
   const int h = lh - li * p.H;
-  const int qrow0 = qb_idx * kQueryTile + rgrp * kCombineRows;   // the workgroup's first query
+  const int qrow0 = qb_out * kQueryTile + rgrp * kCombineRows;   // the workgroup's first query
   if (qrow0 >= p.M) return;                                      // whole workgroup, before any barrier
   // this thread's two pieces: blocks 2*blk and 2*blk+1 of the group (block = 4*db + ig)
   const int b0 = 2 * blk, b1 = 2 * blk + 1;
@@ -1208,6 +1348,7 @@ static hipError_t plan_attn(AttnParams& p, const Geom& g, int nl, int n_total, s
   p.LH = nl * g.H;
   p.QB = (g.M + kQueryTile - 1) / kQueryTile;
   p.T = (n_total + kSlotTile - 1) / kSlotTile;
+  p.share = (p.LH % 2 == 0 && p.QB >= 2) ? 1 : 0;      // every head pair whole, and at least one pair of blocks
   const long total = (long)((p.LH + 1) / 2) * p.QB * p.T;
   if (total > 0x7FFFFFFFL) return hipErrorInvalidValue;
   p.total_units = (int)total;
@@ -1291,6 +1432,27 @@ bool attn_plan_stats(const Geom& g, int nl, int n_total, int n_wgs, size_t ws_by
   if (plan_attn(p, g, nl, n_total, ws_bytes, &n_wgs) != hipSuccess) return false;
   const int pairs = (p.LH + 1) / 2;
   const long n_chunks = (long)p.rounds * n_wgs;
+  {
+    // items x wave sets -> (layer-head, query block): every existing block exactly once, a shared
+    // item on one head and two neighbouring blocks, and the merge pass's inverse agrees
+    std::vector<uint8_t> owned((size_t)2 * pairs * p.QB, 0);
+    for (int hp = 0; hp < pairs; ++hp)
+      for (int j = 0; j < p.QB; ++j) {
+        const SetWork a = work_of_item(hp, j, 0, p.QB, p.share), b = work_of_item(hp, j, 1, p.QB, p.share);
+        if (a.shared != b.shared) return false;
+        if (a.shared && (a.lh != b.lh || b.qb != a.qb + 1 || a.lh >= p.LH)) return false;
+        for (int set = 0; set < 2; ++set) {
+          const SetWork& w = set ? b : a;
+          if (w.lh < 0 || w.lh >= 2 * pairs || w.qb < 0 || w.qb >= p.QB) return false;
+          if (owned[(size_t)w.lh * p.QB + w.qb]++) return false;
+          const ItemOfBlock ib = item_of_block(w.lh, w.qb, p.QB, p.share);
+          if (ib.j != j || ib.set != set || (w.lh >> 1) != hp) return false;
+        }
+      }
+    for (uint8_t o : owned)
+      if (o != 1) return false;
+    st->shared_items = p.share ? pairs * (p.QB & ~1) : 0;
+  }
   std::vector<uint8_t> seen((size_t)pairs * p.QB * p.T, 0);
   std::vector<int> table_refs((size_t)pairs * p.QB, 0);                  // partial pieces seen per item
   st->n_wgs = n_wgs; st->rounds = p.rounds; st->segments = p.NS; st->balanced = p.cpp > 0 ? 1 : 0;

@@ -594,7 +594,7 @@ int ovggt_attn_plan_stats(const ovggt_config* cfg, int32_t layers_in_launch, int
   AttnPlanStats st;
   if (!attn_plan_stats(g, layers_in_launch, n_total, n_wgs, ws_bytes_for(*cfg), &st)) return OVGGT_ERR_STATE;
   out[0] = st.n_wgs; out[1] = st.rounds; out[2] = st.segments; out[3] = st.balanced; out[4] = st.pieces_max;
-  out[5] = st.tiles_min; out[6] = st.tiles_max;
+  out[5] = st.tiles_min; out[6] = st.tiles_max; out[7] = st.shared_items;
   cost[0] = st.cost_max; cost[1] = st.cost_mean;
   return OVGGT_OK;
 }

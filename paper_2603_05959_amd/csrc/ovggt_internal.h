@@ -94,6 +94,7 @@ hipError_t attn_static_ws(char** ptr, size_t* bytes);
 // the plan; false: the plan is inconsistent).  cost = tiles + a fixed charge per piece, in tiles.
 struct AttnPlanStats {
   int n_wgs, rounds, segments, balanced, pieces_max, tiles_min, tiles_max;
+  int shared_items;           // items whose two wave sets take two query blocks of one head (one fetch of its K/V tiles for both)
   float cost_max, cost_mean;
 };
 bool attn_plan_stats(const Geom& g, int nl, int n_total, int n_wgs, size_t ws_bytes, AttnPlanStats* st);

@@ -145,10 +145,12 @@ def test_attention_hard_value_distributions(kind):
     print(f"{kind}: worst attention err/RMS {worst:.3e}")
 
 
-# the last shape has 17 query blocks: more than the merge pass's table of records holds, so the pass
-# lists each item's records itself
+# (2100, 2500) has 17 query blocks: more than the merge pass's table of records holds, so the pass
+# lists each item's records itself; the last two have an even number of heads and three or five
+# query blocks, so workgroups pass from items whose two halves share one head's tiles to the mixed
+# item of the odd last block and back, several pieces each
 @pytest.mark.parametrize("M,B,H,C", [(1, 64, 1, 64), (37, 74, 2, 1024), (130, 1000, 5, 4096), (128, 256, 16, 8),
-                                     (2100, 2500, 2, 64)])
+                                     (2100, 2500, 2, 64), (300, 6000, 4, 64), (520, 3000, 2, 128)])
 def test_bf16_odd_shapes(M, B, H, C):
     cfg = synth.preset(1, M=M, H=H, C=C, B=B, T=max(6, 2 * B // M + 3) if M > 1 else 70, n_special=min(M - 1, 2))
     run_stream(cfg)

@@ -139,4 +139,11 @@ def test_attention_plans_cover_every_tile_once():
     st = B.ovggt_attn_plan_stats(cfg24, 24, 17758, 256)
     assert st["rounds"] == 9 and st["segments"] == 1 and st["tiles_max"] - st["tiles_min"] <= 8
     assert B.ovggt_cache_query_bytes(cfg24)[2] == B.ovggt_cache_query_bytes(B.make_config(1, 16, 64, 1374, 1024, 16384, "bf16"))[2]
+    # items whose two halves of the workgroup share one head's tiles: all block pairs of every head when
+    # the launch has an even number of heads (the odd eleventh block of two heads makes a mixed item)
+    assert st["shared_items"] == 192 * 10
+    assert B.ovggt_attn_plan_stats(B.make_config(1, 16, 64, 1374, 1024, 16384, "bf16"), 1, 17758, 256)["shared_items"] == 80
+    assert B.ovggt_attn_plan_stats(B.make_config(1, 5, 64, 130, 64, 1000, "bf16"), 1, 1130, 256)["shared_items"] == 0
+    assert B.ovggt_attn_plan_stats(B.make_config(1, 2, 64, 256, 64, 1000, "bf16"), 1, 1256, 256)["shared_items"] == 2
+    assert B.ovggt_attn_plan_stats(B.make_config(1, 2, 64, 100, 64, 1000, "bf16"), 1, 1100, 256)["shared_items"] == 0
     print(st)
