@@ -203,7 +203,7 @@ struct AttnParams {
 // aligned in every head pair (one piece per workgroup in all but the last segment).
 struct UnitPos {
   bool valid;                 // false: an empty slot behind the head pair's last unit
-  int hp, s, qb;              // head pair, segment, query block
+  int hp, s, qb;              // head pair, segment, item within the head pair (called query block in the plan: see work_of_item)
   int tile;                   // first tile of the unit's run
   int seg_end;                // end of the segment (exclusive)
   int combo;                  // running index of (hp, s, qb)
